@@ -1,0 +1,143 @@
+/*
+ * dsv_attn.h - C ABI of the MI355X (gfx950) library for the per-step hot path under
+ * micro-request execution: attention of one mixed prefill+decode batch over a paged KV
+ * cache, and the chunked KV pack/unpack that hands a split request's cache between
+ * instances.
+ *
+ * Conventions for every entry point
+ *   - Plain C, no exceptions, no global state that outlives a call, thread-compatible.
+ *   - "device" pointers are HIP device memory on the current device; "host" pointers are
+ *     ordinary host memory.  All buffers are caller-owned; the library allocates no device
+ *     memory and keeps no pointer after the call returns.
+ *   - All GPU work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream).  Calls never synchronise.  Host arrays are consumed before return.
+ *   - Return value: DSV_OK (0) or a negative DSV_E_* code.  When a negative code is
+ *     returned nothing has been enqueued.
+ *   - bf16 = upper 16 bits of IEEE-754 binary32, stored as uint16.
+ *   - Block-table entries are trusted (not range-checked against num_blocks).
+ */
+#ifndef DSV_ATTN_H
+#define DSV_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DSV_OK              0
+#define DSV_E_INVALID      -1   /* null pointer, bad length, chunk outside its table, ...   */
+#define DSV_E_UNSUPPORTED  -2   /* head_dim not 64/128, block_size not 16, group too large   */
+#define DSV_E_WORKSPACE    -3   /* workspace smaller than attn_mixed_batch_workspace_bytes() */
+#define DSV_E_LAUNCH       -4   /* HIP reported an error while enqueueing                    */
+
+#define DSV_OUT_F32 0
+#define DSV_OUT_BF16 1
+
+/*
+ * A paged KV pool (paper sections 2.1 and 4.3: the KV cache is kept in GPU memory in
+ * fixed-size blocks and is append-only).  K and V have identical geometry:
+ *   layer l, block b, slot s, kv head g, dim d  ->
+ *   base[l*layer_stride + ((b*block_size + s)*num_kv_heads + g)*head_dim + d]   (bf16 elements)
+ * Token t of a request lives in block block_table[t / block_size], slot t % block_size.
+ */
+typedef struct {
+  void*   k_base;        /* device */
+  void*   v_base;        /* device */
+  int64_t layer_stride;  /* elements between consecutive layers; ignored when num_layers == 1 */
+  int32_t num_layers;
+  int32_t num_blocks;
+  int32_t block_size;    /* must be 16 */
+  int32_t num_kv_heads;
+  int32_t head_dim;      /* 64 or 128 */
+} dsv_kv_pool;
+
+/*
+ * One contiguous chunk of a request's KV = one transfer unit (paper section 4.3: a
+ * micro-request's KV is shipped in equal-sized chunks regardless of token type; the last
+ * chunk of a range may be shorter and is stored short).
+ * Chunk layout inside chunk_buf, starting at element chunk_offset:
+ *   [layer][K=0|V=1][num_tokens][num_kv_heads][head_dim]  bf16, tight.
+ */
+typedef struct {
+  int32_t seq;           /* row of the block table                                  */
+  int32_t token_begin;   /* first token position of the chunk (need not be a multiple of 16) */
+  int32_t num_tokens;    /* > 0                                                     */
+  int32_t reserved;      /* must be 0                                               */
+  int64_t chunk_offset;  /* element offset of the chunk in chunk_buf; multiple of 8 */
+} dsv_chunk_desc;
+
+/*
+ * Bytes of device workspace attn_mixed_batch needs for this batch (split-context partial
+ * results and work lists).  Arguments as in attn_mixed_batch.  Returns 0 if the batch is
+ * invalid.
+ */
+size_t attn_mixed_batch_workspace_bytes(int32_t num_seqs, const int32_t* q_offsets_host,
+                                        const int32_t* ctx_lens_host, int32_t num_q_heads,
+                                        int32_t num_kv_heads, int32_t head_dim);
+
+/*
+ * Attention of one mixed batch (paper section 3.1 "Unified execution instances", section 4.2
+ * and Alg. 2: each step runs one token-level batch holding all decode tokens plus prefill
+ * spans; section 3.1 "Micro-request abstraction": a span is any contiguous token range of a
+ * request and resumes on the earlier tokens as cached prefix; section 2.1: attention is
+ * autoregressive over the KV cache).
+ *
+ * Segment i has q_len_i = q_offsets[i+1]-q_offsets[i] >= 1 new tokens and ctx_lens[i] >=
+ * q_len_i KV tokens in total, its own new tokens included (their K/V must already be in the
+ * pool).  New token j sits at position p = ctx_lens[i]-q_len_i+j and attends to tokens 0..p
+ * of the segment's block-table row.  Query head h reads KV head h / (num_q_heads/num_kv_heads).
+ *   out[q_offsets[i]+j][h][:] = sum_t softmax_t(softmax_scale * <q, K[t]>) * V[t],  t = 0..p
+ * Segments with q_len 1 (decodes) and longer ones (prefill spans) may come in any order.
+ *
+ *   q            device, bf16 [total_q][num_q_heads][head_dim]
+ *   out          device, [total_q][num_q_heads][head_dim], fp32 (DSV_OUT_F32) or bf16
+ *                (DSV_OUT_BF16: round-to-nearest-even of the fp32 result)
+ *   pool, layer  the pool and the layer attended (0 <= layer < num_layers)
+ *   block_tables device, int32 [num_seqs][max_blocks_per_seq]; row i needs
+ *                ceil(ctx_lens[i]/16) valid entries, the rest is never read
+ *   q_offsets, ctx_lens            device, int32 [num_seqs+1] and [num_seqs]
+ *   q_offsets_host, ctx_lens_host  host copies of the same (the batch was composed on the host)
+ *   workspace    device, 256-byte aligned, at least attn_mixed_batch_workspace_bytes(); may be
+ *                reused once the stream has passed this call
+ * Accumulation is fp32; probabilities entering the PV product of prefill spans are rounded to
+ * bf16.  num_seqs == 0 is a no-op.
+ */
+int attn_mixed_batch(const void* q, void* out, const dsv_kv_pool* pool, int32_t layer,
+                     const int32_t* block_tables, int32_t max_blocks_per_seq,
+                     const int32_t* q_offsets, const int32_t* ctx_lens,
+                     const int32_t* q_offsets_host, const int32_t* ctx_lens_host,
+                     int32_t num_seqs, int32_t num_q_heads, float softmax_scale,
+                     int32_t out_dtype, void* workspace, size_t workspace_bytes,
+                     void* hip_stream);
+
+/*
+ * Gather token ranges of requests from a paged pool into contiguous chunks, all layers
+ * (paper section 4.3: the sender's side of chunk-based KV transfer).  Byte-exact copy.
+ *   descs       device array of num_chunks descriptors;  descs_host: host copy of the same
+ *   chunk_buf   device, 16-byte aligned; chunk c is written at chunk_offset_c
+ * Chunks must not overlap in chunk_buf.  num_chunks == 0 is a no-op.
+ */
+int kv_pack_chunks(const dsv_kv_pool* src, const int32_t* block_tables,
+                   int32_t max_blocks_per_seq, const dsv_chunk_desc* descs,
+                   const dsv_chunk_desc* descs_host, int32_t num_chunks, void* chunk_buf,
+                   void* hip_stream);
+
+/*
+ * Scatter contiguous chunks into a paged pool through the receiver's own block table (paper
+ * section 4.3: placement is chosen on the receiver side).  Only the covered token slots are
+ * written; every other byte of the destination pool is left as it was.  Byte-exact copy.
+ */
+int kv_unpack_chunks(const void* chunk_buf, const dsv_chunk_desc* descs,
+                     const dsv_chunk_desc* descs_host, int32_t num_chunks,
+                     const dsv_kv_pool* dst, const int32_t* dst_block_tables,
+                     int32_t max_blocks_per_seq, void* hip_stream);
+
+/* Library build identification: a static string, e.g. "dsv_attn gfx950 <date>". */
+const char* dsv_build_info(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSV_ATTN_H */

@@ -1,0 +1,168 @@
+"""ctypes binding of libdsv_attn.so: argument marshalling only.
+
+torch is used for device memory and streams; tensors are passed to the library as raw device
+pointers.  Function names and argument order follow ``include/dsv_attn.h``.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libdsv_attn.so")
+_lib = None
+
+DSV_OUT_F32, DSV_OUT_BF16 = 0, 1
+_ERRORS = {-1: "DSV_E_INVALID", -2: "DSV_E_UNSUPPORTED", -3: "DSV_E_WORKSPACE", -4: "DSV_E_LAUNCH"}
+
+
+class DsvError(RuntimeError):
+    def __init__(self, fn: str, code: int):
+        super().__init__("%s failed: %s (%d)" % (fn, _ERRORS.get(code, "?"), code))
+        self.code = code
+
+
+class _Pool(C.Structure):
+    _fields_ = [("k_base", C.c_void_p), ("v_base", C.c_void_p), ("layer_stride", C.c_int64),
+                ("num_layers", C.c_int32), ("num_blocks", C.c_int32), ("block_size", C.c_int32),
+                ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32)]
+
+
+CHUNK_DTYPE = np.dtype([("seq", "<i4"), ("token_begin", "<i4"), ("num_tokens", "<i4"),
+                        ("reserved", "<i4"), ("chunk_offset", "<i8")])
+assert CHUNK_DTYPE.itemsize == 24
+
+EXPORTS = ("attn_mixed_batch_workspace_bytes", "attn_mixed_batch", "kv_pack_chunks",
+           "kv_unpack_chunks", "dsv_build_info")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libdsv_attn.so (built in-tree by ``paper_2504_09285_amd.build``).  Raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError("libdsv_attn.so is not built: run `python -m paper_2504_09285_amd.build` "
+                           "(there is no fallback path)")
+    lib = C.CDLL(_LIB_PATH)
+    i32p, vp = C.POINTER(C.c_int32), C.c_void_p
+    lib.attn_mixed_batch_workspace_bytes.restype = C.c_size_t
+    lib.attn_mixed_batch_workspace_bytes.argtypes = [C.c_int32, i32p, i32p, C.c_int32, C.c_int32, C.c_int32]
+    lib.attn_mixed_batch.restype = C.c_int
+    lib.attn_mixed_batch.argtypes = [vp, vp, C.POINTER(_Pool), C.c_int32, vp, C.c_int32, vp, vp,
+                                     i32p, i32p, C.c_int32, C.c_int32, C.c_float, C.c_int32,
+                                     vp, C.c_size_t, vp]
+    lib.kv_pack_chunks.restype = C.c_int
+    lib.kv_pack_chunks.argtypes = [C.POINTER(_Pool), vp, C.c_int32, vp, vp, C.c_int32, vp, vp]
+    lib.kv_unpack_chunks.restype = C.c_int
+    lib.kv_unpack_chunks.argtypes = [vp, vp, vp, C.c_int32, C.POINTER(_Pool), vp, C.c_int32, vp]
+    lib.dsv_build_info.restype = C.c_char_p
+    lib.dsv_build_info.argtypes = []
+    _lib = lib
+    return lib
+
+
+def build_info() -> str:
+    return load_library().dsv_build_info().decode()
+
+
+def _host_i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a), dtype=np.int32)
+
+
+def _i32_ptr(a: np.ndarray):
+    return a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+class KVPool:
+    """A paged KV pool held in two torch tensors ``[L, num_blocks, 16, Hkv, D]`` (bf16, device)."""
+
+    def __init__(self, k, v):
+        assert k.shape == v.shape and k.dim() == 5 and k.is_contiguous() and v.is_contiguous()
+        assert k.element_size() == 2 and v.element_size() == 2
+        self.k, self.v = k, v
+        L, NB, bs, Hkv, D = k.shape
+        self.L, self.NB, self.bs, self.Hkv, self.D = L, NB, bs, Hkv, D
+        self._c = _Pool(k.data_ptr(), v.data_ptr(), NB * bs * Hkv * D, L, NB, bs, Hkv, D)
+
+    @property
+    def c(self):
+        return C.byref(self._c)
+
+
+class ChunkDescs:
+    """Chunk descriptors: host array (numpy, CHUNK_DTYPE) plus its device copy."""
+
+    def __init__(self, chunks, device="cuda"):
+        import torch
+        ch = np.asarray(chunks, dtype=np.int64).reshape(-1, 4)
+        host = np.zeros(ch.shape[0], dtype=CHUNK_DTYPE)
+        host["seq"], host["token_begin"], host["num_tokens"], host["chunk_offset"] = ch.T
+        self.host = host
+        self.n = int(ch.shape[0])
+        raw = np.frombuffer(host.tobytes(), dtype=np.uint8).copy() if self.n else np.zeros(0, np.uint8)
+        self.dev = torch.from_numpy(raw).to(device)
+
+
+def attn_mixed_batch_workspace_bytes(q_offsets_host, ctx_lens_host, num_q_heads, num_kv_heads,
+                                     head_dim) -> int:
+    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
+    return int(load_library().attn_mixed_batch_workspace_bytes(
+        cl.shape[0], _i32_ptr(qo), _i32_ptr(cl), num_q_heads, num_kv_heads, head_dim))
+
+
+def attn_mixed_batch(q, out, pool: KVPool, layer, block_tables, q_offsets, ctx_lens,
+                     q_offsets_host, ctx_lens_host, num_q_heads, softmax_scale, workspace,
+                     stream=None) -> None:
+    """See ``attn_mixed_batch`` in include/dsv_attn.h.  ``out`` dtype selects fp32 or bf16."""
+    import torch
+    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
+    out_dtype = DSV_OUT_F32 if out.dtype == torch.float32 else DSV_OUT_BF16
+    assert out.dtype in (torch.float32, torch.bfloat16)
+    assert block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous()
+    assert q_offsets.dtype == torch.int32 and ctx_lens.dtype == torch.int32
+    assert q.is_contiguous() and out.is_contiguous() and q.element_size() == 2
+    assert tuple(q.shape) == tuple(out.shape)
+    rc = load_library().attn_mixed_batch(
+        q.data_ptr(), out.data_ptr(), pool.c, int(layer), block_tables.data_ptr(),
+        int(block_tables.shape[1]), q_offsets.data_ptr(), ctx_lens.data_ptr(), _i32_ptr(qo), _i32_ptr(cl),
+        int(cl.shape[0]), int(num_q_heads), float(softmax_scale), out_dtype,
+        workspace.data_ptr(), int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
+    if rc:
+        raise DsvError("attn_mixed_batch", rc)
+
+
+def kv_pack_chunks(src: KVPool, block_tables, descs: ChunkDescs, chunk_buf, stream=None) -> None:
+    """See ``kv_pack_chunks`` in include/dsv_attn.h."""
+    assert block_tables.is_contiguous() and chunk_buf.is_contiguous()
+    rc = load_library().kv_pack_chunks(
+        src.c, block_tables.data_ptr(), int(block_tables.shape[1]), descs.dev.data_ptr(),
+        descs.host.ctypes.data, descs.n, chunk_buf.data_ptr(), _stream_ptr(stream))
+    if rc:
+        raise DsvError("kv_pack_chunks", rc)
+
+
+def kv_unpack_chunks(chunk_buf, descs: ChunkDescs, dst: KVPool, dst_block_tables, stream=None) -> None:
+    """See ``kv_unpack_chunks`` in include/dsv_attn.h."""
+    assert dst_block_tables.is_contiguous() and chunk_buf.is_contiguous()
+    rc = load_library().kv_unpack_chunks(
+        chunk_buf.data_ptr(), descs.dev.data_ptr(), descs.host.ctypes.data, descs.n, dst.c,
+        dst_block_tables.data_ptr(), int(dst_block_tables.shape[1]), _stream_ptr(stream))
+    if rc:
+        raise DsvError("kv_unpack_chunks", rc)

@@ -1,0 +1,312 @@
+// attn_mixed_batch: host entry point, batch planning (host counts + device work lists) and the
+// split-context merge kernel.
+//
+// One step of a unified instance runs a token-level batch that mixes prefill spans and decode
+// tokens (paper section 3.1 "Unified execution instances", section 4.2, Alg. 2).  The host side
+// here only validates the batch and sizes the grids; the work lists themselves are produced by
+// a small planning kernel on the same stream, so a call never synchronises and never copies
+// from host memory.
+#include <math.h>
+#include <stdlib.h>
+
+#include "attn_internal.h"
+
+namespace dsv {
+namespace {
+
+constexpr int kPlanThreads = 1024;
+
+int env_int(const char* name, int fallback) {
+  const char* s = getenv(name);
+  if (!s || !*s) return fallback;
+  return atoi(s);
+}
+
+// ---- plan: counts --------------------------------------------------------------------------
+
+__host__ __device__ inline bool on_row_path(int q_len, const PlanConfig& c) {
+  return q_len < c.mfma_min_qlen;
+}
+__host__ __device__ inline int parts_of(int ctx_eff, const PlanConfig& c) {
+  return (ctx_eff + c.part_tokens - 1) / c.part_tokens;
+}
+
+int validate_batch(int32_t S, const int32_t* qo, const int32_t* cl, int32_t max_blocks) {
+  if (S < 0) return DSV_E_INVALID;
+  if (S == 0) return DSV_OK;
+  if (!qo || !cl) return DSV_E_INVALID;
+  if (qo[0] != 0) return DSV_E_INVALID;
+  for (int i = 0; i < S; ++i) {
+    const int64_t q_len = (int64_t)qo[i + 1] - qo[i];
+    if (q_len < 1 || cl[i] < q_len) return DSV_E_INVALID;
+    if (max_blocks >= 0 && ceil_div(cl[i], kBlockSize) > max_blocks) return DSV_E_INVALID;
+  }
+  return DSV_OK;
+}
+
+PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl) {
+  PlanConfig c;
+  c.mfma_min_qlen = env_int("DSV_MFMA_MIN_QLEN", 1 << 30);
+  c.tile_tokens = 32;
+  // Partition size: enough (row, partition) items to fill 256 CUs several times over, but not so
+  // small that the partial results written per partition matter next to the KV bytes read.
+  int64_t row_tokens = 0;
+  for (int i = 0; i < S; ++i) {
+    const int q_len = qo[i + 1] - qo[i];
+    if (q_len >= c.mfma_min_qlen) continue;
+    const int64_t prefix = cl[i] - q_len;
+    row_tokens += (int64_t)q_len * prefix + (int64_t)q_len * (q_len + 1) / 2;
+  }
+  int64_t part = (row_tokens / 4096 + 15) / 16 * 16;
+  if (part < 128) part = 128;
+  if (part > 1024) part = 1024;
+  const int forced = env_int("DSV_PART_TOKENS", 0);
+  if (forced >= 16) part = forced / 16 * 16;
+  c.part_tokens = (int32_t)part;
+  return c;
+}
+
+PlanCounts count_plan(int32_t S, const int32_t* qo, const int32_t* cl, const PlanConfig& c) {
+  PlanCounts n;
+  for (int i = 0; i < S; ++i) {
+    const int q_len = qo[i + 1] - qo[i];
+    if (on_row_path(q_len, c)) {
+      n.rows += q_len;
+      for (int j = 0; j < q_len; ++j) {
+        const int np = parts_of(cl[i] - q_len + j + 1, c);
+        n.items += np;
+        if (np > 1) n.split_items += np;
+        if (np > n.max_parts) n.max_parts = np;
+      }
+    } else {
+      n.tiles += ceil_div(q_len, c.tile_tokens);
+    }
+  }
+  return n;
+}
+
+// ---- workspace layout ----------------------------------------------------------------------
+
+size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+size_t carve(const PlanCounts& n, int Hq, int D, char* base, WorkLists* w) {
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    char* p = base ? base + off : nullptr;
+    off = align_up(off + bytes);
+    return p;
+  };
+  const size_t rows = (size_t)n.rows, items = (size_t)n.items, tiles = (size_t)n.tiles;
+  char* p0 = take(rows * 4); char* p1 = take(rows * 4); char* p2 = take(rows * 4);
+  char* p3 = take(rows * 4); char* p4 = take(rows * 4);
+  char* p5 = take(items * 4); char* p6 = take(items * 4);
+  char* p7 = take(tiles * 4); char* p8 = take(tiles * 4);
+  char* p9 = take(items * (size_t)Hq * D * 4);
+  char* p10 = take(items * (size_t)Hq * 2 * 4);
+  if (w) {
+    w->row_seq = (int32_t*)p0; w->row_qtok = (int32_t*)p1; w->row_ctx = (int32_t*)p2;
+    w->row_item0 = (int32_t*)p3; w->row_nparts = (int32_t*)p4;
+    w->item_row = (int32_t*)p5; w->item_part = (int32_t*)p6;
+    w->tile_seq = (int32_t*)p7; w->tile_q0 = (int32_t*)p8;
+    w->part_acc = (float*)p9; w->part_ml = (float*)p10;
+  }
+  return off + 256;
+}
+
+// ---- plan: device work lists ---------------------------------------------------------------
+
+// Exclusive scan of one int per thread across the block; returns the block total in *total.
+__device__ int block_exclusive_scan(int v, int* smem, int* total) {
+  const int tid = threadIdx.x;
+  smem[tid] = v;
+  __syncthreads();
+  for (int off = 1; off < kPlanThreads; off <<= 1) {
+    const int add = tid >= off ? smem[tid - off] : 0;
+    __syncthreads();
+    smem[tid] += add;
+    __syncthreads();
+  }
+  const int incl = smem[tid];
+  *total = smem[kPlanThreads - 1];
+  __syncthreads();
+  return incl - v;
+}
+
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __restrict__ q_offsets,
+                                                            const int32_t* __restrict__ ctx_lens,
+                                                            int32_t S, PlanConfig c, WorkLists w) {
+  __shared__ int smem[kPlanThreads];
+  int row_carry = 0, item_carry = 0, tile_carry = 0;
+  for (int base = 0; base < S; base += kPlanThreads) {
+    const int i = base + (int)threadIdx.x;
+    int q0 = 0, q_len = 0, ctx = 0, n_rows = 0, n_items = 0, n_tiles = 0;
+    if (i < S) {
+      q0 = q_offsets[i];
+      q_len = q_offsets[i + 1] - q0;
+      ctx = ctx_lens[i];
+      if (on_row_path(q_len, c)) {
+        n_rows = q_len;
+        for (int j = 0; j < q_len; ++j) n_items += parts_of(ctx - q_len + j + 1, c);
+      } else {
+        n_tiles = (q_len + c.tile_tokens - 1) / c.tile_tokens;
+      }
+    }
+    int tot_rows, tot_items, tot_tiles;
+    int row0 = row_carry + block_exclusive_scan(n_rows, smem, &tot_rows);
+    int item0 = item_carry + block_exclusive_scan(n_items, smem, &tot_items);
+    int tile0 = tile_carry + block_exclusive_scan(n_tiles, smem, &tot_tiles);
+    for (int j = 0; j < n_rows; ++j) {
+      const int ctx_eff = ctx - q_len + j + 1;
+      const int np = parts_of(ctx_eff, c);
+      const int r = row0 + j;
+      w.row_seq[r] = i;
+      w.row_qtok[r] = q0 + j;
+      w.row_ctx[r] = ctx_eff;
+      w.row_item0[r] = item0;
+      w.row_nparts[r] = np;
+      for (int p = 0; p < np; ++p) {
+        w.item_row[item0 + p] = r;
+        w.item_part[item0 + p] = p;
+      }
+      item0 += np;
+    }
+    for (int t = 0; t < n_tiles; ++t) {
+      w.tile_seq[tile0 + t] = i;
+      w.tile_q0[tile0 + t] = t * c.tile_tokens;
+    }
+    row_carry += tot_rows;
+    item_carry += tot_items;
+    tile_carry += tot_tiles;
+  }
+}
+
+// ---- split-context merge -------------------------------------------------------------------
+// Row r with n > 1 partitions: m* = max_p m_p; l* = sum_p l_p 2^(m_p-m*);
+// out = sum_p acc_p 2^(m_p-m*) / l*.   Each thread owns 4 consecutive dims of one head.
+template <int D>
+__global__ __launch_bounds__(256) void merge_kernel(AttnArgs a, WorkLists w) {
+  constexpr int kThreadsPerHead = D / 4;
+  constexpr int kHeadsPerBlock = 256 / kThreadsPerHead;
+  const int r = blockIdx.x;
+  const int np = w.row_nparts[r];
+  if (np <= 1) return;
+  const int h = blockIdx.y * kHeadsPerBlock + (int)threadIdx.x / kThreadsPerHead;
+  if (h >= a.Hq) return;
+  const int d4 = (int)threadIdx.x % kThreadsPerHead;
+  const int item0 = w.row_item0[r];
+  const float2* ml = reinterpret_cast<const float2*>(w.part_ml);
+  float m = -INFINITY;
+  for (int p = 0; p < np; ++p) m = fmaxf(m, ml[(int64_t)(item0 + p) * a.Hq + h].x);
+  float l = 0.f;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  const float4* pa = reinterpret_cast<const float4*>(w.part_acc);
+  for (int p = 0; p < np; ++p) {
+    const int64_t ph = (int64_t)(item0 + p) * a.Hq + h;
+    const float2 v = ml[ph];
+    const float s = exp2f(v.x - m);
+    l += v.y * s;
+    const float4 x = pa[ph * kThreadsPerHead + d4];
+    acc.x += x.x * s; acc.y += x.y * s; acc.z += x.z * s; acc.w += x.w * s;
+  }
+  const float inv = 1.0f / l;
+  acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+  const int64_t o = ((int64_t)w.row_qtok[r] * a.Hq + h) * D + d4 * 4;
+  if (a.out_bf16) {
+    ushort4 ob;
+    ob.x = f32_to_bf16_rne(acc.x); ob.y = f32_to_bf16_rne(acc.y);
+    ob.z = f32_to_bf16_rne(acc.z); ob.w = f32_to_bf16_rne(acc.w);
+    *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(a.out) + o) = ob;
+  } else {
+    *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + o) = acc;
+  }
+}
+
+}  // namespace
+
+int launch_merge(const AttnArgs& a, const WorkLists& w, const PlanCounts& n, hipStream_t stream) {
+  if (n.split_items == 0) return DSV_OK;
+  if (a.D == 128) {
+    dim3 grid((unsigned)n.rows, (unsigned)ceil_div(a.Hq, 8));
+    hipLaunchKernelGGL(merge_kernel<128>, grid, dim3(256), 0, stream, a, w);
+  } else {
+    dim3 grid((unsigned)n.rows, (unsigned)ceil_div(a.Hq, 16));
+    hipLaunchKernelGGL(merge_kernel<64>, grid, dim3(256), 0, stream, a, w);
+  }
+  return launch_status();
+}
+
+}  // namespace dsv
+
+using namespace dsv;
+
+extern "C" size_t attn_mixed_batch_workspace_bytes(int32_t num_seqs, const int32_t* q_offsets_host,
+                                                   const int32_t* ctx_lens_host, int32_t num_q_heads,
+                                                   int32_t num_kv_heads, int32_t head_dim) {
+  if (num_q_heads < 1 || num_kv_heads < 1 || num_q_heads % num_kv_heads) return 0;
+  if (head_dim != 64 && head_dim != 128) return 0;
+  if (validate_batch(num_seqs, q_offsets_host, ctx_lens_host, -1) != DSV_OK) return 0;
+  const PlanConfig c = choose_plan(num_seqs, q_offsets_host, ctx_lens_host);
+  const PlanCounts n = count_plan(num_seqs, q_offsets_host, ctx_lens_host, c);
+  return carve(n, num_q_heads, head_dim, nullptr, nullptr);
+}
+
+extern "C" int attn_mixed_batch(const void* q, void* out, const dsv_kv_pool* pool, int32_t layer,
+                                const int32_t* block_tables, int32_t max_blocks_per_seq,
+                                const int32_t* q_offsets, const int32_t* ctx_lens,
+                                const int32_t* q_offsets_host, const int32_t* ctx_lens_host,
+                                int32_t num_seqs, int32_t num_q_heads, float softmax_scale,
+                                int32_t out_dtype, void* workspace, size_t workspace_bytes,
+                                void* hip_stream) {
+  int rc = check_pool(pool);
+  if (rc) return rc;
+  if (num_seqs < 0) return DSV_E_INVALID;
+  if (num_seqs == 0) return DSV_OK;
+  if (!q || !out || !block_tables || !q_offsets || !ctx_lens || !workspace) return DSV_E_INVALID;
+  if (layer < 0 || layer >= pool->num_layers || max_blocks_per_seq < 1) return DSV_E_INVALID;
+  if (num_q_heads < 1 || num_q_heads % pool->num_kv_heads) return DSV_E_INVALID;
+  if (out_dtype != DSV_OUT_F32 && out_dtype != DSV_OUT_BF16) return DSV_E_INVALID;
+  if (!(softmax_scale == softmax_scale) || isinf(softmax_scale)) return DSV_E_INVALID;
+  if ((reinterpret_cast<uintptr_t>(q) & 15) || (reinterpret_cast<uintptr_t>(out) & 15) ||
+      (reinterpret_cast<uintptr_t>(pool->k_base) & 15) || (reinterpret_cast<uintptr_t>(pool->v_base) & 15) ||
+      (reinterpret_cast<uintptr_t>(workspace) & 255))
+    return DSV_E_INVALID;
+  if (pool->num_layers > 1 && (pool->layer_stride % 8)) return DSV_E_INVALID;
+  rc = validate_batch(num_seqs, q_offsets_host, ctx_lens_host, max_blocks_per_seq);
+  if (rc) return rc;
+
+  const PlanConfig cfg = choose_plan(num_seqs, q_offsets_host, ctx_lens_host);
+  const PlanCounts n = count_plan(num_seqs, q_offsets_host, ctx_lens_host, cfg);
+  if (n.items > 0x7fffffffLL || n.tiles > 0x7fffffffLL || n.rows > 0x7fffffffLL)
+    return DSV_E_UNSUPPORTED;
+  WorkLists w;
+  const size_t need = carve(n, num_q_heads, pool->head_dim, static_cast<char*>(workspace), &w);
+  if (workspace_bytes < need) return DSV_E_WORKSPACE;
+
+  AttnArgs a;
+  const int64_t layer_off = pool->num_layers > 1 ? (int64_t)layer * pool->layer_stride : 0;
+  a.q = static_cast<const uint16_t*>(q);
+  a.out = out;
+  a.k_pool = static_cast<const uint16_t*>(pool->k_base) + layer_off;
+  a.v_pool = static_cast<const uint16_t*>(pool->v_base) + layer_off;
+  a.block_tables = block_tables;
+  a.q_offsets = q_offsets;
+  a.ctx_lens = ctx_lens;
+  a.max_blocks = max_blocks_per_seq;
+  a.num_seqs = num_seqs;
+  a.Hq = num_q_heads;
+  a.Hkv = pool->num_kv_heads;
+  a.D = pool->head_dim;
+  a.scale_log2e = softmax_scale * 1.4426950408889634f;
+  a.out_bf16 = out_dtype == DSV_OUT_BF16;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, q_offsets, ctx_lens,
+                     num_seqs, cfg, w);
+  if ((rc = launch_status())) return rc;
+  if (n.tiles && (rc = launch_prefill_tiles(a, w, cfg, n, stream))) return rc;
+  if (n.items && (rc = launch_rows(a, w, cfg, n, stream))) return rc;
+  if ((rc = launch_merge(a, w, n, stream))) return rc;
+  return DSV_OK;
+}
+
+extern "C" const char* dsv_build_info(void) { return "dsv_attn gfx950 " __DATE__ " " __TIME__; }

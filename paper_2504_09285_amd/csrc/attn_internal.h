@@ -1,0 +1,66 @@
+// Internal interfaces between the attention translation units (not part of the ABI).
+#pragma once
+#include "dsv_common.h"
+
+namespace dsv {
+
+// How a batch is cut into GPU work.  Computed identically on the host (to size grids and the
+// workspace) and on the device (to fill the work lists), from q_offsets / ctx_lens alone.
+//
+//  * "row" work: one query token against its causal context, cut along the context into
+//    partitions of part_tokens tokens (split-K).  Used for decodes and for prefill spans
+//    shorter than mfma_min_qlen tokens.  A row with one partition writes its output directly;
+//    otherwise each partition writes an unnormalised partial and a merge kernel combines them.
+//  * "tile" work: tile_tokens consecutive query tokens of a long prefill span for one KV head,
+//    processed by the MFMA kernel.
+struct PlanConfig {
+  int32_t part_tokens;     // multiple of 16
+  int32_t mfma_min_qlen;   // spans with q_len >= this go to the MFMA kernel
+  int32_t tile_tokens;     // query tokens per MFMA tile
+};
+
+struct PlanCounts {
+  int64_t rows = 0;        // query tokens on the row path
+  int64_t items = 0;       // (row, partition) work items
+  int64_t split_items = 0; // items belonging to rows with more than one partition
+  int64_t tiles = 0;       // (span, q-tile) work items of the MFMA path
+  int32_t max_parts = 0;
+};
+
+// Device-resident work lists, carved out of the caller's workspace.
+struct WorkLists {
+  int32_t* row_seq;        // [rows] segment of the row
+  int32_t* row_qtok;       // [rows] index of the query token in q / out
+  int32_t* row_ctx;        // [rows] number of KV tokens the row attends to (p+1)
+  int32_t* row_item0;      // [rows] first item of the row
+  int32_t* row_nparts;     // [rows]
+  int32_t* item_row;       // [items]
+  int32_t* item_part;      // [items]
+  int32_t* tile_seq;       // [tiles]
+  int32_t* tile_q0;        // [tiles] first new-token index j of the tile
+  float*   part_acc;       // [items][Hq][D]  unnormalised partial outputs
+  float*   part_ml;        // [items][Hq][2]  running max (log2 domain) and sum
+};
+
+struct AttnArgs {
+  const uint16_t* q;
+  void* out;
+  const uint16_t* k_pool;      // layer base already applied
+  const uint16_t* v_pool;
+  const int32_t* block_tables;
+  const int32_t* q_offsets;
+  const int32_t* ctx_lens;
+  int32_t max_blocks;
+  int32_t num_seqs;
+  int32_t Hq, Hkv, D;
+  float scale_log2e;           // softmax_scale * log2(e): scores are kept in the log2 domain
+  int32_t out_bf16;
+};
+
+int launch_rows(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg,
+                const PlanCounts& n, hipStream_t stream);
+int launch_merge(const AttnArgs& a, const WorkLists& w, const PlanCounts& n, hipStream_t stream);
+int launch_prefill_tiles(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg,
+                         const PlanCounts& n, hipStream_t stream);
+
+}  // namespace dsv

@@ -1,0 +1,144 @@
+// kv_pack_chunks / kv_unpack_chunks: the local gather/scatter on either side of chunk-based
+// KV transfer (paper section 4.3).  Pure byte movement, HBM-bound: every payload byte is read
+// once and written once with 16-byte accesses, a wave covering 1 KiB of contiguous memory per
+// instruction on both sides.
+//
+// Work decomposition: one workgroup per (chunk, layer, K|V, tile of kTileTokens tokens).  A
+// token's row (all KV heads) is num_kv_heads*head_dim*2 bytes, contiguous in the chunk and in
+// the pool; consecutive tokens are contiguous in the chunk and, inside one block, in the pool.
+#include "dsv_common.h"
+
+namespace dsv {
+namespace {
+
+constexpr int kCopyThreads = 256;
+constexpr int kTileTokens = 16;
+constexpr int kUnroll = 4;
+
+struct CopyParams {
+  uint4* pool_k;                 // layer 0 bases
+  uint4* pool_v;
+  uint4* chunk_buf;
+  const int32_t* block_tables;
+  const dsv_chunk_desc* descs;
+  int64_t layer_stride_u;        // 16-byte units between layers
+  int32_t max_blocks;
+  int32_t num_layers;
+  int32_t tiles_per_chunk;       // ceil(max num_tokens / kTileTokens)
+  int32_t upr;                   // 16-byte units per token row
+  int32_t upr_shift;             // log2(upr) or -1
+};
+
+// PACK = true: pool -> chunk.  PACK = false: chunk -> pool.
+template <bool PACK>
+__global__ __launch_bounds__(kCopyThreads) void kv_copy_kernel(CopyParams p) {
+  // blockIdx.x = (chunk * 2L + plane) * tiles_per_chunk + tile, plane = layer*2 + (K=0|V=1)
+  const uint32_t planes = 2u * (uint32_t)p.num_layers;
+  const uint32_t tile = blockIdx.x % (uint32_t)p.tiles_per_chunk;
+  const uint32_t cp = blockIdx.x / (uint32_t)p.tiles_per_chunk;
+  const uint32_t plane = cp % planes;
+  const uint32_t c = cp / planes;
+
+  const dsv_chunk_desc d = p.descs[c];
+  const int tok0 = (int)tile * kTileTokens;
+  if (tok0 >= d.num_tokens) return;
+  const int ntok = min(kTileTokens, d.num_tokens - tok0);
+
+  uint4* pool = ((plane & 1u) ? p.pool_v : p.pool_k) + (int64_t)(plane >> 1) * p.layer_stride_u;
+  uint4* chunk = p.chunk_buf + (d.chunk_offset >> 3) +
+                 ((int64_t)plane * d.num_tokens + tok0) * p.upr;
+  const int32_t* table = p.block_tables + (int64_t)d.seq * p.max_blocks;
+
+  const int total = ntok * p.upr;                       // 16-byte units in this tile
+  for (int u0 = threadIdx.x; u0 < total; u0 += kCopyThreads * kUnroll) {
+    uint4 v[kUnroll];
+    int64_t pool_u[kUnroll];
+    int idx[kUnroll];
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k) {
+      const int u = u0 + k * kCopyThreads;
+      idx[k] = u;
+      if (u < total) {
+        const int row = p.upr_shift >= 0 ? (u >> p.upr_shift) : (u / p.upr);
+        const int col = u - row * p.upr;
+        const int t = d.token_begin + tok0 + row;
+        const int64_t blk = table[t >> 4];
+        pool_u[k] = (blk * kBlockSize + (t & 15)) * (int64_t)p.upr + col;
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k)
+      if (idx[k] < total) v[k] = PACK ? pool[pool_u[k]] : chunk[idx[k]];
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k)
+      if (idx[k] < total) {
+        if (PACK) chunk[idx[k]] = v[k];
+        else      pool[pool_u[k]] = v[k];
+      }
+  }
+}
+
+int run_copy(bool pack, const dsv_kv_pool* pool, const int32_t* block_tables, int32_t max_blocks,
+             const dsv_chunk_desc* descs, const dsv_chunk_desc* descs_host, int32_t num_chunks,
+             void* chunk_buf, void* hip_stream) {
+  int rc = check_pool(pool);
+  if (rc) return rc;
+  if (num_chunks < 0 || max_blocks < 1) return DSV_E_INVALID;
+  if (num_chunks == 0) return DSV_OK;
+  if (!block_tables || !descs || !descs_host || !chunk_buf) return DSV_E_INVALID;
+  if ((reinterpret_cast<uintptr_t>(chunk_buf) & 15) || (reinterpret_cast<uintptr_t>(pool->k_base) & 15) ||
+      (reinterpret_cast<uintptr_t>(pool->v_base) & 15))
+    return DSV_E_INVALID;
+  const int64_t row_elems = (int64_t)pool->num_kv_heads * pool->head_dim;   // multiple of 64
+  if (pool->num_layers > 1 && (pool->layer_stride % 8)) return DSV_E_INVALID;
+  if (pool->num_layers > 1 &&
+      pool->layer_stride < (int64_t)pool->num_blocks * kBlockSize * row_elems)
+    return DSV_E_INVALID;
+  int max_tokens = 0;
+  for (int c = 0; c < num_chunks; ++c) {
+    const dsv_chunk_desc& d = descs_host[c];
+    if (d.seq < 0 || d.token_begin < 0 || d.num_tokens < 1 || d.reserved != 0) return DSV_E_INVALID;
+    if (d.chunk_offset < 0 || (d.chunk_offset % 8)) return DSV_E_INVALID;
+    if (ceil_div((int64_t)d.token_begin + d.num_tokens, kBlockSize) > max_blocks) return DSV_E_INVALID;
+    if (d.num_tokens > max_tokens) max_tokens = d.num_tokens;
+  }
+  CopyParams p;
+  p.pool_k = static_cast<uint4*>(pool->k_base);
+  p.pool_v = static_cast<uint4*>(pool->v_base);
+  p.chunk_buf = static_cast<uint4*>(chunk_buf);
+  p.block_tables = block_tables;
+  p.descs = descs;
+  p.layer_stride_u = pool->num_layers > 1 ? pool->layer_stride / 8 : 0;
+  p.max_blocks = max_blocks;
+  p.num_layers = pool->num_layers;
+  p.tiles_per_chunk = ceil_div(max_tokens, kTileTokens);
+  p.upr = (int32_t)(row_elems / 8);
+  p.upr_shift = (p.upr & (p.upr - 1)) == 0 ? __builtin_ctz((unsigned)p.upr) : -1;
+  const int64_t grid = (int64_t)num_chunks * 2 * pool->num_layers * p.tiles_per_chunk;
+  if (grid > 0x7fffffffLL) return DSV_E_UNSUPPORTED;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (pack)
+    hipLaunchKernelGGL(kv_copy_kernel<true>, dim3((unsigned)grid), dim3(kCopyThreads), 0, stream, p);
+  else
+    hipLaunchKernelGGL(kv_copy_kernel<false>, dim3((unsigned)grid), dim3(kCopyThreads), 0, stream, p);
+  return launch_status();
+}
+
+}  // namespace
+}  // namespace dsv
+
+extern "C" int kv_pack_chunks(const dsv_kv_pool* src, const int32_t* block_tables,
+                              int32_t max_blocks_per_seq, const dsv_chunk_desc* descs,
+                              const dsv_chunk_desc* descs_host, int32_t num_chunks,
+                              void* chunk_buf, void* hip_stream) {
+  return dsv::run_copy(true, src, block_tables, max_blocks_per_seq, descs, descs_host, num_chunks,
+                       chunk_buf, hip_stream);
+}
+
+extern "C" int kv_unpack_chunks(const void* chunk_buf, const dsv_chunk_desc* descs,
+                                const dsv_chunk_desc* descs_host, int32_t num_chunks,
+                                const dsv_kv_pool* dst, const int32_t* dst_block_tables,
+                                int32_t max_blocks_per_seq, void* hip_stream) {
+  return dsv::run_copy(false, dst, dst_block_tables, max_blocks_per_seq, descs, descs_host,
+                       num_chunks, const_cast<void*>(chunk_buf), hip_stream);
+}

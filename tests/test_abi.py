@@ -1,0 +1,82 @@
+"""CPU-only checks of the boundary: the C-ABI library loads, exports every symbol the header
+declares, and its host-side validation returns the documented codes without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2504_09285_amd as dsv
+from paper_2504_09285_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "dsv_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return re.findall(r"^\s*(?:size_t|int|const char\*)\s+(\w+)\s*\(", text, flags=re.M)
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(dsv.library_path()):
+        from paper_2504_09285_amd import build
+        build.build()
+    return dsv.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_struct_layouts_match_header():
+    assert C.sizeof(binding._Pool) == 48
+    assert binding.CHUNK_DTYPE.itemsize == 24
+    assert binding.CHUNK_DTYPE.fields["chunk_offset"][1] == 16
+
+
+def test_build_info(lib):
+    assert "gfx950" in dsv.build_info()
+
+
+def test_workspace_bytes_rejects_invalid_batches(lib):
+    f = dsv.attn_mixed_batch_workspace_bytes
+    assert f([0, 1, 3], [10, 20], 32, 8, 128) > 0
+    assert f([0, 1, 3], [10, 1], 32, 8, 128) == 0         # ctx < q_len
+    assert f([0, 1, 1], [10, 20], 32, 8, 128) == 0        # empty segment
+    assert f([0, 1, 3], [10, 20], 32, 5, 128) == 0        # Hq % Hkv
+    assert f([0, 1, 3], [10, 20], 32, 8, 96) == 0         # head_dim
+    assert f([1, 2, 3], [10, 20], 32, 8, 128) == 0        # offsets must start at 0
+
+
+def test_workspace_grows_with_split_work(lib):
+    f = dsv.attn_mixed_batch_workspace_bytes
+    small = f([0, 1], [100], 32, 8, 128)
+    big = f([0, 1], [100000], 32, 8, 128)
+    assert big > small > 0
+
+
+def test_null_and_unsupported_arguments_return_codes_without_gpu(lib):
+    pool = binding._Pool(0, 0, 0, 1, 4, 16, 8, 128)
+    qo = np.array([0, 1], np.int32)
+    cl = np.array([5], np.int32)
+    p = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+    rc = lib.attn_mixed_batch(None, None, C.byref(pool), 0, None, 1, None, None, p(qo), p(cl), 1, 32,
+                              0.1, 0, None, 0, None)
+    assert rc == -1                                        # null pool bases
+    pool = binding._Pool(4096, 4096, 0, 1, 4, 32, 8, 128)
+    rc = lib.attn_mixed_batch(None, None, C.byref(pool), 0, None, 1, None, None, p(qo), p(cl), 1, 32,
+                              0.1, 0, None, 0, None)
+    assert rc == -2                                        # block_size != 16
+    pool = binding._Pool(4096, 4096, 0, 1, 4, 16, 8, 80)
+    assert lib.kv_pack_chunks(C.byref(pool), None, 1, None, None, 1, None, None) == -2
+    pool = binding._Pool(4096, 4096, 0, 1, 4, 16, 8, 128)
+    assert lib.kv_pack_chunks(C.byref(pool), None, 1, None, None, 1, None, None) == -1
+    assert lib.kv_pack_chunks(C.byref(pool), None, 1, None, None, 0, None, None) == 0     # no-op
+    assert lib.attn_mixed_batch(None, None, C.byref(pool), 0, None, 1, None, None, None, None, 0, 32,
+                                0.1, 0, None, 0, None) == 0                               # no-op

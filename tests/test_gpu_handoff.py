@@ -1,0 +1,86 @@
+"""GPU parity of kv_pack_chunks / kv_unpack_chunks against the CPU oracle: bit-exact, through
+the C ABI, on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import gen
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_handoff(h):
+    buf = np.full(max(h.chunk_elems, 8), np.uint16(-21555 & 0xFFFF), np.uint16)
+    oracle.kv_pack_chunks(h.src_k, h.src_v, h.src_tables, h.chunks, buf)
+    dk, dv = h.dst_k.copy(), h.dst_v.copy()
+    oracle.kv_unpack_chunks(buf, h.chunks, dk, dv, h.dst_tables)
+    return buf, dk, dv
+
+
+def check(h):
+    import torch
+    from gpu_harness import DeviceHandoff, host_u16
+    d = DeviceHandoff(h)
+    d.pack()
+    d.unpack()
+    torch.cuda.synchronize()
+    buf, dk, dv = oracle_handoff(h)
+    np.testing.assert_array_equal(host_u16(d.chunk_buf), buf)
+    np.testing.assert_array_equal(host_u16(d.dst.k), dk)
+    np.testing.assert_array_equal(host_u16(d.dst.v), dv)
+    np.testing.assert_array_equal(host_u16(d.src.k), h.src_k)      # source untouched
+
+
+def test_config1_handoff():
+    _, h = gen.config1()
+    check(h)
+
+
+@pytest.mark.parametrize("L,Hkv,D,toks,ranges,chunk", [
+    (3, 2, 64, (50, 17, 96), ((0, 3, 47), (1, 0, 17), (2, 16, 96)), 20),     # unaligned, short last chunks
+    (2, 8, 128, (300, 1, 33), ((0, 0, 300), (1, 0, 1), (2, 5, 33)), 64),     # several tiles, 1-token chunk
+    (1, 3, 128, (70,), ((0, 1, 70),), 7),                                    # row size not a power of two
+    (4, 8, 128, (1024, 777), ((0, 0, 1024), (1, 13, 777)), 256),             # full-size rows, 256-token chunks
+])
+def test_handoff_shapes(L, Hkv, D, toks, ranges, chunk):
+    check(gen.make_handoff("t", 41, L, Hkv, D, list(toks), list(ranges), chunk))
+
+
+def test_config5_handoff_shrunk():
+    check(gen.config5_handoff(shrink=16, layers=4))
+
+
+def test_chunk_order_and_subsets_do_not_matter():
+    """Chunks are independent units (section 4.3): packing/unpacking them in two calls, in reverse
+    order, gives the same destination image."""
+    import torch
+    import paper_2504_09285_amd as dsv
+    from gpu_harness import DeviceHandoff, host_u16
+    h = gen.make_handoff("t", 43, 2, 8, 128, [200, 90], [(0, 0, 200), (1, 10, 90)], 48)
+    d = DeviceHandoff(h)
+    rev = h.chunks[::-1].copy()
+    for part in (rev[: len(rev) // 2], rev[len(rev) // 2:]):
+        descs = dsv.ChunkDescs(part)
+        dsv.kv_pack_chunks(d.src, d.src_tables, descs, d.chunk_buf)
+        dsv.kv_unpack_chunks(d.chunk_buf, descs, d.dst, d.dst_tables)
+    torch.cuda.synchronize()
+    _, dk, dv = oracle_handoff(h)
+    np.testing.assert_array_equal(host_u16(d.dst.k), dk)
+    np.testing.assert_array_equal(host_u16(d.dst.v), dv)
+
+
+def test_empty_and_invalid():
+    import paper_2504_09285_amd as dsv
+    from gpu_harness import DeviceHandoff
+    h = gen.make_handoff("t", 44, 1, 2, 64, [40], [(0, 0, 40)], 16)
+    d = DeviceHandoff(h)
+    dsv.kv_pack_chunks(d.src, d.src_tables, dsv.ChunkDescs(np.zeros((0, 4))), d.chunk_buf)   # no-op
+    bad = h.chunks.copy()
+    bad[0, 1] = 16 * h.src_tables.shape[1]
+    with pytest.raises(dsv.DsvError) as e:
+        dsv.kv_pack_chunks(d.src, d.src_tables, dsv.ChunkDescs(bad), d.chunk_buf)
+    assert e.value.code == -1
+    bad = h.chunks.copy()
+    bad[0, 3] = 4                      # misaligned chunk offset
+    with pytest.raises(dsv.DsvError):
+        dsv.kv_pack_chunks(d.src, d.src_tables, dsv.ChunkDescs(bad), d.chunk_buf)
