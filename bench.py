@@ -1,0 +1,302 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5] [--no-extras]
+                    [--no-cpu-baseline]
+
+A step is one attn_mixed_batch call (plan + attention kernels + merge) over one seeded synthetic
+batch that is already resident in HBM.  The headline workload is the decode-heavy batch
+(256 decodes, 32/8 heads, D=128, lognormal contexts); `value` is query tokens per second.  The
+same JSON line carries the roofline of the dominant kernel (HIP events recorded around that
+kernel on its own stream) and the fp64 CPU oracle timed on this machine's host cores.  Short extra
+measurements of the other workloads (prefill-heavy, micro-request, hand-off copy) are attached
+under "extras".
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "mixed-batch attention tokens/s; decode HBM GB/s & prefill MFMA util vs peak"
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+# ---------------------------------------------------------------------------- HIP events
+class HipEvents:
+    """hipEvent_t pairs created straight on the HIP runtime (the library records them itself)."""
+
+    def __init__(self):
+        self.hip = None
+        for line in open("/proc/self/maps"):
+            if "libamdhip64" in line:
+                self.hip = C.CDLL(line.split()[-1])
+                break
+        if self.hip is None:
+            self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+
+    def create(self):
+        ev = C.c_void_p()
+        rc = self.hip.hipEventCreate(C.byref(ev))
+        assert rc == 0 and ev.value
+        return ev.value
+
+    def record(self, ev, stream_ptr):
+        assert self.hip.hipEventRecord(ev, stream_ptr) == 0
+
+    def elapsed_ms(self, a, b) -> float:
+        ms = C.c_float()
+        rc = self.hip.hipEventElapsedTime(C.byref(ms), a, b)
+        if rc != 0:
+            self.hip.hipGetLastError()        # events never recorded: clear the sticky error
+            raise AssertionError("hipEventElapsedTime rc=%d" % rc)
+        return float(ms.value)
+
+    def destroy(self, ev):
+        self.hip.hipEventDestroy(ev)
+
+
+# ---------------------------------------------------------------------------- algorithmic work
+def decode_bytes(b, out_elem_bytes: int) -> int:
+    """KV bytes of the decode rows (ctx tokens, not padded blocks) + Q + O + block-table entries."""
+    dec = b.q_lens == 1
+    ctx = b.ctx_lens[dec].astype(np.int64)
+    kv = int(ctx.sum()) * 2 * b.Hkv * b.D * 2
+    nq = int(dec.sum())
+    return kv + nq * b.Hq * b.D * (2 + out_elem_bytes) + 4 * int(((ctx + 15) // 16).sum())
+
+
+def prefill_flops(b) -> int:
+    """4*D*Hq per causal (q,k) pair of the prefill spans; masked halves and padding not counted."""
+    pre = b.q_lens > 1
+    ql = b.q_lens[pre].astype(np.int64)
+    prefix = b.ctx_lens[pre].astype(np.int64) - ql
+    pairs = int((ql * prefix + ql * (ql + 1) // 2).sum())
+    return 4 * b.D * b.Hq * pairs
+
+
+# ---------------------------------------------------------------------------- device side
+def upload(b):
+    import torch
+    import paper_2504_09285_amd as dsv
+
+    def dev_bf16(u16):
+        return torch.from_numpy(np.ascontiguousarray(u16).view(np.int16)).cuda().view(torch.bfloat16)
+
+    d = argparse.Namespace()
+    d.b = b
+    d.q = dev_bf16(b.q)
+    d.pool = dsv.KVPool(dev_bf16(b.k_pool[None]), dev_bf16(b.v_pool[None]))
+    d.block_tables = torch.from_numpy(b.block_tables).cuda()
+    d.q_offsets = torch.from_numpy(b.q_offsets).cuda()
+    d.ctx_lens = torch.from_numpy(b.ctx_lens).cuda()
+    nbytes = dsv.attn_mixed_batch_workspace_bytes(b.q_offsets, b.ctx_lens, b.Hq, b.Hkv, b.D)
+    d.workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    d.out = torch.empty(d.q.shape, dtype=torch.bfloat16, device="cuda")
+    return d
+
+
+def attn_step(d):
+    import paper_2504_09285_amd as dsv
+    b = d.b
+    dsv.attn_mixed_batch(d.q, d.out, d.pool, 0, d.block_tables, d.q_offsets, d.ctx_lens,
+                         b.q_offsets, b.ctx_lens, b.Hq, b.scale, d.workspace)
+
+
+def time_attention(d, steps, warmup, kernel_ids, hev):
+    """Wall time of `steps` calls between device synchronisations, plus per-kernel event times."""
+    import torch
+    import paper_2504_09285_amd as dsv
+    for _ in range(warmup):
+        attn_step(d)
+    torch.cuda.synchronize()
+    evs = {k: [(hev.create(), hev.create()) for _ in range(steps)] for k in kernel_ids}
+    t0 = time.perf_counter()
+    for s in range(steps):
+        for k in kernel_ids:
+            dsv.dsv_profile_events(k, *evs[k][s])
+        attn_step(d)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for k in kernel_ids:
+        dsv.dsv_profile_events(k, None, None)
+    per_kernel = {}
+    for k in kernel_ids:
+        try:
+            ms = [hev.elapsed_ms(a, b) for a, b in evs[k]]
+            per_kernel[k] = float(np.mean(ms))
+        except AssertionError:
+            per_kernel[k] = None          # kernel not launched for this batch
+        for a, b in evs[k]:
+            hev.destroy(a)
+            hev.destroy(b)
+    return (t1 - t0) / steps, per_kernel
+
+
+def bench_attention(b, steps, warmup, hev):
+    import paper_2504_09285_amd as dsv
+    d = upload(b)
+    sec, per_kernel = time_attention(d, steps, warmup,
+                                     [dsv.KERNEL_ROWS, dsv.KERNEL_TILES, dsv.KERNEL_MERGE, dsv.KERNEL_PLAN], hev)
+    res = {"workload": b.name, "ms_per_step": sec * 1e3, "tokens_per_s": b.total_q / sec,
+           "total_q": b.total_q, "num_seqs": b.num_seqs}
+    rows_ms, tiles_ms = per_kernel[dsv.KERNEL_ROWS], per_kernel[dsv.KERNEL_TILES]
+    res["kernel_ms"] = {"rows": rows_ms, "tiles": tiles_ms, "merge": per_kernel[dsv.KERNEL_MERGE],
+                        "plan": per_kernel[dsv.KERNEL_PLAN]}
+    nbytes = decode_bytes(b, 2)
+    flops = prefill_flops(b)
+    if rows_ms and nbytes:
+        gbs = nbytes / (rows_ms * 1e-3) / 1e9
+        res["decode"] = {"algorithmic_bytes": nbytes, "GB/s": gbs, "frac_hbm_peak": gbs / HBM_PEAK_GBS}
+    if tiles_ms and flops:
+        tf = flops / (tiles_ms * 1e-3) / 1e12
+        res["prefill"] = {"algorithmic_flops": flops, "TFLOP/s": tf, "frac_mfma_peak": tf / MFMA_BF16_PEAK_TFLOPS}
+    return res, d
+
+
+def bench_handoff(h, steps, warmup, hev):
+    import torch
+    import paper_2504_09285_amd as dsv
+
+    def dev_bf16(u16):
+        return torch.from_numpy(np.ascontiguousarray(u16).view(np.int16)).cuda().view(torch.bfloat16)
+
+    src = dsv.KVPool(dev_bf16(h.src_k), dev_bf16(h.src_v))
+    dst = dsv.KVPool(dev_bf16(h.dst_k), dev_bf16(h.dst_v))
+    st, dt = torch.from_numpy(h.src_tables).cuda(), torch.from_numpy(h.dst_tables).cuda()
+    descs = dsv.ChunkDescs(h.chunks)
+    buf = torch.empty(h.chunk_elems, dtype=torch.bfloat16, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream or None
+    out = {}
+    for name, fn in (("pack", lambda: dsv.kv_pack_chunks(src, st, descs, buf)),
+                     ("unpack", lambda: dsv.kv_unpack_chunks(buf, descs, dst, dt))):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        evs = [(hev.create(), hev.create()) for _ in range(steps)]
+        for a, b in evs:
+            hev.record(a, stream)
+            fn()
+            hev.record(b, stream)
+        torch.cuda.synchronize()
+        ms = float(np.mean([hev.elapsed_ms(a, b) for a, b in evs]))
+        gbs = 2 * h.payload_bytes / (ms * 1e-3) / 1e9
+        out[name] = {"ms": ms, "GB/s": gbs, "frac_hbm_peak": gbs / HBM_PEAK_GBS}
+    out["payload_bytes"] = h.payload_bytes
+    out["workload"] = h.name
+    return out
+
+
+# ---------------------------------------------------------------------------- CPU baseline
+def cpu_baseline(b, max_seconds=30.0):
+    """The fp64 oracle as it stands, on this machine's host cores, on a bounded sample of the batch:
+    whole sequences are added until about max_seconds of work has been done."""
+    import oracle
+    oracle.build()
+    n = b.num_seqs
+    order = np.arange(n)
+    done_tokens, elapsed, used = 0, 0.0, 0
+    step = max(1, n // 8)
+    while used < n and elapsed < max_seconds / 2:
+        idx = order[used:used + step]
+        qo = np.zeros(len(idx) + 1, np.int32)
+        np.cumsum(b.q_lens[idx], out=qo[1:])
+        q = np.concatenate([b.q[b.q_offsets[i]:b.q_offsets[i + 1]] for i in idx])
+        t0 = time.perf_counter()
+        oracle.attn_mixed_batch(q, b.k_pool, b.v_pool, b.block_tables[idx], qo, b.ctx_lens[idx], b.scale)
+        elapsed += time.perf_counter() - t0
+        done_tokens += int(qo[-1])
+        used += len(idx)
+    return {"value": done_tokens / elapsed, "unit": "tokens/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": elapsed,
+            "sample": "first %d of %d sequences of %s (%d query tokens), all heads" % (used, n, b.name, done_tokens)}
+
+
+# ---------------------------------------------------------------------------- main
+def make_workload(name, threads):
+    from workloads import gen
+    if name == "c2":
+        return gen.config2(threads=threads)
+    if name == "c3":
+        return gen.config3(threads=threads)
+    if name == "c4":
+        return gen.config4(threads=threads)[0]
+    if name == "c5":
+        return gen.config5_attention(threads=threads)
+    raise SystemExit("unknown workload " + name)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+                         "use --gpus 1")
+    import torch
+    import paper_2504_09285_amd as dsv
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    dsv.load_library()
+    threads = min(16, os.cpu_count() or 8)
+    hev = HipEvents()
+
+    b = make_workload(args.workload, threads)
+    res, d = bench_attention(b, args.steps, args.warmup, hev)
+    line = {
+        "metric": METRIC, "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": b.name, "num_seqs": b.num_seqs, "total_q": b.total_q,
+                   "q_heads": b.Hq, "kv_heads": b.Hkv, "head_dim": b.D, "block_size": 16,
+                   "kv_tokens": int(b.ctx_lens.sum()), "out_dtype": "bf16"},
+        "kernel_ms": res["kernel_ms"],
+    }
+    if "prefill" in res and (args.workload == "c3"):
+        p = res["prefill"]
+        line["roofline"] = {"bound": "mfma", "achieved": p["TFLOP/s"], "peak": MFMA_BF16_PEAK_TFLOPS,
+                            "unit": "TFLOP/s", "frac": p["frac_mfma_peak"], "traffic": None,
+                            "kernel": "prefill_tiles_kernel"}
+    elif "decode" in res:
+        p = res["decode"]
+        line["roofline"] = {"bound": "hbm", "achieved": p["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": p["frac_hbm_peak"], "traffic": None, "kernel": "rows_kernel",
+                            "algorithmic_bytes": p["algorithmic_bytes"]}
+    if "prefill" in res:
+        line["prefill"] = res["prefill"]
+    if "decode" in res:
+        line["decode"] = res["decode"]
+
+    if not args.no_extras:
+        from workloads import gen
+        extras = {}
+        h = gen.config5_handoff(layers=4, threads=threads)     # 8 x 8192 tokens, 256-token chunks, 4 of 32 layers
+        extras["handoff_c5_4layers"] = bench_handoff(h, 10, 2, hev)
+        del h
+        line["extras"] = extras
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(b)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -11,8 +11,9 @@
  *     memory and keeps no pointer after the call returns.
  *   - All GPU work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the
  *     default stream).  Calls never synchronise.  Host arrays are consumed before return.
- *   - Return value: DSV_OK (0) or a negative DSV_E_* code.  When a negative code is
- *     returned nothing has been enqueued.
+ *   - Return value: DSV_OK (0) or a negative DSV_E_* code.  Arguments are checked before any
+ *     GPU work: with DSV_E_INVALID, DSV_E_UNSUPPORTED or DSV_E_WORKSPACE nothing has been
+ *     enqueued.  DSV_E_LAUNCH means HIP refused a launch part-way; outputs are then undefined.
  *   - bf16 = upper 16 bits of IEEE-754 binary32, stored as uint16.
  *   - Block-table entries are trusted (not range-checked against num_blocks).
  */
@@ -133,6 +134,19 @@ int kv_unpack_chunks(const void* chunk_buf, const dsv_chunk_desc* descs,
                      const dsv_chunk_desc* descs_host, int32_t num_chunks,
                      const dsv_kv_pool* dst, const int32_t* dst_block_tables,
                      int32_t max_blocks_per_seq, void* hip_stream);
+
+/*
+ * Profiling aid for benchmarks (not needed for correct use).  Until cleared with NULLs, every
+ * later attn_mixed_batch call made by the calling host thread records `start_event` on its
+ * stream immediately before, and `stop_event` immediately after, the launch of the named
+ * kernel (both hipEvent_t, created by the caller with timing enabled).  If that kernel is not
+ * launched for a batch the events are not recorded.  Returns DSV_E_INVALID for an unknown id.
+ */
+#define DSV_KERNEL_PLAN   0   /* work-list construction                                   */
+#define DSV_KERNEL_ROWS   1   /* single-token attention split along the context (decodes) */
+#define DSV_KERNEL_TILES  2   /* MFMA attention of long prefill spans                     */
+#define DSV_KERNEL_MERGE  3   /* combination of context partitions                        */
+int dsv_profile_events(int32_t kernel_id, void* start_event, void* stop_event);
 
 /* Library build identification: a static string, e.g. "dsv_attn gfx950 <date>". */
 const char* dsv_build_info(void);

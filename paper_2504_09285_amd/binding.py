@@ -36,7 +36,8 @@ CHUNK_DTYPE = np.dtype([("seq", "<i4"), ("token_begin", "<i4"), ("num_tokens", "
 assert CHUNK_DTYPE.itemsize == 24
 
 EXPORTS = ("attn_mixed_batch_workspace_bytes", "attn_mixed_batch", "kv_pack_chunks",
-           "kv_unpack_chunks", "dsv_build_info")
+           "kv_unpack_chunks", "dsv_profile_events", "dsv_build_info")
+KERNEL_PLAN, KERNEL_ROWS, KERNEL_TILES, KERNEL_MERGE = 0, 1, 2, 3
 
 
 def library_path() -> str:
@@ -63,6 +64,8 @@ def load_library():
     lib.kv_pack_chunks.argtypes = [C.POINTER(_Pool), vp, C.c_int32, vp, vp, C.c_int32, vp, vp]
     lib.kv_unpack_chunks.restype = C.c_int
     lib.kv_unpack_chunks.argtypes = [vp, vp, vp, C.c_int32, C.POINTER(_Pool), vp, C.c_int32, vp]
+    lib.dsv_profile_events.restype = C.c_int
+    lib.dsv_profile_events.argtypes = [C.c_int32, vp, vp]
     lib.dsv_build_info.restype = C.c_char_p
     lib.dsv_build_info.argtypes = []
     _lib = lib
@@ -71,6 +74,13 @@ def load_library():
 
 def build_info() -> str:
     return load_library().dsv_build_info().decode()
+
+
+def dsv_profile_events(kernel_id: int, start_event: Optional[int], stop_event: Optional[int]) -> None:
+    """See ``dsv_profile_events`` in include/dsv_attn.h; events are raw hipEvent_t handles."""
+    rc = load_library().dsv_profile_events(int(kernel_id), start_event, stop_event)
+    if rc:
+        raise DsvError("dsv_profile_events", rc)
 
 
 def _host_i32(a) -> np.ndarray:

@@ -16,6 +16,20 @@ namespace {
 
 constexpr int kPlanThreads = 1024;
 
+// Benchmark hook: event pairs recorded around individual kernels (see dsv_profile_events).
+thread_local hipEvent_t g_events[4][2] = {};
+
+struct EventScope {
+  hipEvent_t stop;
+  hipStream_t stream;
+  EventScope(int id, hipStream_t s) : stop(g_events[id][1]), stream(s) {
+    if (g_events[id][0]) (void)hipEventRecord(g_events[id][0], s);
+  }
+  ~EventScope() {
+    if (stop) (void)hipEventRecord(stop, stream);
+  }
+};
+
 int env_int(const char* name, int fallback) {
   const char* s = getenv(name);
   if (!s || !*s) return fallback;
@@ -300,12 +314,31 @@ extern "C" int attn_mixed_batch(const void* q, void* out, const dsv_kv_pool* poo
   a.out_bf16 = out_dtype == DSV_OUT_BF16;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, q_offsets, ctx_lens,
-                     num_seqs, cfg, w);
-  if ((rc = launch_status())) return rc;
-  if (n.tiles && (rc = launch_prefill_tiles(a, w, cfg, n, stream))) return rc;
-  if (n.items && (rc = launch_rows(a, w, cfg, n, stream))) return rc;
-  if ((rc = launch_merge(a, w, n, stream))) return rc;
+  {
+    EventScope ev(DSV_KERNEL_PLAN, stream);
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, q_offsets, ctx_lens,
+                       num_seqs, cfg, w);
+    if ((rc = launch_status())) return rc;
+  }
+  if (n.tiles) {
+    EventScope ev(DSV_KERNEL_TILES, stream);
+    if ((rc = launch_prefill_tiles(a, w, cfg, n, stream))) return rc;
+  }
+  if (n.items) {
+    EventScope ev(DSV_KERNEL_ROWS, stream);
+    if ((rc = launch_rows(a, w, cfg, n, stream))) return rc;
+  }
+  if (n.split_items) {
+    EventScope ev(DSV_KERNEL_MERGE, stream);
+    if ((rc = launch_merge(a, w, n, stream))) return rc;
+  }
+  return DSV_OK;
+}
+
+extern "C" int dsv_profile_events(int32_t kernel_id, void* start_event, void* stop_event) {
+  if (kernel_id < 0 || kernel_id > 3) return DSV_E_INVALID;
+  g_events[kernel_id][0] = static_cast<hipEvent_t>(start_event);
+  g_events[kernel_id][1] = static_cast<hipEvent_t>(stop_event);
   return DSV_OK;
 }
 
