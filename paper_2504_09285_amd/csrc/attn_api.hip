@@ -60,7 +60,7 @@ int validate_batch(int32_t S, const int32_t* qo, const int32_t* cl, int32_t max_
 
 PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl) {
   PlanConfig c;
-  c.mfma_min_qlen = env_int("DSV_MFMA_MIN_QLEN", 1 << 30);
+  c.mfma_min_qlen = env_int("DSV_MFMA_MIN_QLEN", 16);
   c.tile_tokens = 32;
   // Partition size: enough (row, partition) items to fill 256 CUs several times over, but not so
   // small that the partial results written per partition matter next to the KV bytes read.

@@ -265,10 +265,4 @@ int launch_rows(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, co
   return DSV_E_UNSUPPORTED;
 }
 
-// Placeholder until the MFMA prefill kernel lands: long spans are refused, never mis-computed.
-int launch_prefill_tiles(const AttnArgs&, const WorkLists&, const PlanConfig&, const PlanCounts&,
-                         hipStream_t) {
-  return DSV_E_UNSUPPORTED;
-}
-
 }  // namespace dsv

@@ -146,3 +146,133 @@ def test_invalid_arguments_are_refused():
         with pytest.raises(dsv.DsvError) as e:
             call(**kw)
         assert e.value.code == code
+
+
+# ------------------------------------------------------------------ long prefill spans (MFMA path)
+@pytest.mark.parametrize("Hq,Hkv,D", [(32, 8, 128), (4, 1, 64), (8, 8, 128), (64, 8, 128), (6, 2, 128),
+                                      (16, 1, 64), (2, 1, 128)])
+def test_prefill_ragged_spans(Hq, Hkv, D):
+    """Span lengths around the 32-token query tile and the 64-token KV tile, on prefixes that are
+    empty, sub-block, block-aligned and unaligned; decodes interleaved."""
+    segs = [(16, 16), (17, 18), (31, 46), (32, 32), (33, 49), (1, 77), (63, 113), (64, 264),
+            (65, 65), (100, 103), (1, 300), (47, 1047), (129, 192)]
+    b = gen.make_batch("pre_ragged", 61, Hq, Hkv, D, segs)
+    check(b)
+
+
+def test_split_at_token_boundaries_is_invariant_on_gpu():
+    """Section 3.1: a request cut at any token gives the same outputs as the unsplit request.
+    The two GPU results may differ by rounding (different tiling), each stays within tolerance."""
+    from gpu_harness import run_attention
+    L = 200
+    full = gen.make_batch("req", 62, 8, 2, 128, [(L, L)])
+    ref = oracle_out(full)
+    whole = run_attention(full)
+    assert np.abs(whole - ref).max() <= TOL
+    tbl = np.concatenate([full.block_tables, full.block_tables], axis=0)
+    for s in (1, 15, 16, 17, 63, 64, 100, 184, 199):
+        split = gen.AttnBatch("split", 8, 2, 128, full.scale, full.q, full.k_pool, full.v_pool, tbl,
+                              np.array([0, s, L], np.int32), np.array([s, L], np.int32))
+        got = run_attention(split)
+        assert np.abs(got - ref).max() <= TOL, s
+        assert np.abs(got - whole).max() <= 2e-2, s
+
+
+def test_prefill_poisoned_pool():
+    from gpu_harness import run_attention
+    segs = [(40, 40), (33, 70), (1, 90), (64, 129), (20, 21)]
+    b = gen.make_batch("pre_poison", 63, 16, 4, 128, segs, free_frac=0.5)
+    ref = run_attention(b)
+    owned = np.zeros(b.k_pool.shape[:2], bool)
+    for i in range(b.num_seqs):
+        t = np.arange(int(b.ctx_lens[i]))
+        owned[b.block_tables[i, t // 16], t % 16] = True
+    kp, vp = b.k_pool.copy(), b.v_pool.copy()
+    kp[~owned] = 0x7FC0
+    vp[~owned] = 0x7FC0
+    free_block = int(np.setdiff1d(np.arange(b.k_pool.shape[0]), b.block_tables.ravel())[0])
+    bt = b.block_tables.copy()
+    for i in range(b.num_seqs):
+        bt[i, (int(b.ctx_lens[i]) + 15) // 16:] = free_block
+    got = run_attention(b, k_pool=kp, v_pool=vp, block_tables=bt)
+    assert np.isfinite(got).all()
+    np.testing.assert_array_equal(got, ref)
+    assert np.abs(got - oracle_out(b)).max() <= TOL
+
+
+def test_prefill_constant_v():
+    from gpu_harness import run_attention
+    b = gen.make_batch("pre_cf", 64, 8, 2, 128, [(70, 150), (33, 33)])
+    one = gen.f32_to_bf16_bits(np.float32([1.0]))[0]
+    got = run_attention(b, v_pool=np.full_like(b.v_pool, one))
+    np.testing.assert_allclose(got, 1.0, rtol=0, atol=1e-2)
+
+
+def test_config3_prefill_heavy_shrunk():
+    check(gen.config3(shrink=8))
+
+
+def test_config3_prefill_heavy_full_sampled_rows():
+    """Full-size prefill-heavy batch in the configuration bench.py times; the oracle recomputes a
+    seeded sample of output rows (first/last rows of spans, tile edges, random rows, decodes)."""
+    from gpu_harness import run_attention
+    b = gen.config3()
+    assert b.total_q == 8208 and b.ctx_lens[:4].tolist() == [2048, 2560, 3072, 6144]
+    got = run_attention(b)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(3)
+    rows = []
+    for i in range(4):
+        for j in (0, 1, 31, 32, 33, 1023, 2047):
+            rows.append((i, j, int(rng.integers(b.Hq))))
+        for _ in range(24):
+            rows.append((i, int(rng.integers(2048)), int(rng.integers(b.Hq))))
+    for i in range(4, b.num_seqs):
+        rows.append((i, 0, int(rng.integers(b.Hq))))
+    ref = oracle.attn_rows(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens, b.scale, rows)
+    for r, (i, j, h) in enumerate(rows):
+        err = np.abs(got[b.q_offsets[i] + j, h] - ref[r]).max()
+        assert err <= TOL, (i, j, h, err)
+
+
+def _config4_inputs(shrink):
+    """Config 4 placement, CPU side: row 0 holds the prompt; row 1's tokens [k,L) are made equal to
+    row 0's; tokens [0,k) reach row 1 by pack/unpack (done by the caller, oracle or GPU)."""
+    b, sp = gen.config4(shrink=shrink)
+    t = np.arange(sp.k, sp.total)
+    for pool in (b.k_pool, b.v_pool):
+        pool[b.block_tables[1, t // 16], t % 16] = pool[b.block_tables[0, t // 16], t % 16]
+    return b, sp
+
+
+def test_config4_micro_request_shrunk():
+    """The split prompt's second span attends to a prefix that arrived through the GPU hand-off
+    (pack from row 0, unpack into row 1); result equals the oracle's unsplit 4096/shrink prefill."""
+    import torch
+    import paper_2504_09285_amd as dsv
+    from gpu_harness import DeviceBatch, host_u16
+    b, sp = _config4_inputs(8)
+    d = DeviceBatch(b)
+    descs = dsv.ChunkDescs(sp.chunks)
+    buf = torch.zeros(sp.chunk_elems, dtype=torch.bfloat16, device="cuda")
+    src_tbl = d.block_tables[0:1].contiguous()
+    dst_tbl = d.block_tables[1:2].contiguous()
+    dsv.kv_pack_chunks(d.pool, src_tbl, descs, buf)
+    dsv.kv_unpack_chunks(buf, descs, d.pool, dst_tbl)
+    got = d.run().cpu().numpy()
+    torch.cuda.synchronize()
+    # oracle side: same hand-off with the oracle's copy routines, then attention
+    kp, vp = b.k_pool.copy()[None], b.v_pool.copy()[None]
+    obuf = np.zeros(sp.chunk_elems, np.uint16)
+    oracle.kv_pack_chunks(kp, vp, b.block_tables[0:1], sp.chunks, obuf)
+    oracle.kv_unpack_chunks(obuf, sp.chunks, kp, vp, b.block_tables[1:2])
+    np.testing.assert_array_equal(host_u16(d.pool.k), kp)
+    np.testing.assert_array_equal(host_u16(d.pool.v), vp)
+    ref = oracle_out(b, k_pool=kp[0], v_pool=vp[0])
+    assert np.abs(got - ref).max() <= TOL
+    # the two spans together are the unsplit prompt
+    unsplit = gen.AttnBatch("unsplit", b.Hq, b.Hkv, b.D, b.scale, b.q[:sp.total], kp[0], vp[0],
+                            b.block_tables[0:1], np.array([0, sp.total], np.int32),
+                            np.array([sp.total], np.int32))
+    ref_unsplit = oracle_out(unsplit)
+    assert np.abs(got[:sp.total] - ref_unsplit).max() <= TOL
