@@ -100,6 +100,7 @@ size_t attn_mixed_batch_workspace_bytes(int32_t num_seqs, const int32_t* q_offse
  *                ceil(ctx_lens[i]/16) valid entries, the rest is never read
  *   q_offsets, ctx_lens            device, int32 [num_seqs+1] and [num_seqs]
  *   q_offsets_host, ctx_lens_host  host copies of the same (the batch was composed on the host)
+ *   softmax_scale  finite and >= 0 (1/sqrt(head_dim) in the usual case)
  *   workspace    device, 256-byte aligned, at least attn_mixed_batch_workspace_bytes(); may be
  *                reused once the stream has passed this call
  * Accumulation is fp32; probabilities entering the PV product of prefill spans are rounded to

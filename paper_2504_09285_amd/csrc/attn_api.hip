@@ -62,6 +62,11 @@ PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl) {
   PlanConfig c;
   c.mfma_min_qlen = env_int("DSV_MFMA_MIN_QLEN", 16);
   c.tile_tokens = 32;
+  c.row_waves = env_int("DSV_ROW_WAVES", 4);
+  c.row_nbuf = env_int("DSV_ROW_NBUF", 2);
+  if (c.row_waves != 1 && c.row_waves != 2 && c.row_waves != 8) c.row_waves = 4;
+  if (c.row_nbuf != 3 && c.row_nbuf != 4 && c.row_nbuf != 6 && c.row_nbuf != 8) c.row_nbuf = 2;
+  while (c.row_waves * c.row_nbuf > 16) c.row_waves >>= 1;      // ring must fit the 160 KB of LDS
   // Partition size: enough (row, partition) items to fill 256 CUs several times over, but not so
   // small that the partial results written per partition matter next to the KV bytes read.
   int64_t row_tokens = 0;
@@ -76,6 +81,7 @@ PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl) {
   if (part > 1024) part = 1024;
   const int forced = env_int("DSV_PART_TOKENS", 0);
   if (forced >= 16) part = forced / 16 * 16;
+  if (part > 1024) part = 1024;                 // the row kernel keeps one 64-entry table vector
   c.part_tokens = (int32_t)part;
   return c;
 }
@@ -113,15 +119,17 @@ size_t carve(const PlanCounts& n, int Hq, int D, char* base, WorkLists* w) {
   const size_t rows = (size_t)n.rows, items = (size_t)n.items, tiles = (size_t)n.tiles;
   char* p0 = take(rows * 4); char* p1 = take(rows * 4); char* p2 = take(rows * 4);
   char* p3 = take(rows * 4); char* p4 = take(rows * 4);
-  char* p5 = take(items * 4); char* p6 = take(items * 4);
+  char* p5 = take(items * 32);
   char* p7 = take(tiles * 4); char* p8 = take(tiles * 4);
+  char* pz = take(256);
   char* p9 = take(items * (size_t)Hq * D * 4);
   char* p10 = take(items * (size_t)Hq * 2 * 4);
   if (w) {
     w->row_seq = (int32_t*)p0; w->row_qtok = (int32_t*)p1; w->row_ctx = (int32_t*)p2;
     w->row_item0 = (int32_t*)p3; w->row_nparts = (int32_t*)p4;
-    w->item_row = (int32_t*)p5; w->item_part = (int32_t*)p6;
+    w->item_rec = (int4*)p5;
     w->tile_seq = (int32_t*)p7; w->tile_q0 = (int32_t*)p8;
+    w->zero_line = (uint32_t*)pz;
     w->part_acc = (float*)p9; w->part_ml = (float*)p10;
   }
   return off + 256;
@@ -148,8 +156,11 @@ __device__ int block_exclusive_scan(int v, int* smem, int* total) {
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __restrict__ q_offsets,
                                                             const int32_t* __restrict__ ctx_lens,
-                                                            int32_t S, PlanConfig c, WorkLists w) {
+                                                            const int32_t* __restrict__ block_tables,
+                                                            int32_t max_blocks, int32_t S, PlanConfig c,
+                                                            WorkLists w) {
   __shared__ int smem[kPlanThreads];
+  if (threadIdx.x < 64) w.zero_line[threadIdx.x] = 0u;
   int row_carry = 0, item_carry = 0, tile_carry = 0;
   for (int base = 0; base < S; base += kPlanThreads) {
     const int i = base + (int)threadIdx.x;
@@ -179,8 +190,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
       w.row_item0[r] = item0;
       w.row_nparts[r] = np;
       for (int p = 0; p < np; ++p) {
-        w.item_row[item0 + p] = r;
-        w.item_part[item0 + p] = p;
+        const int b0 = p * c.part_tokens / kBlockSize;
+        w.item_rec[2 * (item0 + p)] = make_int4(i, q0 + j, ctx_eff, p);
+        w.item_rec[2 * (item0 + p) + 1] = make_int4(np, block_tables[(int64_t)i * max_blocks + b0], r, 0);
       }
       item0 += np;
     }
@@ -279,7 +291,7 @@ extern "C" int attn_mixed_batch(const void* q, void* out, const dsv_kv_pool* poo
   if (layer < 0 || layer >= pool->num_layers || max_blocks_per_seq < 1) return DSV_E_INVALID;
   if (num_q_heads < 1 || num_q_heads % pool->num_kv_heads) return DSV_E_INVALID;
   if (out_dtype != DSV_OUT_F32 && out_dtype != DSV_OUT_BF16) return DSV_E_INVALID;
-  if (!(softmax_scale == softmax_scale) || isinf(softmax_scale)) return DSV_E_INVALID;
+  if (!(softmax_scale >= 0.0f) || isinf(softmax_scale)) return DSV_E_INVALID;
   if ((reinterpret_cast<uintptr_t>(q) & 15) || (reinterpret_cast<uintptr_t>(out) & 15) ||
       (reinterpret_cast<uintptr_t>(pool->k_base) & 15) || (reinterpret_cast<uintptr_t>(pool->v_base) & 15) ||
       (reinterpret_cast<uintptr_t>(workspace) & 255))
@@ -317,7 +329,7 @@ extern "C" int attn_mixed_batch(const void* q, void* out, const dsv_kv_pool* poo
   {
     EventScope ev(DSV_KERNEL_PLAN, stream);
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, q_offsets, ctx_lens,
-                       num_seqs, cfg, w);
+                       block_tables, max_blocks_per_seq, num_seqs, cfg, w);
     if ((rc = launch_status())) return rc;
   }
   if (n.tiles) {

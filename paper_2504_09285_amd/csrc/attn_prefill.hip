@@ -57,8 +57,13 @@ struct TileGeom {
   static constexpr int LDS_BYTES = 2 * kTileKV * (KSTR + VSTR) * 2;
 };
 
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+
+// Two fp32 -> packed bf16, round to nearest even (the hardware conversion of gfx950).
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  return (uint32_t)f32_to_bf16_rne(lo) | ((uint32_t)f32_to_bf16_rne(hi) << 16);
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 template <int D>
@@ -170,21 +175,26 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
     }
 
     // Online softmax; lane owns query row jrow and tokens T + 32*sub + 8a + 4hh + b.
-    float mx = kMinusBig;
+    // The row max is taken on raw scores (softmax_scale > 0), the scale is folded into the
+    // exp2 argument: p = 2^(s*scale - m).
+    if (need_mask || !two) {
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int t = T + sub * 32 + (r / 4) * 8 + hh * 4 + (r % 4);
+          if (t > p_j || (sub == 1 && !two)) s[sub][r] = -INFINITY;
+        }
+    }
+    float mx = -INFINITY;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float x = s[sub][r] * scale;
-        const int t = T + sub * 32 + (r / 4) * 8 + hh * 4 + (r % 4);
-        if ((need_mask && t > p_j) || (sub == 1 && !two)) x = -INFINITY;
-        s[sub][r] = x;
-        mx = fmaxf(mx, x);
-      }
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sub][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
+    const float m_new = fmaxf(m_run, mx * scale);
     if (__any(m_new > m_run)) {
-      const float corr = exp2f(m_run - m_new);
+      const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
       l_run *= corr;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
@@ -197,7 +207,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float p = exp2f(s[sub][r] - m_run);
+        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][r], scale, -m_run));
         s[sub][r] = p;
         psum += p;
       }

@@ -2,115 +2,44 @@
 //
 // Serves the decode tokens of a mixed batch - one new token attending to its whole cached
 // context, the memory-bound part of a step (paper sections 2.1 and 4.2) - and the tokens of
-// prefill spans too short for the MFMA kernel.  A work item is (query token, context
-// partition); a workgroup takes one item and gives each of its waves one KV head, so that the
-// waves of a workgroup together stream whole 16-token blocks (all heads of a block are
-// contiguous in the pool).
+// prefill spans too short for the tile kernel.  The job is to stream K and V from HBM once, at
+// full bandwidth, with as little else in the way as possible:
 //
-// Inside a wave a token's head row (D bf16) is spread over D/8 lanes, 16 bytes each, so one
-// load instruction covers 64/(D/8) tokens with fully used cache lines.  Each group of lanes
-// that shares a token slot keeps its own online-softmax state (running max m, sum l, acc) over
-// the tokens it sees; the groups are merged once, at the end of the partition.  All G query
-// heads that share the KV head are processed against the same loaded K/V registers.
-// Scores live in the log2 domain (scale*log2(e) folded into the dot product, exp2 for exp).
+//  * A work item is (query token, context partition); a workgroup takes one item and gives
+//    each of its waves one KV head, so the waves of a workgroup together stream whole 16-token
+//    blocks (all heads of a block are contiguous in the pool).
+//  * Each wave owns a private ring of block slots in LDS and fills it with direct
+//    global->LDS loads (16 bytes per lane, no staging registers).  R-1 blocks are always in
+//    flight behind the one being consumed; with the whole 160 KB of LDS of a CU used this way
+//    the bytes in flight cover the HBM latency.  No workgroup barrier is needed: a wave only
+//    ever reads what it loaded itself, ordered by the vector-memory counter.
+//  * The arithmetic runs on the matrix cores so that the vector ALU stays nearly idle: the G
+//    query heads that share the KV head (padded to 16 rows) form the MFMA column, scores are
+//    S^T = K Q^T (16x16x32), the output is O^T = V^T P^T (16x16x16) with the V^T operand fetched
+//    by LDS transpose reads.  S^T comes out with lane (head, j) holding tokens 4j..4j+3, which
+//    is exactly the B operand layout of the second product; P stays in registers.
+//  * LDS rows are XOR-swizzled (free: each lane picks which 16 bytes of the row it loads) so
+//    that both the K fragment reads and the V transpose reads are bank-conflict free.
+// Scores are kept in the log2 domain (scale*log2(e) folded in, exp2 for exp).  Token slots
+// beyond the partition are excluded by select, and their V rows are replaced by zeros at load
+// time, so pool garbage (possibly NaN/Inf) cannot reach the output.
 #include "attn_internal.h"
 
 namespace dsv {
 namespace {
 
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((address_space(3))) void* lds_void_t;
+typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_t;
+typedef const __attribute__((address_space(1))) void* gbl_void_t;
 
 constexpr float kMinusBig = -1.0e30f;    // finite stand-in for "no token seen yet"
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float x) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL,
-                                                               0xf, 0xf, true));
-}
-
-// Sum over the LPT (8 or 16) adjacent lanes that hold one token's row; result in every lane.
-template <int LPT>
-__device__ __forceinline__ float group_sum(float x) {
-  x += dpp_move<0xB1>(x);     // quad_perm [1,0,3,2]
-  x += dpp_move<0x4E>(x);     // quad_perm [2,3,0,1]
-  x += dpp_move<0x141>(x);    // row_half_mirror: lane i <-> 7-i
-  if (LPT == 16) x += dpp_move<0x140>(x);   // row_mirror: lane i <-> 15-i
-  return x;
-}
-
-__device__ __forceinline__ float dot8(const uint4& a, const uint4& b, float acc) {
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.x), __builtin_bit_cast(bf16x2_t, b.x), acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.y), __builtin_bit_cast(bf16x2_t, b.y), acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.z), __builtin_bit_cast(bf16x2_t, b.z), acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.w), __builtin_bit_cast(bf16x2_t, b.w), acc, false);
-  return acc;
-}
-
-__device__ __forceinline__ void unpack8(const uint4& u, float (&f)[8]) {
-  f[0] = __builtin_bit_cast(float, u.x << 16); f[1] = __builtin_bit_cast(float, u.x & 0xffff0000u);
-  f[2] = __builtin_bit_cast(float, u.y << 16); f[3] = __builtin_bit_cast(float, u.y & 0xffff0000u);
-  f[4] = __builtin_bit_cast(float, u.z << 16); f[5] = __builtin_bit_cast(float, u.z & 0xffff0000u);
-  f[6] = __builtin_bit_cast(float, u.w << 16); f[7] = __builtin_bit_cast(float, u.w & 0xffff0000u);
-}
-
-template <int D, int GT>
-struct RowState {
-  static constexpr int LPT = D / 8;          // lanes per token row
-  static constexpr int TPL = kWave / LPT;    // tokens per load instruction
-  static constexpr int LPB = kBlockSize / TPL;   // load instructions per block (per K, per V)
-  float m[GT], l[GT], acc[GT][8];
-};
-
-// One 16-token block.  tok0 = absolute position of the block's slot 0; grp = this lane's token
-// sub-slot; MASKED: slots at positions >= ctx are excluded by select (pool garbage, possibly
-// NaN/Inf, must not leak: neither through the score nor through 0 * V).
-template <int D, int GT, bool MASKED>
-__device__ __forceinline__ void process_block(RowState<D, GT>& st, const uint4 (&kreg)[RowState<D, GT>::LPB],
-                                              const uint4 (&vreg)[RowState<D, GT>::LPB],
-                                              const uint4 (&qreg)[GT], float scale, int tok0, int grp,
-                                              int ctx) {
-  constexpr int LPT = RowState<D, GT>::LPT, TPL = RowState<D, GT>::TPL, LPB = RowState<D, GT>::LPB;
-  float s[LPB][GT];
-#pragma unroll
-  for (int i = 0; i < LPB; ++i) {
-    const bool valid = !MASKED || (tok0 + grp + TPL * i < ctx);
-#pragma unroll
-    for (int g = 0; g < GT; ++g) {
-      const float d = group_sum<LPT>(dot8(qreg[g], kreg[i], 0.f));
-      s[i][g] = valid ? d * scale : -INFINITY;
-    }
-  }
-  float corr[GT], p[LPB][GT];
-#pragma unroll
-  for (int g = 0; g < GT; ++g) {
-    float mb = s[0][g];
-#pragma unroll
-    for (int i = 1; i < LPB; ++i) mb = fmaxf(mb, s[i][g]);
-    const float mn = fmaxf(st.m[g], mb);
-    corr[g] = exp2f(st.m[g] - mn);
-    st.m[g] = mn;
-    float ps = 0.f;
-#pragma unroll
-    for (int i = 0; i < LPB; ++i) {
-      p[i][g] = exp2f(s[i][g] - mn);
-      ps += p[i][g];
-    }
-    st.l[g] = st.l[g] * corr[g] + ps;
-#pragma unroll
-    for (int d = 0; d < 8; ++d) st.acc[g][d] *= corr[g];
-  }
-#pragma unroll
-  for (int i = 0; i < LPB; ++i) {
-    uint4 vr = vreg[i];
-    if (MASKED && !(tok0 + grp + TPL * i < ctx)) vr = make_uint4(0u, 0u, 0u, 0u);
-    float v[8];
-    unpack8(vr, v);
-#pragma unroll
-    for (int g = 0; g < GT; ++g)
-#pragma unroll
-      for (int d = 0; d < 8; ++d) st.acc[g][d] += p[i][g] * v[d];
-  }
-}
+constexpr int kRowHeads = 16;            // query heads per wave (MFMA column count)
 
 struct RowsParams {
   AttnArgs a;
@@ -119,148 +48,259 @@ struct RowsParams {
   int32_t G;            // query heads per KV head
 };
 
-template <int D, int GT>
+template <int D>
+struct RowGeom {
+  static constexpr int ROWB = D * 2;              // bytes per token row of one head
+  static constexpr int CPR = D / 8;               // 16-byte chunks per row
+  static constexpr int TPI = kWave / CPR;         // token rows per load instruction
+  static constexpr int IPB = kBlockSize / TPI;    // load instructions per block, per tensor
+  static constexpr int KS = D / 32;               // 16x16x32 k-steps of K Q^T
+  static constexpr int DB = D / 16;               // 16-dim blocks of O^T
+  static constexpr int TENSOR_BYTES = kBlockSize * ROWB;
+  static constexpr int SLOT_BYTES = 2 * TENSOR_BYTES;
+  static constexpr int LOADS_PER_BLOCK = 2 * IPB;
+};
+
+// Row swizzles: 16-byte chunk c of token row n is stored at chunk position c ^ swz(n).
+template <int D> __device__ __forceinline__ int k_swz(int n) { return n & (RowGeom<D>::CPR - 1); }
+template <int D> __device__ __forceinline__ int v_swz(int n) { return 2 * (n & (RowGeom<D>::CPR / 2 - 1)); }
+
+// max / sum across the four lane groups j (lanes l, l^16, l^32, l^48).
+__device__ __forceinline__ float cross16_max(float x) {
+  x = fmaxf(x, __shfl_xor(x, 16));
+  return fmaxf(x, __shfl_xor(x, 32));
+}
+__device__ __forceinline__ float cross16_sum(float x) {
+  x += __shfl_xor(x, 16);
+  return x + __shfl_xor(x, 32);
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// LDS transpose reads of the V^T fragments, issued as one group and waited for together.  They
+// are written in assembly because the compiler, not knowing which LDS bytes the direct
+// global->LDS loads in flight will write, would otherwise drain every one of those loads
+// before each transpose read and serialise the ring.  The caller has already waited (vmcnt)
+// for the block that is read here.
+__device__ __forceinline__ void read_vt4(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3,
+                                         s16x4_t& v0, s16x4_t& v1, s16x4_t& v2, s16x4_t& v3) {
+  asm volatile(
+      "ds_read_b64_tr_b16 %0, %4\n\t"
+      "ds_read_b64_tr_b16 %1, %5\n\t"
+      "ds_read_b64_tr_b16 %2, %6\n\t"
+      "ds_read_b64_tr_b16 %3, %7\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3)
+      : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+      : "memory");
+}
+
+template <int D, int R>
 __global__ __launch_bounds__(512) void rows_kernel(RowsParams prm) {
-  using St = RowState<D, GT>;
-  constexpr int LPT = St::LPT, TPL = St::TPL, LPB = St::LPB;
+  using Geo = RowGeom<D>;
+  constexpr int ROWB = Geo::ROWB, CPR = Geo::CPR, TPI = Geo::TPI, IPB = Geo::IPB, KS = Geo::KS, DB = Geo::DB;
+  extern __shared__ __align__(16) unsigned char smem[];
+
   const AttnArgs& a = prm.a;
-  const int wave = (int)threadIdx.x / kWave;
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave);
   const int lane = (int)threadIdx.x % kWave;
   const int kvh = blockIdx.y * (blockDim.x / kWave) + wave;
   if (kvh >= a.Hkv) return;                      // no workgroup barrier below: safe
-  const int h0 = kvh * prm.G + blockIdx.z * GT;  // first query head of this wave
-  const int nh = min(GT, prm.G - (int)blockIdx.z * GT);
+  const int h0 = kvh * prm.G + blockIdx.z * kRowHeads;   // first query head of this wave
+  const int nh = min(kRowHeads, prm.G - (int)blockIdx.z * kRowHeads);
 
   const int item = blockIdx.x;
-  const int r = prm.w.item_row[item];
-  const int part = prm.w.item_part[item];
-  const int qtok = prm.w.row_qtok[r];
-  const int ctx = prm.w.row_ctx[r];
-  const int nparts = prm.w.row_nparts[r];
-  const int32_t* table = a.block_tables + (int64_t)prm.w.row_seq[r] * a.max_blocks;
+  const int4 rec0 = prm.w.item_rec[2 * item];          // {seq, qtok, ctx, part}
+  const int4 rec1 = prm.w.item_rec[2 * item + 1];      // {nparts, first block id, row, -}
+  const int qtok = rec0.y;
+  const int ctx = rec0.z;
+  const int part = rec0.w;
+  const int nparts = rec1.x;
+  const int32_t* table = a.block_tables + (int64_t)rec0.x * a.max_blocks;
 
   const int t0 = part * prm.part_tokens;
   const int t1 = min(ctx, t0 + prm.part_tokens);
   const int b0 = t0 / kBlockSize;
-  const int b1 = (t1 + kBlockSize - 1) / kBlockSize;
+  const int b1 = (t1 + kBlockSize - 1) / kBlockSize;   // b1 - b0 <= 64 (part_tokens <= 1024)
 
-  const int col = lane % LPT;                    // which 8 dims of the row
-  const int grp = lane / LPT;                    // which token sub-slot
+  const int qcol = lane % 16;                    // query head within the wave (MFMA column)
+  const int jj = lane / 16;                      // lane group
 
-  uint4 qreg[GT];
+  // Block ids of the partition: lane i holds the id of block b0+i; a uniform readlane hands one
+  // to the address computation.  The first id comes with the item record.
+  const int tab_vec = table[min(b0 + lane, b1 - 1)];
+
+  // Query fragments, B operand of S^T = K Q^T: lane (head qcol, jj) holds dims 32*ks + 8*jj .. +8.
+  bf16x8_t qf[KS];
 #pragma unroll
-  for (int g = 0; g < GT; ++g) {
-    qreg[g] = make_uint4(0u, 0u, 0u, 0u);
-    if (g < nh)
-      qreg[g] = *reinterpret_cast<const uint4*>(a.q + ((int64_t)qtok * a.Hq + h0 + g) * D + col * 8);
+  for (int ks = 0; ks < KS; ++ks) {
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (qcol < nh)
+      v = *reinterpret_cast<const uint4*>(a.q + ((int64_t)qtok * a.Hq + h0 + qcol) * D + ks * 32 + jj * 8);
+    qf[ks] = __builtin_bit_cast(bf16x8_t, v);
   }
 
-  St st;
+  // ---- loader: lane l fills 16-byte position l of each 1 KiB piece of the slot ----
+  unsigned char* const ring = smem + (size_t)wave * R * Geo::SLOT_BYTES;
+  const int ld_row = lane / CPR;                 // token row inside a piece
+  const int ld_pos = lane % CPR;                 // chunk position inside the row
+  const uint32_t tok_stride = (uint32_t)a.Hkv * D;          // elements between token slots
+  const int64_t blk_elems = (int64_t)kBlockSize * tok_stride;
+  const uint16_t* const zero_line = reinterpret_cast<const uint16_t*>(prm.w.zero_line);
+  auto issue_block = [&](int b, int slot) {
+    const int bid = (b == b0) ? rec1.y : __builtin_amdgcn_readlane(tab_vec, b - b0);
+    const uint16_t* kb = a.k_pool + (int64_t)bid * blk_elems + (uint32_t)kvh * D;
+    const uint16_t* vb = a.v_pool + (int64_t)bid * blk_elems + (uint32_t)kvh * D;
+    unsigned char* ks_base = ring + slot * Geo::SLOT_BYTES;
+    unsigned char* vs_base = ks_base + Geo::TENSOR_BYTES;
 #pragma unroll
-  for (int g = 0; g < GT; ++g) {
-    st.m[g] = kMinusBig;
-    st.l[g] = 0.f;
-#pragma unroll
-    for (int d = 0; d < 8; ++d) st.acc[g][d] = 0.f;
-  }
-
-  const int64_t tok_stride = (int64_t)a.Hkv * D;            // elements between token slots
-  const int64_t lane_off = (int64_t)grp * tok_stride + (int64_t)kvh * D + col * 8;
-  auto load_block = [&](int b, uint4 (&kr)[LPB], uint4 (&vr)[LPB]) {
-    const int64_t base = (int64_t)table[b] * kBlockSize * tok_stride + lane_off;
-#pragma unroll
-    for (int i = 0; i < LPB; ++i) {
-      const int64_t off = base + (int64_t)(TPL * i) * tok_stride;
-      kr[i] = *reinterpret_cast<const uint4*>(a.k_pool + off);
-      vr[i] = *reinterpret_cast<const uint4*>(a.v_pool + off);
+    for (int i = 0; i < IPB; ++i) {
+      const int n = i * TPI + ld_row;            // token slot in the block
+      const uint16_t* kp = kb + (uint32_t)n * tok_stride + ((ld_pos ^ k_swz<D>(n)) * 8);
+      const uint16_t* vp = vb + (uint32_t)n * tok_stride + ((ld_pos ^ v_swz<D>(n)) * 8);
+      if (b * kBlockSize + n >= t1) vp = zero_line + ld_pos * 8;     // beyond the partition: V := 0
+      __builtin_amdgcn_global_load_lds((gbl_void_t)kp, (lds_void_t)(ks_base + i * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gbl_void_t)vp, (lds_void_t)(vs_base + i * 1024), 16, 0, 0);
     }
   };
-  auto consume = [&](int b, const uint4 (&kr)[LPB], const uint4 (&vr)[LPB]) {
-    const int tok0 = b * kBlockSize;
-    if (tok0 + kBlockSize <= t1)
-      process_block<D, GT, false>(st, kr, vr, qreg, a.scale_log2e, tok0, grp, t1);
-    else
-      process_block<D, GT, true>(st, kr, vr, qreg, a.scale_log2e, tok0, grp, t1);
-  };
 
-  // Two register buffers: the next block's loads are in flight while the current one is used.
-  uint4 kA[LPB], vA[LPB], kB[LPB], vB[LPB];
-  load_block(b0, kA, vA);
-  for (int b = b0; b < b1; b += 2) {
-    if (b + 1 < b1) load_block(b + 1, kB, vB);
-    consume(b, kA, vA);
-    if (b + 1 < b1) {
-      if (b + 2 < b1) load_block(b + 2, kA, vA);
-      consume(b + 1, kB, vB);
+  // ---- per-lane state: lane (qcol, jj) owns head qcol; O^T rows are dims 16*db + 4*jj + e ----
+  f32x4_t o[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) o[db] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  float m_run = kMinusBig, l_run = 0.f;
+  const float scale = a.scale_log2e;
+
+  // LDS read offsets (bytes) inside a slot.
+  // K fragment (A operand, rows = tokens): lane (token qcol, jj) reads dims 32*ks + 8*jj .. +8.
+  int k_off[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) k_off[ks] = qcol * ROWB + (((ks * 4 + jj) ^ k_swz<D>(qcol)) * 16);
+  // V^T fragment by transpose read: the 16 lanes of group jj fetch token rows 4jj..4jj+3 x 16 dims.
+  const int v_row = jj * 4 + (lane % 16) / 4;
+  const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)ring;
+  uint32_t v_off[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+    v_off[db] = ring_lds + Geo::TENSOR_BYTES + v_row * ROWB + (((2 * db + (lane % 4) / 2) ^ v_swz<D>(v_row)) * 16) + (lane % 2) * 8;
+
+  wait_vmcnt<0>();                               // q, table and item record have arrived
+  const int blast = b1 - 1;
+#pragma unroll
+  for (int u = 0; u + 1 < R; ++u) issue_block(min(b0 + u, blast), u);
+
+  for (int b = b0; b < b1; ++b) {
+    const int slot = (b - b0) % R;
+    // Refill the slot consumed in the previous step (unconditionally, so that the number of
+    // loads in flight is static), then wait until only the R-1 younger blocks are outstanding.
+    issue_block(min(b + R - 1, blast), (b - b0 + R - 1) % R);
+    wait_vmcnt<(R - 1) * Geo::LOADS_PER_BLOCK>();
+    const unsigned char* sl = ring + slot * Geo::SLOT_BYTES;
+
+    // S^T = K Q^T: lane (head qcol, jj) gets tokens 4jj..4jj+3 of the block.
+    f32x4_t s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sl + k_off[ks]);
+      s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[ks], s, 0, 0, 0);
     }
-  }
-
-  // Merge the TPL token-slot groups of the wave.
+    const int tok = b * kBlockSize + jj * 4;
+    if (tok + 3 >= t1) {
 #pragma unroll
-  for (int off = LPT; off < kWave; off <<= 1) {
-#pragma unroll
-    for (int g = 0; g < GT; ++g) {
-      const float mo = __shfl_xor(st.m[g], off);
-      const float lo = __shfl_xor(st.l[g], off);
-      const float mn = fmaxf(st.m[g], mo);
-      const float c0 = exp2f(st.m[g] - mn), c1 = exp2f(mo - mn);
-      st.l[g] = st.l[g] * c0 + lo * c1;
-#pragma unroll
-      for (int d = 0; d < 8; ++d) st.acc[g][d] = st.acc[g][d] * c0 + __shfl_xor(st.acc[g][d], off) * c1;
-      st.m[g] = mn;
+      for (int e = 0; e < 4; ++e)
+        if (tok + e >= t1) s[e] = -INFINITY;
     }
-  }
-
-  if (grp != 0) return;
+    const float mx = cross16_max(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])));
+    const float m_new = fmaxf(m_run, mx * scale);
+    const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    float p[4];
 #pragma unroll
-  for (int g = 0; g < GT; ++g) {
-    if (g >= nh) break;
-    const int h = h0 + g;
-    if (nparts == 1) {
-      const float inv = 1.0f / st.l[g];
-      const int64_t o = ((int64_t)qtok * a.Hq + h) * D + col * 8;
-      if (a.out_bf16) {
-        uint4 pk;
-        pk.x = f32_to_bf16_rne(st.acc[g][0] * inv) | ((uint32_t)f32_to_bf16_rne(st.acc[g][1] * inv) << 16);
-        pk.y = f32_to_bf16_rne(st.acc[g][2] * inv) | ((uint32_t)f32_to_bf16_rne(st.acc[g][3] * inv) << 16);
-        pk.z = f32_to_bf16_rne(st.acc[g][4] * inv) | ((uint32_t)f32_to_bf16_rne(st.acc[g][5] * inv) << 16);
-        pk.w = f32_to_bf16_rne(st.acc[g][6] * inv) | ((uint32_t)f32_to_bf16_rne(st.acc[g][7] * inv) << 16);
-        *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(a.out) + o) = pk;
-      } else {
-        float4* op = reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + o);
-        op[0] = make_float4(st.acc[g][0] * inv, st.acc[g][1] * inv, st.acc[g][2] * inv, st.acc[g][3] * inv);
-        op[1] = make_float4(st.acc[g][4] * inv, st.acc[g][5] * inv, st.acc[g][6] * inv, st.acc[g][7] * inv);
+    for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], scale, -m_new));
+    const f32x2_t p01 = {p[0], p[1]}, p23 = {p[2], p[3]};
+    const bf16x2_t b01 = __builtin_convertvector(p01, bf16x2_t), b23 = __builtin_convertvector(p23, bf16x2_t);
+    const bf16x4_t pf = __builtin_shufflevector(b01, b23, 0, 1, 2, 3);
+    // The row sum is taken over the bf16-rounded probabilities that enter the PV product, so
+    // that the weights actually applied sum to one.
+    const uint32_t u01 = __builtin_bit_cast(uint32_t, b01), u23 = __builtin_bit_cast(uint32_t, b23);
+    l_run = l_run * corr + (__builtin_bit_cast(float, u01 << 16) + __builtin_bit_cast(float, u01 & 0xffff0000u)) +
+            (__builtin_bit_cast(float, u23 << 16) + __builtin_bit_cast(float, u23 & 0xffff0000u));
+
+    // O^T = O^T * corr + V^T P^T.
+    const uint32_t slot_off = (uint32_t)slot * Geo::SLOT_BYTES;
+#pragma unroll
+    for (int d4 = 0; d4 < DB; d4 += 4) {
+      s16x4_t vt[4];
+      read_vt4(v_off[d4] + slot_off, v_off[d4 + 1] + slot_off, v_off[d4 + 2] + slot_off,
+               v_off[d4 + 3] + slot_off, vt[0], vt[1], vt[2], vt[3]);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        o[d4 + u] *= corr;
+        o[d4 + u] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt[u], __builtin_bit_cast(s16x4_t, pf), o[d4 + u], 0, 0, 0);
       }
-    } else {
-      const int64_t ph = (int64_t)item * a.Hq + h;
-      float4* op = reinterpret_cast<float4*>(prm.w.part_acc + ph * D + col * 8);
-      op[0] = make_float4(st.acc[g][0], st.acc[g][1], st.acc[g][2], st.acc[g][3]);
-      op[1] = make_float4(st.acc[g][4], st.acc[g][5], st.acc[g][6], st.acc[g][7]);
-      if (col == 0) *reinterpret_cast<float2*>(prm.w.part_ml + ph * 2) = make_float2(st.m[g], st.l[g]);
     }
+  }
+  wait_vmcnt<0>();                               // drain the (duplicate) prefetches before exit
+
+  const float l_tot = cross16_sum(l_run);
+  if (qcol >= nh) return;
+  const int h = h0 + qcol;
+  if (nparts == 1) {
+    const float inv = 1.0f / l_tot;
+    const int64_t ob = ((int64_t)qtok * a.Hq + h) * D + jj * 4;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      const float x0 = o[db][0] * inv, x1 = o[db][1] * inv, x2 = o[db][2] * inv, x3 = o[db][3] * inv;
+      if (a.out_bf16) {
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16_rne(x0) | ((uint32_t)f32_to_bf16_rne(x1) << 16);
+        pk.y = (uint32_t)f32_to_bf16_rne(x2) | ((uint32_t)f32_to_bf16_rne(x3) << 16);
+        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + ob + db * 16) = pk;
+      } else {
+        *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + ob + db * 16) = make_float4(x0, x1, x2, x3);
+      }
+    }
+  } else {
+    const int64_t ph = (int64_t)item * a.Hq + h;
+    float* pa = prm.w.part_acc + ph * D + jj * 4;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      *reinterpret_cast<float4*>(pa + db * 16) = make_float4(o[db][0], o[db][1], o[db][2], o[db][3]);
+    if (jj == 0) *reinterpret_cast<float2*>(prm.w.part_ml + ph * 2) = make_float2(m_run, l_tot);
   }
 }
 
-template <int D, int GT>
-void launch_rows_t(const RowsParams& prm, dim3 grid, int threads, hipStream_t stream) {
-  hipLaunchKernelGGL((rows_kernel<D, GT>), grid, dim3(threads), 0, stream, prm);
+template <int D, int R>
+int launch_rows_t(const RowsParams& prm, dim3 grid, int waves, hipStream_t stream) {
+  const int lds = waves * R * RowGeom<D>::SLOT_BYTES;
+  static int configured = 0;          // raising the dynamic-LDS limit is idempotent; races are benign
+  if (lds > configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(rows_kernel<D, R>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+      return DSV_E_LAUNCH;
+    configured = lds;
+  }
+  hipLaunchKernelGGL((rows_kernel<D, R>), grid, dim3(waves * kWave), lds, stream, prm);
+  return launch_status();
 }
 
 }  // namespace
 
 int launch_rows(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, const PlanCounts& n,
                 hipStream_t stream) {
+  if (cfg.part_tokens > 64 * kBlockSize) return DSV_E_UNSUPPORTED;   // one table vector per partition
   RowsParams prm{a, w, cfg.part_tokens, a.Hq / a.Hkv};
   int waves = 1;
-  while (waves < a.Hkv && waves < 8) waves <<= 1;
-  int gt = 1;
-  while (gt < prm.G && gt < 8) gt <<= 1;
-  dim3 grid((unsigned)n.items, (unsigned)ceil_div(a.Hkv, waves), (unsigned)ceil_div(prm.G, gt));
-  const int threads = waves * kWave;
-#define DSV_ROWS_CASE(DD, GG) \
-  if (a.D == DD && gt == GG) { launch_rows_t<DD, GG>(prm, grid, threads, stream); return launch_status(); }
-  DSV_ROWS_CASE(128, 1) DSV_ROWS_CASE(128, 2) DSV_ROWS_CASE(128, 4) DSV_ROWS_CASE(128, 8)
-  DSV_ROWS_CASE(64, 1) DSV_ROWS_CASE(64, 2) DSV_ROWS_CASE(64, 4) DSV_ROWS_CASE(64, 8)
+  while (waves < a.Hkv && waves < cfg.row_waves) waves <<= 1;
+  dim3 grid((unsigned)n.items, (unsigned)ceil_div(a.Hkv, waves), (unsigned)ceil_div(prm.G, kRowHeads));
+  const int r = cfg.row_nbuf;
+#define DSV_ROWS_CASE(DD, RR) \
+  if (a.D == DD && r == RR) return launch_rows_t<DD, RR>(prm, grid, waves, stream);
+  DSV_ROWS_CASE(128, 2) DSV_ROWS_CASE(128, 3) DSV_ROWS_CASE(128, 4) DSV_ROWS_CASE(128, 6) DSV_ROWS_CASE(128, 8)
+  DSV_ROWS_CASE(64, 2) DSV_ROWS_CASE(64, 3) DSV_ROWS_CASE(64, 4) DSV_ROWS_CASE(64, 6) DSV_ROWS_CASE(64, 8)
 #undef DSV_ROWS_CASE
   return DSV_E_UNSUPPORTED;
 }
