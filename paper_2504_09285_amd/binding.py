@@ -12,7 +12,7 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libdsv_attn.so")
+_LIB_PATH = os.environ.get("DSV_ATTN_LIB") or os.path.join(_HERE, "libdsv_attn.so")
 _lib = None
 
 DSV_OUT_F32, DSV_OUT_BF16 = 0, 1

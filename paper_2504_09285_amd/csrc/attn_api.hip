@@ -36,6 +36,20 @@ int env_int(const char* name, int fallback) {
   return atoi(s);
 }
 
+// Compute units of the current device (256 on MI355X); falls back to that when no device answers.
+int device_cus() {
+  static int cached = 0;
+  if (cached > 0) return cached;
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) {
+    cached = n;
+    return n;
+  }
+  (void)hipGetLastError();
+  return 256;
+}
+
 // ---- plan: counts --------------------------------------------------------------------------
 
 __host__ __device__ inline bool on_row_path(int q_len, const PlanConfig& c) {
@@ -62,11 +76,9 @@ PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl) {
   PlanConfig c;
   c.mfma_min_qlen = env_int("DSV_MFMA_MIN_QLEN", 16);
   c.tile_tokens = 32;
-  c.row_waves = env_int("DSV_ROW_WAVES", 4);
   c.row_nbuf = env_int("DSV_ROW_NBUF", 2);
-  if (c.row_waves != 1 && c.row_waves != 2 && c.row_waves != 8) c.row_waves = 4;
-  if (c.row_nbuf != 3 && c.row_nbuf != 4 && c.row_nbuf != 6 && c.row_nbuf != 8) c.row_nbuf = 2;
-  while (c.row_waves * c.row_nbuf > 16) c.row_waves >>= 1;      // ring must fit the 160 KB of LDS
+  if (c.row_nbuf != 3 && c.row_nbuf != 4) c.row_nbuf = 2;
+  c.num_cus = device_cus();
   // Partition size: enough (row, partition) items to fill 256 CUs several times over, but not so
   // small that the partial results written per partition matter next to the KV bytes read.
   int64_t row_tokens = 0;
@@ -76,8 +88,9 @@ PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl) {
     const int64_t prefix = cl[i] - q_len;
     row_tokens += (int64_t)q_len * prefix + (int64_t)q_len * (q_len + 1) / 2;
   }
-  int64_t part = (row_tokens / 4096 + 15) / 16 * 16;
-  if (part < 128) part = 128;
+  // (Measured: 256 tokens is best for ~0.4M streamed tokens, 1024 for several millions.)
+  int64_t part = (row_tokens / 1400 + 15) / 16 * 16;
+  if (part < 256) part = 256;
   if (part > 1024) part = 1024;
   const int forced = env_int("DSV_PART_TOKENS", 0);
   if (forced >= 16) part = forced / 16 * 16;
@@ -119,7 +132,7 @@ size_t carve(const PlanCounts& n, int Hq, int D, char* base, WorkLists* w) {
   const size_t rows = (size_t)n.rows, items = (size_t)n.items, tiles = (size_t)n.tiles;
   char* p0 = take(rows * 4); char* p1 = take(rows * 4); char* p2 = take(rows * 4);
   char* p3 = take(rows * 4); char* p4 = take(rows * 4);
-  char* p5 = take(items * 32);
+  char* p5 = take(items * 16);
   char* p7 = take(tiles * 4); char* p8 = take(tiles * 4);
   char* pz = take(256);
   char* p9 = take(items * (size_t)Hq * D * 4);
@@ -156,9 +169,7 @@ __device__ int block_exclusive_scan(int v, int* smem, int* total) {
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __restrict__ q_offsets,
                                                             const int32_t* __restrict__ ctx_lens,
-                                                            const int32_t* __restrict__ block_tables,
-                                                            int32_t max_blocks, int32_t S, PlanConfig c,
-                                                            WorkLists w) {
+                                                            int32_t S, PlanConfig c, WorkLists w) {
   __shared__ int smem[kPlanThreads];
   if (threadIdx.x < 64) w.zero_line[threadIdx.x] = 0u;
   int row_carry = 0, item_carry = 0, tile_carry = 0;
@@ -189,11 +200,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
       w.row_ctx[r] = ctx_eff;
       w.row_item0[r] = item0;
       w.row_nparts[r] = np;
-      for (int p = 0; p < np; ++p) {
-        const int b0 = p * c.part_tokens / kBlockSize;
-        w.item_rec[2 * (item0 + p)] = make_int4(i, q0 + j, ctx_eff, p);
-        w.item_rec[2 * (item0 + p) + 1] = make_int4(np, block_tables[(int64_t)i * max_blocks + b0], r, 0);
-      }
+      for (int p = 0; p < np; ++p) w.item_rec[item0 + p] = make_int4(i, q0 + j, ctx_eff, p | (np << 16));
       item0 += np;
     }
     for (int t = 0; t < n_tiles; ++t) {
@@ -302,7 +309,8 @@ extern "C" int attn_mixed_batch(const void* q, void* out, const dsv_kv_pool* poo
 
   const PlanConfig cfg = choose_plan(num_seqs, q_offsets_host, ctx_lens_host);
   const PlanCounts n = count_plan(num_seqs, q_offsets_host, ctx_lens_host, cfg);
-  if (n.items > 0x7fffffffLL || n.tiles > 0x7fffffffLL || n.rows > 0x7fffffffLL)
+  if (n.items > 0x7fffffffLL || n.tiles > 0x7fffffffLL || n.rows > 0x7fffffffLL ||
+      n.max_parts > 0xffff)
     return DSV_E_UNSUPPORTED;
   WorkLists w;
   const size_t need = carve(n, num_q_heads, pool->head_dim, static_cast<char*>(workspace), &w);
@@ -329,7 +337,7 @@ extern "C" int attn_mixed_batch(const void* q, void* out, const dsv_kv_pool* poo
   {
     EventScope ev(DSV_KERNEL_PLAN, stream);
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, q_offsets, ctx_lens,
-                       block_tables, max_blocks_per_seq, num_seqs, cfg, w);
+                       num_seqs, cfg, w);
     if ((rc = launch_status())) return rc;
   }
   if (n.tiles) {

@@ -17,8 +17,8 @@ struct PlanConfig {
   int32_t part_tokens;     // multiple of 16
   int32_t mfma_min_qlen;   // spans with q_len >= this go to the MFMA kernel
   int32_t tile_tokens;     // query tokens per MFMA tile
-  int32_t row_waves;       // waves (= KV heads) per workgroup of the row kernel: 1, 2, 4 or 8
   int32_t row_nbuf;        // LDS ring slots (blocks) per wave of the row kernel: 2, 3, 4, 6 or 8
+  int32_t num_cus;         // compute units of the device (sizes the persistent grid)
 };
 
 struct PlanCounts {
@@ -36,8 +36,8 @@ struct WorkLists {
   int32_t* row_ctx;        // [rows] number of KV tokens the row attends to (p+1)
   int32_t* row_item0;      // [rows] first item of the row
   int32_t* row_nparts;     // [rows]
-  int4*    item_rec;       // [items][2]: {seq, qtok, ctx, part}, {nparts, first block id, row, 0}
-                           // everything a (row, partition) work item needs, in one 32-byte read
+  int4*    item_rec;       // [items]: {seq, qtok, ctx, part | nparts << 16}: everything a
+                           // (row, partition) work item needs, in one 16-byte scalar read
   int32_t* tile_seq;       // [tiles]
   int32_t* tile_q0;        // [tiles] first new-token index j of the tile
   uint32_t* zero_line;     // 256 bytes of zeros (stands in for V rows that must not be read)

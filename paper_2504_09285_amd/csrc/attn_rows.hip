@@ -113,13 +113,12 @@ __global__ __launch_bounds__(512) void rows_kernel(RowsParams prm) {
   const int nh = min(kRowHeads, prm.G - (int)blockIdx.z * kRowHeads);
 
   const int item = blockIdx.x;
-  const int4 rec0 = prm.w.item_rec[2 * item];          // {seq, qtok, ctx, part}
-  const int4 rec1 = prm.w.item_rec[2 * item + 1];      // {nparts, first block id, row, -}
-  const int qtok = rec0.y;
-  const int ctx = rec0.z;
-  const int part = rec0.w;
-  const int nparts = rec1.x;
-  const int32_t* table = a.block_tables + (int64_t)rec0.x * a.max_blocks;
+  const int4 rec = prm.w.item_rec[item];         // {seq, qtok, ctx, part | nparts << 16}
+  const int qtok = rec.y;
+  const int ctx = rec.z;
+  const int part = rec.w & 0xffff;
+  const int nparts = (int)((uint32_t)rec.w >> 16);
+  const int32_t* table = a.block_tables + (int64_t)rec.x * a.max_blocks;
 
   const int t0 = part * prm.part_tokens;
   const int t1 = min(ctx, t0 + prm.part_tokens);
@@ -130,7 +129,7 @@ __global__ __launch_bounds__(512) void rows_kernel(RowsParams prm) {
   const int jj = lane / 16;                      // lane group
 
   // Block ids of the partition: lane i holds the id of block b0+i; a uniform readlane hands one
-  // to the address computation.  The first id comes with the item record.
+  // to the address computation.
   const int tab_vec = table[min(b0 + lane, b1 - 1)];
 
   // Query fragments, B operand of S^T = K Q^T: lane (head qcol, jj) holds dims 32*ks + 8*jj .. +8.
@@ -151,7 +150,7 @@ __global__ __launch_bounds__(512) void rows_kernel(RowsParams prm) {
   const int64_t blk_elems = (int64_t)kBlockSize * tok_stride;
   const uint16_t* const zero_line = reinterpret_cast<const uint16_t*>(prm.w.zero_line);
   auto issue_block = [&](int b, int slot) {
-    const int bid = (b == b0) ? rec1.y : __builtin_amdgcn_readlane(tab_vec, b - b0);
+    const int bid = __builtin_amdgcn_readlane(tab_vec, b - b0);
     const uint16_t* kb = a.k_pool + (int64_t)bid * blk_elems + (uint32_t)kvh * D;
     const uint16_t* vb = a.v_pool + (int64_t)bid * blk_elems + (uint32_t)kvh * D;
     unsigned char* ks_base = ring + slot * Geo::SLOT_BYTES;
@@ -294,7 +293,8 @@ int launch_rows(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, co
   if (cfg.part_tokens > 64 * kBlockSize) return DSV_E_UNSUPPORTED;   // one table vector per partition
   RowsParams prm{a, w, cfg.part_tokens, a.Hq / a.Hkv};
   int waves = 1;
-  while (waves < a.Hkv && waves < cfg.row_waves) waves <<= 1;
+  const int max_waves = cfg.row_nbuf <= 2 ? 8 : 4;     // waves * slots * 8 KiB must fit in LDS
+  while (waves < a.Hkv && waves < max_waves) waves <<= 1;
   dim3 grid((unsigned)n.items, (unsigned)ceil_div(a.Hkv, waves), (unsigned)ceil_div(prm.G, kRowHeads));
   const int r = cfg.row_nbuf;
 #define DSV_ROWS_CASE(DD, RR) \
