@@ -27,6 +27,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 METRIC = "mixed-batch attention tokens/s; decode HBM GB/s & prefill MFMA util vs peak"
+# HBM bytes per rows_kernel launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the
+# counter reads for a plain 1 GiB copy (profiles/rows_kernel_c2_decode_heavy.md).
+MEASURED_TRAFFIC_BYTES = {"c2_decode_heavy": 1.515e9}
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
@@ -201,17 +204,17 @@ def bench_handoff(h, steps, warmup, hev):
 
 
 # ---------------------------------------------------------------------------- CPU baseline
-def cpu_baseline(b, max_seconds=30.0):
+def cpu_baseline(b, target_seconds=12.0):
     """The fp64 oracle as it stands, on this machine's host cores, on a bounded sample of the batch:
-    whole sequences are added until about max_seconds of work has been done."""
+    eighths of the batch (whole sequences, all heads) are processed in turn, wrapping around,
+    until about target_seconds of CPU work has been done."""
     import oracle
     oracle.build()
     n = b.num_seqs
-    order = np.arange(n)
     done_tokens, elapsed, used = 0, 0.0, 0
     step = max(1, n // 8)
-    while used < n and elapsed < max_seconds / 2:
-        idx = order[used:used + step]
+    while elapsed < target_seconds and used < 40 * n:
+        idx = (np.arange(used, used + step)) % n
         qo = np.zeros(len(idx) + 1, np.int32)
         np.cumsum(b.q_lens[idx], out=qo[1:])
         q = np.concatenate([b.q[b.q_offsets[i]:b.q_offsets[i + 1]] for i in idx])
@@ -222,7 +225,8 @@ def cpu_baseline(b, max_seconds=30.0):
         used += len(idx)
     return {"value": done_tokens / elapsed, "unit": "tokens/s", "cores": oracle.num_threads(),
             "kind": "oracle", "seconds": elapsed,
-            "sample": "first %d of %d sequences of %s (%d query tokens), all heads" % (used, n, b.name, done_tokens)}
+            "sample": "%d sequences (%.1f passes over the %d of %s; %d query tokens), all heads"
+                      % (used, used / n, n, b.name, done_tokens)}
 
 
 # ---------------------------------------------------------------------------- main
@@ -247,6 +251,8 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain 1 GiB device copy, 10 times (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -255,6 +261,14 @@ def main():
     import paper_2504_09285_amd as dsv
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU")
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "copies": 10}))
+        return
     dsv.load_library()
     threads = min(16, os.cpu_count() or 8)
     hev = HipEvents()
@@ -279,7 +293,8 @@ def main():
     elif "decode" in res:
         p = res["decode"]
         line["roofline"] = {"bound": "hbm", "achieved": p["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                            "frac": p["frac_hbm_peak"], "traffic": None, "kernel": "rows_kernel",
+                            "frac": p["frac_hbm_peak"], "traffic": MEASURED_TRAFFIC_BYTES.get(b.name),
+                            "kernel": "rows_kernel",
                             "algorithmic_bytes": p["algorithmic_bytes"]}
     if "prefill" in res:
         line["prefill"] = res["prefill"]
@@ -292,6 +307,10 @@ def main():
         h = gen.config5_handoff(layers=4, threads=threads)     # 8 x 8192 tokens, 256-token chunks, 4 of 32 layers
         extras["handoff_c5_4layers"] = bench_handoff(h, 10, 2, hev)
         del h
+        if args.workload != "c3":
+            r3, d3 = bench_attention(gen.config3(threads=threads), 10, 2, hev)
+            extras["c3_prefill_heavy"] = {k: r3[k] for k in ("ms_per_step", "tokens_per_s", "kernel_ms", "prefill", "decode") if k in r3}
+            del d3
         line["extras"] = extras
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(b)
