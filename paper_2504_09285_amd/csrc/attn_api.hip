@@ -75,7 +75,7 @@ int validate_batch(int32_t S, const int32_t* qo, const int32_t* cl, int32_t max_
 PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl) {
   PlanConfig c;
   c.mfma_min_qlen = env_int("DSV_MFMA_MIN_QLEN", 16);
-  c.tile_tokens = 32;
+  c.tile_tokens = 64;
   c.row_nbuf = env_int("DSV_ROW_NBUF", 2);
   if (c.row_nbuf != 3 && c.row_nbuf != 4) c.row_nbuf = 2;
   c.num_cus = device_cus();

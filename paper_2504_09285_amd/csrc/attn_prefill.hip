@@ -6,38 +6,56 @@
 // sections 2.1, 4.2): QK^T and PV are dense contractions and run on bf16 MFMA with fp32
 // accumulation and an online softmax.
 //
-// Work item: (span, 32 consecutive query tokens, KV head).  The four waves of a workgroup take
-// the (up to) four query heads that share that KV head, so every K/V tile staged in LDS is used
-// by all of them.  K/V tiles of 64 tokens (four 16-token blocks, gathered through the block
-// table) are double-buffered in LDS: the global loads of tile i+1 are issued before the math of
-// tile i and written to the other buffer after it.
+// Work item: (span, 64 consecutive query tokens, KV head, group of 4 query heads).  One
+// workgroup of four waves per item, one wave per SIMD; wave w takes query tokens
+// 32*(w/2)..+32 and the two query heads 2*(w%2), 2*(w%2)+1 of the group, i.e. 64 query rows.
+// Every K or V fragment read from LDS therefore feeds two MFMAs, which keeps the LDS read
+// traffic (the transpose reads of V in particular are slow) well under the MFMA time.
+//
+// K/V tiles of 64 tokens (four 16-token blocks gathered through the block table, one block per
+// wave) go straight from global memory into a ring of four LDS buffers with direct loads; tile
+// t+3 is requested while tile t is used.  One workgroup barrier per tile.
 //
 // The products are computed transposed, S^T = K Q^T and O^T = V^T P^T, with the 32x32x16 MFMA:
-//   - the query row is then the MFMA *column*, so a lane owns one query row for the whole
-//     kernel: row max / sum / rescale are per-lane scalars (one cross-lane exchange with the
-//     lane that holds the other 16 tokens of the row);
+//   - the query row is the MFMA column, so a lane owns one query row for the whole kernel: row
+//     max / sum / rescale are per-lane scalars (one exchange with the lane holding the other 16
+//     tokens of the row);
 //   - S^T comes out with lane (row j, half h) holding tokens 8a+4h+b (a,b = 0..3) of a 32-token
-//     sub-tile, which is exactly a valid B operand for the next MFMA once the contraction index
-//     (token) of the A operand V^T is enumerated in the same order.  P never leaves registers.
-//   - V^T as A operand needs, per lane, consecutive tokens of one dim, while memory is
-//     dim-contiguous: the LDS transpose read (ds_read_b64_tr_b16) delivers that from the
-//     natural [token][dim] layout.
-// Scores are kept in the log2 domain.  Slots past the span's context (pool garbage) are zeroed
-// while V is staged, and masked scores are excluded by select, so NaN/Inf there cannot leak.
+//     sub-tile, which is a valid B operand of the next MFMA once the contraction index (token)
+//     of the A operand V^T is enumerated in the same order: P never leaves registers;
+//   - V^T as A operand needs, per lane, consecutive tokens of one dim while memory is
+//     dim-contiguous: the LDS transpose read (ds_read_b64_tr_b16) delivers that from the natural
+//     [token][dim] layout.  LDS rows are XOR-swizzled at load time (each lane chooses which
+//     16 bytes of a row it fetches) so that both kinds of fragment reads are conflict-free.
+//
+// The loop over 32-token sub-tiles is software-pipelined: for sub-tile s the wave computes the
+// scores, then issues the V^T P^T MFMAs of sub-tile s-1 while its vector ALU does the softmax of
+// sub-tile s.  LDS reads are written in assembly: the compiler cannot know which bytes the direct
+// loads in flight will write and would drain all of them before every read.
+//
+// Scores are kept in the log2 domain.  Slots past the span's context (pool garbage) are fetched
+// from a line of zeros instead, and masked scores are excluded by select, so NaN/Inf there
+// cannot leak.
 #include "attn_internal.h"
 
 namespace dsv {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
-typedef __attribute__((ext_vector_type(4))) short s16x4_t;
-typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+typedef uint32_t __attribute__((ext_vector_type(4))) u32x4_t;
+typedef uint32_t __attribute__((ext_vector_type(2))) u32x2_t;
+typedef __attribute__((address_space(3))) void* lds_void_t;
+typedef const __attribute__((address_space(1))) void* gbl_void_t;
 
-constexpr int kTileQ = 32;        // query tokens per work item
+constexpr int kTileQ = 64;        // query tokens per work item
 constexpr int kTileKV = 64;       // KV tokens per LDS tile
 constexpr int kThreads = 256;
+constexpr int kRing = 4;          // LDS tile buffers
 constexpr float kMinusBig = -1.0e30f;
+constexpr float kMaxSlack = 8.0f;
 
 struct TilesParams {
   AttnArgs a;
@@ -48,37 +66,92 @@ struct TilesParams {
 
 template <int D>
 struct TileGeom {
-  static constexpr int KS = D / 16;          // MFMA k-steps of QK^T
+  static constexpr int KS = D / 16;          // MFMA k-steps of K Q^T
   static constexpr int DB = D / 32;          // 32-dim blocks of O^T
-  static constexpr int KSTR = D + 8;         // LDS row stride of K (elements): spreads b128 reads over banks
-  static constexpr int VSTR = D + 16;        // LDS row stride of V: spreads the 4-row transpose reads
-  static constexpr int UPR = D / 8;          // 16-byte units per token row
-  static constexpr int UPT = kTileKV * UPR / kThreads;   // units staged per thread per tile
-  static constexpr int LDS_BYTES = 2 * kTileKV * (KSTR + VSTR) * 2;
+  static constexpr int ROWB = D * 2;         // bytes per token row of one head
+  static constexpr int CPR = D / 8;          // 16-byte chunks per row
+  static constexpr int RPP = kWave / CPR;    // token rows per 1 KiB load piece
+  static constexpr int PPB = kBlockSize / RPP;       // pieces per 16-token block
+  static constexpr int TENSOR_BYTES = kTileKV * ROWB;
+  static constexpr int TILE_BYTES = 2 * TENSOR_BYTES;
+  static constexpr int LDS_BYTES = kRing * TILE_BYTES;
+  static constexpr int LOADS = 2 * PPB;      // direct loads per wave per tile
 };
 
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
-typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+template <int CPR> __device__ __forceinline__ int k_swz(int row) { return row & (CPR - 1); }
+template <int CPR> __device__ __forceinline__ int v_swz(int row) { return 2 * (row & (CPR / 2 - 1)); }
 
-// Two fp32 -> packed bf16, round to nearest even (the hardware conversion of gfx950).
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   const f32x2_t v = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// LDS reads of data written by the direct loads, issued as a group and waited for together.
+__device__ __forceinline__ void lds_read_b128x4(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3,
+                                                u32x4_t& v0, u32x4_t& v1, u32x4_t& v2, u32x4_t& v3) {
+  asm volatile(
+      "ds_read_b128 %0, %4\n\t"
+      "ds_read_b128 %1, %5\n\t"
+      "ds_read_b128 %2, %6\n\t"
+      "ds_read_b128 %3, %7\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3)
+      : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+      : "memory");
+}
+__device__ __forceinline__ void lds_read_tr4(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3,
+                                             u32x2_t& v0, u32x2_t& v1, u32x2_t& v2, u32x2_t& v3) {
+  asm volatile(
+      "ds_read_b64_tr_b16 %0, %4\n\t"
+      "ds_read_b64_tr_b16 %1, %5\n\t"
+      "ds_read_b64_tr_b16 %2, %6\n\t"
+      "ds_read_b64_tr_b16 %3, %7\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3)
+      : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+      : "memory");
+}
+
+// Exchange with lane ^ 32: after v_permlane32_swap a holds the value of the lower half-wave
+// lane and b that of the upper one, in both lanes.  Written in assembly: given the same value
+// for both operands, the compiler's builtin folds the two results into one.
+__device__ __forceinline__ void half_swap(float x, float& lo, float& hi) {
+  lo = x;
+  hi = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
+}
+__device__ __forceinline__ float other_half_max(float x) {       // max with lane ^ 32
+  float lo, hi;
+  half_swap(x, lo, hi);
+  return fmaxf(lo, hi);
+}
+__device__ __forceinline__ float other_half_sum(float x) {
+  float lo, hi;
+  half_swap(x, lo, hi);
+  return lo + hi;
+}
+
 template <int D>
-__global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams prm) {
+__global__ __launch_bounds__(kThreads, 1) void prefill_tiles_kernel(TilesParams prm) {
   using Geo = TileGeom<D>;
-  constexpr int KS = Geo::KS, DB = Geo::DB, KSTR = Geo::KSTR, VSTR = Geo::VSTR, UPR = Geo::UPR, UPT = Geo::UPT;
-  extern __shared__ __align__(16) uint16_t smem[];
-  uint16_t* const ksm0 = smem;
-  uint16_t* const vsm0 = smem + 2 * kTileKV * KSTR;
+  constexpr int KS = Geo::KS, DB = Geo::DB, ROWB = Geo::ROWB, CPR = Geo::CPR, RPP = Geo::RPP, PPB = Geo::PPB;
+  static_assert(KS % 4 == 0, "K fragments are fetched in groups of four");
+  extern __shared__ __align__(16) unsigned char smem[];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
   const AttnArgs& a = prm.a;
   const int tid = (int)threadIdx.x;
-  const int wave = tid / kWave, lane = tid % kWave;
-  const int jrow = lane % 32;            // query row of the tile (MFMA column) / token row of a K sub-tile
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int lane = tid % kWave;
+  const int jrow = lane % 32;            // query row of the wave (MFMA column) / token row of a K sub-tile
   const int hh = lane / 32;
+  const int tg = wave / 2;               // which 32 query tokens of the tile
+  const int hp = wave % 2;               // which pair of query heads
 
   // Heaviest tiles (late tiles of late spans) first.
   const int tile = prm.num_tiles - 1 - (int)blockIdx.x;
@@ -89,179 +162,234 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
   const int ctx = a.ctx_lens[seq];
   const int prefix = ctx - q_len;
   const int kvh = blockIdx.y;
-  const int hsub = (int)blockIdx.z * 4 + wave;
-  const bool head_ok = hsub < prm.G;
-  const int head = kvh * prm.G + (head_ok ? hsub : 0);
   const int32_t* table = a.block_tables + (int64_t)seq * a.max_blocks;
   const int nblk = (ctx + kBlockSize - 1) / kBlockSize;
   const int kv_end = min(ctx, prefix + j0 + kTileQ);          // exclusive: last visible token + 1
-  const int n_kv_tiles = (kv_end + kTileKV - 1) / kTileKV;
+  const int n_tiles = (kv_end + kTileKV - 1) / kTileKV;
+  const int NS = 2 * n_tiles;                                  // 32-token sub-tiles
 
   // Query fragments: B operand of S^T = K Q^T; lane (jrow, hh) holds dims 16*ks + 8*hh .. +8.
-  const bool q_ok = head_ok && (j0 + jrow < q_len);
-  const int64_t q_row_off = ((int64_t)(q0 + j0 + (q_ok ? jrow : 0)) * a.Hq + head) * D;
-  bf16x8_t qf[KS];
+  const int jq = j0 + 32 * tg + jrow;    // new-token index of this lane's query row
+  const int p_j = prefix + jq;           // its absolute position
+  bool head_ok[2];
+  int head[2];
+  uint4 qf[2][KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (q_ok) v = *reinterpret_cast<const uint4*>(a.q + q_row_off + ks * 16 + hh * 8);
-    qf[ks] = __builtin_bit_cast(bf16x8_t, v);
+  for (int c = 0; c < 2; ++c) {
+    const int hsub = (int)blockIdx.z * 4 + hp * 2 + c;
+    head_ok[c] = hsub < prm.G && jq < q_len;
+    head[c] = kvh * prm.G + (hsub < prm.G ? hsub : 0);
+    const int64_t off = ((int64_t)(q0 + (jq < q_len ? jq : 0)) * a.Hq + head[c]) * D + hh * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      qf[c][ks] = make_uint4(0u, 0u, 0u, 0u);
+      if (head_ok[c]) qf[c][ks] = *reinterpret_cast<const uint4*>(a.q + off + ks * 16);
+    }
   }
-  const int p_j = prefix + j0 + jrow;    // absolute position of this lane's query row
 
-  // ---- staging: global -> registers -> LDS ----
-  uint4 kst[UPT], vst[UPT];
-  auto gload = [&](int kt) {
+  // ---- direct global->LDS loads: wave w fetches block 4t+w of tile t (K and V) ----
+  const uint16_t* const zero_line = reinterpret_cast<const uint16_t*>(prm.w.zero_line);
+  const uint32_t tok_stride = (uint32_t)a.Hkv * D;
+  const int ld_row = lane / CPR, ld_pos = lane % CPR;
+  auto issue_tile = [&](int t) {
+    const int b = t * (kTileKV / kBlockSize) + wave;
+    const bool have = t < n_tiles && b < nblk;
+    const int64_t base = have ? ((int64_t)table[b] * kBlockSize * tok_stride + (uint32_t)kvh * D) : 0;
+    unsigned char* kdst = smem + (t % kRing) * Geo::TILE_BYTES + wave * (kBlockSize * ROWB);
+    unsigned char* vdst = kdst + Geo::TENSOR_BYTES;
 #pragma unroll
-    for (int k = 0; k < UPT; ++k) {
-      const int u = tid + kThreads * k;
-      const int tok = u / UPR, col = u % UPR;
-      const int b = kt * (kTileKV / kBlockSize) + tok / kBlockSize;
-      kst[k] = make_uint4(0u, 0u, 0u, 0u);
-      vst[k] = make_uint4(0u, 0u, 0u, 0u);
-      if (b < nblk) {
-        const int64_t off = (((int64_t)table[b] * kBlockSize + tok % kBlockSize) * a.Hkv + kvh) * D + col * 8;
-        kst[k] = *reinterpret_cast<const uint4*>(a.k_pool + off);
-        if (kt * kTileKV + tok < ctx) vst[k] = *reinterpret_cast<const uint4*>(a.v_pool + off);
-      }
-    }
-  };
-  auto sstore = [&](int buf) {
-#pragma unroll
-    for (int k = 0; k < UPT; ++k) {
-      const int u = tid + kThreads * k;
-      const int tok = u / UPR, col = u % UPR;
-      *reinterpret_cast<uint4*>(ksm0 + buf * kTileKV * KSTR + tok * KSTR + col * 8) = kst[k];
-      *reinterpret_cast<uint4*>(vsm0 + buf * kTileKV * VSTR + tok * VSTR + col * 8) = vst[k];
+    for (int i = 0; i < PPB; ++i) {
+      const int n = i * RPP + ld_row;                  // token slot in the block
+      const int row = wave * kBlockSize + n;           // row in the tile
+      const uint16_t* kp = a.k_pool + base + (uint32_t)n * tok_stride + ((ld_pos ^ k_swz<CPR>(row)) * 8);
+      const uint16_t* vp = a.v_pool + base + (uint32_t)n * tok_stride + ((ld_pos ^ v_swz<CPR>(row)) * 8);
+      if (!have) kp = zero_line + ld_pos * 8;
+      if (!have || b * kBlockSize + n >= ctx) vp = zero_line + ld_pos * 8;
+      __builtin_amdgcn_global_load_lds((gbl_void_t)kp, (lds_void_t)(kdst + i * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gbl_void_t)vp, (lds_void_t)(vdst + i * 1024), 16, 0, 0);
     }
   };
 
-  f32x16_t o[DB];
+  // ---- LDS fragment addresses (bytes, relative to the tile buffer) ----
+  // K fragment of sub-tile row jrow: chunk 2*ks + hh.  V^T fragment: 16 lanes fetch 4 token rows x
+  // 16 dims; tokens 16*ks16 + 4*hh + (lane%16)/4 (+8 for the second read), dims 32*db + ...
+  // The swizzles depend on row % 16 only, so fragments of other sub-tiles / k-steps are a
+  // constant number of rows further on.
+  uint32_t k_off[KS], v_off[DB];
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
+  for (int ks = 0; ks < KS; ++ks) k_off[ks] = lds0 + jrow * ROWB + (((2 * ks + hh) ^ k_swz<CPR>(jrow)) * 16);
+  {
+    const int row = hh * 4 + (lane % 16) / 4;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-  float m_run = kMinusBig, l_run = 0.f;
+    for (int db = 0; db < DB; ++db) {
+      const int chunk = 4 * db + 2 * ((lane / 16) % 2) + (lane % 4) / 2;
+      v_off[db] = lds0 + Geo::TENSOR_BYTES + row * ROWB + ((chunk ^ v_swz<CPR>(row)) * 16) + (lane % 2) * 8;
+    }
+  }
+
+  f32x16_t o[2][DB];
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[c][db][r] = 0.f;
+  float m_run[2] = {kMinusBig, kMinusBig}, l_run[2] = {0.f, 0.f};
   const float scale = a.scale_log2e;
 
-  gload(0);
-  sstore(0);
-  __syncthreads();
-
-  for (int kt = 0; kt < n_kv_tiles; ++kt) {
-    const int cur = kt & 1;
-    const bool more = kt + 1 < n_kv_tiles;
-    if (more) gload(kt + 1);
-
-    const uint16_t* ksm = ksm0 + cur * kTileKV * KSTR;
-    const uint16_t* vsm = vsm0 + cur * kTileKV * VSTR;
-    const int T = kt * kTileKV;
-    const bool two = T + 32 < kv_end;                 // second 32-token sub-tile has visible tokens
-    const bool need_mask = T + kTileKV - 1 > prefix + j0;
-
-    // S^T = K Q^T for the two 32-token sub-tiles.
-    f32x16_t s[2];
+  // K Q^T of sub-tile s into sc[2] (both heads), K fragments fetched in two groups of KS/2.
+  auto qk = [&](int s, f32x16_t (&sc)[2]) {
+    const uint32_t buf = (uint32_t)((s / 2) % kRing) * Geo::TILE_BYTES + (uint32_t)(s & 1) * (32 * ROWB);
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
+    for (int c = 0; c < 2; ++c)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
-      if (sub == 0 || two) {
+      for (int r = 0; r < 16; ++r) sc[c][r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(ksm + (sub * 32 + jrow) * KSTR + ks * 16 + hh * 8);
-          s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[sub], 0, 0, 0);
+    for (int g4 = 0; g4 < KS; g4 += 4) {
+      u32x4_t kf[4];
+      lds_read_b128x4(k_off[g4] + buf, k_off[g4 + 1] + buf, k_off[g4 + 2] + buf, k_off[g4 + 3] + buf,
+                      kf[0], kf[1], kf[2], kf[3]);
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+          sc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[k]),
+                                                          __builtin_bit_cast(bf16x8_t, qf[c][g4 + k]), sc[c], 0, 0, 0);
+    }
+  };
+  // Softmax of sub-tile s: sc -> bf16 probabilities pf[c][ks16] (B operand), updates m_run/l_run;
+  // corr[c] is the factor the accumulators of head c must be multiplied with before P joins them.
+  auto softmax = [&](int s, f32x16_t (&sc)[2], uint4 (&pf)[2][2], float (&corr)[2], bool& any_corr) {
+    const int T = s * 32;
+    const bool need_mask = T + 31 > prefix + j0 + 32 * tg;     // wave-uniform
+    any_corr = false;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      if (need_mask) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (T + (r / 4) * 8 + hh * 4 + (r % 4) > p_j) sc[c][r] = -INFINITY;
+      }
+      float mx = sc[c][0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[c][r]);
+      mx = other_half_max(mx);
+      // The reference value m only follows the row max when it has grown by more than
+      // kMaxSlack (log2 units): probabilities may then exceed 1 by up to 2^kMaxSlack, which
+      // fp32 sums and bf16 operands hold without loss, and the 128-register rescale of the
+      // accumulators becomes rare instead of hitting some row of the wave at almost every step.
+      const float m_cand = mx * scale;
+      const float m_new = m_cand > m_run[c] + kMaxSlack ? m_cand : m_run[c];
+      corr[c] = __builtin_amdgcn_exp2f(m_run[c] - m_new);
+      any_corr |= m_new != m_run[c];
+      m_run[c] = m_new;
+      float ps = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        sc[c][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[c][r], scale, -m_new));
+        ps += sc[c][r];
+      }
+      l_run[c] = l_run[c] * corr[c] + ps;
+#pragma unroll
+      for (int k16 = 0; k16 < 2; ++k16) {
+        pf[c][k16].x = pack_bf16(sc[c][8 * k16 + 0], sc[c][8 * k16 + 1]);
+        pf[c][k16].y = pack_bf16(sc[c][8 * k16 + 2], sc[c][8 * k16 + 3]);
+        pf[c][k16].z = pack_bf16(sc[c][8 * k16 + 4], sc[c][8 * k16 + 5]);
+        pf[c][k16].w = pack_bf16(sc[c][8 * k16 + 6], sc[c][8 * k16 + 7]);
+      }
+    }
+  };
+  // O^T += V^T P^T for sub-tile s.
+  auto pv = [&](int s, const uint4 (&pf)[2][2]) {
+    const uint32_t buf = (uint32_t)((s / 2) % kRing) * Geo::TILE_BYTES + (uint32_t)(s & 1) * (32 * ROWB);
+#pragma unroll
+    for (int k16 = 0; k16 < 2; ++k16) {
+#pragma unroll
+      for (int d2 = 0; d2 < DB; d2 += 2) {
+        u32x2_t v0[2], v1[2];
+        const uint32_t base = buf + (k16 * 16) * ROWB;
+        lds_read_tr4(v_off[d2] + base, v_off[d2] + base + 8 * ROWB, v_off[d2 + 1] + base,
+                     v_off[d2 + 1] + base + 8 * ROWB, v0[0], v1[0], v0[1], v1[1]);
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const u32x4_t vv = {v0[e][0], v0[e][1], v1[e][0], v1[e][1]};
+#pragma unroll
+          for (int c = 0; c < 2; ++c)
+            o[c][d2 + e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vv),
+                                                                   __builtin_bit_cast(bf16x8_t, pf[c][k16]),
+                                                                   o[c][d2 + e], 0, 0, 0);
         }
       }
     }
-
-    // Online softmax; lane owns query row jrow and tokens T + 32*sub + 8a + 4hh + b.
-    // The row max is taken on raw scores (softmax_scale > 0), the scale is folded into the
-    // exp2 argument: p = 2^(s*scale - m).
-    if (need_mask || !two) {
+  };
+  auto rescale = [&](const float (&corr)[2]) {
 #pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int t = T + sub * 32 + (r / 4) * 8 + hh * 4 + (r % 4);
-          if (t > p_j || (sub == 1 && !two)) s[sub][r] = -INFINITY;
-        }
-    }
-    float mx = -INFINITY;
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sub][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx * scale);
-    if (__any(m_new > m_run)) {
-      const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
-      l_run *= corr;
+    for (int c = 0; c < 2; ++c)
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] *= corr;
-      m_run = m_new;
-    }
-    float psum = 0.f;
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][r], scale, -m_run));
-        s[sub][r] = p;
-        psum += p;
-      }
-    l_run += psum;
+        for (int r = 0; r < 16; ++r) o[c][db][r] *= corr[c];
+  };
 
-    // O^T += V^T P^T, 16 tokens per k-step.
-#pragma unroll
-    for (int s4 = 0; s4 < 4; ++s4) {
-      if (s4 >= 2 && !two) break;
-      const int sub = s4 / 2, a0 = (s4 % 2) * 8;
-      uint4 pk;
-      pk.x = pack_bf16(s[sub][a0 + 0], s[sub][a0 + 1]);
-      pk.y = pack_bf16(s[sub][a0 + 2], s[sub][a0 + 3]);
-      pk.z = pack_bf16(s[sub][a0 + 4], s[sub][a0 + 5]);
-      pk.w = pack_bf16(s[sub][a0 + 6], s[sub][a0 + 7]);
-      const bf16x8_t pf = __builtin_bit_cast(bf16x8_t, pk);
-      // transpose reads: 16 lanes fetch 4 token rows x 16 dims; lane gets 4 tokens of its dim
-      const int trow = s4 * 16 + hh * 4 + (lane % 16) / 4;
-      const int tcol = ((lane / 16) % 2) * 16 + (lane % 4) * 4;
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        typedef __attribute__((address_space(3))) s16x4_t* lds_ptr_t;
-        const uint16_t* p0 = vsm + trow * VSTR + db * 32 + tcol;
-        const s16x4_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p0));
-        const s16x4_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p0 + 8 * VSTR));
-        const s16x8_t vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vv), pf, o[db], 0, 0, 0);
-      }
-    }
+  // ---- prologue: tiles 0..2 requested, tile 0 awaited ----
+  issue_tile(0);
+  issue_tile(1);
+  issue_tile(2);
+  wait_vmcnt<2 * Geo::LOADS>();
+  __builtin_amdgcn_s_barrier();
 
-    if (more) sstore(cur ^ 1);
-    __syncthreads();
+  f32x16_t sc[2];
+  uint4 pf[2][2];
+  float corr[2];
+  bool any_corr;
+
+  for (int u = 0; u < n_tiles; ++u) {
+    // Sub-tile 2u: scores, then V^T P^T of the previous sub-tile (previous tile) on the matrix
+    // cores while the vector ALU does this sub-tile's softmax.
+    qk(2 * u, sc);
+    if (u > 0) pv(2 * u - 1, pf);
+    softmax(2 * u, sc, pf, corr, any_corr);
+    if (__any(any_corr)) rescale(corr);
+    // Sub-tile 2u+1.
+    qk(2 * u + 1, sc);
+    pv(2 * u, pf);
+    softmax(2 * u + 1, sc, pf, corr, any_corr);
+    if (__any(any_corr)) rescale(corr);
+
+    // Tile u+1 must be complete before the next iteration (tile u+2 may still be in flight);
+    // every wave is past its last read of tile u-1, whose buffer now takes tile u+3.
+    // (A bare s_barrier: __syncthreads() would add a fence that drains every load in flight.
+    // Each wave has waited for its own loads, and LDS reads complete inside their asm groups.)
+    wait_vmcnt<Geo::LOADS>();
+    __builtin_amdgcn_s_barrier();
+    issue_tile(u + 3);
   }
+  pv(NS - 1, pf);
+  wait_vmcnt<0>();                       // the last (dummy) tile requests
 
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
-  if (!q_ok) return;
-  const float inv = 1.0f / l_tot;
-  const int64_t o_row = ((int64_t)(q0 + j0 + jrow) * a.Hq + head) * D;
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
+  for (int c = 0; c < 2; ++c) {
+    const float l_tot = other_half_sum(l_run[c]);
+    if (!head_ok[c]) continue;
+    const float inv = 1.0f / l_tot;
+    const int64_t o_row = ((int64_t)(q0 + jq) * a.Hq + head[c]) * D;
 #pragma unroll
-    for (int aa = 0; aa < 4; ++aa) {
-      const int dim = db * 32 + aa * 8 + hh * 4;
-      const float x0 = o[db][aa * 4 + 0] * inv, x1 = o[db][aa * 4 + 1] * inv;
-      const float x2 = o[db][aa * 4 + 2] * inv, x3 = o[db][aa * 4 + 3] * inv;
-      if (a.out_bf16) {
-        uint2 pk;
-        pk.x = pack_bf16(x0, x1);
-        pk.y = pack_bf16(x2, x3);
-        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + o_row + dim) = pk;
-      } else {
-        *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + o_row + dim) = make_float4(x0, x1, x2, x3);
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int aa = 0; aa < 4; ++aa) {
+        const int dim = db * 32 + aa * 8 + hh * 4;
+        const float x0 = o[c][db][aa * 4 + 0] * inv, x1 = o[c][db][aa * 4 + 1] * inv;
+        const float x2 = o[c][db][aa * 4 + 2] * inv, x3 = o[c][db][aa * 4 + 3] * inv;
+        if (a.out_bf16) {
+          uint2 pk;
+          pk.x = pack_bf16(x0, x1);
+          pk.y = pack_bf16(x2, x3);
+          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + o_row + dim) = pk;
+        } else {
+          *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + o_row + dim) = make_float4(x0, x1, x2, x3);
+        }
       }
-    }
+  }
 }
 
 template <int D>
