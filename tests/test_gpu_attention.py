@@ -276,3 +276,62 @@ def test_config4_micro_request_shrunk():
                             np.array([sp.total], np.int32))
     ref_unsplit = oracle_out(unsplit)
     assert np.abs(got[:sp.total] - ref_unsplit).max() <= TOL
+
+
+# ------------------------------------------------------------------ full-size spot checks
+def _sampled_rows_check(b, rows, got):
+    ref = oracle.attn_rows(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens, b.scale, rows)
+    for r, (i, j, h) in enumerate(rows):
+        err = np.abs(got[b.q_offsets[i] + j, h] - ref[r]).max()
+        assert err <= TOL, (i, j, h, err)
+
+
+@pytest.mark.timeout(600)
+def test_config4_micro_request_full_sampled_rows():
+    """Config 4 at full size (64/8 heads, 4096-token prompt split at the seeded boundary, 128 decodes
+    with contexts up to 32768), hand-off through the GPU pack/unpack, sampled rows vs the oracle."""
+    import torch
+    import paper_2504_09285_amd as dsv
+    from gpu_harness import DeviceBatch, host_u16
+    b, sp = _config4_inputs(1)
+    assert b.Hq == 64 and sp.total == 4096 and b.num_seqs == 130
+    d = DeviceBatch(b)
+    descs = dsv.ChunkDescs(sp.chunks)
+    buf = torch.zeros(sp.chunk_elems, dtype=torch.bfloat16, device="cuda")
+    dsv.kv_pack_chunks(d.pool, d.block_tables[0:1].contiguous(), descs, buf)
+    dsv.kv_unpack_chunks(buf, descs, d.pool, d.block_tables[1:2].contiguous())
+    got = d.run().cpu().numpy()
+    assert np.isfinite(got).all()
+    kp, vp = b.k_pool[None].copy(), b.v_pool[None].copy()
+    obuf = np.zeros(sp.chunk_elems, np.uint16)
+    oracle.kv_pack_chunks(kp, vp, b.block_tables[0:1], sp.chunks, obuf)
+    oracle.kv_unpack_chunks(obuf, sp.chunks, kp, vp, b.block_tables[1:2])
+    np.testing.assert_array_equal(host_u16(buf), obuf)
+    np.testing.assert_array_equal(host_u16(d.pool.k), kp)
+    moved = gen.AttnBatch(b.name, b.Hq, b.Hkv, b.D, b.scale, b.q, kp[0], vp[0], b.block_tables,
+                          b.q_offsets, b.ctx_lens)
+    rng = np.random.default_rng(4)
+    rows = [(0, 0, 0), (0, sp.k - 1, 63), (1, 0, 5), (1, sp.total - sp.k - 1, 17)]
+    rows += [(0, int(rng.integers(sp.k)), int(rng.integers(64))) for _ in range(20)]
+    rows += [(1, int(rng.integers(sp.total - sp.k)), int(rng.integers(64))) for _ in range(20)]
+    rows += [(int(i), 0, int(rng.integers(64))) for i in rng.choice(np.arange(2, 130), 24, replace=False)]
+    rows.append((2 + int(np.argmax(b.ctx_lens[2:])), 0, 7))
+    _sampled_rows_check(moved, rows, got)
+
+
+@pytest.mark.timeout(900)
+def test_config5_long_context_full_sampled_rows():
+    """Config 5's attention at full size (64 decodes, contexts 16K..128K, one layer's pool of
+    ~0.24M blocks: block offsets exceed 2^32 elements); sampled (sequence, head) rows vs the oracle."""
+    from gpu_harness import run_attention
+    b = gen.config5_attention(threads=16)
+    assert b.num_seqs == 64 and int(b.k_pool.size) > 2 ** 31
+    got = run_attention(b)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(5)
+    rows = [(int(i), 0, int(rng.integers(32))) for i in rng.choice(64, 20, replace=False)]
+    rows += [(int(np.argmax(b.ctx_lens)), 0, h) for h in (0, 31)]
+    rows += [(int(np.argmin(b.ctx_lens)), 0, 13)]
+    far = int(np.argmax(b.block_tables.max(axis=1)))          # the sequence owning the highest block id
+    rows.append((far, 0, 3))
+    _sampled_rows_check(b, rows, got)

@@ -84,3 +84,25 @@ def test_empty_and_invalid():
     bad[0, 3] = 4                      # misaligned chunk offset
     with pytest.raises(dsv.DsvError):
         dsv.kv_pack_chunks(d.src, d.src_tables, dsv.ChunkDescs(bad), d.chunk_buf)
+
+
+@pytest.mark.timeout(1200)
+def test_config5_handoff_full_size():
+    """Config 5's hand-off at full size: 8 requests x 8192 tokens x 32 layers (8.59 GB payload) in
+    256-token chunks from one paged pool into another with a different block table.  The copied
+    bytes are compared layer by layer; untouched destination blocks must keep their bytes."""
+    import torch
+    from gpu_harness import DeviceHandoff, host_u16
+    h = gen.config5_handoff(threads=16)
+    assert h.L == 32 and h.chunks.shape[0] == 256 and h.payload_bytes == 8 * 8192 * 32 * 4096
+    d = DeviceHandoff(h)
+    d.pack()
+    d.unpack()
+    torch.cuda.synchronize()
+    buf = np.zeros(h.chunk_elems, np.uint16)
+    oracle.kv_pack_chunks(h.src_k, h.src_v, h.src_tables, h.chunks, buf)
+    assert np.array_equal(host_u16(d.chunk_buf), buf)
+    oracle.kv_unpack_chunks(buf, h.chunks, h.dst_k, h.dst_v, h.dst_tables)      # in place: h.dst_* now expected
+    for l in range(h.L):
+        assert np.array_equal(host_u16(d.dst.k[l]), h.dst_k[l]), l
+        assert np.array_equal(host_u16(d.dst.v[l]), h.dst_v[l]), l
