@@ -203,6 +203,87 @@ def bench_handoff(h, steps, warmup, hev):
     return out
 
 
+def bench_config4(threads, steps, warmup, hev):
+    """Config 4: the split prompt's prefix reaches its second span through GPU pack/unpack, then
+    one mixed batch (two prefill spans + 128 decodes).  Reports the hand-off time and the step."""
+    import torch
+    import paper_2504_09285_amd as dsv
+    from workloads import gen
+    b, sp = gen.config4(threads=threads)
+    t = np.arange(sp.k, sp.total)
+    for pool in (b.k_pool, b.v_pool):
+        pool[b.block_tables[1, t // 16], t % 16] = pool[b.block_tables[0, t // 16], t % 16]
+    d = upload(b)
+    descs = dsv.ChunkDescs(sp.chunks)
+    buf = torch.zeros(sp.chunk_elems, dtype=torch.bfloat16, device="cuda")
+    src_tbl, dst_tbl = d.block_tables[0:1].contiguous(), d.block_tables[1:2].contiguous()
+    stream = torch.cuda.current_stream().cuda_stream or None
+    e0, e1 = hev.create(), hev.create()
+    torch.cuda.synchronize()
+    hev.record(e0, stream)
+    dsv.kv_pack_chunks(d.pool, src_tbl, descs, buf)
+    dsv.kv_unpack_chunks(buf, descs, d.pool, dst_tbl)
+    hev.record(e1, stream)
+    torch.cuda.synchronize()
+    handoff_ms = hev.elapsed_ms(e0, e1)
+    sec, pk = time_attention(d, steps, warmup, [dsv.KERNEL_ROWS, dsv.KERNEL_TILES, dsv.KERNEL_MERGE, dsv.KERNEL_PLAN], hev)
+    nbytes, flops = decode_bytes(b, 2), prefill_flops(b)
+    t_mem, t_mfma = nbytes / (HBM_PEAK_GBS * 1e9), flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    rows_ms, tiles_ms = pk[dsv.KERNEL_ROWS], pk[dsv.KERNEL_TILES]
+    return {"workload": b.name, "split_k": sp.k, "ms_per_step": sec * 1e3, "tokens_per_s": b.total_q / sec,
+            "kernel_ms": {"rows": rows_ms, "tiles": tiles_ms, "merge": pk[dsv.KERNEL_MERGE], "plan": pk[dsv.KERNEL_PLAN]},
+            "handoff_pack_unpack_ms": handoff_ms, "handoff_chunks": int(len(sp.chunks)),
+            "decode": {"GB/s": nbytes / (rows_ms * 1e-3) / 1e9, "frac_hbm_peak": nbytes / (rows_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "prefill": {"TFLOP/s": flops / (tiles_ms * 1e-3) / 1e12, "frac_mfma_peak": flops / (tiles_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+            "bound_ms": {"hbm": t_mem * 1e3, "mfma": t_mfma * 1e3},
+            "frac_of_overlap_bound": max(t_mem, t_mfma) / sec}
+
+
+def bench_concurrent(b, h, rounds, hev):
+    """Attention on one stream, pack+unpack on a second one (config 5): each alone, then together."""
+    import torch
+    import paper_2504_09285_amd as dsv
+    d = upload(b)
+
+    def dev_bf16(u16):
+        return torch.from_numpy(np.ascontiguousarray(u16).view(np.int16)).cuda().view(torch.bfloat16)
+
+    src = dsv.KVPool(dev_bf16(h.src_k), dev_bf16(h.src_v))
+    dst = dsv.KVPool(dev_bf16(h.dst_k), dev_bf16(h.dst_v))
+    st, dt = torch.from_numpy(h.src_tables).cuda(), torch.from_numpy(h.dst_tables).cuda()
+    descs = dsv.ChunkDescs(h.chunks)
+    buf = torch.empty(h.chunk_elems, dtype=torch.bfloat16, device="cuda")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def attn():
+        bb = d.b
+        dsv.attn_mixed_batch(d.q, d.out, d.pool, 0, d.block_tables, d.q_offsets, d.ctx_lens, bb.q_offsets,
+                             bb.ctx_lens, bb.Hq, bb.scale, d.workspace, stream=s1)
+
+    def copy():
+        dsv.kv_pack_chunks(src, st, descs, buf, stream=s2)
+        dsv.kv_unpack_chunks(buf, descs, dst, dt, stream=s2)
+
+    def timed(fns):
+        for f in fns:
+            f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(rounds):
+            for f in fns:
+                f()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / rounds
+
+    ta, tc, tb = timed([attn]), timed([copy]), timed([attn, copy])
+    ab, cb = decode_bytes(b, 2), 4 * h.payload_bytes
+    return {"attention": b.name, "handoff": h.name, "handoff_layers": h.L,
+            "attn_alone_ms": ta * 1e3, "handoff_alone_ms": tc * 1e3, "together_ms": tb * 1e3,
+            "attn_alone_GB/s": ab / ta / 1e9, "handoff_alone_GB/s": cb / tc / 1e9,
+            "together_GB/s": (ab + cb) / tb / 1e9, "together_frac_hbm_peak": (ab + cb) / tb / 1e9 / HBM_PEAK_GBS,
+            "overlap_gain": (ta + tc) / tb}
+
+
 # ---------------------------------------------------------------------------- CPU baseline
 def cpu_baseline(b, target_seconds=12.0):
     """The fp64 oracle as it stands, on this machine's host cores, on a bounded sample of the batch:
@@ -251,6 +332,7 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--full-extras", action="store_true", help="config 5 at full context lengths (16 GB of KV)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy, 10 times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -311,6 +393,13 @@ def main():
             r3, d3 = bench_attention(gen.config3(threads=threads), 10, 2, hev)
             extras["c3_prefill_heavy"] = {k: r3[k] for k in ("ms_per_step", "tokens_per_s", "kernel_ms", "prefill", "decode") if k in r3}
             del d3
+        extras["c4_micro_request"] = bench_config4(threads, 10, 2, hev)
+        if args.full_extras:
+            extras["c5_two_streams"] = bench_concurrent(gen.config5_attention(threads=threads),
+                                                        gen.config5_handoff(layers=8, threads=threads), 5, hev)
+        else:
+            extras["c5_two_streams_quarter_contexts"] = bench_concurrent(
+                gen.config5_attention(shrink=4, threads=threads), gen.config5_handoff(layers=4, threads=threads), 5, hev)
         line["extras"] = extras
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(b)
