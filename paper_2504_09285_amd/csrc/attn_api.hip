@@ -135,6 +135,7 @@ size_t carve(const PlanCounts& n, int Hq, int D, char* base, WorkLists* w) {
   char* p5 = take(items * 16);
   char* p7 = take(tiles * 4); char* p8 = take(tiles * 4);
   char* pz = take(256);
+  char* pc = take(items * 4);
   char* p9 = take(items * (size_t)Hq * D * 4);
   char* p10 = take(items * (size_t)Hq * 2 * 4);
   if (w) {
@@ -143,6 +144,7 @@ size_t carve(const PlanCounts& n, int Hq, int D, char* base, WorkLists* w) {
     w->item_rec = (int4*)p5;
     w->tile_seq = (int32_t*)p7; w->tile_q0 = (int32_t*)p8;
     w->zero_line = (uint32_t*)pz;
+    w->item_blk0 = (int32_t*)pc;
     w->part_acc = (float*)p9; w->part_ml = (float*)p10;
   }
   return off + 256;
@@ -169,7 +171,9 @@ __device__ int block_exclusive_scan(int v, int* smem, int* total) {
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __restrict__ q_offsets,
                                                             const int32_t* __restrict__ ctx_lens,
-                                                            int32_t S, PlanConfig c, WorkLists w) {
+                                                            const int32_t* __restrict__ block_tables,
+                                                            int32_t max_blocks, int32_t S, PlanConfig c,
+                                                            WorkLists w) {
   __shared__ int smem[kPlanThreads];
   if (threadIdx.x < 64) w.zero_line[threadIdx.x] = 0u;
   int row_carry = 0, item_carry = 0, tile_carry = 0;
@@ -210,6 +214,14 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
     row_carry += tot_rows;
     item_carry += tot_items;
     tile_carry += tot_tiles;
+  }
+  // Second pass, all threads: the id of each item's first block, so that the row kernel can
+  // request its first K/V block as soon as it has read the item record.
+  __syncthreads();
+  for (int it = (int)threadIdx.x; it < item_carry; it += kPlanThreads) {
+    const int4 rec = w.item_rec[it];
+    const int b0 = (rec.w & 0xffff) * c.part_tokens / kBlockSize;
+    w.item_blk0[it] = block_tables[(int64_t)rec.x * max_blocks + b0];
   }
 }
 
@@ -337,7 +349,7 @@ extern "C" int attn_mixed_batch(const void* q, void* out, const dsv_kv_pool* poo
   {
     EventScope ev(DSV_KERNEL_PLAN, stream);
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, q_offsets, ctx_lens,
-                       num_seqs, cfg, w);
+                       block_tables, max_blocks_per_seq, num_seqs, cfg, w);
     if ((rc = launch_status())) return rc;
   }
   if (n.tiles) {

@@ -41,6 +41,7 @@ struct WorkLists {
   int32_t* tile_seq;       // [tiles]
   int32_t* tile_q0;        // [tiles] first new-token index j of the tile
   uint32_t* zero_line;     // 256 bytes of zeros (stands in for V rows that must not be read)
+  int32_t* item_blk0;      // [items] pool block id of the item's first block
   float*   part_acc;       // [items][Hq][D]  unnormalised partial outputs
   float*   part_ml;        // [items][Hq][2]  running max (log2 domain) and sum
 };

@@ -114,6 +114,7 @@ __global__ __launch_bounds__(512) void rows_kernel(RowsParams prm) {
 
   const int item = blockIdx.x;
   const int4 rec = prm.w.item_rec[item];         // {seq, qtok, ctx, part | nparts << 16}
+  const int bid0 = prm.w.item_blk0[item];        // id of the partition's first block
   const int qtok = rec.y;
   const int ctx = rec.z;
   const int part = rec.w & 0xffff;
@@ -149,8 +150,7 @@ __global__ __launch_bounds__(512) void rows_kernel(RowsParams prm) {
   const uint32_t tok_stride = (uint32_t)a.Hkv * D;          // elements between token slots
   const int64_t blk_elems = (int64_t)kBlockSize * tok_stride;
   const uint16_t* const zero_line = reinterpret_cast<const uint16_t*>(prm.w.zero_line);
-  auto issue_block = [&](int b, int slot) {
-    const int bid = __builtin_amdgcn_readlane(tab_vec, b - b0);
+  auto issue_block_id = [&](int bid, int b, int slot) {
     const uint16_t* kb = a.k_pool + (int64_t)bid * blk_elems + (uint32_t)kvh * D;
     const uint16_t* vb = a.v_pool + (int64_t)bid * blk_elems + (uint32_t)kvh * D;
     unsigned char* ks_base = ring + slot * Geo::SLOT_BYTES;
@@ -164,6 +164,9 @@ __global__ __launch_bounds__(512) void rows_kernel(RowsParams prm) {
       __builtin_amdgcn_global_load_lds((gbl_void_t)kp, (lds_void_t)(ks_base + i * 1024), 16, 0, 0);
       __builtin_amdgcn_global_load_lds((gbl_void_t)vp, (lds_void_t)(vs_base + i * 1024), 16, 0, 0);
     }
+  };
+  auto issue_block = [&](int b, int slot) {
+    issue_block_id(__builtin_amdgcn_readlane(tab_vec, b - b0), b, slot);
   };
 
   // ---- per-lane state: lane (qcol, jj) owns head qcol; O^T rows are dims 16*db + 4*jj + e ----
@@ -186,10 +189,12 @@ __global__ __launch_bounds__(512) void rows_kernel(RowsParams prm) {
   for (int db = 0; db < DB; ++db)
     v_off[db] = ring_lds + Geo::TENSOR_BYTES + v_row * ROWB + (((2 * db + (lane % 4) / 2) ^ v_swz<D>(v_row)) * 16) + (lane % 2) * 8;
 
-  wait_vmcnt<0>();                               // q, table and item record have arrived
+  // The first block is requested at once (its id came with the item); the table slice and the
+  // query rows are only waited for where they are first used.
   const int blast = b1 - 1;
+  issue_block_id(bid0, b0, 0);
 #pragma unroll
-  for (int u = 0; u + 1 < R; ++u) issue_block(min(b0 + u, blast), u);
+  for (int u = 1; u + 1 < R; ++u) issue_block(min(b0 + u, blast), u);
 
   for (int b = b0; b < b1; ++b) {
     const int slot = (b - b0) % R;
