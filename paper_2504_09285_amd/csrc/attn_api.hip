@@ -227,33 +227,76 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
 
 // ---- split-context merge -------------------------------------------------------------------
 // Row r with n > 1 partitions: m* = max_p m_p; l* = sum_p l_p 2^(m_p-m*);
-// out = sum_p acc_p 2^(m_p-m*) / l*.   Each thread owns 4 consecutive dims of one head.
+// out = sum_p acc_p 2^(m_p-m*) / l*.
+// One workgroup per (row, group of heads); each thread owns 4 consecutive dims of one head.  The
+// (m, l) pairs of up to kMergeChunk partitions are fetched by all threads at once into LDS and
+// turned into weights there, and the partial outputs are then read with four independent loads
+// in flight per thread, so the kernel is not a chain of dependent memory round trips.
+constexpr int kMergeChunk = 64;
+
 template <int D>
 __global__ __launch_bounds__(256) void merge_kernel(AttnArgs a, WorkLists w) {
   constexpr int kThreadsPerHead = D / 4;
   constexpr int kHeadsPerBlock = 256 / kThreadsPerHead;
+  __shared__ float s_m[kHeadsPerBlock][kMergeChunk];
+  __shared__ float s_l[kHeadsPerBlock][kMergeChunk];
   const int r = blockIdx.x;
   const int np = w.row_nparts[r];
-  if (np <= 1) return;
-  const int h = blockIdx.y * kHeadsPerBlock + (int)threadIdx.x / kThreadsPerHead;
-  if (h >= a.Hq) return;
+  if (np <= 1) return;                                   // uniform for the workgroup
+  const int hl = (int)threadIdx.x / kThreadsPerHead;     // head within the block
+  const int h = blockIdx.y * kHeadsPerBlock + hl;
+  const bool h_ok = h < a.Hq;
   const int d4 = (int)threadIdx.x % kThreadsPerHead;
   const int item0 = w.row_item0[r];
   const float2* ml = reinterpret_cast<const float2*>(w.part_ml);
-  float m = -INFINITY;
-  for (int p = 0; p < np; ++p) m = fmaxf(m, ml[(int64_t)(item0 + p) * a.Hq + h].x);
-  float l = 0.f;
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   const float4* pa = reinterpret_cast<const float4*>(w.part_acc);
-  for (int p = 0; p < np; ++p) {
-    const int64_t ph = (int64_t)(item0 + p) * a.Hq + h;
-    const float2 v = ml[ph];
-    const float s = exp2f(v.x - m);
-    l += v.y * s;
-    const float4 x = pa[ph * kThreadsPerHead + d4];
-    acc.x += x.x * s; acc.y += x.y * s; acc.z += x.z * s; acc.w += x.w * s;
+
+  float m_run = -INFINITY, l_run = 0.f;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int p0 = 0; p0 < np; p0 += kMergeChunk) {
+    const int n = min(kMergeChunk, np - p0);
+    __syncthreads();
+    for (int i = (int)threadIdx.x; i < kHeadsPerBlock * n; i += 256) {
+      const int hh = i / n, p = i - hh * n;
+      const int hq = blockIdx.y * kHeadsPerBlock + hh;
+      float2 v = make_float2(-INFINITY, 0.f);
+      if (hq < a.Hq) v = ml[(int64_t)(item0 + p0 + p) * a.Hq + hq];
+      s_m[hh][p] = v.x;
+      s_l[hh][p] = v.y;
+    }
+    __syncthreads();
+    float m_new = m_run;
+    for (int p = 0; p < n; ++p) m_new = fmaxf(m_new, s_m[hl][p]);
+    const float c_old = exp2f(m_run - m_new);            // 0 on the first chunk (m_run = -inf)
+    l_run *= c_old;
+    acc.x *= c_old; acc.y *= c_old; acc.z *= c_old; acc.w *= c_old;
+    m_run = m_new;
+    if (h_ok) {
+      int p = 0;
+      for (; p + 4 <= n; p += 4) {
+        float4 x[4];
+        float sc[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          x[u] = pa[((int64_t)(item0 + p0 + p + u) * a.Hq + h) * kThreadsPerHead + d4];
+          sc[u] = exp2f(s_m[hl][p + u] - m_run);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          l_run += s_l[hl][p + u] * sc[u];
+          acc.x += x[u].x * sc[u]; acc.y += x[u].y * sc[u]; acc.z += x[u].z * sc[u]; acc.w += x[u].w * sc[u];
+        }
+      }
+      for (; p < n; ++p) {
+        const float4 x = pa[((int64_t)(item0 + p0 + p) * a.Hq + h) * kThreadsPerHead + d4];
+        const float sc = exp2f(s_m[hl][p] - m_run);
+        l_run += s_l[hl][p] * sc;
+        acc.x += x.x * sc; acc.y += x.y * sc; acc.z += x.z * sc; acc.w += x.w * sc;
+      }
+    }
   }
-  const float inv = 1.0f / l;
+  if (!h_ok) return;
+  const float inv = 1.0f / l_run;
   acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
   const int64_t o = ((int64_t)w.row_qtok[r] * a.Hq + h) * D + d4 * 4;
   if (a.out_bf16) {
