@@ -7,14 +7,13 @@
 // accumulation and an online softmax.
 //
 // Work item: (span, 64 consecutive query tokens, KV head, group of 4 query heads).  One
-// workgroup of four waves per item, one wave per SIMD; wave w takes query tokens
-// 32*(w/2)..+32 and the two query heads 2*(w%2), 2*(w%2)+1 of the group, i.e. 64 query rows.
-// Every K or V fragment read from LDS therefore feeds two MFMAs, which keeps the LDS read
-// traffic (the transpose reads of V in particular are slow) well under the MFMA time.
+// workgroup of eight waves per item, two per SIMD, so that one wave's MFMAs run while the other
+// does its softmax on the vector ALU; wave w takes query tokens 32*(w/4)..+32 of query head
+// w%4 of the group (32 query rows).  All eight share every K/V tile in LDS.
 //
-// K/V tiles of 64 tokens (four 16-token blocks gathered through the block table, one block per
-// wave) go straight from global memory into a ring of four LDS buffers with direct loads; tile
-// t+3 is requested while tile t is used.  One workgroup barrier per tile.
+// K/V tiles of 64 tokens (four 16-token blocks gathered through the block table, half a block
+// per wave) go straight from global memory into a ring of four LDS buffers with direct loads;
+// tile t+3 is requested while tile t is used.  One workgroup barrier per tile.
 //
 // The products are computed transposed, S^T = K Q^T and O^T = V^T P^T, with the 32x32x16 MFMA:
 //   - the query row is the MFMA column, so a lane owns one query row for the whole kernel: row
@@ -52,7 +51,9 @@ typedef const __attribute__((address_space(1))) void* gbl_void_t;
 
 constexpr int kTileQ = 64;        // query tokens per work item
 constexpr int kTileKV = 64;       // KV tokens per LDS tile
-constexpr int kThreads = 256;
+constexpr int kThreads = 512;
+constexpr int kWaves = kThreads / kWave;
+constexpr int NH = 1;             // query heads (32-row MFMA columns) per wave
 constexpr int kRing = 4;          // LDS tile buffers
 constexpr float kMinusBig = -1.0e30f;
 constexpr float kMaxSlack = 8.0f;
@@ -75,7 +76,7 @@ struct TileGeom {
   static constexpr int TENSOR_BYTES = kTileKV * ROWB;
   static constexpr int TILE_BYTES = 2 * TENSOR_BYTES;
   static constexpr int LDS_BYTES = kRing * TILE_BYTES;
-  static constexpr int LOADS = 2 * PPB;      // direct loads per wave per tile
+  static constexpr int LOADS = PPB;          // direct loads per wave per tile (half a block of K and of V)
 };
 
 template <int CPR> __device__ __forceinline__ int k_swz(int row) { return row & (CPR - 1); }
@@ -137,7 +138,7 @@ __device__ __forceinline__ float other_half_sum(float x) {
 }
 
 template <int D>
-__global__ __launch_bounds__(kThreads, 1) void prefill_tiles_kernel(TilesParams prm) {
+__global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams prm) {
   using Geo = TileGeom<D>;
   constexpr int KS = Geo::KS, DB = Geo::DB, ROWB = Geo::ROWB, CPR = Geo::CPR, RPP = Geo::RPP, PPB = Geo::PPB;
   static_assert(KS % 4 == 0, "K fragments are fetched in groups of four");
@@ -150,8 +151,8 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_tiles_kernel(TilesParams 
   const int lane = tid % kWave;
   const int jrow = lane % 32;            // query row of the wave (MFMA column) / token row of a K sub-tile
   const int hh = lane / 32;
-  const int tg = wave / 2;               // which 32 query tokens of the tile
-  const int hp = wave % 2;               // which pair of query heads
+  const int tg = wave / 4;               // which 32 query tokens of the tile
+  const int hp = wave % 4;               // which query head of the group of four
 
   // Heaviest tiles (late tiles of late spans) first.
   const int tile = prm.num_tiles - 1 - (int)blockIdx.x;
@@ -171,12 +172,12 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_tiles_kernel(TilesParams 
   // Query fragments: B operand of S^T = K Q^T; lane (jrow, hh) holds dims 16*ks + 8*hh .. +8.
   const int jq = j0 + 32 * tg + jrow;    // new-token index of this lane's query row
   const int p_j = prefix + jq;           // its absolute position
-  bool head_ok[2];
-  int head[2];
-  uint4 qf[2][KS];
+  bool head_ok[NH];
+  int head[NH];
+  uint4 qf[NH][KS];
 #pragma unroll
-  for (int c = 0; c < 2; ++c) {
-    const int hsub = (int)blockIdx.z * 4 + hp * 2 + c;
+  for (int c = 0; c < NH; ++c) {
+    const int hsub = (int)blockIdx.z * 4 + hp * NH + c;
     head_ok[c] = hsub < prm.G && jq < q_len;
     head[c] = kvh * prm.G + (hsub < prm.G ? hsub : 0);
     const int64_t off = ((int64_t)(q0 + (jq < q_len ? jq : 0)) * a.Hq + head[c]) * D + hh * 8;
@@ -192,15 +193,17 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_tiles_kernel(TilesParams 
   const uint32_t tok_stride = (uint32_t)a.Hkv * D;
   const int ld_row = lane / CPR, ld_pos = lane % CPR;
   auto issue_tile = [&](int t) {
-    const int b = t * (kTileKV / kBlockSize) + wave;
+    const int blk_in_tile = wave / 2, half = wave % 2;         // two waves share a block
+    const int b = t * (kTileKV / kBlockSize) + blk_in_tile;
     const bool have = t < n_tiles && b < nblk;
     const int64_t base = have ? ((int64_t)table[b] * kBlockSize * tok_stride + (uint32_t)kvh * D) : 0;
-    unsigned char* kdst = smem + (t % kRing) * Geo::TILE_BYTES + wave * (kBlockSize * ROWB);
+    unsigned char* kdst = smem + (t % kRing) * Geo::TILE_BYTES + blk_in_tile * (kBlockSize * ROWB);
     unsigned char* vdst = kdst + Geo::TENSOR_BYTES;
 #pragma unroll
-    for (int i = 0; i < PPB; ++i) {
+    for (int ii = 0; ii < PPB / 2; ++ii) {
+      const int i = half * (PPB / 2) + ii;
       const int n = i * RPP + ld_row;                  // token slot in the block
-      const int row = wave * kBlockSize + n;           // row in the tile
+      const int row = blk_in_tile * kBlockSize + n;    // row in the tile
       const uint16_t* kp = a.k_pool + base + (uint32_t)n * tok_stride + ((ld_pos ^ k_swz<CPR>(row)) * 8);
       const uint16_t* vp = a.v_pool + base + (uint32_t)n * tok_stride + ((ld_pos ^ v_swz<CPR>(row)) * 8);
       if (!have) kp = zero_line + ld_pos * 8;
@@ -227,21 +230,26 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_tiles_kernel(TilesParams 
     }
   }
 
-  f32x16_t o[2][DB];
+  f32x16_t o[NH][DB];
 #pragma unroll
-  for (int c = 0; c < 2; ++c)
+  for (int c = 0; c < NH; ++c)
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[c][db][r] = 0.f;
-  float m_run[2] = {kMinusBig, kMinusBig}, l_run[2] = {0.f, 0.f};
+  float m_run[NH], l_run[NH];
+#pragma unroll
+  for (int c = 0; c < NH; ++c) {
+    m_run[c] = kMinusBig;
+    l_run[c] = 0.f;
+  }
   const float scale = a.scale_log2e;
 
-  // K Q^T of sub-tile s into sc[2] (both heads), K fragments fetched in two groups of KS/2.
-  auto qk = [&](int s, f32x16_t (&sc)[2]) {
+  // K Q^T of sub-tile s into sc, K fragments fetched in groups of four.
+  auto qk = [&](int s, f32x16_t (&sc)[NH]) {
     const uint32_t buf = (uint32_t)((s / 2) % kRing) * Geo::TILE_BYTES + (uint32_t)(s & 1) * (32 * ROWB);
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
+    for (int c = 0; c < NH; ++c)
 #pragma unroll
       for (int r = 0; r < 16; ++r) sc[c][r] = 0.f;
 #pragma unroll
@@ -252,19 +260,19 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_tiles_kernel(TilesParams 
 #pragma unroll
       for (int k = 0; k < 4; ++k)
 #pragma unroll
-        for (int c = 0; c < 2; ++c)
+        for (int c = 0; c < NH; ++c)
           sc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[k]),
                                                           __builtin_bit_cast(bf16x8_t, qf[c][g4 + k]), sc[c], 0, 0, 0);
     }
   };
   // Softmax of sub-tile s: sc -> bf16 probabilities pf[c][ks16] (B operand), updates m_run/l_run;
   // corr[c] is the factor the accumulators of head c must be multiplied with before P joins them.
-  auto softmax = [&](int s, f32x16_t (&sc)[2], uint4 (&pf)[2][2], float (&corr)[2], bool& any_corr) {
+  auto softmax = [&](int s, f32x16_t (&sc)[NH], uint4 (&pf)[NH][2], float (&corr)[NH], bool& any_corr) {
     const int T = s * 32;
     const bool need_mask = T + 31 > prefix + j0 + 32 * tg;     // wave-uniform
     any_corr = false;
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
+    for (int c = 0; c < NH; ++c) {
       if (need_mask) {
 #pragma unroll
         for (int r = 0; r < 16; ++r)
@@ -300,7 +308,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_tiles_kernel(TilesParams 
     }
   };
   // O^T += V^T P^T for sub-tile s.
-  auto pv = [&](int s, const uint4 (&pf)[2][2]) {
+  auto pv = [&](int s, const uint4 (&pf)[NH][2]) {
     const uint32_t buf = (uint32_t)((s / 2) % kRing) * Geo::TILE_BYTES + (uint32_t)(s & 1) * (32 * ROWB);
 #pragma unroll
     for (int k16 = 0; k16 < 2; ++k16) {
@@ -314,7 +322,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_tiles_kernel(TilesParams 
         for (int e = 0; e < 2; ++e) {
           const u32x4_t vv = {v0[e][0], v0[e][1], v1[e][0], v1[e][1]};
 #pragma unroll
-          for (int c = 0; c < 2; ++c)
+          for (int c = 0; c < NH; ++c)
             o[c][d2 + e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vv),
                                                                    __builtin_bit_cast(bf16x8_t, pf[c][k16]),
                                                                    o[c][d2 + e], 0, 0, 0);
@@ -322,9 +330,9 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_tiles_kernel(TilesParams 
       }
     }
   };
-  auto rescale = [&](const float (&corr)[2]) {
+  auto rescale = [&](const float (&corr)[NH]) {
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
+    for (int c = 0; c < NH; ++c)
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -338,9 +346,9 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_tiles_kernel(TilesParams 
   wait_vmcnt<2 * Geo::LOADS>();
   __builtin_amdgcn_s_barrier();
 
-  f32x16_t sc[2];
-  uint4 pf[2][2];
-  float corr[2];
+  f32x16_t sc[NH];
+  uint4 pf[NH][2];
+  float corr[NH];
   bool any_corr;
 
   for (int u = 0; u < n_tiles; ++u) {
@@ -368,7 +376,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_tiles_kernel(TilesParams 
   wait_vmcnt<0>();                       // the last (dummy) tile requests
 
 #pragma unroll
-  for (int c = 0; c < 2; ++c) {
+  for (int c = 0; c < NH; ++c) {
     const float l_tot = other_half_sum(l_run[c]);
     if (!head_ok[c]) continue;
     const float inv = 1.0f / l_tot;
