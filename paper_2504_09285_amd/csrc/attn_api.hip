@@ -169,14 +169,47 @@ __device__ int block_exclusive_scan(int v, int* smem, int* total) {
   return incl - v;
 }
 
+// Sort key of a tile: bucket 0 holds the tiles with the most KV tiles to visit.
+constexpr int kTileBuckets = 4 * kPlanThreads;
+__device__ __forceinline__ int tile_bucket(int ctx, int q_len, int t, const PlanConfig& c) {
+  const int kv_end = min(ctx, ctx - q_len + (t + 1) * c.tile_tokens);
+  const int n = (kv_end + c.tile_tokens - 1) / c.tile_tokens;
+  return kTileBuckets - 1 - min(n, kTileBuckets - 1);
+}
+
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __restrict__ q_offsets,
                                                             const int32_t* __restrict__ ctx_lens,
                                                             const int32_t* __restrict__ block_tables,
                                                             int32_t max_blocks, int32_t S, PlanConfig c,
                                                             WorkLists w) {
   __shared__ int smem[kPlanThreads];
+  __shared__ int tile_slot[kTileBuckets];
   if (threadIdx.x < 64) w.zero_line[threadIdx.x] = 0u;
-  int row_carry = 0, item_carry = 0, tile_carry = 0;
+
+  // Tiles are listed heaviest first (most KV tiles to visit), so that the MFMA kernel's
+  // workgroups, dispatched in list order, leave no long tile for the end: a counting sort on
+  // the KV tile count.  The order of equal keys is left to the atomics; it affects nothing but
+  // the dispatch order.
+  for (int b = (int)threadIdx.x; b < kTileBuckets; b += kPlanThreads) tile_slot[b] = 0;
+  __syncthreads();
+  for (int i = (int)threadIdx.x; i < S; i += kPlanThreads) {
+    const int q_len = q_offsets[i + 1] - q_offsets[i], ctx = ctx_lens[i];
+    if (q_len > 0 && !on_row_path(q_len, c)) {
+      const int n_tiles = (q_len + c.tile_tokens - 1) / c.tile_tokens;
+      for (int t = 0; t < n_tiles; ++t) atomicAdd(&tile_slot[tile_bucket(ctx, q_len, t, c)], 1);
+    }
+  }
+  __syncthreads();
+  {
+    constexpr int kPer = kTileBuckets / kPlanThreads;
+    int cnt[kPer], sum = 0, total;
+    for (int k = 0; k < kPer; ++k) { cnt[k] = tile_slot[threadIdx.x * kPer + k]; sum += cnt[k]; }
+    int ex = block_exclusive_scan(sum, smem, &total);
+    for (int k = 0; k < kPer; ++k) { tile_slot[threadIdx.x * kPer + k] = ex; ex += cnt[k]; }
+    __syncthreads();
+  }
+
+  int row_carry = 0, item_carry = 0;
   for (int base = 0; base < S; base += kPlanThreads) {
     const int i = base + (int)threadIdx.x;
     int q0 = 0, q_len = 0, ctx = 0, n_rows = 0, n_items = 0, n_tiles = 0;
@@ -191,10 +224,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
         n_tiles = (q_len + c.tile_tokens - 1) / c.tile_tokens;
       }
     }
-    int tot_rows, tot_items, tot_tiles;
+    int tot_rows, tot_items;
     int row0 = row_carry + block_exclusive_scan(n_rows, smem, &tot_rows);
     int item0 = item_carry + block_exclusive_scan(n_items, smem, &tot_items);
-    int tile0 = tile_carry + block_exclusive_scan(n_tiles, smem, &tot_tiles);
     for (int j = 0; j < n_rows; ++j) {
       const int ctx_eff = ctx - q_len + j + 1;
       const int np = parts_of(ctx_eff, c);
@@ -208,12 +240,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
       item0 += np;
     }
     for (int t = 0; t < n_tiles; ++t) {
-      w.tile_seq[tile0 + t] = i;
-      w.tile_q0[tile0 + t] = t * c.tile_tokens;
+      const int pos = atomicAdd(&tile_slot[tile_bucket(ctx, q_len, t, c)], 1);
+      w.tile_seq[pos] = i;
+      w.tile_q0[pos] = t * c.tile_tokens;
     }
     row_carry += tot_rows;
     item_carry += tot_items;
-    tile_carry += tot_tiles;
   }
   // Second pass, all threads: the id of each item's first block, so that the row kernel can
   // request its first K/V block as soon as it has read the item record.

@@ -92,30 +92,38 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// LDS reads of data written by the direct loads, issued as a group and waited for together.
-__device__ __forceinline__ void lds_read_b128x4(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3,
+// LDS reads of data written by the direct loads.  A stage issues all its fragment reads back to
+// back (lds_issue4_*), waits once (lds_wait_all) and then passes every result through
+// lds_ready4(): an empty asm that redefines the registers, so that no consumer can be scheduled
+// ahead of the wait while the read results are still in flight.
+__device__ __forceinline__ void lds_issue4_b128(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3,
                                                 u32x4_t& v0, u32x4_t& v1, u32x4_t& v2, u32x4_t& v3) {
   asm volatile(
       "ds_read_b128 %0, %4\n\t"
       "ds_read_b128 %1, %5\n\t"
       "ds_read_b128 %2, %6\n\t"
-      "ds_read_b128 %3, %7\n\t"
-      "s_waitcnt lgkmcnt(0)"
+      "ds_read_b128 %3, %7"
       : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3)
       : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
       : "memory");
 }
-__device__ __forceinline__ void lds_read_tr4(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3,
-                                             u32x2_t& v0, u32x2_t& v1, u32x2_t& v2, u32x2_t& v3) {
+__device__ __forceinline__ void lds_issue4_tr(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3,
+                                              u32x2_t& v0, u32x2_t& v1, u32x2_t& v2, u32x2_t& v3) {
   asm volatile(
       "ds_read_b64_tr_b16 %0, %4\n\t"
       "ds_read_b64_tr_b16 %1, %5\n\t"
       "ds_read_b64_tr_b16 %2, %6\n\t"
-      "ds_read_b64_tr_b16 %3, %7\n\t"
-      "s_waitcnt lgkmcnt(0)"
+      "ds_read_b64_tr_b16 %3, %7"
       : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3)
       : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
       : "memory");
+}
+__device__ __forceinline__ void lds_wait_all() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void lds_ready4(u32x4_t& v0, u32x4_t& v1, u32x4_t& v2, u32x4_t& v3) {
+  asm volatile("" : "+v"(v0), "+v"(v1), "+v"(v2), "+v"(v3));
+}
+__device__ __forceinline__ void lds_ready4(u32x2_t& v0, u32x2_t& v1, u32x2_t& v2, u32x2_t& v3) {
+  asm volatile("" : "+v"(v0), "+v"(v1), "+v"(v2), "+v"(v3));
 }
 
 // Exchange with lane ^ 32: after v_permlane32_swap a holds the value of the lower half-wave
@@ -154,15 +162,17 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
   const int tg = wave / 4;               // which 32 query tokens of the tile
   const int hp = wave % 4;               // which query head of the group of four
 
-  // Heaviest tiles (late tiles of late spans) first.
-  const int tile = prm.num_tiles - 1 - (int)blockIdx.x;
+  // Workgroups are dispatched in blockIdx.x order and dealt round-robin to the eight XCDs: the
+  // KV head is the fastest index, so the heaviest tiles (the list is sorted) of every head start
+  // first and (with eight KV heads) all tiles of one head share one XCD's L2.
+  const int kvh = (int)blockIdx.x % a.Hkv;
+  const int tile = (int)blockIdx.x / a.Hkv;
   const int seq = prm.w.tile_seq[tile];
   const int j0 = prm.w.tile_q0[tile];
   const int q0 = a.q_offsets[seq];
   const int q_len = a.q_offsets[seq + 1] - q0;
   const int ctx = a.ctx_lens[seq];
   const int prefix = ctx - q_len;
-  const int kvh = blockIdx.y;
   const int32_t* table = a.block_tables + (int64_t)seq * a.max_blocks;
   const int nblk = (ctx + kBlockSize - 1) / kBlockSize;
   const int kv_end = min(ctx, prefix + j0 + kTileQ);          // exclusive: last visible token + 1
@@ -245,24 +255,60 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
   }
   const float scale = a.scale_log2e;
 
-  // K Q^T of sub-tile s into sc, K fragments fetched in groups of four.
-  auto qk = [&](int s, f32x16_t (&sc)[NH]) {
-    const uint32_t buf = (uint32_t)((s / 2) % kRing) * Geo::TILE_BYTES + (uint32_t)(s & 1) * (32 * ROWB);
+  // Matrix-core part of a stage: S^T = K Q^T for sub-tile s into sc and, if with_pv, O^T += V^T P^T
+  // for sub-tile s-1 (with the probabilities in pf).  All fragment reads are issued first and
+  // waited for once; the MFMAs that follow form one straight-line block with the softmax, so
+  // the compiler is free to interleave them with vector-ALU work.
+  auto mfma_stage = [&](int s, bool with_pv, f32x16_t (&sc)[NH], const uint4 (&pf)[NH][2]) {
+    const uint32_t kbuf = (uint32_t)((s / 2) % kRing) * Geo::TILE_BYTES + (uint32_t)(s & 1) * (32 * ROWB);
+    const int sv = with_pv ? s - 1 : 0;
+    const uint32_t vbuf = (uint32_t)((sv / 2) % kRing) * Geo::TILE_BYTES + (uint32_t)(sv & 1) * (32 * ROWB);
+    u32x4_t kf[KS];
+    u32x2_t v0[2][DB], v1[2][DB];          // [k16][db]: tokens +0..3 and +8..11 of the fragment
+#pragma unroll
+    for (int g4 = 0; g4 < KS; g4 += 4)
+      lds_issue4_b128(k_off[g4] + kbuf, k_off[g4 + 1] + kbuf, k_off[g4 + 2] + kbuf, k_off[g4 + 3] + kbuf,
+                      kf[g4], kf[g4 + 1], kf[g4 + 2], kf[g4 + 3]);
+    if (with_pv) {
+#pragma unroll
+      for (int k16 = 0; k16 < 2; ++k16)
+#pragma unroll
+        for (int d2 = 0; d2 < DB; d2 += 2) {
+          const uint32_t base = vbuf + (k16 * 16) * ROWB;
+          lds_issue4_tr(v_off[d2] + base, v_off[d2] + base + 8 * ROWB, v_off[d2 + 1] + base,
+                        v_off[d2 + 1] + base + 8 * ROWB, v0[k16][d2], v1[k16][d2], v0[k16][d2 + 1], v1[k16][d2 + 1]);
+        }
+    }
+    lds_wait_all();
+#pragma unroll
+    for (int g4 = 0; g4 < KS; g4 += 4) lds_ready4(kf[g4], kf[g4 + 1], kf[g4 + 2], kf[g4 + 3]);
+    if (with_pv) {
+#pragma unroll
+      for (int k16 = 0; k16 < 2; ++k16)
+#pragma unroll
+        for (int d2 = 0; d2 < DB; d2 += 2) lds_ready4(v0[k16][d2], v1[k16][d2], v0[k16][d2 + 1], v1[k16][d2 + 1]);
+    }
 #pragma unroll
     for (int c = 0; c < NH; ++c)
 #pragma unroll
       for (int r = 0; r < 16; ++r) sc[c][r] = 0.f;
 #pragma unroll
-    for (int g4 = 0; g4 < KS; g4 += 4) {
-      u32x4_t kf[4];
-      lds_read_b128x4(k_off[g4] + buf, k_off[g4 + 1] + buf, k_off[g4 + 2] + buf, k_off[g4 + 3] + buf,
-                      kf[0], kf[1], kf[2], kf[3]);
+    for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
+      for (int c = 0; c < NH; ++c)
+        sc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[ks]),
+                                                        __builtin_bit_cast(bf16x8_t, qf[c][ks]), sc[c], 0, 0, 0);
+    if (with_pv) {
 #pragma unroll
-        for (int c = 0; c < NH; ++c)
-          sc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[k]),
-                                                          __builtin_bit_cast(bf16x8_t, qf[c][g4 + k]), sc[c], 0, 0, 0);
+      for (int k16 = 0; k16 < 2; ++k16)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const u32x4_t vv = {v0[k16][db][0], v0[k16][db][1], v1[k16][db][0], v1[k16][db][1]};
+#pragma unroll
+          for (int c = 0; c < NH; ++c)
+            o[c][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vv),
+                                                               __builtin_bit_cast(bf16x8_t, pf[c][k16]), o[c][db], 0, 0, 0);
+        }
     }
   };
   // Softmax of sub-tile s: sc -> bf16 probabilities pf[c][ks16] (B operand), updates m_run/l_run;
@@ -307,29 +353,6 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
       }
     }
   };
-  // O^T += V^T P^T for sub-tile s.
-  auto pv = [&](int s, const uint4 (&pf)[NH][2]) {
-    const uint32_t buf = (uint32_t)((s / 2) % kRing) * Geo::TILE_BYTES + (uint32_t)(s & 1) * (32 * ROWB);
-#pragma unroll
-    for (int k16 = 0; k16 < 2; ++k16) {
-#pragma unroll
-      for (int d2 = 0; d2 < DB; d2 += 2) {
-        u32x2_t v0[2], v1[2];
-        const uint32_t base = buf + (k16 * 16) * ROWB;
-        lds_read_tr4(v_off[d2] + base, v_off[d2] + base + 8 * ROWB, v_off[d2 + 1] + base,
-                     v_off[d2 + 1] + base + 8 * ROWB, v0[0], v1[0], v0[1], v1[1]);
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          const u32x4_t vv = {v0[e][0], v0[e][1], v1[e][0], v1[e][1]};
-#pragma unroll
-          for (int c = 0; c < NH; ++c)
-            o[c][d2 + e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vv),
-                                                                   __builtin_bit_cast(bf16x8_t, pf[c][k16]),
-                                                                   o[c][d2 + e], 0, 0, 0);
-        }
-      }
-    }
-  };
   auto rescale = [&](const float (&corr)[NH]) {
 #pragma unroll
     for (int c = 0; c < NH; ++c)
@@ -352,27 +375,49 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
   bool any_corr;
 
   for (int u = 0; u < n_tiles; ++u) {
-    // Sub-tile 2u: scores, then V^T P^T of the previous sub-tile (previous tile) on the matrix
-    // cores while the vector ALU does this sub-tile's softmax.
-    qk(2 * u, sc);
-    if (u > 0) pv(2 * u - 1, pf);
+    // Sub-tile 2u: its scores and the V^T P^T of the previous sub-tile (previous tile) go to the
+    // matrix cores, then the vector ALU does this sub-tile's softmax.
+    mfma_stage(2 * u, u > 0, sc, pf);
     softmax(2 * u, sc, pf, corr, any_corr);
     if (__any(any_corr)) rescale(corr);
     // Sub-tile 2u+1.
-    qk(2 * u + 1, sc);
-    pv(2 * u, pf);
+    mfma_stage(2 * u + 1, true, sc, pf);
     softmax(2 * u + 1, sc, pf, corr, any_corr);
     if (__any(any_corr)) rescale(corr);
 
     // Tile u+1 must be complete before the next iteration (tile u+2 may still be in flight);
     // every wave is past its last read of tile u-1, whose buffer now takes tile u+3.
     // (A bare s_barrier: __syncthreads() would add a fence that drains every load in flight.
-    // Each wave has waited for its own loads, and LDS reads complete inside their asm groups.)
+    // Each wave has waited for its own loads, and LDS reads complete before the MFMAs start.)
     wait_vmcnt<Geo::LOADS>();
     __builtin_amdgcn_s_barrier();
     issue_tile(u + 3);
   }
-  pv(NS - 1, pf);
+  // V^T P^T of the last sub-tile.
+  {
+    const int s = NS - 1;
+    const uint32_t vbuf = (uint32_t)((s / 2) % kRing) * Geo::TILE_BYTES + (uint32_t)(s & 1) * (32 * ROWB);
+#pragma unroll
+    for (int k16 = 0; k16 < 2; ++k16)
+#pragma unroll
+      for (int d2 = 0; d2 < DB; d2 += 2) {
+        u32x2_t v0[2], v1[2];
+        const uint32_t base = vbuf + (k16 * 16) * ROWB;
+        lds_issue4_tr(v_off[d2] + base, v_off[d2] + base + 8 * ROWB, v_off[d2 + 1] + base,
+                      v_off[d2 + 1] + base + 8 * ROWB, v0[0], v1[0], v0[1], v1[1]);
+        lds_wait_all();
+        lds_ready4(v0[0], v1[0], v0[1], v1[1]);
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const u32x4_t vv = {v0[e][0], v0[e][1], v1[e][0], v1[e][1]};
+#pragma unroll
+          for (int c = 0; c < NH; ++c)
+            o[c][d2 + e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vv),
+                                                                   __builtin_bit_cast(bf16x8_t, pf[c][k16]),
+                                                                   o[c][d2 + e], 0, 0, 0);
+        }
+      }
+  }
   wait_vmcnt<0>();                       // the last (dummy) tile requests
 
 #pragma unroll
@@ -419,7 +464,7 @@ int launch_prefill_tiles(const AttnArgs& a, const WorkLists& w, const PlanConfig
                          const PlanCounts& n, hipStream_t stream) {
   if (cfg.tile_tokens != kTileQ) return DSV_E_UNSUPPORTED;
   TilesParams prm{a, w, (int32_t)n.tiles, a.Hq / a.Hkv};
-  dim3 grid((unsigned)n.tiles, (unsigned)a.Hkv, (unsigned)ceil_div(prm.G, 4));
+  dim3 grid((unsigned)(n.tiles * a.Hkv), 1u, (unsigned)ceil_div(prm.G, 4));
   if (a.D == 128) return launch_t<128>(prm, grid, stream);
   if (a.D == 64) return launch_t<64>(prm, grid, stream);
   return DSV_E_UNSUPPORTED;
