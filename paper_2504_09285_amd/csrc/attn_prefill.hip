@@ -193,33 +193,66 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
     const int64_t off = ((int64_t)(q0 + (jq < q_len ? jq : 0)) * a.Hq + head[c]) * D + hh * 8;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      qf[c][ks] = make_uint4(0u, 0u, 0u, 0u);
-      if (head_ok[c]) qf[c][ks] = *reinterpret_cast<const uint4*>(a.q + off + ks * 16);
+      // Unconditional (the address is clamped to a valid row), so that all loads are in flight
+      // together; rows that do not exist are zeroed afterwards.
+      qf[c][ks] = *reinterpret_cast<const uint4*>(a.q + off + ks * 16);
+      if (!head_ok[c]) qf[c][ks] = make_uint4(0u, 0u, 0u, 0u);
     }
   }
 
-  // ---- direct global->LDS loads: wave w fetches block 4t+w of tile t (K and V) ----
-  const uint16_t* const zero_line = reinterpret_cast<const uint16_t*>(prm.w.zero_line);
-  const uint32_t tok_stride = (uint32_t)a.Hkv * D;
-  const int ld_row = lane / CPR, ld_pos = lane % CPR;
-  auto issue_tile = [&](int t) {
-    const int blk_in_tile = wave / 2, half = wave % 2;         // two waves share a block
-    const int b = t * (kTileKV / kBlockSize) + blk_in_tile;
-    const bool have = t < n_tiles && b < nblk;
-    const int64_t base = have ? ((int64_t)table[b] * kBlockSize * tok_stride + (uint32_t)kvh * D) : 0;
-    unsigned char* kdst = smem + (t % kRing) * Geo::TILE_BYTES + blk_in_tile * (kBlockSize * ROWB);
-    unsigned char* vdst = kdst + Geo::TENSOR_BYTES;
+  // ---- direct global->LDS loads: waves 2i and 2i+1 fetch one half each of block 4t+i of tile t ----
+  // The block id comes from the table by a scalar load (constant address space: the table is
+  // not written while the kernel runs), requested one tile ahead of its use, so it never queues
+  // behind, or waits for, the vector-memory tile requests.  Everything per lane is a 32-bit
+  // offset fixed for the whole kernel; per tile only the scalar block base changes.
+  typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+  const const_i32_ptr ctable = (const_i32_ptr)(uintptr_t)table;
+  const unsigned char* const zero_line = reinterpret_cast<const unsigned char*>(prm.w.zero_line);
+  const uint32_t tok_stride = (uint32_t)a.Hkv * D;             // elements between tokens of a block
+  const int blk_in_tile = wave / 2, half = wave % 2;
+  uint32_t k_src[PPB / 2], v_src[PPB / 2];                     // byte offsets from the block's head slice
+  int slot_n[PPB / 2];                                         // token slot in the block
 #pragma unroll
-    for (int ii = 0; ii < PPB / 2; ++ii) {
-      const int i = half * (PPB / 2) + ii;
-      const int n = i * RPP + ld_row;                  // token slot in the block
-      const int row = blk_in_tile * kBlockSize + n;    // row in the tile
-      const uint16_t* kp = a.k_pool + base + (uint32_t)n * tok_stride + ((ld_pos ^ k_swz<CPR>(row)) * 8);
-      const uint16_t* vp = a.v_pool + base + (uint32_t)n * tok_stride + ((ld_pos ^ v_swz<CPR>(row)) * 8);
-      if (!have) kp = zero_line + ld_pos * 8;
-      if (!have || b * kBlockSize + n >= ctx) vp = zero_line + ld_pos * 8;
-      __builtin_amdgcn_global_load_lds((gbl_void_t)kp, (lds_void_t)(kdst + i * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gbl_void_t)vp, (lds_void_t)(vdst + i * 1024), 16, 0, 0);
+  for (int ii = 0; ii < PPB / 2; ++ii) {
+    const int n = (half * (PPB / 2) + ii) * RPP + lane / CPR;
+    const int row = blk_in_tile * kBlockSize + n;              // row in the tile
+    const int pos = lane % CPR;
+    slot_n[ii] = n;
+    k_src[ii] = ((uint32_t)n * tok_stride + (uint32_t)((pos ^ k_swz<CPR>(row)) * 8)) * 2u;
+    v_src[ii] = ((uint32_t)n * tok_stride + (uint32_t)((pos ^ v_swz<CPR>(row)) * 8)) * 2u;
+  }
+  const uint32_t zero_src = (uint32_t)(lane % CPR) * 16u;
+  const unsigned char* const k_head = reinterpret_cast<const unsigned char*>(a.k_pool + (uint32_t)kvh * D);
+  const unsigned char* const v_head = reinterpret_cast<const unsigned char*>(a.v_pool + (uint32_t)kvh * D);
+  auto block_id = [&](int t) -> int {                          // -1: nothing to fetch
+    const int b = t * (kTileKV / kBlockSize) + blk_in_tile;
+    return (t < n_tiles && b < nblk) ? ctable[b] : -1;
+  };
+  auto issue_tile = [&](int t, int bid) {
+    const int b = t * (kTileKV / kBlockSize) + blk_in_tile;
+    unsigned char* kdst = smem + (t % kRing) * Geo::TILE_BYTES + blk_in_tile * (kBlockSize * ROWB) +
+                          half * (PPB / 2) * 1024;
+    unsigned char* vdst = kdst + Geo::TENSOR_BYTES;
+    const int64_t blk_bytes = (int64_t)bid * kBlockSize * tok_stride * 2;
+    if (bid >= 0 && (b + 1) * kBlockSize <= ctx) {             // whole block visible: the common case
+      const unsigned char* kb = k_head + blk_bytes;
+      const unsigned char* vb = v_head + blk_bytes;
+#pragma unroll
+      for (int ii = 0; ii < PPB / 2; ++ii) {
+        __builtin_amdgcn_global_load_lds((gbl_void_t)(kb + k_src[ii]), (lds_void_t)(kdst + ii * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gbl_void_t)(vb + v_src[ii]), (lds_void_t)(vdst + ii * 1024), 16, 0, 0);
+      }
+    } else {
+      // Past the table, or a block that straddles ctx: K may hold anything finite or not (its
+      // columns are masked), but V rows that must not be read come from the zero line.
+#pragma unroll
+      for (int ii = 0; ii < PPB / 2; ++ii) {
+        const unsigned char* kp = bid >= 0 ? k_head + blk_bytes + k_src[ii] : zero_line + zero_src;
+        const unsigned char* vp = (bid >= 0 && b * kBlockSize + slot_n[ii] < ctx) ? v_head + blk_bytes + v_src[ii]
+                                                                                   : zero_line + zero_src;
+        __builtin_amdgcn_global_load_lds((gbl_void_t)kp, (lds_void_t)(kdst + ii * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gbl_void_t)vp, (lds_void_t)(vdst + ii * 1024), 16, 0, 0);
+      }
     }
   };
 
@@ -363,11 +396,20 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
   };
 
   // ---- prologue: tiles 0..2 requested, tile 0 awaited ----
-  issue_tile(0);
-  issue_tile(1);
-  issue_tile(2);
+  issue_tile(0, block_id(0));
+  issue_tile(1, block_id(1));
+  issue_tile(2, block_id(2));
+  int next_bid = block_id(3);
   wait_vmcnt<2 * Geo::LOADS>();
   __builtin_amdgcn_s_barrier();
+  // The query fragments were requested before the tiles, so they have arrived.  Redefining them
+  // here keeps the compiler from guarding their first use inside the loop with a wait that
+  // would drain the tile requests in flight on every iteration.
+#pragma unroll
+  for (int c = 0; c < NH; ++c)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      asm volatile("" : "+v"(qf[c][ks].x), "+v"(qf[c][ks].y), "+v"(qf[c][ks].z), "+v"(qf[c][ks].w));
 
   f32x16_t sc[NH];
   uint4 pf[NH][2];
@@ -391,7 +433,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
     // Each wave has waited for its own loads, and LDS reads complete before the MFMAs start.)
     wait_vmcnt<Geo::LOADS>();
     __builtin_amdgcn_s_barrier();
-    issue_tile(u + 3);
+    issue_tile(u + 3, next_bid);
+    next_bid = block_id(u + 4);
   }
   // V^T P^T of the last sub-tile.
   {
