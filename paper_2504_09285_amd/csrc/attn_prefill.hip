@@ -37,6 +37,8 @@
 // cannot leak.
 #include "attn_internal.h"
 
+#include <type_traits>
+
 namespace dsv {
 namespace {
 
@@ -107,15 +109,17 @@ __device__ __forceinline__ void lds_issue4_b128(uint32_t a0, uint32_t a1, uint32
       : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
       : "memory");
 }
-__device__ __forceinline__ void lds_issue4_tr(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3,
-                                              u32x2_t& v0, u32x2_t& v1, u32x2_t& v2, u32x2_t& v3) {
+// Two addresses, each read at byte offsets OFF and OFF + STEP (immediates of the instruction).
+template <int OFF, int STEP>
+__device__ __forceinline__ void lds_issue4_tr(uint32_t a0, uint32_t a1, u32x2_t& v0, u32x2_t& v1, u32x2_t& v2,
+                                              u32x2_t& v3) {
   asm volatile(
-      "ds_read_b64_tr_b16 %0, %4\n\t"
-      "ds_read_b64_tr_b16 %1, %5\n\t"
-      "ds_read_b64_tr_b16 %2, %6\n\t"
-      "ds_read_b64_tr_b16 %3, %7"
+      "ds_read_b64_tr_b16 %0, %4 offset:%6\n\t"
+      "ds_read_b64_tr_b16 %1, %4 offset:%7\n\t"
+      "ds_read_b64_tr_b16 %2, %5 offset:%6\n\t"
+      "ds_read_b64_tr_b16 %3, %5 offset:%7"
       : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3)
-      : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+      : "v"(a0), "v"(a1), "n"(OFF), "n"(OFF + STEP)
       : "memory");
 }
 __device__ __forceinline__ void lds_wait_all() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
@@ -126,13 +130,24 @@ __device__ __forceinline__ void lds_ready4(u32x2_t& v0, u32x2_t& v1, u32x2_t& v2
   asm volatile("" : "+v"(v0), "+v"(v1), "+v"(v2), "+v"(v3));
 }
 
-// Exchange with lane ^ 32: after v_permlane32_swap a holds the value of the lower half-wave
-// lane and b that of the upper one, in both lanes.  Written in assembly: given the same value
-// for both operands, the compiler's builtin folds the two results into one.
+// acc + lo + hi of a packed bf16 pair.
+__device__ __forceinline__ float sum2_bf16(uint32_t pair, float acc) {
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pair), __builtin_bit_cast(bf16x2_t, 0x3f803f80u),
+                                         acc, false);
+}
+
+// Exchange with lane ^ 32: after v_permlane32_swap lo holds the value of the lower half-wave
+// lane and hi that of the upper one, in both lanes.  Given the same value for both operands
+// the compiler folds the two results into one, so the second operand is passed through an
+// empty asm that hides where it came from.
 __device__ __forceinline__ void half_swap(float x, float& lo, float& hi) {
-  lo = x;
-  hi = x;
-  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
+  uint32_t a = __float_as_uint(x), b;
+  asm("" : "=v"(b) : "0"(a));
+  typedef unsigned int u32x2v __attribute__((ext_vector_type(2)));
+  const u32x2v r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+  lo = __uint_as_float(r[0]);
+  hi = __uint_as_float(r[1]);
 }
 __device__ __forceinline__ float other_half_max(float x) {       // max with lane ^ 32
   float lo, hi;
@@ -233,26 +248,20 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
     unsigned char* kdst = smem + (t % kRing) * Geo::TILE_BYTES + blk_in_tile * (kBlockSize * ROWB) +
                           half * (PPB / 2) * 1024;
     unsigned char* vdst = kdst + Geo::TENSOR_BYTES;
-    const int64_t blk_bytes = (int64_t)bid * kBlockSize * tok_stride * 2;
-    if (bid >= 0 && (b + 1) * kBlockSize <= ctx) {             // whole block visible: the common case
-      const unsigned char* kb = k_head + blk_bytes;
-      const unsigned char* vb = v_head + blk_bytes;
+    // Past the table every lane reads the zero line.  In a block that straddles ctx, K may hold
+    // anything (its columns are masked) but V rows that must not be read come from the zero
+    // line as well.  Branch-free: selects on the source address.
+    const bool have = bid >= 0;
+    const int64_t blk_bytes = (int64_t)(have ? bid : 0) * kBlockSize * tok_stride * 2;
+    const unsigned char* kb = k_head + blk_bytes;
+    const unsigned char* vb = v_head + blk_bytes;
+    const int visible = ctx - b * kBlockSize;                  // token slots < visible may be read
 #pragma unroll
-      for (int ii = 0; ii < PPB / 2; ++ii) {
-        __builtin_amdgcn_global_load_lds((gbl_void_t)(kb + k_src[ii]), (lds_void_t)(kdst + ii * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((gbl_void_t)(vb + v_src[ii]), (lds_void_t)(vdst + ii * 1024), 16, 0, 0);
-      }
-    } else {
-      // Past the table, or a block that straddles ctx: K may hold anything finite or not (its
-      // columns are masked), but V rows that must not be read come from the zero line.
-#pragma unroll
-      for (int ii = 0; ii < PPB / 2; ++ii) {
-        const unsigned char* kp = bid >= 0 ? k_head + blk_bytes + k_src[ii] : zero_line + zero_src;
-        const unsigned char* vp = (bid >= 0 && b * kBlockSize + slot_n[ii] < ctx) ? v_head + blk_bytes + v_src[ii]
-                                                                                   : zero_line + zero_src;
-        __builtin_amdgcn_global_load_lds((gbl_void_t)kp, (lds_void_t)(kdst + ii * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((gbl_void_t)vp, (lds_void_t)(vdst + ii * 1024), 16, 0, 0);
-      }
+    for (int ii = 0; ii < PPB / 2; ++ii) {
+      const unsigned char* kp = have ? kb + k_src[ii] : zero_line + zero_src;
+      const unsigned char* vp = (have && slot_n[ii] < visible) ? vb + v_src[ii] : zero_line + zero_src;
+      __builtin_amdgcn_global_load_lds((gbl_void_t)kp, (lds_void_t)(kdst + ii * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gbl_void_t)vp, (lds_void_t)(vdst + ii * 1024), 16, 0, 0);
     }
   };
 
@@ -288,39 +297,42 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
   }
   const float scale = a.scale_log2e;
 
-  // Matrix-core part of a stage: S^T = K Q^T for sub-tile s into sc and, if with_pv, O^T += V^T P^T
-  // for sub-tile s-1 (with the probabilities in pf).  All fragment reads are issued first and
-  // waited for once; the MFMAs that follow form one straight-line block with the softmax, so
-  // the compiler is free to interleave them with vector-ALU work.
-  auto mfma_stage = [&](int s, bool with_pv, f32x16_t (&sc)[NH], const uint4 (&pf)[NH][2]) {
+  // The loop is software-pipelined over 32-token sub-tiles.  Stage s finds the scores of
+  // sub-tile s already computed and, in one basic block, gives the matrix cores the scores of
+  // sub-tile s+1 and O^T += V^T P^T of sub-tile s-1 while the vector ALU does the softmax of
+  // sub-tile s: three independent pieces of work whose instructions interleave, so that the
+  // softmax runs in the shadow of the MFMAs.  Scores and probabilities are double-buffered.
+  f32x16_t scb[2][NH];
+  uint4 pfb[2][NH][2];
+  float corr[NH];
+  bool any_corr;
+  u32x4_t kf[KS];
+  u32x2_t vf0[2][DB], vf1[2][DB];          // V^T fragments [k16][db]: tokens +0..3 and +8..11
+  auto issue_k = [&](int s) {
     const uint32_t kbuf = (uint32_t)((s / 2) % kRing) * Geo::TILE_BYTES + (uint32_t)(s & 1) * (32 * ROWB);
-    const int sv = with_pv ? s - 1 : 0;
-    const uint32_t vbuf = (uint32_t)((sv / 2) % kRing) * Geo::TILE_BYTES + (uint32_t)(sv & 1) * (32 * ROWB);
-    u32x4_t kf[KS];
-    u32x2_t v0[2][DB], v1[2][DB];          // [k16][db]: tokens +0..3 and +8..11 of the fragment
 #pragma unroll
     for (int g4 = 0; g4 < KS; g4 += 4)
       lds_issue4_b128(k_off[g4] + kbuf, k_off[g4 + 1] + kbuf, k_off[g4 + 2] + kbuf, k_off[g4 + 3] + kbuf,
                       kf[g4], kf[g4 + 1], kf[g4 + 2], kf[g4 + 3]);
-    if (with_pv) {
-#pragma unroll
-      for (int k16 = 0; k16 < 2; ++k16)
-#pragma unroll
-        for (int d2 = 0; d2 < DB; d2 += 2) {
-          const uint32_t base = vbuf + (k16 * 16) * ROWB;
-          lds_issue4_tr(v_off[d2] + base, v_off[d2] + base + 8 * ROWB, v_off[d2 + 1] + base,
-                        v_off[d2 + 1] + base + 8 * ROWB, v0[k16][d2], v1[k16][d2], v0[k16][d2 + 1], v1[k16][d2 + 1]);
-        }
-    }
-    lds_wait_all();
+  };
+  auto ready_k = [&]() {
 #pragma unroll
     for (int g4 = 0; g4 < KS; g4 += 4) lds_ready4(kf[g4], kf[g4 + 1], kf[g4 + 2], kf[g4 + 3]);
-    if (with_pv) {
+  };
+  auto issue_v = [&](int sv, auto k16_c) {
+    constexpr int k16 = decltype(k16_c)::value;
+    const uint32_t vbuf = (uint32_t)((sv / 2) % kRing) * Geo::TILE_BYTES + (uint32_t)(sv & 1) * (32 * ROWB);
 #pragma unroll
-      for (int k16 = 0; k16 < 2; ++k16)
+    for (int d2 = 0; d2 < DB; d2 += 2)
+      lds_issue4_tr<k16 * 16 * ROWB, 8 * ROWB>(v_off[d2] + vbuf, v_off[d2 + 1] + vbuf, vf0[k16][d2], vf1[k16][d2],
+                                               vf0[k16][d2 + 1], vf1[k16][d2 + 1]);
+  };
+  auto ready_v = [&](int k16) {
 #pragma unroll
-        for (int d2 = 0; d2 < DB; d2 += 2) lds_ready4(v0[k16][d2], v1[k16][d2], v0[k16][d2 + 1], v1[k16][d2 + 1]);
-    }
+    for (int d2 = 0; d2 < DB; d2 += 2) lds_ready4(vf0[k16][d2], vf1[k16][d2], vf0[k16][d2 + 1], vf1[k16][d2 + 1]);
+  };
+  // S^T = K Q^T from the K fragments in kf.
+  auto qk = [&](f32x16_t (&sc)[NH]) {
 #pragma unroll
     for (int c = 0; c < NH; ++c)
 #pragma unroll
@@ -331,52 +343,40 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
       for (int c = 0; c < NH; ++c)
         sc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[ks]),
                                                         __builtin_bit_cast(bf16x8_t, qf[c][ks]), sc[c], 0, 0, 0);
-    if (with_pv) {
+  };
+  // O^T += V^T P^T from the V^T fragments in vf0 / vf1.
+  auto pv = [&](const uint4 (&pf)[NH][2], int k16) {
 #pragma unroll
-      for (int k16 = 0; k16 < 2; ++k16)
+    for (int db = 0; db < DB; ++db) {
+      const u32x4_t vv = {vf0[k16][db][0], vf0[k16][db][1], vf1[k16][db][0], vf1[k16][db][1]};
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const u32x4_t vv = {v0[k16][db][0], v0[k16][db][1], v1[k16][db][0], v1[k16][db][1]};
-#pragma unroll
-          for (int c = 0; c < NH; ++c)
-            o[c][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vv),
-                                                               __builtin_bit_cast(bf16x8_t, pf[c][k16]), o[c][db], 0, 0, 0);
-        }
+      for (int c = 0; c < NH; ++c)
+        o[c][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vv),
+                                                           __builtin_bit_cast(bf16x8_t, pf[c][k16]), o[c][db], 0, 0, 0);
     }
   };
-  // Softmax of sub-tile s: sc -> bf16 probabilities pf[c][ks16] (B operand), updates m_run/l_run;
-  // corr[c] is the factor the accumulators of head c must be multiplied with before P joins them.
-  auto softmax = [&](int s, f32x16_t (&sc)[NH], uint4 (&pf)[NH][2], float (&corr)[NH], bool& any_corr) {
-    const int T = s * 32;
-    const bool need_mask = T + 31 > prefix + j0 + 32 * tg;     // wave-uniform
+  // Softmax of the scores in sc -> bf16 probabilities pf[c][k16] (B operand of V^T P^T),
+  // updating m_run / l_run; corr[c] is the factor the accumulators of head c must be multiplied
+  // with before these probabilities join them.
+  auto softmax = [&](f32x16_t (&sc)[NH], uint4 (&pf)[NH][2]) {
     any_corr = false;
 #pragma unroll
     for (int c = 0; c < NH; ++c) {
-      if (need_mask) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (T + (r / 4) * 8 + hh * 4 + (r % 4) > p_j) sc[c][r] = -INFINITY;
-      }
       float mx = sc[c][0];
 #pragma unroll
       for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[c][r]);
       mx = other_half_max(mx);
       // The reference value m only follows the row max when it has grown by more than
       // kMaxSlack (log2 units): probabilities may then exceed 1 by up to 2^kMaxSlack, which
-      // fp32 sums and bf16 operands hold without loss, and the 128-register rescale of the
+      // fp32 sums and bf16 operands hold without loss, and the 64-register rescale of the
       // accumulators becomes rare instead of hitting some row of the wave at almost every step.
       const float m_cand = mx * scale;
       const float m_new = m_cand > m_run[c] + kMaxSlack ? m_cand : m_run[c];
       corr[c] = __builtin_amdgcn_exp2f(m_run[c] - m_new);
       any_corr |= m_new != m_run[c];
       m_run[c] = m_new;
-      float ps = 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        sc[c][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[c][r], scale, -m_new));
-        ps += sc[c][r];
-      }
-      l_run[c] = l_run[c] * corr[c] + ps;
+      for (int r = 0; r < 16; ++r) sc[c][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[c][r], scale, -m_new));
 #pragma unroll
       for (int k16 = 0; k16 < 2; ++k16) {
         pf[c][k16].x = pack_bf16(sc[c][8 * k16 + 0], sc[c][8 * k16 + 1]);
@@ -384,6 +384,17 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
         pf[c][k16].z = pack_bf16(sc[c][8 * k16 + 4], sc[c][8 * k16 + 5]);
         pf[c][k16].w = pack_bf16(sc[c][8 * k16 + 6], sc[c][8 * k16 + 7]);
       }
+      // Row sum over the rounded probabilities (the values V^T P^T really uses), two per
+      // instruction: a bf16 dot product with (1, 1).
+      float ps = l_run[c] * corr[c];
+#pragma unroll
+      for (int k16 = 0; k16 < 2; ++k16) {
+        ps = sum2_bf16(pf[c][k16].x, ps);
+        ps = sum2_bf16(pf[c][k16].y, ps);
+        ps = sum2_bf16(pf[c][k16].z, ps);
+        ps = sum2_bf16(pf[c][k16].w, ps);
+      }
+      l_run[c] = ps;
     }
   };
   auto rescale = [&](const float (&corr)[NH]) {
@@ -393,6 +404,59 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[c][db][r] *= corr[c];
+  };
+  // Stage s; CUR = s % 2 selects the buffers.  On entry scb[CUR] holds S^T of sub-tile s and
+  // pfb[CUR ^ 1] the probabilities of sub-tile s-1.
+  auto stage = [&](int s, auto cur_c, auto with_pv_c) {
+    constexpr int CUR = decltype(cur_c)::value;
+    constexpr bool with_pv = decltype(with_pv_c)::value;
+    issue_k(s + 1);
+    if constexpr (with_pv) {
+      issue_v(s - 1, std::integral_constant<int, 0>{});
+      issue_v(s - 1, std::integral_constant<int, 1>{});
+    }
+    lds_wait_all();
+    ready_k();
+    if constexpr (with_pv) {
+      ready_v(0);
+      ready_v(1);
+    }
+    // Only sub-tiles that reach past some row's own position need the causal mask (a
+    // wave-uniform branch, so the unmasked path pays one scalar compare).
+    if (s * 32 + 31 > prefix + j0 + 32 * tg) {
+#pragma unroll
+      for (int c = 0; c < NH; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (s * 32 + (r / 4) * 8 + hh * 4 + (r % 4) > p_j) scb[CUR][c][r] = -INFINITY;
+    }
+    // The accumulators take the correction found by the previous stage's softmax before that
+    // stage's probabilities join them (a rare, wave-uniform branch kept out of the block below).
+    if constexpr (with_pv) {
+      if (__any(any_corr)) rescale(corr);
+    }
+    qk(scb[CUR ^ 1]);
+    if constexpr (with_pv) {
+      pv(pfb[CUR ^ 1], 0);
+      pv(pfb[CUR ^ 1], 1);
+    }
+    softmax(scb[CUR], pfb[CUR]);
+    // Ask the scheduler for one MFMA followed by a handful of vector-ALU instructions, repeated:
+    // the softmax then runs in the shadow of the matrix-core work of the same wave.
+#pragma unroll
+    for (int i = 0; i < (with_pv ? 2 * KS : KS); ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                      // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x402, with_pv ? 6 : 12, 0);       // VALU or transcendental
+    }
+    // The probabilities are pinned to this block (an empty asm that "uses" them): otherwise
+    // the compiler sinks the exponentials to their first use, past the next stage's branches,
+    // where no MFMA is left to hide them.
+#pragma unroll
+    for (int c = 0; c < NH; ++c)
+#pragma unroll
+      for (int k16 = 0; k16 < 2; ++k16)
+        asm volatile("" : "+v"(pfb[CUR][c][k16].x), "+v"(pfb[CUR][c][k16].y), "+v"(pfb[CUR][c][k16].z),
+                          "+v"(pfb[CUR][c][k16].w));
   };
 
   // ---- prologue: tiles 0..2 requested, tile 0 awaited ----
@@ -411,56 +475,43 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
     for (int ks = 0; ks < KS; ++ks)
       asm volatile("" : "+v"(qf[c][ks].x), "+v"(qf[c][ks].y), "+v"(qf[c][ks].z), "+v"(qf[c][ks].w));
 
-  f32x16_t sc[NH];
-  uint4 pf[NH][2];
-  float corr[NH];
-  bool any_corr;
-
-  for (int u = 0; u < n_tiles; ++u) {
-    // Sub-tile 2u: its scores and the V^T P^T of the previous sub-tile (previous tile) go to the
-    // matrix cores, then the vector ALU does this sub-tile's softmax.
-    mfma_stage(2 * u, u > 0, sc, pf);
-    softmax(2 * u, sc, pf, corr, any_corr);
-    if (__any(any_corr)) rescale(corr);
-    // Sub-tile 2u+1.
-    mfma_stage(2 * u + 1, true, sc, pf);
-    softmax(2 * u + 1, sc, pf, corr, any_corr);
-    if (__any(any_corr)) rescale(corr);
-
-    // Tile u+1 must be complete before the next iteration (tile u+2 may still be in flight);
-    // every wave is past its last read of tile u-1, whose buffer now takes tile u+3.
-    // (A bare s_barrier: __syncthreads() would add a fence that drains every load in flight.
-    // Each wave has waited for its own loads, and LDS reads complete before the MFMAs start.)
+  // Barrier of tile u, between stages 2u and 2u+1: tile u+1 (first read by stage 2u+1, which
+  // fetches the K fragments of sub-tile 2u+2) must be complete, while tile u+2 may still be in
+  // flight; and every wave has finished its last read of tile u-1 (the V^T fragments of
+  // sub-tile 2u-1, in stage 2u), whose buffer now takes tile u+3.
+  // (A bare s_barrier: __syncthreads() would add a fence that drains every load in flight.
+  // Each wave has waited for its own loads, and LDS reads are complete before the MFMAs start.)
+  auto next_tile = [&](int u) {
     wait_vmcnt<Geo::LOADS>();
     __builtin_amdgcn_s_barrier();
     issue_tile(u + 3, next_bid);
     next_bid = block_id(u + 4);
+  };
+  using i0 = std::integral_constant<int, 0>;
+  using i1 = std::integral_constant<int, 1>;
+  issue_k(0);
+  lds_wait_all();
+  ready_k();
+  qk(scb[0]);
+  stage(0, i0{}, std::false_type{});
+  next_tile(0);
+  stage(1, i1{}, std::true_type{});
+  for (int u = 1; u < n_tiles; ++u) {
+    stage(2 * u, i0{}, std::true_type{});
+    next_tile(u);
+    // The last stage also scores sub-tile NS, which does not exist: its buffer holds the zeros
+    // of a tile request past the end, and the result is never used.
+    stage(2 * u + 1, i1{}, std::true_type{});
   }
   // V^T P^T of the last sub-tile.
-  {
-    const int s = NS - 1;
-    const uint32_t vbuf = (uint32_t)((s / 2) % kRing) * Geo::TILE_BYTES + (uint32_t)(s & 1) * (32 * ROWB);
-#pragma unroll
-    for (int k16 = 0; k16 < 2; ++k16)
-#pragma unroll
-      for (int d2 = 0; d2 < DB; d2 += 2) {
-        u32x2_t v0[2], v1[2];
-        const uint32_t base = vbuf + (k16 * 16) * ROWB;
-        lds_issue4_tr(v_off[d2] + base, v_off[d2] + base + 8 * ROWB, v_off[d2 + 1] + base,
-                      v_off[d2 + 1] + base + 8 * ROWB, v0[0], v1[0], v0[1], v1[1]);
-        lds_wait_all();
-        lds_ready4(v0[0], v1[0], v0[1], v1[1]);
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          const u32x4_t vv = {v0[e][0], v0[e][1], v1[e][0], v1[e][1]};
-#pragma unroll
-          for (int c = 0; c < NH; ++c)
-            o[c][d2 + e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vv),
-                                                                   __builtin_bit_cast(bf16x8_t, pf[c][k16]),
-                                                                   o[c][d2 + e], 0, 0, 0);
-        }
-      }
-  }
+  if (__any(any_corr)) rescale(corr);
+  issue_v(NS - 1, i0{});
+  issue_v(NS - 1, i1{});
+  lds_wait_all();
+  ready_v(0);
+  ready_v(1);
+  pv(pfb[1], 0);
+  pv(pfb[1], 1);
   wait_vmcnt<0>();                       // the last (dummy) tile requests
 
 #pragma unroll
