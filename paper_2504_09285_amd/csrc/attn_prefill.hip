@@ -95,7 +95,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 
 // LDS reads of data written by the direct loads.  A stage issues all its fragment reads back to
-// back (lds_issue4_*), waits once (lds_wait_all) and then passes every result through
+// back (lds_issue4_*), waits (lds_wait) and then passes every result through
 // lds_ready4(): an empty asm that redefines the registers, so that no consumer can be scheduled
 // ahead of the wait while the read results are still in flight.
 __device__ __forceinline__ void lds_issue4_b128(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3,
@@ -122,7 +122,13 @@ __device__ __forceinline__ void lds_issue4_tr(uint32_t a0, uint32_t a1, u32x2_t&
       : "v"(a0), "v"(a1), "n"(OFF), "n"(OFF + STEP)
       : "memory");
 }
-__device__ __forceinline__ void lds_wait_all() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+// Waits until at most N of the LDS reads issued so far are outstanding (they complete in order,
+// so all but the youngest N are in).  A scalar load in flight only makes the wait longer.
+template <int N>
+__device__ __forceinline__ void lds_wait() {
+  static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
 __device__ __forceinline__ void lds_ready4(u32x4_t& v0, u32x4_t& v1, u32x4_t& v2, u32x4_t& v3) {
   asm volatile("" : "+v"(v0), "+v"(v1), "+v"(v2), "+v"(v3));
 }
@@ -239,9 +245,12 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
   const uint32_t zero_src = (uint32_t)(lane % CPR) * 16u;
   const unsigned char* const k_head = reinterpret_cast<const unsigned char*>(a.k_pool + (uint32_t)kvh * D);
   const unsigned char* const v_head = reinterpret_cast<const unsigned char*>(a.v_pool + (uint32_t)kvh * D);
-  auto block_id = [&](int t) -> int {                          // -1: nothing to fetch
+  // Table entry for this wave's block of tile t, clamped into the table so that the load never
+  // needs a branch; whether the block exists is decided when the id is used, so nothing waits
+  // for the load here.
+  auto block_id = [&](int t) -> int {
     const int b = t * (kTileKV / kBlockSize) + blk_in_tile;
-    return (t < n_tiles && b < nblk) ? ctable[b] : -1;
+    return ctable[min(b, nblk - 1)];
   };
   auto issue_tile = [&](int t, int bid) {
     const int b = t * (kTileKV / kBlockSize) + blk_in_tile;
@@ -251,8 +260,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
     // Past the table every lane reads the zero line.  In a block that straddles ctx, K may hold
     // anything (its columns are masked) but V rows that must not be read come from the zero
     // line as well.  Branch-free: selects on the source address.
-    const bool have = bid >= 0;
-    const int64_t blk_bytes = (int64_t)(have ? bid : 0) * kBlockSize * tok_stride * 2;
+    const bool have = t < n_tiles && b < nblk;
+    const int64_t blk_bytes = (int64_t)bid * kBlockSize * tok_stride * 2;
     const unsigned char* kb = k_head + blk_bytes;
     const unsigned char* vb = v_head + blk_bytes;
     const int visible = ctx - b * kBlockSize;                  // token slots < visible may be read
@@ -405,22 +414,23 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[c][db][r] *= corr[c];
   };
-  // Stage s; CUR = s % 2 selects the buffers.  On entry scb[CUR] holds S^T of sub-tile s and
-  // pfb[CUR ^ 1] the probabilities of sub-tile s-1.
-  auto stage = [&](int s, auto cur_c, auto with_pv_c) {
+  // Stage s; CUR = s % 2 selects the buffers.  On entry scb[CUR] holds S^T of sub-tile s,
+  // pfb[CUR ^ 1] the probabilities of sub-tile s-1, and the K fragments of sub-tile s+1 are on
+  // their way from LDS.  The fragment reads roll along with the MFMAs that consume them: the
+  // first half of the V^T fragments is requested before the K Q^T MFMAs, the second half after
+  // them, and the K fragments of sub-tile s+2 once their registers are free, so each read has
+  // four or eight MFMAs (128-256 cycles) to arrive and no registers are double-buffered.
+  // Even stages (s = 2u) hold the barrier of tile u: see next_tile().
+  auto stage = [&](int s, auto cur_c, auto with_pv_c, auto&& tile_sync) {
     constexpr int CUR = decltype(cur_c)::value;
     constexpr bool with_pv = decltype(with_pv_c)::value;
-    issue_k(s + 1);
     if constexpr (with_pv) {
       issue_v(s - 1, std::integral_constant<int, 0>{});
-      issue_v(s - 1, std::integral_constant<int, 1>{});
+      lds_wait<2 * DB>();                // the K fragments (older than these 2*DB reads) are in
+    } else {
+      lds_wait<0>();
     }
-    lds_wait_all();
     ready_k();
-    if constexpr (with_pv) {
-      ready_v(0);
-      ready_v(1);
-    }
     // Only sub-tiles that reach past some row's own position need the causal mask (a
     // wave-uniform branch, so the unmasked path pays one scalar compare).
     if (s * 32 + 31 > prefix + j0 + 32 * tg) {
@@ -436,8 +446,27 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
       if (__any(any_corr)) rescale(corr);
     }
     qk(scb[CUR ^ 1]);
+    // The asm statements keep their order among themselves, but nothing orders them against
+    // the MFMAs except registers: an empty asm that "writes" the last operand an MFMA group
+    // reads cannot move above that group, and so anchors what follows it behind the group.
+    asm volatile("" : "+v"(kf[KS - 1]));
     if constexpr (with_pv) {
+      issue_v(s - 1, std::integral_constant<int, 1>{});
+      lds_wait<2 * DB>();                // first half of V^T in
+      ready_v(0);
       pv(pfb[CUR ^ 1], 0);
+      asm volatile("" : "+v"(vf1[0][DB - 1]));
+    }
+    if constexpr (CUR == 0) {
+      lds_wait<0>();                     // this wave's last read of tile u-1 is complete
+      tile_sync();
+      issue_k(s + 2);
+    } else {
+      issue_k(s + 2);
+      lds_wait<KS>();                    // second half of V^T in (the K reads may be in flight)
+    }
+    if constexpr (with_pv) {
+      ready_v(1);
       pv(pfb[CUR ^ 1], 1);
     }
     softmax(scb[CUR], pfb[CUR]);
@@ -455,8 +484,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
     for (int c = 0; c < NH; ++c)
 #pragma unroll
       for (int k16 = 0; k16 < 2; ++k16)
-        asm volatile("" : "+v"(pfb[CUR][c][k16].x), "+v"(pfb[CUR][c][k16].y), "+v"(pfb[CUR][c][k16].z),
-                          "+v"(pfb[CUR][c][k16].w));
+        asm volatile("" ::"v"(pfb[CUR][c][k16].x), "v"(pfb[CUR][c][k16].y), "v"(pfb[CUR][c][k16].z),
+                     "v"(pfb[CUR][c][k16].w));
   };
 
   // ---- prologue: tiles 0..2 requested, tile 0 awaited ----
@@ -475,39 +504,46 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
     for (int ks = 0; ks < KS; ++ks)
       asm volatile("" : "+v"(qf[c][ks].x), "+v"(qf[c][ks].y), "+v"(qf[c][ks].z), "+v"(qf[c][ks].w));
 
-  // Barrier of tile u, between stages 2u and 2u+1: tile u+1 (first read by stage 2u+1, which
-  // fetches the K fragments of sub-tile 2u+2) must be complete, while tile u+2 may still be in
-  // flight; and every wave has finished its last read of tile u-1 (the V^T fragments of
-  // sub-tile 2u-1, in stage 2u), whose buffer now takes tile u+3.
+  // Barrier of tile u, inside stage 2u, after the wave's last read of tile u-1 (the second half
+  // of the V^T fragments of sub-tile 2u-1) and before its first read of tile u+1 (the K
+  // fragments of sub-tile 2u+2): tile u+1 must be complete, while tile u+2 may still be in
+  // flight, and the buffer of tile u-1 now takes tile u+3.
   // (A bare s_barrier: __syncthreads() would add a fence that drains every load in flight.
-  // Each wave has waited for its own loads, and LDS reads are complete before the MFMAs start.)
-  auto next_tile = [&](int u) {
+  // Each wave has waited for its own loads and for its own LDS reads.)
+  int u_sync = 0;
+  auto next_tile = [&]() {
+    // Called with no LDS read outstanding: the block id requested a tile ago is taken over
+    // here, so that the wait the compiler puts before its first use is already satisfied and
+    // is not moved up to where fragment reads are in flight.
+    asm volatile("" : "+s"(next_bid));
     wait_vmcnt<Geo::LOADS>();
     __builtin_amdgcn_s_barrier();
-    issue_tile(u + 3, next_bid);
-    next_bid = block_id(u + 4);
+    issue_tile(u_sync + 3, next_bid);
+    next_bid = block_id(u_sync + 4);
+    ++u_sync;
   };
+  auto no_sync = [] {};
   using i0 = std::integral_constant<int, 0>;
   using i1 = std::integral_constant<int, 1>;
   issue_k(0);
-  lds_wait_all();
+  lds_wait<0>();
   ready_k();
   qk(scb[0]);
-  stage(0, i0{}, std::false_type{});
-  next_tile(0);
-  stage(1, i1{}, std::true_type{});
+  issue_k(1);
+  stage(0, i0{}, std::false_type{}, next_tile);
+  stage(1, i1{}, std::true_type{}, no_sync);
   for (int u = 1; u < n_tiles; ++u) {
-    stage(2 * u, i0{}, std::true_type{});
-    next_tile(u);
-    // The last stage also scores sub-tile NS, which does not exist: its buffer holds the zeros
-    // of a tile request past the end, and the result is never used.
-    stage(2 * u + 1, i1{}, std::true_type{});
+    stage(2 * u, i0{}, std::true_type{}, next_tile);
+    // The last stages also fetch and score sub-tiles past the end: their buffers hold the
+    // zeros of tile requests past the end, and the results are never used.
+    stage(2 * u + 1, i1{}, std::true_type{}, no_sync);
   }
+  lds_wait<0>();                         // the K fragment reads of the last stage
   // V^T P^T of the last sub-tile.
   if (__any(any_corr)) rescale(corr);
   issue_v(NS - 1, i0{});
   issue_v(NS - 1, i1{});
-  lds_wait_all();
+  lds_wait<0>();
   ready_v(0);
   ready_v(1);
   pv(pfb[1], 0);
