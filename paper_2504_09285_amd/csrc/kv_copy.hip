@@ -3,7 +3,11 @@
 // once and written once with 16-byte accesses, a wave covering 1 KiB of contiguous memory per
 // instruction on both sides.
 //
-// Work decomposition: one workgroup per (chunk, layer, K|V, tile of kTileTokens tokens).  A
+// Work decomposition: one workgroup per (chunk, layer, K|V, tile of about 16 KiB of tokens), so
+// that every thread issues its four loads and then its four stores exactly once: many small
+// one-shot workgroups measured faster here than fewer looping ones.  Loads and stores carry the
+// nontemporal hint (the data is touched once; it should not displace the attention kernels'
+// block tables and queries from L2).  A
 // token's row (all KV heads) is num_kv_heads*head_dim*2 bytes, contiguous in the chunk and in
 // the pool; consecutive tokens are contiguous in the chunk and, inside one block, in the pool.
 #include "dsv_common.h"
@@ -12,19 +16,22 @@ namespace dsv {
 namespace {
 
 constexpr int kCopyThreads = 256;
-constexpr int kTileTokens = 16;
+constexpr int kTileUnits = kCopyThreads * 4;   // 16-byte units per workgroup: one load and one store round
 constexpr int kUnroll = 4;
 
+typedef uint32_t unit_t __attribute__((ext_vector_type(4)));   // one 16-byte unit
+
 struct CopyParams {
-  uint4* pool_k;                 // layer 0 bases
-  uint4* pool_v;
-  uint4* chunk_buf;
+  unit_t* pool_k;                 // layer 0 bases
+  unit_t* pool_v;
+  unit_t* chunk_buf;
   const int32_t* block_tables;
   const dsv_chunk_desc* descs;
   int64_t layer_stride_u;        // 16-byte units between layers
   int32_t max_blocks;
   int32_t num_layers;
-  int32_t tiles_per_chunk;       // ceil(max num_tokens / kTileTokens)
+  int32_t tile_tokens;           // tokens per workgroup: about kTileUnits units, at least one token
+  int32_t tiles_per_chunk;       // ceil(max num_tokens / tile_tokens)
   int32_t upr;                   // 16-byte units per token row
   int32_t upr_shift;             // log2(upr) or -1
 };
@@ -40,18 +47,18 @@ __global__ __launch_bounds__(kCopyThreads) void kv_copy_kernel(CopyParams p) {
   const uint32_t c = cp / planes;
 
   const dsv_chunk_desc d = p.descs[c];
-  const int tok0 = (int)tile * kTileTokens;
+  const int tok0 = (int)tile * p.tile_tokens;
   if (tok0 >= d.num_tokens) return;
-  const int ntok = min(kTileTokens, d.num_tokens - tok0);
+  const int ntok = min(p.tile_tokens, d.num_tokens - tok0);
 
-  uint4* pool = ((plane & 1u) ? p.pool_v : p.pool_k) + (int64_t)(plane >> 1) * p.layer_stride_u;
-  uint4* chunk = p.chunk_buf + (d.chunk_offset >> 3) +
+  unit_t* pool = ((plane & 1u) ? p.pool_v : p.pool_k) + (int64_t)(plane >> 1) * p.layer_stride_u;
+  unit_t* chunk = p.chunk_buf + (d.chunk_offset >> 3) +
                  ((int64_t)plane * d.num_tokens + tok0) * p.upr;
   const int32_t* table = p.block_tables + (int64_t)d.seq * p.max_blocks;
 
   const int total = ntok * p.upr;                       // 16-byte units in this tile
   for (int u0 = threadIdx.x; u0 < total; u0 += kCopyThreads * kUnroll) {
-    uint4 v[kUnroll];
+    unit_t v[kUnroll];
     int64_t pool_u[kUnroll];
     int idx[kUnroll];
 #pragma unroll
@@ -68,12 +75,11 @@ __global__ __launch_bounds__(kCopyThreads) void kv_copy_kernel(CopyParams p) {
     }
 #pragma unroll
     for (int k = 0; k < kUnroll; ++k)
-      if (idx[k] < total) v[k] = PACK ? pool[pool_u[k]] : chunk[idx[k]];
+      if (idx[k] < total) v[k] = __builtin_nontemporal_load(PACK ? &pool[pool_u[k]] : &chunk[idx[k]]);
 #pragma unroll
     for (int k = 0; k < kUnroll; ++k)
       if (idx[k] < total) {
-        if (PACK) chunk[idx[k]] = v[k];
-        else      pool[pool_u[k]] = v[k];
+        __builtin_nontemporal_store(v[k], PACK ? &chunk[idx[k]] : &pool[pool_u[k]]);
       }
   }
 }
@@ -103,16 +109,17 @@ int run_copy(bool pack, const dsv_kv_pool* pool, const int32_t* block_tables, in
     if (d.num_tokens > max_tokens) max_tokens = d.num_tokens;
   }
   CopyParams p;
-  p.pool_k = static_cast<uint4*>(pool->k_base);
-  p.pool_v = static_cast<uint4*>(pool->v_base);
-  p.chunk_buf = static_cast<uint4*>(chunk_buf);
+  p.pool_k = static_cast<unit_t*>(pool->k_base);
+  p.pool_v = static_cast<unit_t*>(pool->v_base);
+  p.chunk_buf = static_cast<unit_t*>(chunk_buf);
   p.block_tables = block_tables;
   p.descs = descs;
   p.layer_stride_u = pool->num_layers > 1 ? pool->layer_stride / 8 : 0;
   p.max_blocks = max_blocks;
   p.num_layers = pool->num_layers;
-  p.tiles_per_chunk = ceil_div(max_tokens, kTileTokens);
   p.upr = (int32_t)(row_elems / 8);
+  p.tile_tokens = p.upr >= kTileUnits ? 1 : kTileUnits / p.upr;
+  p.tiles_per_chunk = ceil_div(max_tokens, p.tile_tokens);
   p.upr_shift = (p.upr & (p.upr - 1)) == 0 ? __builtin_ctz((unsigned)p.upr) : -1;
   const int64_t grid = (int64_t)num_chunks * 2 * pool->num_layers * p.tiles_per_chunk;
   if (grid > 0x7fffffffLL) return DSV_E_UNSUPPORTED;
