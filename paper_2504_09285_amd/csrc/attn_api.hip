@@ -88,8 +88,9 @@ PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl) {
     const int64_t prefix = cl[i] - q_len;
     row_tokens += (int64_t)q_len * prefix + (int64_t)q_len * (q_len + 1) / 2;
   }
-  // (Measured: 256 tokens is best for ~0.4M streamed tokens, 1024 for several millions.)
-  int64_t part = (row_tokens / 1400 + 15) / 16 * 16;
+  // (Measured: about 1100 items, i.e. 320 tokens for 0.36M streamed tokens; 1024 tokens for
+  // a million and more.)
+  int64_t part = (row_tokens / 1120 + 15) / 16 * 16;
   if (part < 256) part = 256;
   if (part > 1024) part = 1024;
   const int forced = env_int("DSV_PART_TOKENS", 0);
