@@ -56,9 +56,12 @@ constexpr int kTileKV = 64;       // KV tokens per LDS tile
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / kWave;
 constexpr int NH = 1;             // query heads (32-row MFMA columns) per wave
+constexpr int kWavesPerBlock = kWaves / (kTileKV / kBlockSize);   // waves sharing the fetch of one KV block
+constexpr int kHeadWaves = 4 / NH;                                 // waves that cover a group of four query heads
 constexpr int kRing = 4;          // LDS tile buffers
 constexpr float kMinusBig = -1.0e30f;
 constexpr float kMaxSlack = 8.0f;
+constexpr float kSumLimit = 1.0e19f;   // about 2^63: far from the fp32 range, reached only by extreme inputs
 
 struct TilesParams {
   AttnArgs a;
@@ -78,7 +81,8 @@ struct TileGeom {
   static constexpr int TENSOR_BYTES = kTileKV * ROWB;
   static constexpr int TILE_BYTES = 2 * TENSOR_BYTES;
   static constexpr int LDS_BYTES = kRing * TILE_BYTES;
-  static constexpr int LOADS = PPB;          // direct loads per wave per tile (half a block of K and of V)
+  static constexpr int PPW = PPB / kWavesPerBlock;   // pieces per wave
+  static constexpr int LOADS = 2 * PPW;      // direct loads per wave per tile (its share of a block of K and of V)
 };
 
 template <int CPR> __device__ __forceinline__ int k_swz(int row) { return row & (CPR - 1); }
@@ -167,9 +171,9 @@ __device__ __forceinline__ float other_half_sum(float x) {
 }
 
 template <int D>
-__global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams prm) {
+__global__ __launch_bounds__(kThreads, kThreads / 256) void prefill_tiles_kernel(TilesParams prm) {
   using Geo = TileGeom<D>;
-  constexpr int KS = Geo::KS, DB = Geo::DB, ROWB = Geo::ROWB, CPR = Geo::CPR, RPP = Geo::RPP, PPB = Geo::PPB;
+  constexpr int KS = Geo::KS, DB = Geo::DB, ROWB = Geo::ROWB, CPR = Geo::CPR, RPP = Geo::RPP, PPW = Geo::PPW;
   static_assert(KS % 4 == 0, "K fragments are fetched in groups of four");
   extern __shared__ __align__(16) unsigned char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
@@ -180,8 +184,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
   const int lane = tid % kWave;
   const int jrow = lane % 32;            // query row of the wave (MFMA column) / token row of a K sub-tile
   const int hh = lane / 32;
-  const int tg = wave / 4;               // which 32 query tokens of the tile
-  const int hp = wave % 4;               // which query head of the group of four
+  const int tg = wave / kHeadWaves;      // which 32 query tokens of the tile
+  const int hp = wave % kHeadWaves;      // which NH query heads of the group of four
 
   // Workgroups are dispatched in blockIdx.x order and dealt round-robin to the eight XCDs: the
   // KV head is the fastest index, so the heaviest tiles (the list is sorted) of every head start
@@ -230,12 +234,12 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
   const const_i32_ptr ctable = (const_i32_ptr)(uintptr_t)table;
   const unsigned char* const zero_line = reinterpret_cast<const unsigned char*>(prm.w.zero_line);
   const uint32_t tok_stride = (uint32_t)a.Hkv * D;             // elements between tokens of a block
-  const int blk_in_tile = wave / 2, half = wave % 2;
-  uint32_t k_src[PPB / 2], v_src[PPB / 2];                     // byte offsets from the block's head slice
-  int slot_n[PPB / 2];                                         // token slot in the block
+  const int blk_in_tile = wave / kWavesPerBlock, half = wave % kWavesPerBlock;
+  uint32_t k_src[PPW], v_src[PPW];                     // byte offsets from the block's head slice
+  int slot_n[PPW];                                         // token slot in the block
 #pragma unroll
-  for (int ii = 0; ii < PPB / 2; ++ii) {
-    const int n = (half * (PPB / 2) + ii) * RPP + lane / CPR;
+  for (int ii = 0; ii < PPW; ++ii) {
+    const int n = (half * (PPW) + ii) * RPP + lane / CPR;
     const int row = blk_in_tile * kBlockSize + n;              // row in the tile
     const int pos = lane % CPR;
     slot_n[ii] = n;
@@ -248,14 +252,14 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
   // Table entry for this wave's block of tile t, clamped into the table so that the load never
   // needs a branch; whether the block exists is decided when the id is used, so nothing waits
   // for the load here.
-  auto block_id = [&](int t) -> int {
+  auto block_id = [&](int t) __attribute__((always_inline)) -> int {
     const int b = t * (kTileKV / kBlockSize) + blk_in_tile;
     return ctable[min(b, nblk - 1)];
   };
-  auto issue_tile = [&](int t, int bid) {
+  auto issue_tile = [&](int t, int bid) __attribute__((always_inline)) {
     const int b = t * (kTileKV / kBlockSize) + blk_in_tile;
     unsigned char* kdst = smem + (t % kRing) * Geo::TILE_BYTES + blk_in_tile * (kBlockSize * ROWB) +
-                          half * (PPB / 2) * 1024;
+                          half * (PPW) * 1024;
     unsigned char* vdst = kdst + Geo::TENSOR_BYTES;
     // Past the table every lane reads the zero line.  In a block that straddles ctx, K may hold
     // anything (its columns are masked) but V rows that must not be read come from the zero
@@ -266,7 +270,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
     const unsigned char* vb = v_head + blk_bytes;
     const int visible = ctx - b * kBlockSize;                  // token slots < visible may be read
 #pragma unroll
-    for (int ii = 0; ii < PPB / 2; ++ii) {
+    for (int ii = 0; ii < PPW; ++ii) {
       const unsigned char* kp = have ? kb + k_src[ii] : zero_line + zero_src;
       const unsigned char* vp = (have && slot_n[ii] < visible) ? vb + v_src[ii] : zero_line + zero_src;
       __builtin_amdgcn_global_load_lds((gbl_void_t)kp, (lds_void_t)(kdst + ii * 1024), 16, 0, 0);
@@ -292,18 +296,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
   }
 
   f32x16_t o[NH][DB];
-#pragma unroll
-  for (int c = 0; c < NH; ++c)
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[c][db][r] = 0.f;
   float m_run[NH], l_run[NH];
-#pragma unroll
-  for (int c = 0; c < NH; ++c) {
-    m_run[c] = kMinusBig;
-    l_run[c] = 0.f;
-  }
   const float scale = a.scale_log2e;
 
   // The loop is software-pipelined over 32-token sub-tiles.  Stage s finds the scores of
@@ -317,18 +310,18 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
   bool any_corr;
   u32x4_t kf[KS];
   u32x2_t vf0[2][DB], vf1[2][DB];          // V^T fragments [k16][db]: tokens +0..3 and +8..11
-  auto issue_k = [&](int s) {
+  auto issue_k = [&](int s) __attribute__((always_inline)) {
     const uint32_t kbuf = (uint32_t)((s / 2) % kRing) * Geo::TILE_BYTES + (uint32_t)(s & 1) * (32 * ROWB);
 #pragma unroll
     for (int g4 = 0; g4 < KS; g4 += 4)
       lds_issue4_b128(k_off[g4] + kbuf, k_off[g4 + 1] + kbuf, k_off[g4 + 2] + kbuf, k_off[g4 + 3] + kbuf,
                       kf[g4], kf[g4 + 1], kf[g4 + 2], kf[g4 + 3]);
   };
-  auto ready_k = [&]() {
+  auto ready_k = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int g4 = 0; g4 < KS; g4 += 4) lds_ready4(kf[g4], kf[g4 + 1], kf[g4 + 2], kf[g4 + 3]);
   };
-  auto issue_v = [&](int sv, auto k16_c) {
+  auto issue_v = [&](int sv, auto k16_c) __attribute__((always_inline)) {
     constexpr int k16 = decltype(k16_c)::value;
     const uint32_t vbuf = (uint32_t)((sv / 2) % kRing) * Geo::TILE_BYTES + (uint32_t)(sv & 1) * (32 * ROWB);
 #pragma unroll
@@ -336,12 +329,12 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
       lds_issue4_tr<k16 * 16 * ROWB, 8 * ROWB>(v_off[d2] + vbuf, v_off[d2 + 1] + vbuf, vf0[k16][d2], vf1[k16][d2],
                                                vf0[k16][d2 + 1], vf1[k16][d2 + 1]);
   };
-  auto ready_v = [&](int k16) {
+  auto ready_v = [&](int k16) __attribute__((always_inline)) {
 #pragma unroll
     for (int d2 = 0; d2 < DB; d2 += 2) lds_ready4(vf0[k16][d2], vf1[k16][d2], vf0[k16][d2 + 1], vf1[k16][d2 + 1]);
   };
   // S^T = K Q^T from the K fragments in kf.
-  auto qk = [&](f32x16_t (&sc)[NH]) {
+  auto qk = [&](f32x16_t (&sc)[NH]) __attribute__((always_inline)) {
 #pragma unroll
     for (int c = 0; c < NH; ++c)
 #pragma unroll
@@ -354,7 +347,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
                                                         __builtin_bit_cast(bf16x8_t, qf[c][ks]), sc[c], 0, 0, 0);
   };
   // O^T += V^T P^T from the V^T fragments in vf0 / vf1.
-  auto pv = [&](const uint4 (&pf)[NH][2], int k16) {
+  auto pv = [&](const uint4 (&pf)[NH][2], int k16) __attribute__((always_inline)) {
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
       const u32x4_t vv = {vf0[k16][db][0], vf0[k16][db][1], vf1[k16][db][0], vf1[k16][db][1]};
@@ -364,38 +357,53 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
                                                            __builtin_bit_cast(bf16x8_t, pf[c][k16]), o[c][db], 0, 0, 0);
     }
   };
-  // Softmax of the scores in sc -> bf16 probabilities pf[c][k16] (B operand of V^T P^T),
-  // updating m_run / l_run; corr[c] is the factor the accumulators of head c must be multiplied
-  // with before these probabilities join them.
-  auto softmax = [&](f32x16_t (&sc)[NH], uint4 (&pf)[NH][2]) {
+  // Softmax of the scores in sc -> bf16 probabilities pf[c][k16] (B operand of V^T P^T), in one
+  // of two modes.
+  //  fast:   the reference value m of a row is the max of its first sub-tile and never changes,
+  //          so there is no per-stage row max and no accumulator rescale: probabilities may
+  //          grow far beyond 1, which fp32 sums and bf16 operands (same exponent range) hold
+  //          without loss.  If a row sum passes kSumLimit (a later score exceeds the first
+  //          sub-tile's max by about 60 in log2 units) or stops being a number, the wave
+  //          reports it and the workgroup repeats the tile in robust mode.
+  //  robust: the usual running max, except that m only follows the row max when it has grown
+  //          by more than kMaxSlack (log2 units), so that the 64-register rescale of the
+  //          accumulators is rare; corr[c] is the factor the accumulators of head c must be
+  //          multiplied with before these probabilities join them.
+  bool overflow = false;
+  auto softmax = [&](f32x16_t (&sc)[NH], uint4 (&pf)[NH][2], auto robust_c, auto first_c) __attribute__((always_inline)) {
+    constexpr bool robust = decltype(robust_c)::value;
+    constexpr bool first = decltype(first_c)::value;
     any_corr = false;
 #pragma unroll
     for (int c = 0; c < NH; ++c) {
-      float mx = sc[c][0];
+      corr[c] = 1.0f;
+      if constexpr (robust || first) {
+        float mx = sc[c][0];
 #pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[c][r]);
-      mx = other_half_max(mx);
-      // The reference value m only follows the row max when it has grown by more than
-      // kMaxSlack (log2 units): probabilities may then exceed 1 by up to 2^kMaxSlack, which
-      // fp32 sums and bf16 operands hold without loss, and the 64-register rescale of the
-      // accumulators becomes rare instead of hitting some row of the wave at almost every step.
-      const float m_cand = mx * scale;
-      const float m_new = m_cand > m_run[c] + kMaxSlack ? m_cand : m_run[c];
-      corr[c] = __builtin_amdgcn_exp2f(m_run[c] - m_new);
-      any_corr |= m_new != m_run[c];
-      m_run[c] = m_new;
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[c][r]);
+        mx = other_half_max(mx);
+        const float m_cand = mx * scale;
+        const float m_new = (first || m_cand > m_run[c] + kMaxSlack) ? m_cand : m_run[c];
+        if constexpr (robust && !first) {
+          corr[c] = __builtin_amdgcn_exp2f(m_run[c] - m_new);
+          any_corr |= m_new != m_run[c];
+        }
+        m_run[c] = m_new;
+      }
+      const float m_ref = m_run[c];
+      float t[16];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sc[c][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[c][r], scale, -m_new));
+      for (int r = 0; r < 16; ++r) t[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[c][r], scale, -m_ref));
 #pragma unroll
       for (int k16 = 0; k16 < 2; ++k16) {
-        pf[c][k16].x = pack_bf16(sc[c][8 * k16 + 0], sc[c][8 * k16 + 1]);
-        pf[c][k16].y = pack_bf16(sc[c][8 * k16 + 2], sc[c][8 * k16 + 3]);
-        pf[c][k16].z = pack_bf16(sc[c][8 * k16 + 4], sc[c][8 * k16 + 5]);
-        pf[c][k16].w = pack_bf16(sc[c][8 * k16 + 6], sc[c][8 * k16 + 7]);
+        pf[c][k16].x = pack_bf16(t[8 * k16 + 0], t[8 * k16 + 1]);
+        pf[c][k16].y = pack_bf16(t[8 * k16 + 2], t[8 * k16 + 3]);
+        pf[c][k16].z = pack_bf16(t[8 * k16 + 4], t[8 * k16 + 5]);
+        pf[c][k16].w = pack_bf16(t[8 * k16 + 6], t[8 * k16 + 7]);
       }
       // Row sum over the rounded probabilities (the values V^T P^T really uses), two per
       // instruction: a bf16 dot product with (1, 1).
-      float ps = l_run[c] * corr[c];
+      float ps = robust ? l_run[c] * corr[c] : l_run[c];
 #pragma unroll
       for (int k16 = 0; k16 < 2; ++k16) {
         ps = sum2_bf16(pf[c][k16].x, ps);
@@ -404,9 +412,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
         ps = sum2_bf16(pf[c][k16].w, ps);
       }
       l_run[c] = ps;
+      if constexpr (!robust) overflow |= !(ps < kSumLimit);
     }
   };
-  auto rescale = [&](const float (&corr)[NH]) {
+  auto rescale = [&](const float (&corr)[NH]) __attribute__((always_inline)) {
 #pragma unroll
     for (int c = 0; c < NH; ++c)
 #pragma unroll
@@ -421,9 +430,14 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
   // them, and the K fragments of sub-tile s+2 once their registers are free, so each read has
   // four or eight MFMAs (128-256 cycles) to arrive and no registers are double-buffered.
   // Even stages (s = 2u) hold the barrier of tile u: see next_tile().
-  auto stage = [&](int s, auto cur_c, auto with_pv_c, auto&& tile_sync) {
+  auto stage = [&](int s, auto cur_c, auto with_pv_c, auto robust_c, auto&& tile_sync) __attribute__((always_inline)) {
     constexpr int CUR = decltype(cur_c)::value;
     constexpr bool with_pv = decltype(with_pv_c)::value;
+    constexpr bool robust = decltype(robust_c)::value;
+    // The two waves of a SIMD (the two halves of the query tile, same head) take turns at the
+    // higher issue priority, stage by stage: left to the default arbitration the older wave is
+    // served first throughout and then idles at the tile barrier while the other finishes.
+    if (tg) __builtin_amdgcn_s_setprio(CUR); else __builtin_amdgcn_s_setprio(CUR ^ 1);
     if constexpr (with_pv) {
       issue_v(s - 1, std::integral_constant<int, 0>{});
       lds_wait<2 * DB>();                // the K fragments (older than these 2*DB reads) are in
@@ -440,9 +454,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
         for (int r = 0; r < 16; ++r)
           if (s * 32 + (r / 4) * 8 + hh * 4 + (r % 4) > p_j) scb[CUR][c][r] = -INFINITY;
     }
-    // The accumulators take the correction found by the previous stage's softmax before that
-    // stage's probabilities join them (a rare, wave-uniform branch kept out of the block below).
-    if constexpr (with_pv) {
+    // Robust mode: the accumulators take the correction found by the previous stage's softmax
+    // before that stage's probabilities join them (a rare, wave-uniform branch kept out of the
+    // block below).
+    if constexpr (with_pv && robust) {
       if (__any(any_corr)) rescale(corr);
     }
     qk(scb[CUR ^ 1]);
@@ -469,13 +484,13 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
       ready_v(1);
       pv(pfb[CUR ^ 1], 1);
     }
-    softmax(scb[CUR], pfb[CUR]);
+    softmax(scb[CUR], pfb[CUR], robust_c, std::integral_constant<bool, !with_pv>{});
     // Ask the scheduler for one MFMA followed by a handful of vector-ALU instructions, repeated:
     // the softmax then runs in the shadow of the matrix-core work of the same wave.
 #pragma unroll
     for (int i = 0; i < (with_pv ? 2 * KS : KS); ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                      // MFMA
-      __builtin_amdgcn_sched_group_barrier(0x402, with_pv ? 6 : 12, 0);       // VALU or transcendental
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                  // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x402, with_pv ? (robust ? 6 : 4) : 12, 0);    // VALU or transcendental
     }
     // The probabilities are pinned to this block (an empty asm that "uses" them): otherwise
     // the compiler sinks the exponentials to their first use, past the next stage's branches,
@@ -488,67 +503,90 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_tiles_kernel(TilesParams 
                      "v"(pfb[CUR][c][k16].w));
   };
 
-  // ---- prologue: tiles 0..2 requested, tile 0 awaited ----
-  issue_tile(0, block_id(0));
-  issue_tile(1, block_id(1));
-  issue_tile(2, block_id(2));
-  int next_bid = block_id(3);
-  wait_vmcnt<2 * Geo::LOADS>();
-  __builtin_amdgcn_s_barrier();
-  // The query fragments were requested before the tiles, so they have arrived.  Redefining them
-  // here keeps the compiler from guarding their first use inside the loop with a wait that
-  // would drain the tile requests in flight on every iteration.
-#pragma unroll
-  for (int c = 0; c < NH; ++c)
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-      asm volatile("" : "+v"(qf[c][ks].x), "+v"(qf[c][ks].y), "+v"(qf[c][ks].z), "+v"(qf[c][ks].w));
-
-  // Barrier of tile u, inside stage 2u, after the wave's last read of tile u-1 (the second half
-  // of the V^T fragments of sub-tile 2u-1) and before its first read of tile u+1 (the K
-  // fragments of sub-tile 2u+2): tile u+1 must be complete, while tile u+2 may still be in
-  // flight, and the buffer of tile u-1 now takes tile u+3.
-  // (A bare s_barrier: __syncthreads() would add a fence that drains every load in flight.
-  // Each wave has waited for its own loads and for its own LDS reads.)
-  int u_sync = 0;
-  auto next_tile = [&]() {
-    // Called with no LDS read outstanding: the block id requested a tile ago is taken over
-    // here, so that the wait the compiler puts before its first use is already satisfied and
-    // is not moved up to where fragment reads are in flight.
-    asm volatile("" : "+s"(next_bid));
-    wait_vmcnt<Geo::LOADS>();
-    __builtin_amdgcn_s_barrier();
-    issue_tile(u_sync + 3, next_bid);
-    next_bid = block_id(u_sync + 4);
-    ++u_sync;
-  };
-  auto no_sync = [] {};
   using i0 = std::integral_constant<int, 0>;
   using i1 = std::integral_constant<int, 1>;
-  issue_k(0);
-  lds_wait<0>();
-  ready_k();
-  qk(scb[0]);
-  issue_k(1);
-  stage(0, i0{}, std::false_type{}, next_tile);
-  stage(1, i1{}, std::true_type{}, no_sync);
-  for (int u = 1; u < n_tiles; ++u) {
-    stage(2 * u, i0{}, std::true_type{}, next_tile);
-    // The last stages also fetch and score sub-tiles past the end: their buffers hold the
-    // zeros of tile requests past the end, and the results are never used.
-    stage(2 * u + 1, i1{}, std::true_type{}, no_sync);
-  }
-  lds_wait<0>();                         // the K fragment reads of the last stage
-  // V^T P^T of the last sub-tile.
-  if (__any(any_corr)) rescale(corr);
-  issue_v(NS - 1, i0{});
-  issue_v(NS - 1, i1{});
-  lds_wait<0>();
-  ready_v(0);
-  ready_v(1);
-  pv(pfb[1], 0);
-  pv(pfb[1], 1);
-  wait_vmcnt<0>();                       // the last (dummy) tile requests
+  __shared__ int wg_overflow;
+  if (tid == 0) wg_overflow = 0;
+  // One pass over the KV tiles of this work item, in fast or robust mode.
+  auto attend = [&](auto robust_c) __attribute__((always_inline)) {
+#pragma unroll
+    for (int c = 0; c < NH; ++c) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[c][db][r] = 0.f;
+      m_run[c] = kMinusBig;
+      l_run[c] = 0.f;
+    }
+    any_corr = false;
+    // ---- prologue: tiles 0..2 requested, tile 0 awaited ----
+    issue_tile(0, block_id(0));
+    issue_tile(1, block_id(1));
+    issue_tile(2, block_id(2));
+    int next_bid = block_id(3);
+    wait_vmcnt<2 * Geo::LOADS>();
+    __builtin_amdgcn_s_barrier();
+    // The query fragments were requested before the tiles, so they have arrived.  Redefining them
+    // here keeps the compiler from guarding their first use inside the loop with a wait that
+    // would drain the tile requests in flight on every iteration.
+  #pragma unroll
+    for (int c = 0; c < NH; ++c)
+  #pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        asm volatile("" : "+v"(qf[c][ks].x), "+v"(qf[c][ks].y), "+v"(qf[c][ks].z), "+v"(qf[c][ks].w));
+
+    // Barrier of tile u, inside stage 2u, after the wave's last read of tile u-1 (the second half
+    // of the V^T fragments of sub-tile 2u-1) and before its first read of tile u+1 (the K
+    // fragments of sub-tile 2u+2): tile u+1 must be complete, while tile u+2 may still be in
+    // flight, and the buffer of tile u-1 now takes tile u+3.
+    // (A bare s_barrier: __syncthreads() would add a fence that drains every load in flight.
+    // Each wave has waited for its own loads and for its own LDS reads.)
+    int u_sync = 0;
+    auto next_tile = [&]() __attribute__((always_inline)) {
+      // Called with no LDS read outstanding: the block id requested a tile ago is taken over
+      // here, so that the wait the compiler puts before its first use is already satisfied and
+      // is not moved up to where fragment reads are in flight.
+      asm volatile("" : "+s"(next_bid));
+      wait_vmcnt<Geo::LOADS>();
+      __builtin_amdgcn_s_barrier();
+      issue_tile(u_sync + 3, next_bid);
+      next_bid = block_id(u_sync + 4);
+      ++u_sync;
+    };
+    auto no_sync = []() __attribute__((always_inline)) {};
+    issue_k(0);
+    lds_wait<0>();
+    ready_k();
+    qk(scb[0]);
+    issue_k(1);
+    stage(0, i0{}, std::false_type{}, robust_c, next_tile);
+    stage(1, i1{}, std::true_type{}, robust_c, no_sync);
+    for (int u = 1; u < n_tiles; ++u) {
+      stage(2 * u, i0{}, std::true_type{}, robust_c, next_tile);
+      // The last stages also fetch and score sub-tiles past the end: their buffers hold the
+      // zeros of tile requests past the end, and the results are never used.
+      stage(2 * u + 1, i1{}, std::true_type{}, robust_c, no_sync);
+    }
+    lds_wait<0>();                         // the K fragment reads of the last stage
+    // V^T P^T of the last sub-tile.
+    if constexpr (decltype(robust_c)::value) {
+      if (__any(any_corr)) rescale(corr);
+    }
+    issue_v(NS - 1, i0{});
+    issue_v(NS - 1, i1{});
+    lds_wait<0>();
+    ready_v(0);
+    ready_v(1);
+    pv(pfb[1], 0);
+    pv(pfb[1], 1);
+    wait_vmcnt<0>();                     // the last (dummy) tile requests
+  };
+  attend(std::false_type{});
+  // Any wave that saw a row sum leave the safe range makes the whole workgroup (the tile
+  // requests and barriers are collective) repeat the work item in robust mode.
+  if (__any(overflow) && lane == 0) wg_overflow = 1;
+  __syncthreads();
+  if (wg_overflow) attend(std::true_type{});
 
 #pragma unroll
   for (int c = 0; c < NH; ++c) {

@@ -208,6 +208,25 @@ def test_prefill_constant_v():
     np.testing.assert_allclose(got, 1.0, rtol=0, atol=1e-2)
 
 
+def test_prefill_scores_far_above_first_subtile():
+    """Keys from token 96 on are 64 times larger than the first ones, so later scores exceed the
+    maximum over the first 32 tokens by hundreds of log2 units: the MFMA kernel's fast pass
+    (reference value fixed after the first sub-tile) must notice that its sums leave the safe
+    range and the robust pass must deliver the result.  Rows whose large scores are all negative
+    stay on the fast pass within the same workgroups."""
+    from gpu_harness import run_attention
+    b = gen.make_batch("pre_growing", 65, 8, 2, 128, [(200, 300), (64, 64), (130, 260)])
+    kp = b.k_pool.copy()
+    for i in range(b.num_seqs):
+        t = np.arange(96, int(b.ctx_lens[i])) if b.ctx_lens[i] > 96 else np.arange(0)
+        rows = kp[b.block_tables[i, t // 16], t % 16]                  # bf16 bits [n, Hkv, D]
+        kp[b.block_tables[i, t // 16], t % 16] = rows + np.uint16(6 << 7)   # exponent + 6: x64
+    got = run_attention(b, k_pool=kp)
+    ref = oracle_out(b, k_pool=kp)
+    assert np.isfinite(got).all()
+    assert np.abs(got - ref).max() <= TOL
+
+
 def test_config3_prefill_heavy_shrunk():
     check(gen.config3(shrink=8))
 
