@@ -57,9 +57,12 @@ def _load():
             lib.oracle_kv_unpack_chunks.argtypes = [
                 _u16p, _c.c_int32, _i32p, _i32p, _i32p, _i64p, _u16p, _u16p, _c.c_int64,
                 _c.c_int32, _c.c_int32, _c.c_int32, _c.c_int32, _i32p, _c.c_int32, _c.c_int32]
+            lib.oracle_kv_append.argtypes = [
+                _u16p, _u16p, _u16p, _u16p, _c.c_int32, _c.c_int32, _c.c_int32, _i32p, _c.c_int32,
+                _c.c_int32, _i32p, _i32p]
             for f in (lib.oracle_attn_mixed_batch, lib.oracle_attn_rows,
                       lib.oracle_attn_row_weights, lib.oracle_kv_pack_chunks,
-                      lib.oracle_kv_unpack_chunks, lib.oracle_num_threads):
+                      lib.oracle_kv_unpack_chunks, lib.oracle_kv_append, lib.oracle_num_threads):
                 f.restype = _c.c_int
             _lib = lib
     return _lib
@@ -160,3 +163,21 @@ def kv_unpack_chunks(chunk_buf, chunks, k_pool, v_pool, block_tables):
                                          Hkv, D, bt, bt.shape[1], bt.shape[0])
     if rc:
         raise ValueError("oracle_kv_unpack_chunks: invalid problem (%d)" % rc)
+
+
+def kv_append(k_new, v_new, k_pool, v_pool, block_tables, q_offsets, ctx_lens):
+    """Writes the new tokens' K/V rows [total_q, Hkv, D] (bf16 bits) into the one-layer pool
+    [NB, 16, Hkv, D] in place, at the positions [ctx_len - q_len, ctx_len) of each segment."""
+    assert k_pool.ndim == 4 and k_pool.shape == v_pool.shape
+    for a in (k_new, v_new, k_pool, v_pool):
+        assert a.dtype == np.uint16 and a.flags.c_contiguous
+    _, bs, Hkv, D = k_pool.shape
+    assert k_new.shape == v_new.shape and k_new.shape[1:] == (Hkv, D)
+    bt, qo, cl = _c32(block_tables), _c32(q_offsets), _c32(ctx_lens)
+    assert k_new.shape[0] == int(qo[-1])
+    rc = _load().oracle_kv_append(k_new.reshape(-1), v_new.reshape(-1), k_pool.reshape(-1),
+                                  v_pool.reshape(-1), bs, Hkv, D, bt, bt.shape[1], bt.shape[0],
+                                  qo, cl)
+    if rc:
+        raise ValueError("oracle_kv_append: invalid problem (%d)" % rc)
+    return k_pool, v_pool

@@ -23,6 +23,8 @@
  *     shipped as equal-sized contiguous chunks, and the receiver places it
  *     into blocks of its own choosing.  pack = paged -> contiguous chunk,
  *     unpack = contiguous chunk -> paged (only the covered slots are written).
+ *   - KV append (paper section 2.1): before a step's attention reads the cache,
+ *     the keys/values of the step's new tokens are written into it.
  *
  * The paper gives no formula beyond citing the standard scaled dot-product
  * attention; the definition written out here is
@@ -298,6 +300,45 @@ int oracle_kv_unpack_chunks(const uint16_t *chunk_buf, int32_t num_chunks, const
     return copy_chunks(1, k_pool, v_pool, layer_stride, num_layers, bs, Hkv, D, block_tables,
                        max_blocks, num_seqs, num_chunks, seq, token_begin, num_tokens,
                        chunk_offset, (uint16_t *)chunk_buf);
+}
+
+/* ---- KV append --------------------------------------------------------------- */
+
+/*
+ * The step right before attention reads the cache (paper section 2.1: prefill populates the
+ * KV cache, each decode step appends to it): the keys/values of the batch's new tokens,
+ * k_new/v_new [total_q][Hkv][D], are written into one layer of the pool at the positions the
+ * new tokens occupy, through the block table.  For segment i and its j-th new token:
+ *   p = ctx_len_i - q_len_i + j
+ *   pool_kv[(table[i][p/bs]*bs + p%bs)*Hkv*D + ...] = kv_new[(q_off_i + j)*Hkv*D + ...]
+ * Every other element of the pool keeps its value.
+ */
+int oracle_kv_append(const uint16_t *k_new, const uint16_t *v_new, uint16_t *k_pool,
+                     uint16_t *v_pool, int32_t bs, int32_t Hkv, int32_t D,
+                     const int32_t *block_tables, int32_t max_blocks, int32_t num_seqs,
+                     const int32_t *q_offsets, const int32_t *ctx_lens)
+{
+    if (!k_new || !v_new || !k_pool || !v_pool || !block_tables || !q_offsets || !ctx_lens)
+        return -1;
+    if (bs < 1 || Hkv < 1 || D < 1 || num_seqs < 1 || q_offsets[0] != 0) return -1;
+    for (int i = 0; i < num_seqs; ++i) {
+        const int64_t q_len = (int64_t)q_offsets[i + 1] - q_offsets[i];
+        if (q_len < 1 || ctx_lens[i] < q_len) return -1;
+        if (((int64_t)ctx_lens[i] + bs - 1) / bs > max_blocks) return -1;
+    }
+    const int64_t row = (int64_t)Hkv * D;
+    for (int i = 0; i < num_seqs; ++i) {
+        const int32_t q_len = q_offsets[i + 1] - q_offsets[i];
+        for (int32_t j = 0; j < q_len; ++j) {
+            const int64_t p = (int64_t)ctx_lens[i] - q_len + j;
+            const int64_t b = block_tables[(int64_t)i * max_blocks + p / bs];
+            const int64_t dst = (b * bs + p % bs) * row;
+            const int64_t src = ((int64_t)q_offsets[i] + j) * row;
+            memcpy(k_pool + dst, k_new + src, sizeof(uint16_t) * (size_t)row);
+            memcpy(v_pool + dst, v_new + src, sizeof(uint16_t) * (size_t)row);
+        }
+    }
+    return 0;
 }
 
 int oracle_num_threads(void)
