@@ -170,6 +170,37 @@ def bench_attention(b, steps, warmup, hev):
     return res, d
 
 
+def bench_append(b, steps, warmup, hev):
+    """kv_append of the batch's new tokens (the step before attention): read once, written once."""
+    import torch
+    import paper_2504_09285_amd as dsv
+
+    def dev_bf16(u16):
+        return torch.from_numpy(np.ascontiguousarray(u16).view(np.int16)).cuda().view(torch.bfloat16)
+
+    pool = dsv.KVPool(dev_bf16(b.k_pool[None]), dev_bf16(b.v_pool[None]))
+    bt = torch.from_numpy(np.ascontiguousarray(b.block_tables, dtype=np.int32)).cuda()
+    qo, cl = torch.from_numpy(b.q_offsets).cuda(), torch.from_numpy(b.ctx_lens).cuda()
+    k_new = torch.randn((b.total_q, b.Hkv, b.D), device="cuda").to(torch.bfloat16)
+    v_new = torch.randn((b.total_q, b.Hkv, b.D), device="cuda").to(torch.bfloat16)
+    stream = torch.cuda.current_stream().cuda_stream or None
+    fn = lambda: dsv.kv_append(k_new, v_new, pool, 0, bt, qo, cl, b.q_offsets, b.ctx_lens)
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    evs = [(hev.create(), hev.create()) for _ in range(steps)]
+    for e0, e1 in evs:
+        hev.record(e0, stream)
+        fn()
+        hev.record(e1, stream)
+    torch.cuda.synchronize()
+    ms = float(np.median([hev.elapsed_ms(e0, e1) for e0, e1 in evs]))
+    nbytes = 2 * 2 * b.total_q * b.Hkv * b.D * 2          # K and V, read + written
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    return {"workload": b.name, "new_tokens": int(b.total_q), "ms": ms, "bytes": nbytes, "GB/s": gbs,
+            "frac_hbm_peak": gbs / HBM_PEAK_GBS}
+
+
 def bench_handoff(h, steps, warmup, hev):
     import torch
     import paper_2504_09285_amd as dsv
@@ -393,6 +424,7 @@ def main():
             r3, d3 = bench_attention(gen.config3(threads=threads), 10, 2, hev)
             extras["c3_prefill_heavy"] = {k: r3[k] for k in ("ms_per_step", "tokens_per_s", "kernel_ms", "prefill", "decode") if k in r3}
             del d3
+        extras["kv_append_c3"] = bench_append(gen.config3(threads=threads), 20, 3, hev)
         extras["c4_micro_request"] = bench_config4(threads, 10, 2, hev)
         if args.full_extras:
             extras["c5_two_streams"] = bench_concurrent(gen.config5_attention(threads=threads),

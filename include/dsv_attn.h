@@ -137,6 +137,24 @@ int kv_unpack_chunks(const void* chunk_buf, const dsv_chunk_desc* descs,
                      int32_t max_blocks_per_seq, void* hip_stream);
 
 /*
+ * Write the keys/values of the batch's new tokens into layer `layer` of the paged pool, at the
+ * positions they occupy (paper section 2.1: prefill populates the KV cache and every decode
+ * step appends to it, before attention reads it).  For segment i and its j-th new token the
+ * destination is token position ctx_len_i - q_len_i + j of row i of the block table.
+ *   k_new, v_new   device, bf16 [total_q][num_kv_heads][head_dim], 16-byte aligned
+ *   block_tables, q_offsets, ctx_lens, the host mirrors, num_seqs: as for attn_mixed_batch
+ * Byte-exact copy; every other byte of the pool is left as it was.  Two new tokens must not
+ * map to the same pool slot (the result for that slot would be either one).  Enqueues one
+ * kernel on hip_stream; an attn_mixed_batch call on the same stream afterwards sees the rows.
+ * num_seqs == 0 is a no-op.  Errors as for attn_mixed_batch (no workspace is needed).
+ */
+int kv_append(const void* k_new, const void* v_new, const dsv_kv_pool* pool, int32_t layer,
+              const int32_t* block_tables, int32_t max_blocks_per_seq,
+              const int32_t* q_offsets, const int32_t* ctx_lens,
+              const int32_t* q_offsets_host, const int32_t* ctx_lens_host, int32_t num_seqs,
+              void* hip_stream);
+
+/*
  * Profiling aid for benchmarks (not needed for correct use).  Until cleared with NULLs, every
  * later attn_mixed_batch call made by the calling host thread records `start_event` on its
  * stream immediately before, and `stop_event` immediately after, the launch of the named

@@ -1,5 +1,5 @@
-"""MI355X-native hot path under micro-request execution: mixed-batch paged-KV attention and
-chunked KV pack/unpack, as hand-written HIP kernels behind a C ABI (``include/dsv_attn.h``).
+"""MI355X-native hot path under micro-request execution: mixed-batch paged-KV attention,
+KV append and chunked KV pack/unpack, as hand-written HIP kernels behind a C ABI (``include/dsv_attn.h``).
 
 This package is only the thin Python binding; importing it does not load the library.  Every
 call goes to ``libdsv_attn.so``; there is no CPU or eager fallback, and a missing library raises.
@@ -7,6 +7,6 @@ call goes to ``libdsv_attn.so``; there is no CPU or eager fallback, and a missin
 from .binding import (  # noqa: F401
     DSV_OUT_BF16, DSV_OUT_F32, ChunkDescs, DsvError, KVPool, attn_mixed_batch,
     attn_mixed_batch_workspace_bytes, build_info, dsv_profile_events, KERNEL_PLAN, KERNEL_ROWS,
-    KERNEL_TILES, KERNEL_MERGE, kv_pack_chunks, kv_unpack_chunks, library_path,
+    KERNEL_TILES, KERNEL_MERGE, kv_append, kv_pack_chunks, kv_unpack_chunks, library_path,
     load_library,
 )

@@ -36,7 +36,7 @@ CHUNK_DTYPE = np.dtype([("seq", "<i4"), ("token_begin", "<i4"), ("num_tokens", "
 assert CHUNK_DTYPE.itemsize == 24
 
 EXPORTS = ("attn_mixed_batch_workspace_bytes", "attn_mixed_batch", "kv_pack_chunks",
-           "kv_unpack_chunks", "dsv_profile_events", "dsv_build_info")
+           "kv_unpack_chunks", "kv_append", "dsv_profile_events", "dsv_build_info")
 KERNEL_PLAN, KERNEL_ROWS, KERNEL_TILES, KERNEL_MERGE = 0, 1, 2, 3
 
 
@@ -60,6 +60,9 @@ def load_library():
     lib.attn_mixed_batch.argtypes = [vp, vp, C.POINTER(_Pool), C.c_int32, vp, C.c_int32, vp, vp,
                                      i32p, i32p, C.c_int32, C.c_int32, C.c_float, C.c_int32,
                                      vp, C.c_size_t, vp]
+    lib.kv_append.restype = C.c_int
+    lib.kv_append.argtypes = [vp, vp, C.POINTER(_Pool), C.c_int32, vp, C.c_int32, vp, vp, i32p, i32p,
+                              C.c_int32, vp]
     lib.kv_pack_chunks.restype = C.c_int
     lib.kv_pack_chunks.argtypes = [C.POINTER(_Pool), vp, C.c_int32, vp, vp, C.c_int32, vp, vp]
     lib.kv_unpack_chunks.restype = C.c_int
@@ -156,6 +159,23 @@ def attn_mixed_batch(q, out, pool: KVPool, layer, block_tables, q_offsets, ctx_l
         workspace.data_ptr(), int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
     if rc:
         raise DsvError("attn_mixed_batch", rc)
+
+
+def kv_append(k_new, v_new, pool: KVPool, layer, block_tables, q_offsets, ctx_lens, q_offsets_host,
+              ctx_lens_host, stream=None) -> None:
+    """See ``kv_append`` in include/dsv_attn.h."""
+    import torch
+    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
+    assert k_new.is_contiguous() and v_new.is_contiguous() and k_new.element_size() == 2
+    assert tuple(k_new.shape) == tuple(v_new.shape)
+    assert block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous()
+    assert q_offsets.dtype == torch.int32 and ctx_lens.dtype == torch.int32
+    rc = load_library().kv_append(
+        k_new.data_ptr(), v_new.data_ptr(), pool.c, int(layer), block_tables.data_ptr(),
+        int(block_tables.shape[1]), q_offsets.data_ptr(), ctx_lens.data_ptr(), _i32_ptr(qo), _i32_ptr(cl),
+        int(cl.shape[0]), _stream_ptr(stream))
+    if rc:
+        raise DsvError("kv_append", rc)
 
 
 def kv_pack_chunks(src: KVPool, block_tables, descs: ChunkDescs, chunk_buf, stream=None) -> None:
