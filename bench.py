@@ -150,12 +150,23 @@ def time_attention(d, steps, warmup, kernel_ids, hev):
 
 
 def bench_attention(b, steps, warmup, hev):
+    """The step is timed as the library runs it (a batch holding prefill tiles and row items runs
+    them in one launch).  The per-kernel times that feed the roofline fractions come from a second
+    pass with the two kernels launched apart (DSV_MIXED_LAUNCH=0), where each can be timed."""
     import paper_2504_09285_amd as dsv
     d = upload(b)
-    sec, per_kernel = time_attention(d, steps, warmup,
-                                     [dsv.KERNEL_ROWS, dsv.KERNEL_TILES, dsv.KERNEL_MERGE, dsv.KERNEL_PLAN], hev)
+    ids = [dsv.KERNEL_ROWS, dsv.KERNEL_TILES, dsv.KERNEL_MERGE, dsv.KERNEL_PLAN, dsv.KERNEL_MIXED]
+    sec, per_kernel = time_attention(d, steps, warmup, ids, hev)
     res = {"workload": b.name, "ms_per_step": sec * 1e3, "tokens_per_s": b.total_q / sec,
            "total_q": b.total_q, "num_seqs": b.num_seqs}
+    if per_kernel[dsv.KERNEL_MIXED] is not None:
+        res["mixed_launch_ms"] = per_kernel[dsv.KERNEL_MIXED]
+        os.environ["DSV_MIXED_LAUNCH"] = "0"
+        try:
+            sec_apart, per_kernel = time_attention(d, max(steps // 2, 3), 2, ids, hev)
+        finally:
+            del os.environ["DSV_MIXED_LAUNCH"]
+        res["ms_per_step_kernels_apart"] = sec_apart * 1e3
     rows_ms, tiles_ms = per_kernel[dsv.KERNEL_ROWS], per_kernel[dsv.KERNEL_TILES]
     res["kernel_ms"] = {"rows": rows_ms, "tiles": tiles_ms, "merge": per_kernel[dsv.KERNEL_MERGE],
                         "plan": per_kernel[dsv.KERNEL_PLAN]}
@@ -257,11 +268,19 @@ def bench_config4(threads, steps, warmup, hev):
     hev.record(e1, stream)
     torch.cuda.synchronize()
     handoff_ms = hev.elapsed_ms(e0, e1)
-    sec, pk = time_attention(d, steps, warmup, [dsv.KERNEL_ROWS, dsv.KERNEL_TILES, dsv.KERNEL_MERGE, dsv.KERNEL_PLAN], hev)
+    ids = [dsv.KERNEL_ROWS, dsv.KERNEL_TILES, dsv.KERNEL_MERGE, dsv.KERNEL_PLAN, dsv.KERNEL_MIXED]
+    sec, pk = time_attention(d, steps, warmup, ids, hev)               # as the library runs it: one mixed launch
+    mixed_ms = pk[dsv.KERNEL_MIXED]
+    os.environ["DSV_MIXED_LAUNCH"] = "0"                               # the two kernels apart, to time each
+    try:
+        sec_apart, pk = time_attention(d, steps, warmup, ids, hev)
+    finally:
+        del os.environ["DSV_MIXED_LAUNCH"]
     nbytes, flops = decode_bytes(b, 2), prefill_flops(b)
     t_mem, t_mfma = nbytes / (HBM_PEAK_GBS * 1e9), flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
     rows_ms, tiles_ms = pk[dsv.KERNEL_ROWS], pk[dsv.KERNEL_TILES]
     return {"workload": b.name, "split_k": sp.k, "ms_per_step": sec * 1e3, "tokens_per_s": b.total_q / sec,
+            "mixed_launch_ms": mixed_ms, "ms_per_step_kernels_apart": sec_apart * 1e3,
             "kernel_ms": {"rows": rows_ms, "tiles": tiles_ms, "merge": pk[dsv.KERNEL_MERGE], "plan": pk[dsv.KERNEL_PLAN]},
             "handoff_pack_unpack_ms": handoff_ms, "handoff_chunks": int(len(sp.chunks)),
             "decode": {"GB/s": nbytes / (rows_ms * 1e-3) / 1e9, "frac_hbm_peak": nbytes / (rows_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
@@ -422,7 +441,7 @@ def main():
         del h
         if args.workload != "c3":
             r3, d3 = bench_attention(gen.config3(threads=threads), 10, 2, hev)
-            extras["c3_prefill_heavy"] = {k: r3[k] for k in ("ms_per_step", "tokens_per_s", "kernel_ms", "prefill", "decode") if k in r3}
+            extras["c3_prefill_heavy"] = {k: r3[k] for k in ("ms_per_step", "tokens_per_s", "mixed_launch_ms", "ms_per_step_kernels_apart", "kernel_ms", "prefill", "decode") if k in r3}
             del d3
         extras["kv_append_c3"] = bench_append(gen.config3(threads=threads), 20, 3, hev)
         extras["c4_micro_request"] = bench_config4(threads, 10, 2, hev)

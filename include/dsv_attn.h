@@ -165,6 +165,10 @@ int kv_append(const void* k_new, const void* v_new, const dsv_kv_pool* pool, int
 #define DSV_KERNEL_ROWS   1   /* single-token attention split along the context (decodes) */
 #define DSV_KERNEL_TILES  2   /* MFMA attention of long prefill spans                     */
 #define DSV_KERNEL_MERGE  3   /* combination of context partitions                        */
+#define DSV_KERNEL_MIXED  4   /* rows and tiles in one launch: what a batch holding         */
+                              /* comparable amounts of both kinds of work runs instead of  */
+                              /* ids 1 and 2 (environment DSV_MIXED_LAUNCH=0 / 1 forces    */
+                              /* the two launches / the single one)                        */
 int dsv_profile_events(int32_t kernel_id, void* start_event, void* stop_event);
 
 /* Library build identification: a static string, e.g. "dsv_attn gfx950 <date>". */

@@ -37,7 +37,7 @@ assert CHUNK_DTYPE.itemsize == 24
 
 EXPORTS = ("attn_mixed_batch_workspace_bytes", "attn_mixed_batch", "kv_pack_chunks",
            "kv_unpack_chunks", "kv_append", "dsv_profile_events", "dsv_build_info")
-KERNEL_PLAN, KERNEL_ROWS, KERNEL_TILES, KERNEL_MERGE = 0, 1, 2, 3
+KERNEL_PLAN, KERNEL_ROWS, KERNEL_TILES, KERNEL_MERGE, KERNEL_MIXED = 0, 1, 2, 3, 4
 
 
 def library_path() -> str:

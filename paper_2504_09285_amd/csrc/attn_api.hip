@@ -17,7 +17,7 @@ namespace {
 constexpr int kPlanThreads = 1024;
 
 // Benchmark hook: event pairs recorded around individual kernels (see dsv_profile_events).
-thread_local hipEvent_t g_events[4][2] = {};
+thread_local hipEvent_t g_events[5][2] = {};
 
 struct EventScope {
   hipEvent_t stop;
@@ -107,6 +107,7 @@ PlanCounts count_plan(int32_t S, const int32_t* qo, const int32_t* cl, const Pla
     if (on_row_path(q_len, c)) {
       n.rows += q_len;
       for (int j = 0; j < q_len; ++j) {
+        n.row_tokens += cl[i] - q_len + j + 1;
         const int np = parts_of(cl[i] - q_len + j + 1, c);
         n.items += np;
         if (np > 1) n.split_items += np;
@@ -114,6 +115,7 @@ PlanCounts count_plan(int32_t S, const int32_t* qo, const int32_t* cl, const Pla
       }
     } else {
       n.tiles += ceil_div(q_len, c.tile_tokens);
+      n.tile_pairs += (int64_t)q_len * (cl[i] - q_len) + (int64_t)q_len * (q_len + 1) / 2;
     }
   }
   return n;
@@ -428,13 +430,31 @@ extern "C" int attn_mixed_batch(const void* q, void* out, const dsv_kv_pool* poo
                        block_tables, max_blocks_per_seq, num_seqs, cfg, w);
     if ((rc = launch_status())) return rc;
   }
-  if (n.tiles) {
-    EventScope ev(DSV_KERNEL_TILES, stream);
-    if ((rc = launch_prefill_tiles(a, w, cfg, n, stream))) return rc;
+  // A batch with both prefill tiles and row items can run them in one launch.
+  // Mixing pays when neither kind of work is a small fraction of the other (measured: a fifth
+  // faster on config 4, a few percent slower on config 3 where the decodes are 1/8 of the
+  // step), so it is chosen from rough time estimates: streamed bytes at 5.5 TB/s against
+  // matrix-core work at 0.9 PFLOP/s.  DSV_MIXED_LAUNCH=1 / 0 forces the choice.
+  bool mix = mixed_launch_supported(a, cfg, n);
+  if (mix) {
+    const double t_rows = (double)n.row_tokens * a.Hkv * a.D * 4.0 / 5.5e12;
+    const double t_tiles = (double)n.tile_pairs * a.Hq * a.D * 4.0 / 0.9e15;
+    mix = t_rows >= 0.25 * t_tiles && t_tiles >= 0.25 * t_rows;
+    const int forced = env_int("DSV_MIXED_LAUNCH", -1);
+    if (forced >= 0) mix = forced != 0;
   }
-  if (n.items) {
-    EventScope ev(DSV_KERNEL_ROWS, stream);
-    if ((rc = launch_rows(a, w, cfg, n, stream))) return rc;
+  if (mix) {
+    EventScope ev(DSV_KERNEL_MIXED, stream);
+    if ((rc = launch_mixed(a, w, cfg, n, stream))) return rc;
+  } else {
+    if (n.tiles) {
+      EventScope ev(DSV_KERNEL_TILES, stream);
+      if ((rc = launch_prefill_tiles(a, w, cfg, n, stream))) return rc;
+    }
+    if (n.items) {
+      EventScope ev(DSV_KERNEL_ROWS, stream);
+      if ((rc = launch_rows(a, w, cfg, n, stream))) return rc;
+    }
   }
   if (n.split_items) {
     EventScope ev(DSV_KERNEL_MERGE, stream);
@@ -444,7 +464,7 @@ extern "C" int attn_mixed_batch(const void* q, void* out, const dsv_kv_pool* poo
 }
 
 extern "C" int dsv_profile_events(int32_t kernel_id, void* start_event, void* stop_event) {
-  if (kernel_id < 0 || kernel_id > 3) return DSV_E_INVALID;
+  if (kernel_id < 0 || kernel_id > 4) return DSV_E_INVALID;
   g_events[kernel_id][0] = static_cast<hipEvent_t>(start_event);
   g_events[kernel_id][1] = static_cast<hipEvent_t>(stop_event);
   return DSV_OK;

@@ -27,6 +27,8 @@ struct PlanCounts {
   int64_t split_items = 0; // items belonging to rows with more than one partition
   int64_t tiles = 0;       // (span, q-tile) work items of the MFMA path
   int32_t max_parts = 0;
+  int64_t row_tokens = 0;  // KV tokens the row path streams (per KV head)
+  int64_t tile_pairs = 0;  // causal (query, key) pairs of the MFMA path (per query head)
 };
 
 // Device-resident work lists, carved out of the caller's workspace.
@@ -66,5 +68,9 @@ int launch_rows(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg,
 int launch_merge(const AttnArgs& a, const WorkLists& w, const PlanCounts& n, hipStream_t stream);
 int launch_prefill_tiles(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg,
                          const PlanCounts& n, hipStream_t stream);
+// Prefill tiles and row items in one launch (same results as the two launches above).
+bool mixed_launch_supported(const AttnArgs& a, const PlanConfig& cfg, const PlanCounts& n);
+int launch_mixed(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, const PlanCounts& n,
+                 hipStream_t stream);
 
 }  // namespace dsv

@@ -1,0 +1,100 @@
+// One launch for a batch that holds both kinds of work: prefill tiles (matrix-core bound) and
+// row items (HBM bound).  The paper runs prefill and decode tokens of a step in one hybrid
+// launch and observes that mixing them raises utilisation (sections 4.2 and 4.4); here the two
+// kernels' workgroups are dealt out in one grid, in alternating groups sized in proportion to
+// their counts, so that from the first moment some compute units stream KV for the decodes
+// while the others run MFMAs for the prefill spans, instead of one kernel waiting for the
+// other's tail.  A workgroup runs exactly one of the two kernel bodies; both are written for
+// 512 threads and about 128 KiB of LDS, so a compute unit holds one workgroup of either kind.
+//
+// Groups are eight consecutive workgroups: the hardware deals consecutive workgroups to the
+// eight XCDs in turn, so a group of tile workgroups still puts KV head k on XCD k (see
+// attn_prefill_kernel.h), and heaviest-first tile order is kept.
+#include "attn_prefill_kernel.h"
+#include "attn_rows_kernel.h"
+
+namespace dsv {
+namespace {
+
+constexpr int kGroup = 8;
+
+struct MixParams {
+  uint32_t tile_wgs;        // prefill workgroups: tiles * Hkv * ceil(G / 4)
+  uint32_t tiles_x;         // tiles * Hkv (the prefill kernel's x extent)
+  uint32_t row_wgs;         // row workgroups: items * rows_y * rows_z
+  uint32_t rows_x, rows_y;  // the row kernel's x and y extents
+  uint32_t tile_groups, total_groups;
+  int32_t rows_waves;
+};
+
+template <int D>
+__global__ __launch_bounds__(512, 2) void mixed_kernel(prefill_impl::TilesParams tp,
+                                                       rows_impl::RowsParams rp, MixParams mp) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const uint32_t g = blockIdx.x / kGroup, lane_in_group = blockIdx.x % kGroup;
+  // Group g is a tile group iff the running count of tile groups steps at g.
+  // (Measured on configs 3 and 4: spreading the tile groups evenly over the whole grid beats
+  // packing them towards the front or giving the row groups a head start.)
+  const uint32_t t0 = (uint32_t)((uint64_t)g * mp.tile_groups / mp.total_groups);
+  const uint32_t t1 = (uint32_t)((uint64_t)(g + 1) * mp.tile_groups / mp.total_groups);
+  if (t1 != t0) {
+    const uint32_t wg = t0 * kGroup + lane_in_group;
+    if (wg >= mp.tile_wgs) return;                               // uniform for the workgroup
+    prefill_impl::prefill_tiles_body<D>(tp, (int)(wg % mp.tiles_x), (int)(wg / mp.tiles_x), smem);
+  } else {
+    const uint32_t wg = (g - t0) * kGroup + lane_in_group;
+    if (wg >= mp.row_wgs) return;
+    const uint32_t bx = wg % mp.rows_x, rest = wg / mp.rows_x;
+    rows_impl::rows_body<D, 2>(rp, (int)bx, (int)(rest % mp.rows_y), (int)(rest / mp.rows_y), mp.rows_waves, smem);
+  }
+}
+
+template <int D>
+int launch_mixed_t(const prefill_impl::TilesParams& tp, const rows_impl::RowsParams& rp,
+                   const MixParams& mp, int lds, hipStream_t stream) {
+  static int configured = 0;          // raising the dynamic-LDS limit is idempotent; races are benign
+  if (lds > configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(mixed_kernel<D>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+      return DSV_E_LAUNCH;
+    configured = lds;
+  }
+  hipLaunchKernelGGL((mixed_kernel<D>), dim3(mp.total_groups * kGroup), dim3(512), lds, stream, tp, rp, mp);
+  return launch_status();
+}
+
+}  // namespace
+
+bool mixed_launch_supported(const AttnArgs& a, const PlanConfig& cfg, const PlanCounts& n) {
+  return n.tiles > 0 && n.items > 0 && cfg.row_nbuf == 2 && cfg.tile_tokens == prefill_impl::kTileQ &&
+         cfg.part_tokens <= 64 * kBlockSize && prefill_impl::kThreads == 512 && (a.D == 128 || a.D == 64);
+}
+
+int launch_mixed(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, const PlanCounts& n,
+                 hipStream_t stream) {
+  if (!mixed_launch_supported(a, cfg, n)) return DSV_E_UNSUPPORTED;
+  const int G = a.Hq / a.Hkv;
+  prefill_impl::TilesParams tp{a, w, (int32_t)n.tiles, G};
+  rows_impl::RowsParams rp{a, w, cfg.part_tokens, G};
+  int waves = 1;
+  while (waves < a.Hkv && waves < 8) waves <<= 1;
+  MixParams mp;
+  mp.tiles_x = (uint32_t)(n.tiles * a.Hkv);
+  const int64_t tile_wgs = (int64_t)mp.tiles_x * ceil_div(G, 4);
+  mp.rows_x = (uint32_t)n.items;
+  mp.rows_y = (uint32_t)ceil_div(a.Hkv, waves);
+  const int64_t row_wgs = (int64_t)n.items * mp.rows_y * ceil_div(G, rows_impl::kRowHeads);
+  const int64_t tg = ceil_div(tile_wgs, (int64_t)kGroup), rg = ceil_div(row_wgs, (int64_t)kGroup);
+  if ((tg + rg) * kGroup > 0x7fffffffLL) return DSV_E_UNSUPPORTED;
+  mp.tile_wgs = (uint32_t)tile_wgs;
+  mp.row_wgs = (uint32_t)row_wgs;
+  mp.tile_groups = (uint32_t)tg;
+  mp.total_groups = (uint32_t)(tg + rg);
+  mp.rows_waves = waves;
+  const int rows_lds = waves * 2 * (a.D == 128 ? rows_impl::RowGeom<128>::SLOT_BYTES : rows_impl::RowGeom<64>::SLOT_BYTES);
+  if (a.D == 128)
+    return launch_mixed_t<128>(tp, rp, mp, max(rows_lds, (int)prefill_impl::TileGeom<128>::LDS_BYTES), stream);
+  return launch_mixed_t<64>(tp, rp, mp, max(rows_lds, (int)prefill_impl::TileGeom<64>::LDS_BYTES), stream);
+}
+
+}  // namespace dsv

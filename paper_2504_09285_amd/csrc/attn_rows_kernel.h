@@ -1,0 +1,290 @@
+// Single-query-token attention over a paged KV cache, split along the context ("row" work).
+//
+// Serves the decode tokens of a mixed batch - one new token attending to its whole cached
+// context, the memory-bound part of a step (paper sections 2.1 and 4.2) - and the tokens of
+// prefill spans too short for the tile kernel.  The job is to stream K and V from HBM once, at
+// full bandwidth, with as little else in the way as possible:
+//
+//  * A work item is (query token, context partition); a workgroup takes one item and gives
+//    each of its waves one KV head, so the waves of a workgroup together stream whole 16-token
+//    blocks (all heads of a block are contiguous in the pool).
+//  * Each wave owns a private ring of block slots in LDS and fills it with direct
+//    global->LDS loads (16 bytes per lane, no staging registers).  R-1 blocks are always in
+//    flight behind the one being consumed; with the whole 160 KB of LDS of a CU used this way
+//    the bytes in flight cover the HBM latency.  No workgroup barrier is needed: a wave only
+//    ever reads what it loaded itself, ordered by the vector-memory counter.
+//  * The arithmetic runs on the matrix cores so that the vector ALU stays nearly idle: the G
+//    query heads that share the KV head (padded to 16 rows) form the MFMA column, scores are
+//    S^T = K Q^T (16x16x32), the output is O^T = V^T P^T (16x16x16) with the V^T operand fetched
+//    by LDS transpose reads.  S^T comes out with lane (head, j) holding tokens 4j..4j+3, which
+//    is exactly the B operand layout of the second product; P stays in registers.
+//  * LDS rows are XOR-swizzled (free: each lane picks which 16 bytes of the row it loads) so
+//    that both the K fragment reads and the V transpose reads are bank-conflict free.
+// Scores are kept in the log2 domain (scale*log2(e) folded in, exp2 for exp).  Token slots
+// beyond the partition are excluded by select, and their V rows are replaced by zeros at load
+// time, so pool garbage (possibly NaN/Inf) cannot reach the output.
+#pragma once
+#include "attn_internal.h"
+
+namespace dsv {
+namespace rows_impl {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((address_space(3))) void* lds_void_t;
+typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_t;
+typedef const __attribute__((address_space(1))) void* gbl_void_t;
+
+constexpr float kMinusBig = -1.0e30f;    // finite stand-in for "no token seen yet"
+constexpr int kRowHeads = 16;            // query heads per wave (MFMA column count)
+// Cache policy of the K/V block requests: the "nt" bit.  Every K/V byte is read exactly once by
+// this kernel, so it should not displace block tables, queries, work lists and the partials
+// that the merge kernel re-reads from L2 (measured: rows kernel -4 %, merge kernel -25 %).
+constexpr int kStreamOnce = 2;
+
+struct RowsParams {
+  AttnArgs a;
+  WorkLists w;
+  int32_t part_tokens;
+  int32_t G;            // query heads per KV head
+};
+
+template <int D>
+struct RowGeom {
+  static constexpr int ROWB = D * 2;              // bytes per token row of one head
+  static constexpr int CPR = D / 8;               // 16-byte chunks per row
+  static constexpr int TPI = kWave / CPR;         // token rows per load instruction
+  static constexpr int IPB = kBlockSize / TPI;    // load instructions per block, per tensor
+  static constexpr int KS = D / 32;               // 16x16x32 k-steps of K Q^T
+  static constexpr int DB = D / 16;               // 16-dim blocks of O^T
+  static constexpr int TENSOR_BYTES = kBlockSize * ROWB;
+  static constexpr int SLOT_BYTES = 2 * TENSOR_BYTES;
+  static constexpr int LOADS_PER_BLOCK = 2 * IPB;
+};
+
+// Row swizzles: 16-byte chunk c of token row n is stored at chunk position c ^ swz(n).
+template <int D> __device__ __forceinline__ int k_swz(int n) { return n & (RowGeom<D>::CPR - 1); }
+template <int D> __device__ __forceinline__ int v_swz(int n) { return 2 * (n & (RowGeom<D>::CPR / 2 - 1)); }
+
+// max / sum across the four lane groups j (lanes l, l^16, l^32, l^48).
+__device__ __forceinline__ float cross16_max(float x) {
+  x = fmaxf(x, __shfl_xor(x, 16));
+  return fmaxf(x, __shfl_xor(x, 32));
+}
+__device__ __forceinline__ float cross16_sum(float x) {
+  x += __shfl_xor(x, 16);
+  return x + __shfl_xor(x, 32);
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// LDS transpose reads of the V^T fragments, issued as one group and waited for together.  They
+// are written in assembly because the compiler, not knowing which LDS bytes the direct
+// global->LDS loads in flight will write, would otherwise drain every one of those loads
+// before each transpose read and serialise the ring.  The caller has already waited (vmcnt)
+// for the block that is read here.
+__device__ __forceinline__ void read_vt4(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3,
+                                         s16x4_t& v0, s16x4_t& v1, s16x4_t& v2, s16x4_t& v3) {
+  asm volatile(
+      "ds_read_b64_tr_b16 %0, %4\n\t"
+      "ds_read_b64_tr_b16 %1, %5\n\t"
+      "ds_read_b64_tr_b16 %2, %6\n\t"
+      "ds_read_b64_tr_b16 %3, %7\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3)
+      : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+      : "memory");
+}
+
+// The kernel body as a device function, so that the same code serves the kernel of its own and
+// the launch that mixes row work with prefill tiles.  (bx, by, bz) stand in for the block
+// index, `waves` is the number of waves per workgroup that are given a KV head, `smem` the
+// dynamic LDS.
+template <int D, int R>
+__device__ __forceinline__ void rows_body(const RowsParams& prm, int bx, int by, int bz, int waves,
+                                          unsigned char* smem) {
+  using Geo = RowGeom<D>;
+  constexpr int ROWB = Geo::ROWB, CPR = Geo::CPR, TPI = Geo::TPI, IPB = Geo::IPB, KS = Geo::KS, DB = Geo::DB;
+
+  const AttnArgs& a = prm.a;
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave);
+  const int lane = (int)threadIdx.x % kWave;
+  const int kvh = by * waves + wave;
+  if (wave >= waves || kvh >= a.Hkv) return;                      // no workgroup barrier below: safe
+  const int h0 = kvh * prm.G + bz * kRowHeads;   // first query head of this wave
+  const int nh = min(kRowHeads, prm.G - bz * kRowHeads);
+
+  const int item = bx;
+  const int4 rec = prm.w.item_rec[item];         // {seq, qtok, ctx, part | nparts << 16}
+  const int bid0 = prm.w.item_blk0[item];        // id of the partition's first block
+  const int qtok = rec.y;
+  const int ctx = rec.z;
+  const int part = rec.w & 0xffff;
+  const int nparts = (int)((uint32_t)rec.w >> 16);
+  const int32_t* table = a.block_tables + (int64_t)rec.x * a.max_blocks;
+
+  const int t0 = part * prm.part_tokens;
+  const int t1 = min(ctx, t0 + prm.part_tokens);
+  const int b0 = t0 / kBlockSize;
+  const int b1 = (t1 + kBlockSize - 1) / kBlockSize;   // b1 - b0 <= 64 (part_tokens <= 1024)
+
+  const int qcol = lane % 16;                    // query head within the wave (MFMA column)
+  const int jj = lane / 16;                      // lane group
+
+  // Block ids of the partition: lane i holds the id of block b0+i; a uniform readlane hands one
+  // to the address computation.
+  const int tab_vec = table[min(b0 + lane, b1 - 1)];
+
+  // Query fragments, B operand of S^T = K Q^T: lane (head qcol, jj) holds dims 32*ks + 8*jj .. +8.
+  bf16x8_t qf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (qcol < nh)
+      v = *reinterpret_cast<const uint4*>(a.q + ((int64_t)qtok * a.Hq + h0 + qcol) * D + ks * 32 + jj * 8);
+    qf[ks] = __builtin_bit_cast(bf16x8_t, v);
+  }
+
+  // ---- loader: lane l fills 16-byte position l of each 1 KiB piece of the slot ----
+  unsigned char* const ring = smem + (size_t)wave * R * Geo::SLOT_BYTES;
+  const int ld_row = lane / CPR;                 // token row inside a piece
+  const int ld_pos = lane % CPR;                 // chunk position inside the row
+  const uint32_t tok_stride = (uint32_t)a.Hkv * D;          // elements between token slots
+  const int64_t blk_elems = (int64_t)kBlockSize * tok_stride;
+  const uint16_t* const zero_line = reinterpret_cast<const uint16_t*>(prm.w.zero_line);
+  auto issue_block_id = [&](int bid, int b, int slot) {
+    const uint16_t* kb = a.k_pool + (int64_t)bid * blk_elems + (uint32_t)kvh * D;
+    const uint16_t* vb = a.v_pool + (int64_t)bid * blk_elems + (uint32_t)kvh * D;
+    unsigned char* ks_base = ring + slot * Geo::SLOT_BYTES;
+    unsigned char* vs_base = ks_base + Geo::TENSOR_BYTES;
+#pragma unroll
+    for (int i = 0; i < IPB; ++i) {
+      const int n = i * TPI + ld_row;            // token slot in the block
+      const uint16_t* kp = kb + (uint32_t)n * tok_stride + ((ld_pos ^ k_swz<D>(n)) * 8);
+      const uint16_t* vp = vb + (uint32_t)n * tok_stride + ((ld_pos ^ v_swz<D>(n)) * 8);
+      if (b * kBlockSize + n >= t1) vp = zero_line + ld_pos * 8;     // beyond the partition: V := 0
+      __builtin_amdgcn_global_load_lds((gbl_void_t)kp, (lds_void_t)(ks_base + i * 1024), 16, 0, kStreamOnce);
+      __builtin_amdgcn_global_load_lds((gbl_void_t)vp, (lds_void_t)(vs_base + i * 1024), 16, 0, kStreamOnce);
+    }
+  };
+  auto issue_block = [&](int b, int slot) {
+    issue_block_id(__builtin_amdgcn_readlane(tab_vec, b - b0), b, slot);
+  };
+
+  // ---- per-lane state: lane (qcol, jj) owns head qcol; O^T rows are dims 16*db + 4*jj + e ----
+  f32x4_t o[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) o[db] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  float m_run = kMinusBig, l_run = 0.f;
+  const float scale = a.scale_log2e;
+
+  // LDS read offsets (bytes) inside a slot.
+  // K fragment (A operand, rows = tokens): lane (token qcol, jj) reads dims 32*ks + 8*jj .. +8.
+  int k_off[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) k_off[ks] = qcol * ROWB + (((ks * 4 + jj) ^ k_swz<D>(qcol)) * 16);
+  // V^T fragment by transpose read: the 16 lanes of group jj fetch token rows 4jj..4jj+3 x 16 dims.
+  const int v_row = jj * 4 + (lane % 16) / 4;
+  const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)ring;
+  uint32_t v_off[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+    v_off[db] = ring_lds + Geo::TENSOR_BYTES + v_row * ROWB + (((2 * db + (lane % 4) / 2) ^ v_swz<D>(v_row)) * 16) + (lane % 2) * 8;
+
+  // The first block is requested at once (its id came with the item); the table slice and the
+  // query rows are only waited for where they are first used.
+  const int blast = b1 - 1;
+  issue_block_id(bid0, b0, 0);
+#pragma unroll
+  for (int u = 1; u + 1 < R; ++u) issue_block(min(b0 + u, blast), u);
+
+  for (int b = b0; b < b1; ++b) {
+    const int slot = (b - b0) % R;
+    // Refill the slot consumed in the previous step (unconditionally, so that the number of
+    // loads in flight is static), then wait until only the R-1 younger blocks are outstanding.
+    issue_block(min(b + R - 1, blast), (b - b0 + R - 1) % R);
+    wait_vmcnt<(R - 1) * Geo::LOADS_PER_BLOCK>();
+    const unsigned char* sl = ring + slot * Geo::SLOT_BYTES;
+
+    // S^T = K Q^T: lane (head qcol, jj) gets tokens 4jj..4jj+3 of the block.
+    f32x4_t s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sl + k_off[ks]);
+      s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[ks], s, 0, 0, 0);
+    }
+    const int tok = b * kBlockSize + jj * 4;
+    if (tok + 3 >= t1) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (tok + e >= t1) s[e] = -INFINITY;
+    }
+    const float mx = cross16_max(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])));
+    const float m_new = fmaxf(m_run, mx * scale);
+    const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    float p[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], scale, -m_new));
+    const f32x2_t p01 = {p[0], p[1]}, p23 = {p[2], p[3]};
+    const bf16x2_t b01 = __builtin_convertvector(p01, bf16x2_t), b23 = __builtin_convertvector(p23, bf16x2_t);
+    const bf16x4_t pf = __builtin_shufflevector(b01, b23, 0, 1, 2, 3);
+    // The row sum is taken over the bf16-rounded probabilities that enter the PV product, so
+    // that the weights actually applied sum to one.
+    const uint32_t u01 = __builtin_bit_cast(uint32_t, b01), u23 = __builtin_bit_cast(uint32_t, b23);
+    l_run = l_run * corr + (__builtin_bit_cast(float, u01 << 16) + __builtin_bit_cast(float, u01 & 0xffff0000u)) +
+            (__builtin_bit_cast(float, u23 << 16) + __builtin_bit_cast(float, u23 & 0xffff0000u));
+
+    // O^T = O^T * corr + V^T P^T.
+    const uint32_t slot_off = (uint32_t)slot * Geo::SLOT_BYTES;
+#pragma unroll
+    for (int d4 = 0; d4 < DB; d4 += 4) {
+      s16x4_t vt[4];
+      read_vt4(v_off[d4] + slot_off, v_off[d4 + 1] + slot_off, v_off[d4 + 2] + slot_off,
+               v_off[d4 + 3] + slot_off, vt[0], vt[1], vt[2], vt[3]);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        o[d4 + u] *= corr;
+        o[d4 + u] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt[u], __builtin_bit_cast(s16x4_t, pf), o[d4 + u], 0, 0, 0);
+      }
+    }
+  }
+  wait_vmcnt<0>();                               // drain the (duplicate) prefetches before exit
+
+  const float l_tot = cross16_sum(l_run);
+  if (qcol >= nh) return;
+  const int h = h0 + qcol;
+  if (nparts == 1) {
+    const float inv = 1.0f / l_tot;
+    const int64_t ob = ((int64_t)qtok * a.Hq + h) * D + jj * 4;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      const float x0 = o[db][0] * inv, x1 = o[db][1] * inv, x2 = o[db][2] * inv, x3 = o[db][3] * inv;
+      if (a.out_bf16) {
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16_rne(x0) | ((uint32_t)f32_to_bf16_rne(x1) << 16);
+        pk.y = (uint32_t)f32_to_bf16_rne(x2) | ((uint32_t)f32_to_bf16_rne(x3) << 16);
+        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + ob + db * 16) = pk;
+      } else {
+        *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + ob + db * 16) = make_float4(x0, x1, x2, x3);
+      }
+    }
+  } else {
+    const int64_t ph = (int64_t)item * a.Hq + h;
+    float* pa = prm.w.part_acc + ph * D + jj * 4;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      *reinterpret_cast<float4*>(pa + db * 16) = make_float4(o[db][0], o[db][1], o[db][2], o[db][3]);
+    if (jj == 0) *reinterpret_cast<float2*>(prm.w.part_ml + ph * 2) = make_float2(m_run, l_tot);
+  }
+}
+
+}  // namespace rows_impl
+}  // namespace dsv

@@ -227,6 +227,26 @@ def test_prefill_scores_far_above_first_subtile():
     assert np.abs(got - ref).max() <= TOL
 
 
+def test_mixed_launch_equals_the_two_kernels_apart(monkeypatch):
+    """A batch with prefill tiles and row items can run both in one launch (DSV_MIXED_LAUNCH=1
+    forces it, =0 forces the two kernels one after the other; unset, the library chooses).  Same
+    kernel bodies, so the outputs are bit-equal."""
+    from gpu_harness import run_attention
+    for Hq, Hkv, D, segs in [(32, 8, 128, [(300, 420), (1, 900), (64, 64), (1, 17), (3, 200), (1, 5000)]),
+                             (16, 2, 64, [(70, 70), (1, 33), (2, 40)]),
+                             (64, 8, 128, [(129, 300), (1, 2500)])]:
+        b = gen.make_batch("mixed_eq", 66, Hq, Hkv, D, segs)
+        monkeypatch.setenv("DSV_MIXED_LAUNCH", "1")
+        one = run_attention(b)
+        monkeypatch.setenv("DSV_MIXED_LAUNCH", "0")
+        two = run_attention(b)
+        monkeypatch.delenv("DSV_MIXED_LAUNCH", raising=False)
+        auto = run_attention(b)
+        np.testing.assert_array_equal(one, two)
+        np.testing.assert_array_equal(auto, two)
+        assert np.abs(one - oracle_out(b)).max() <= TOL
+
+
 def test_config3_prefill_heavy_shrunk():
     check(gen.config3(shrink=8))
 
