@@ -445,6 +445,13 @@ def main():
             del d3
         extras["kv_append_c3"] = bench_append(gen.config3(threads=threads), 20, 3, hev)
         extras["c4_micro_request"] = bench_config4(threads, 10, 2, hev)
+        # The local scheduler's profile table (paper section 4.2) on the grid of the paper's
+        # batch-latency figure: prefill length x decode context x number of decodes -> step ms.
+        from paper_2504_09285_amd.local_scheduler import ProfileTable, sweep
+        tbl = sweep(ProfileTable(plen_step=512), plens=(0, 512, 1024), ctxs=(128, 1024), dnums=(8, 32, 64), steps=5)
+        extras["profile_table_ms"] = {"plen=%d,ctx=%d,dnum=%d" % k: round(v, 4) for k, v in sorted(tbl.entries().items())}
+        extras["max_prefill_allowed"] = {"target_ms=0.1,ctx=1024,dnum=32": tbl.max_prefill_allowed(0.1, 1024, 32),
+                                         "target_ms=0.2,ctx=1024,dnum=32": tbl.max_prefill_allowed(0.2, 1024, 32)}
         if args.full_extras:
             extras["c5_two_streams"] = bench_concurrent(gen.config5_attention(threads=threads),
                                                         gen.config5_handoff(layers=8, threads=threads), 5, hev)

@@ -1,0 +1,97 @@
+"""Host logic of the local scheduler (paper section 4.2, Algorithm 2): hand-worked cases from
+tests/golden/local_scheduler_cases.txt, and properties of the profile table."""
+import os
+
+import pytest
+
+from paper_2504_09285_amd.local_scheduler import PrefillRequest, ProfileTable, compose_batch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def load_cases():
+    recs, cases = [], []
+    for line in open(os.path.join(HERE, "golden", "local_scheduler_cases.txt")):
+        line = line.strip()
+        if line.startswith("T "):
+            p, c, d, t = line[2:].split()
+            recs.append((int(p), int(c), int(d), float(t)))
+        elif line.startswith("C "):
+            slo, ctxs, queue, m, picks = [x.strip() for x in line[2:].split("|")]
+            cases.append((float(slo), [int(x) for x in ctxs.split()], [int(x) for x in queue.split()], int(m),
+                          [tuple(int(y) for y in x.split(":")) for x in picks.split()]))
+    return recs, cases
+
+
+def table_from(recs):
+    t = ProfileTable(plen_step=256)
+    for r in recs:
+        t.record(*r)
+    return t
+
+
+def test_hand_worked_compositions():
+    recs, cases = load_cases()
+    assert len(cases) == 6
+    for slo, ctxs, queue, m, picks in cases:
+        b = compose_batch([PrefillRequest(i, n) for i, n in enumerate(queue)],
+                          [(100 + i, c) for i, c in enumerate(ctxs)], slo, table_from(recs))
+        assert b.dnum == len(ctxs) and b.decodes == [100 + i for i in range(len(ctxs))]   # every decode joins
+        assert b.budget == m, (slo, b.budget, m)
+        assert b.prefills == picks
+        assert b.plen == sum(t for _, t in picks) <= m
+
+
+def test_previous_batch_is_recorded_before_the_budget_is_read():
+    recs, _ = load_cases()
+    t = table_from(recs)
+    dq = [(i, 1000) for i in range(8)]
+    assert compose_batch([PrefillRequest(0, 5000)], dq, 30.0, t).budget == 768
+    # The last batch (1024 prefill tokens, 8 decodes at 1024) ran much faster than the table said:
+    # three such records pull the bucket's mean under the target.
+    for _ in range(3):
+        b = compose_batch([PrefillRequest(0, 5000)], dq, 30.0, t, previous=(1024, 1000, 8, 20.0))
+    assert b.budget == 1024 and b.prefills == [(0, 1024)]
+
+
+def test_buckets_round_up_and_predictions_are_never_optimistic():
+    t = ProfileTable(plen_step=256)
+    assert t.key(1, 1000, 5) == (256, 1024, 8) and t.key(0, 1000, 0) == (0, 0, 0) and t.key(257, 1025, 9) == (512, 2048, 16)
+    t.record(512, 1024, 8, 20.0)
+    assert t.predict(512, 1000, 7) == 20.0
+    assert t.predict(300, 600, 3) == 20.0          # falls back to the nearest record that dominates it
+    assert t.predict(513, 1024, 8) is None         # nothing at least as large: not affordable
+    assert t.max_prefill_allowed(25.0, 1024, 8) == 512
+    assert t.max_prefill_allowed(25.0, 4096, 8) == 0
+
+
+def test_budget_is_monotone_in_the_target_and_in_the_decode_load():
+    recs, _ = load_cases()
+    t = table_from(recs)
+    budgets = [t.max_prefill_allowed(s, 1024, 8) for s in (5, 12, 15, 20, 27, 36, 100)]
+    assert budgets == sorted(budgets) and budgets[0] == 0 and budgets[-1] == 1024
+    assert t.max_prefill_allowed(30, 1024, 32) <= t.max_prefill_allowed(30, 1024, 8)
+
+
+@pytest.mark.gpu
+def test_sweep_fills_the_table_and_the_budget_holds_on_the_gpu():
+    """The table measured on the GPU is monotone in plen, and a batch composed for a target
+    really runs within that target (with slack for timing noise)."""
+    import time
+
+    import numpy as np
+    import torch
+
+    import paper_2504_09285_amd as dsv
+    from paper_2504_09285_amd.local_scheduler import sweep
+    t = sweep(ProfileTable(plen_step=512), plens=(0, 512, 1024, 2048), ctxs=(1024,), dnums=(8, 64), steps=5)
+    e = t.entries()
+    assert len(e) == 8
+    for d in (8, 64):
+        lat = [e[(p, 1024, d)] for p in (0, 512, 1024, 2048)]
+        assert all(b > a * 0.9 for a, b in zip(lat, lat[1:])), lat          # grows with plen (10% noise margin)
+    slo = 0.5 * (e[(512, 1024, 64)] + e[(1024, 1024, 64)])
+    b = compose_batch([PrefillRequest(0, 4000)], [(i, 1000) for i in range(64)], slo, t)
+    assert b.budget == 512 and b.plen == 512
+    fresh = sweep(ProfileTable(plen_step=512), plens=(b.plen,), ctxs=(1024,), dnums=(64,), steps=5)
+    assert list(fresh.entries().values())[0] <= slo * 1.25
