@@ -445,6 +445,9 @@ def main():
             del d3
         extras["kv_append_c3"] = bench_append(gen.config3(threads=threads), 20, 3, hev)
         extras["c4_micro_request"] = bench_config4(threads, 10, 2, hev)
+        # Chunk-pipelined hand-off (paper section 4.3): transfer of chunk k next to computation of k+1.
+        from paper_2504_09285_amd.chunk_pipeline import measure as measure_chunk_pipeline
+        extras["chunk_pipelined_handoff"] = measure_chunk_pipeline(8192, 512, 8)
         # The local scheduler's profile table (paper section 4.2) on the grid of the paper's
         # batch-latency figure: prefill length x decode context x number of decodes -> step ms.
         from paper_2504_09285_amd.local_scheduler import ProfileTable, sweep

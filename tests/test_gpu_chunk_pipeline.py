@@ -1,0 +1,47 @@
+"""Chunk-pipelined hand-off on the GPU (paper section 4.3): with the transfer of chunk k chained
+by an event behind its computation and running next to chunk k+1, the receiver's pool must end
+up byte-identical to what the oracle's pack/unpack gives, untouched slots included, and the
+attention output must match the oracle's attention over the whole prompt."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2504_09285_amd.chunk_pipeline import ChunkedPrefill
+
+pytestmark = pytest.mark.gpu
+
+
+def host_u16(t):
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("pipelined", [True, False])
+def test_pipelined_handoff_matches_the_oracle(pipelined):
+    total, chunk, L, Hq, Hkv, D = 512, 64, 3, 8, 2, 128
+    p = ChunkedPrefill(total, chunk, L, Hq, Hkv, D, seed=77, dst_fill=0x7FC0)
+    p.run(pipelined)
+    k_new, v_new, q = host_u16(p.k_new), host_u16(p.v_new), host_u16(p.q)
+    # Oracle: the source pool after appending every token, then pack + unpack of all chunks.
+    nb = total // 16
+    src_k = np.zeros((L, nb, 16, Hkv, D), np.uint16)
+    src_v = np.zeros_like(src_k)
+    qo, cl = np.array([0, total], np.int32), np.array([total], np.int32)
+    for l in range(L):
+        oracle.kv_append(k_new[l], v_new[l], src_k[l], src_v[l], p.src_table_host, qo, cl)
+    np.testing.assert_array_equal(host_u16(p.src.k), src_k)
+    chunks = np.array([[0, k * chunk, chunk, k * p.chunk_elems] for k in range(p.n_chunks)], np.int64)
+    buf = np.zeros(p.n_chunks * p.chunk_elems, np.uint16)
+    oracle.kv_pack_chunks(src_k, src_v, p.src_table_host, chunks, buf)
+    dst_k = np.full_like(src_k, 0x7FC0)
+    dst_v = np.full_like(src_k, 0x7FC0)
+    oracle.kv_unpack_chunks(buf, chunks, dst_k, dst_v, p.dst_table_host)
+    np.testing.assert_array_equal(host_u16(p.recv_buf), buf)
+    np.testing.assert_array_equal(host_u16(p.dst.k), dst_k)
+    np.testing.assert_array_equal(host_u16(p.dst.v), dst_v)
+    # Attention of the chunked prefill == attention of the whole prompt (split-anywhere semantics).
+    for l in range(L):
+        ref = oracle.attn_mixed_batch(q=q[l], k_pool=src_k[l], v_pool=src_v[l], block_tables=p.src_table_host,
+                                      q_offsets=qo, ctx_lens=cl, scale=p.scale)
+        got = p.out[l].cpu().numpy()
+        assert np.isfinite(got).all() and np.abs(got - ref).max() <= 1e-2
