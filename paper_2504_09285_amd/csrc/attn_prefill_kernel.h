@@ -27,10 +27,15 @@
 //     [token][dim] layout.  LDS rows are XOR-swizzled at load time (each lane chooses which
 //     16 bytes of a row it fetches) so that both kinds of fragment reads are conflict-free.
 //
-// The loop over 32-token sub-tiles is software-pipelined: for sub-tile s the wave computes the
-// scores, then issues the V^T P^T MFMAs of sub-tile s-1 while its vector ALU does the softmax of
-// sub-tile s.  LDS reads are written in assembly: the compiler cannot know which bytes the direct
-// loads in flight will write and would drain all of them before every read.
+// The loop over 32-token sub-tiles is software-pipelined: stage s issues the MFMAs for the scores
+// of sub-tile s+1 and for V^T P^T of sub-tile s-1 together with the softmax of sub-tile s, one
+// basic block whose instructions interleave; the fragment reads from LDS roll along with the
+// MFMAs that consume them.  LDS reads are written in assembly: the compiler cannot know which
+// bytes the direct loads in flight will write and would drain all of them before every read.
+//
+// A first, fast pass keeps the softmax reference of a row fixed after its first sub-tile (no
+// per-stage row max, no accumulator rescale); if a row sum leaves the safe range the workgroup
+// repeats its work item in a robust pass with the usual running max.
 //
 // Scores are kept in the log2 domain.  Slots past the span's context (pool garbage) are fetched
 // from a line of zeros instead, and masked scores are excluded by select, so NaN/Inf there
