@@ -274,6 +274,26 @@ def test_config3_prefill_heavy_full_sampled_rows():
         assert err <= TOL, (i, j, h, err)
 
 
+def test_long_prefill_on_a_long_prefix_sampled_rows():
+    """A 8,192-token span resuming on a 24,576-token prefix (ctx 32,768: 512 KV tiles for the last
+    query tile), an unaligned one (ctx 20,011) and a few decodes, 64/8 heads: many tiles per work
+    item, the tile list sorted across spans, the mixed launch.  Sampled rows against the oracle."""
+    from gpu_harness import run_attention
+    b = gen.make_batch("long_prefill", 67, 64, 8, 128, [(8192, 32768), (1, 30000), (3011, 20011), (1, 777), (5, 9000)])
+    got = run_attention(b)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(4)
+    rows = [(0, j, int(rng.integers(b.Hq))) for j in (0, 1, 63, 64, 4095, 8127, 8128, 8191)]
+    rows += [(0, int(rng.integers(8192)), int(rng.integers(b.Hq))) for _ in range(10)]
+    rows += [(2, j, int(rng.integers(b.Hq))) for j in (0, 10, 2999, 3010)]
+    rows += [(2, int(rng.integers(3011)), int(rng.integers(b.Hq))) for _ in range(6)]
+    rows += [(1, 0, 5), (3, 0, 63), (4, 0, 0), (4, 4, 17)]
+    ref = oracle.attn_rows(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens, b.scale, rows)
+    for r, (i, j, h) in enumerate(rows):
+        err = np.abs(got[b.q_offsets[i] + j, h] - ref[r]).max()
+        assert err <= TOL, (i, j, h, err)
+
+
 def _config4_inputs(shrink):
     """Config 4 placement, CPU side: row 0 holds the prompt; row 1's tokens [k,L) are made equal to
     row 0's; tokens [0,k) reach row 1 by pack/unpack (done by the caller, oracle or GPU)."""
