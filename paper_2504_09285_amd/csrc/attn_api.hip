@@ -156,20 +156,29 @@ size_t carve(const PlanCounts& n, int Hq, int D, char* base, WorkLists* w) {
 // ---- plan: device work lists ---------------------------------------------------------------
 
 // Exclusive scan of one int per thread across the block; returns the block total in *total.
+// Each wave scans its 64 values with lane shuffles, the wave totals go through LDS, and every
+// thread adds the totals of the waves before its own: two barriers instead of two per doubling.
 __device__ int block_exclusive_scan(int v, int* smem, int* total) {
-  const int tid = threadIdx.x;
-  smem[tid] = v;
-  __syncthreads();
-  for (int off = 1; off < kPlanThreads; off <<= 1) {
-    const int add = tid >= off ? smem[tid - off] : 0;
-    __syncthreads();
-    smem[tid] += add;
-    __syncthreads();
+  constexpr int kPlanWaves = kPlanThreads / 64;
+  const int lane = (int)threadIdx.x & 63, wave = (int)threadIdx.x >> 6;
+  int incl = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int up = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += up;
   }
-  const int incl = smem[tid];
-  *total = smem[kPlanThreads - 1];
+  if (lane == 63) smem[wave] = incl;
   __syncthreads();
-  return incl - v;
+  int before = 0, all = 0;
+#pragma unroll
+  for (int k = 0; k < kPlanWaves; ++k) {
+    const int t = smem[k];
+    before += k < wave ? t : 0;
+    all += t;
+  }
+  *total = all;
+  __syncthreads();
+  return before + incl - v;
 }
 
 // Sort key of a tile: bucket 0 holds the tiles with the most KV tiles to visit.
@@ -184,7 +193,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
                                                             const int32_t* __restrict__ ctx_lens,
                                                             const int32_t* __restrict__ block_tables,
                                                             int32_t max_blocks, int32_t S, PlanConfig c,
-                                                            WorkLists w) {
+                                                            WorkLists w, int32_t has_tiles) {
   __shared__ int smem[kPlanThreads];
   __shared__ int tile_slot[kTileBuckets];
   if (threadIdx.x < 64) w.zero_line[threadIdx.x] = 0u;
@@ -193,9 +202,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
   // workgroups, dispatched in list order, leave no long tile for the end: a counting sort on
   // the KV tile count.  The order of equal keys is left to the atomics; it affects nothing but
   // the dispatch order.
-  for (int b = (int)threadIdx.x; b < kTileBuckets; b += kPlanThreads) tile_slot[b] = 0;
+  // A batch the host found no tile in (has_tiles == 0, uniform) skips the sort.
+  for (int b = (int)threadIdx.x; has_tiles && b < kTileBuckets; b += kPlanThreads) tile_slot[b] = 0;
   __syncthreads();
-  for (int i = (int)threadIdx.x; i < S; i += kPlanThreads) {
+  for (int i = (int)threadIdx.x; has_tiles && i < S; i += kPlanThreads) {
     const int q_len = q_offsets[i + 1] - q_offsets[i], ctx = ctx_lens[i];
     if (q_len > 0 && !on_row_path(q_len, c)) {
       const int n_tiles = (q_len + c.tile_tokens - 1) / c.tile_tokens;
@@ -203,7 +213,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
     }
   }
   __syncthreads();
-  {
+  if (has_tiles) {
     constexpr int kPer = kTileBuckets / kPlanThreads;
     int cnt[kPer], sum = 0, total;
     for (int k = 0; k < kPer; ++k) { cnt[k] = tile_slot[threadIdx.x * kPer + k]; sum += cnt[k]; }
@@ -427,7 +437,7 @@ extern "C" int attn_mixed_batch(const void* q, void* out, const dsv_kv_pool* poo
   {
     EventScope ev(DSV_KERNEL_PLAN, stream);
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, q_offsets, ctx_lens,
-                       block_tables, max_blocks_per_seq, num_seqs, cfg, w);
+                       block_tables, max_blocks_per_seq, num_seqs, cfg, w, n.tiles > 0 ? 1 : 0);
     if ((rc = launch_status())) return rc;
   }
   // A batch with both prefill tiles and row items can run them in one launch.
