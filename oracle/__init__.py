@@ -17,19 +17,21 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "oracle.c")
+_SRCS = [_SRC, os.path.join(_HERE, "oracle_fp8.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lock = threading.Lock()
 _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile oracle.c with gcc (OpenMP) into liboracle.so next to it."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    """Compile oracle.c and oracle_fp8.c with gcc (OpenMP) into liboracle.so next to them."""
+    stale = (not os.path.exists(_LIB)) or any(
+        os.path.getmtime(_LIB) < os.path.getmtime(src) for src in _SRCS)
     if force or stale:
         tmp = _LIB + ".tmp%d" % os.getpid()
         subprocess.check_call(
             ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
-             "-o", tmp, _SRC, "-lm"])
+             "-o", tmp] + _SRCS + ["-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -37,6 +39,8 @@ def build(force: bool = False) -> str:
 _i32p = np.ctypeslib.ndpointer(np.int32, flags="C_CONTIGUOUS")
 _i64p = np.ctypeslib.ndpointer(np.int64, flags="C_CONTIGUOUS")
 _u16p = np.ctypeslib.ndpointer(np.uint16, flags="C_CONTIGUOUS")
+_u8p = np.ctypeslib.ndpointer(np.uint8, flags="C_CONTIGUOUS")
+_f32p = np.ctypeslib.ndpointer(np.float32, flags="C_CONTIGUOUS")
 _f64p = np.ctypeslib.ndpointer(np.float64, flags="C_CONTIGUOUS")
 _c = ctypes
 
@@ -60,6 +64,19 @@ def _load():
             lib.oracle_kv_append.argtypes = [
                 _u16p, _u16p, _u16p, _u16p, _c.c_int32, _c.c_int32, _c.c_int32, _i32p, _c.c_int32,
                 _c.c_int32, _i32p, _i32p]
+            lib.oracle_e4m3_decode.argtypes = [_u8p, _c.c_int64, _f64p]
+            lib.oracle_e4m3_quantize.argtypes = [_u16p, _c.c_int64, _c.c_float, _u8p]
+            lib.oracle_e4m3_from_float.argtypes = [_f32p, _c.c_int64, _u8p]
+            lib.oracle_attn_rows_fp8kv.argtypes = [
+                _u16p, _u8p, _u8p, _i32p, _c.c_int32, _i32p, _i32p, _c.c_int32, _c.c_int32,
+                _c.c_int32, _c.c_int32, _c.c_int32, _c.c_double, _c.c_double, _c.c_double,
+                _c.c_int32, _i32p, _f64p]
+            lib.oracle_kv_append_fp8.argtypes = [
+                _u16p, _u16p, _u8p, _u8p, _c.c_int32, _c.c_int32, _c.c_int32, _i32p, _c.c_int32,
+                _c.c_int32, _i32p, _i32p, _c.c_float, _c.c_float]
+            for f in (lib.oracle_e4m3_decode, lib.oracle_e4m3_quantize, lib.oracle_e4m3_from_float,
+                      lib.oracle_attn_rows_fp8kv, lib.oracle_kv_append_fp8):
+                f.restype = _c.c_int
             for f in (lib.oracle_attn_mixed_batch, lib.oracle_attn_rows,
                       lib.oracle_attn_row_weights, lib.oracle_kv_pack_chunks,
                       lib.oracle_kv_unpack_chunks, lib.oracle_kv_append, lib.oracle_num_threads):
@@ -180,4 +197,97 @@ def kv_append(k_new, v_new, k_pool, v_pool, block_tables, q_offsets, ctx_lens):
                                   qo, cl)
     if rc:
         raise ValueError("oracle_kv_append: invalid problem (%d)" % rc)
+    return k_pool, v_pool
+
+
+# ---- 8-bit (E4M3) KV variant: oracle_fp8.c -------------------------------------------------
+
+def e4m3_decode(codes):
+    """Values of E4M3 codes (uint8, any shape) -> float64, NaN for 0x7f / 0xff."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    out = np.empty(codes.shape, dtype=np.float64)
+    rc = _load().oracle_e4m3_decode(codes.reshape(-1), codes.size, out.reshape(-1))
+    if rc:
+        raise ValueError("oracle_e4m3_decode: invalid arguments (%d)" % rc)
+    return out
+
+
+def e4m3_quantize(x_bf16, scale):
+    """Codes of bf16 inputs (uint16 bits, any shape): nearest E4M3 value of fp32(x)/scale."""
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
+    out = np.empty(x.shape, dtype=np.uint8)
+    rc = _load().oracle_e4m3_quantize(x.reshape(-1), x.size, float(scale), out.reshape(-1))
+    if rc:
+        raise ValueError("oracle_e4m3_quantize: invalid arguments (%d)" % rc)
+    return out
+
+
+def e4m3_from_float(y):
+    """Nearest E4M3 codes of fp32 values (the rounding rule alone, no scale)."""
+    y = np.ascontiguousarray(y, dtype=np.float32)
+    out = np.empty(y.shape, dtype=np.uint8)
+    rc = _load().oracle_e4m3_from_float(y.reshape(-1), y.size, out.reshape(-1))
+    if rc:
+        raise ValueError("oracle_e4m3_from_float: invalid arguments (%d)" % rc)
+    return out
+
+
+def _attn8_args(q, k_pool, v_pool, block_tables, q_offsets, ctx_lens, scale, k_scale, v_scale):
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    k_pool = np.ascontiguousarray(k_pool, dtype=np.uint8)
+    v_pool = np.ascontiguousarray(v_pool, dtype=np.uint8)
+    assert q.ndim == 3 and k_pool.ndim == 4 and k_pool.shape == v_pool.shape
+    _, Hq, D = q.shape
+    _, bs, Hkv, Dk = k_pool.shape
+    assert D == Dk
+    bt = _c32(block_tables)
+    qo, cl = _c32(q_offsets), _c32(ctx_lens)
+    S = cl.shape[0]
+    assert bt.ndim == 2 and qo.shape[0] == S + 1 and bt.shape[0] == S and qo[-1] == q.shape[0]
+    return (q, k_pool, v_pool, bt, bt.shape[1], qo, cl, S, Hq, Hkv, D, bs, float(scale),
+            float(k_scale), float(v_scale))
+
+
+def attn_rows_fp8kv(q, k_pool, v_pool, block_tables, q_offsets, ctx_lens, scale, k_scale, v_scale,
+                    rows):
+    """Selected rows on an E4M3 cache; rows: [n,3] = (segment, new-token index, head) -> [n,D]."""
+    args = _attn8_args(q, k_pool, v_pool, block_tables, q_offsets, ctx_lens, scale, k_scale, v_scale)
+    rows = _c32(rows).reshape(-1, 3)
+    out = np.empty((rows.shape[0], args[0].shape[2]), dtype=np.float64)
+    rc = _load().oracle_attn_rows_fp8kv(*args, rows.shape[0], rows, out)
+    if rc:
+        raise ValueError("oracle_attn_rows_fp8kv: invalid problem (%d)" % rc)
+    return out
+
+
+def attn_mixed_batch_fp8kv(q, k_pool, v_pool, block_tables, q_offsets, ctx_lens, scale, k_scale,
+                           v_scale):
+    """All rows on an E4M3 cache.  q: [total_q,Hq,D] u16; pools: [NB,bs,Hkv,D] u8 -> f64."""
+    qo = _c32(q_offsets)
+    Hq = q.shape[1]
+    rows = [(i, j, h) for i in range(len(qo) - 1) for j in range(int(qo[i + 1] - qo[i]))
+            for h in range(Hq)]
+    out = attn_rows_fp8kv(q, k_pool, v_pool, block_tables, q_offsets, ctx_lens, scale, k_scale,
+                          v_scale, np.asarray(rows, dtype=np.int32).reshape(-1, 3))
+    return out.reshape(q.shape[0], Hq, q.shape[2])
+
+
+def kv_append_fp8(k_new, v_new, k_pool, v_pool, block_tables, q_offsets, ctx_lens, k_scale,
+                  v_scale):
+    """Quantises the new tokens' K/V rows [total_q, Hkv, D] (bf16 bits) and writes the codes into
+    the one-layer uint8 pool [NB, 16, Hkv, D] in place."""
+    assert k_pool.ndim == 4 and k_pool.shape == v_pool.shape
+    for a in (k_new, v_new):
+        assert a.dtype == np.uint16 and a.flags.c_contiguous
+    for a in (k_pool, v_pool):
+        assert a.dtype == np.uint8 and a.flags.c_contiguous
+    _, bs, Hkv, D = k_pool.shape
+    assert k_new.shape == v_new.shape and k_new.shape[1:] == (Hkv, D)
+    bt, qo, cl = _c32(block_tables), _c32(q_offsets), _c32(ctx_lens)
+    assert k_new.shape[0] == int(qo[-1])
+    rc = _load().oracle_kv_append_fp8(k_new.reshape(-1), v_new.reshape(-1), k_pool.reshape(-1),
+                                      v_pool.reshape(-1), bs, Hkv, D, bt, bt.shape[1],
+                                      bt.shape[0], qo, cl, float(k_scale), float(v_scale))
+    if rc:
+        raise ValueError("oracle_kv_append_fp8: invalid problem (%d)" % rc)
     return k_pool, v_pool

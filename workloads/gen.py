@@ -164,6 +164,47 @@ def make_batch(name: str, seed: int, Hq: int, Hkv: int, D: int,
                      q_offsets, ctx_lens, dict(meta or {}))
 
 
+# ---- 8-bit KV variant --------------------------------------------------------------------
+# Exponent field of a drawn E4M3 code, indexed by four random bits: mostly around 1.0, a few
+# small and subnormal magnitudes, nothing above 7.5, never the NaN code.
+_E4M3_EXP_OF_NIBBLE = np.asarray([0, 1, 4, 5, 5, 6, 6, 6, 7, 7, 7, 7, 8, 8, 8, 9], dtype=np.uint8)
+TID_K8, TID_V8 = 21, 22
+
+
+def e4m3_codes(seed: int, tensor_id: int, shape) -> np.ndarray:
+    """Random E4M3 codes (uint8): sign and mantissa bits uniform, exponent field drawn from the
+    table above.  A pure bit recipe: no rounding or scaling of real values is involved."""
+    n = int(np.prod(shape))
+    out = np.empty(n, dtype=np.uint8)
+    for p in range((n + _PIECE - 1) // _PIECE):
+        lo, hi = p * _PIECE, min(n, (p + 1) * _PIECE)
+        u = _rng(seed, tensor_id, p).integers(0, 256, size=hi - lo, dtype=np.uint8)
+        out[lo:hi] = (u & np.uint8(0x87)) | (_E4M3_EXP_OF_NIBBLE[(u >> np.uint8(3)) & np.uint8(15)] << np.uint8(3))
+    return out.reshape(shape)
+
+
+def make_batch_fp8kv(name: str, seed: int, Hq: int, Hkv: int, D: int,
+                     segments: Sequence[Tuple[int, int]], k_scale: float = 0.5,
+                     v_scale: float = 0.5, free_frac: float = 0.10, min_blocks: int = 0,
+                     meta: Optional[dict] = None) -> AttnBatch:
+    """As make_batch, with the pools holding E4M3 codes (uint8) drawn by e4m3_codes; the two
+    dequantisation scales travel in ``meta``.  With the default scales the cached values have a
+    root mean square near 1 and magnitudes up to 3.75."""
+    q_lens = np.asarray([s[0] for s in segments], dtype=np.int32)
+    ctx_lens = np.asarray([s[1] for s in segments], dtype=np.int32)
+    assert (q_lens >= 1).all() and (ctx_lens >= q_lens).all()
+    q_offsets = np.zeros(len(segments) + 1, dtype=np.int32)
+    np.cumsum(q_lens, out=q_offsets[1:])
+    tables, nb = build_block_tables(seed, TID_PERM, ctx_lens, free_frac, min_blocks)
+    q = normal_bf16(seed, TID_Q, (int(q_offsets[-1]), Hq, D))
+    k_pool = e4m3_codes(seed, TID_K8, (nb, BLOCK_SIZE, Hkv, D))
+    v_pool = e4m3_codes(seed, TID_V8, (nb, BLOCK_SIZE, Hkv, D))
+    m = dict(meta or {})
+    m.update(k_scale=float(k_scale), v_scale=float(v_scale))
+    return AttnBatch(name, Hq, Hkv, D, 1.0 / math.sqrt(D), q, k_pool, v_pool, tables,
+                     q_offsets, ctx_lens, m)
+
+
 @dataclass
 class Handoff:
     """Chunked KV hand-off: source pool/table -> chunks -> destination pool/table."""
