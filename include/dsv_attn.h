@@ -155,6 +155,66 @@ int kv_append(const void* k_new, const void* v_new, const dsv_kv_pool* pool, int
               void* hip_stream);
 
 /*
+ * ---- 8-bit KV cache variant --------------------------------------------------------------
+ * The paper (sections 2.1, 3.1, 4.3) treats a token's KV as a payload whose size sets both the
+ * bytes a decode step streams and the bytes a hand-off ships, and leaves its number format
+ * open.  The entry points below are the same operations on a cache stored as one byte per
+ * element: codes of the OCP 8-bit floating point format E4M3 (1 sign, 4 exponent bits with bias
+ * 7, 3 mantissa bits; subnormals; no infinities; 0x7f/0xff = NaN; largest finite 448), with one
+ * positive finite fp32 scale per tensor:  value = scale * decode(code).
+ * The pool descriptor is the same struct; its elements are then bytes (layer_stride in bytes,
+ * a multiple of 16), and the chunk layout is the same with 1-byte elements (chunk_offset in
+ * bytes, a multiple of 16).
+ */
+
+/*
+ * attn_mixed_batch on a cache of E4M3 codes:
+ *   out[q_offsets[i]+j][h][:] = sum_t softmax_t(softmax_scale * <q, k_scale*K8[t]>) * v_scale*V8[t]
+ * Every argument as for attn_mixed_batch; k_scale, v_scale: the dequantisation scales of the
+ * layer (positive, finite, else DSV_E_INVALID).  The workspace is larger: prefill spans of 16
+ * and more tokens are computed from a bf16 copy of their whole contexts, made inside the call
+ * (exact: every code is a bf16 value), of 4 * head_dim * num_kv_heads bytes per cached token.
+ * Codes of cached tokens must not be NaN.
+ */
+size_t attn_mixed_batch_fp8kv_workspace_bytes(int32_t num_seqs, const int32_t* q_offsets_host,
+                                              const int32_t* ctx_lens_host, int32_t num_q_heads,
+                                              int32_t num_kv_heads, int32_t head_dim);
+int attn_mixed_batch_fp8kv(const void* q, void* out, const dsv_kv_pool* pool, int32_t layer,
+                           const int32_t* block_tables, int32_t max_blocks_per_seq,
+                           const int32_t* q_offsets, const int32_t* ctx_lens,
+                           const int32_t* q_offsets_host, const int32_t* ctx_lens_host,
+                           int32_t num_seqs, int32_t num_q_heads, float softmax_scale,
+                           float k_scale, float v_scale, int32_t out_dtype, void* workspace,
+                           size_t workspace_bytes, void* hip_stream);
+
+/*
+ * kv_append for a cache of E4M3 codes: the new tokens' bf16 keys/values are quantised on the
+ * way in.  The code of an input x is decided in fp32: y = fp32(x) / scale (one IEEE division),
+ * then the E4M3 value nearest to y, ties to the even mantissa; |y| >= 448 (infinities
+ * included) gives +-448; a NaN input gives a NaN code; the sign of zero is kept.
+ * Arguments as for kv_append; k_scale, v_scale positive and finite.
+ */
+int kv_append_fp8(const void* k_new, const void* v_new, const dsv_kv_pool* pool, int32_t layer,
+                  const int32_t* block_tables, int32_t max_blocks_per_seq,
+                  const int32_t* q_offsets, const int32_t* ctx_lens,
+                  const int32_t* q_offsets_host, const int32_t* ctx_lens_host, int32_t num_seqs,
+                  float k_scale, float v_scale, void* hip_stream);
+
+/*
+ * kv_pack_chunks / kv_unpack_chunks for a cache of 1-byte elements (paper section 4.3: the
+ * chunk is the unit of transfer whatever the payload).  Byte-exact copies; a chunk is half the
+ * size of its bf16 counterpart.  Arguments as for the bf16 calls, offsets in bytes.
+ */
+int kv_pack_chunks_fp8(const dsv_kv_pool* src, const int32_t* block_tables,
+                       int32_t max_blocks_per_seq, const dsv_chunk_desc* descs,
+                       const dsv_chunk_desc* descs_host, int32_t num_chunks, void* chunk_buf,
+                       void* hip_stream);
+int kv_unpack_chunks_fp8(const void* chunk_buf, const dsv_chunk_desc* descs,
+                         const dsv_chunk_desc* descs_host, int32_t num_chunks,
+                         const dsv_kv_pool* dst, const int32_t* dst_block_tables,
+                         int32_t max_blocks_per_seq, void* hip_stream);
+
+/*
  * Profiling aid for benchmarks (not needed for correct use).  Until cleared with NULLs, every
  * later attn_mixed_batch call made by the calling host thread records `start_event` on its
  * stream immediately before, and `stop_event` immediately after, the launch of the named
@@ -169,6 +229,7 @@ int kv_append(const void* k_new, const void* v_new, const dsv_kv_pool* pool, int
                               /* comparable amounts of both kinds of work runs instead of  */
                               /* ids 1 and 2 (environment DSV_MIXED_LAUNCH=0 / 1 forces    */
                               /* the two launches / the single one)                        */
+#define DSV_KERNEL_STAGE  5   /* bf16 copy of the prefill spans' contexts (8-bit cache only)  */
 int dsv_profile_events(int32_t kernel_id, void* start_event, void* stop_event);
 
 /* Library build identification: a static string, e.g. "dsv_attn gfx950 <date>". */

@@ -7,6 +7,7 @@ call goes to ``libdsv_attn.so``; there is no CPU or eager fallback, and a missin
 from .binding import (  # noqa: F401
     DSV_OUT_BF16, DSV_OUT_F32, ChunkDescs, DsvError, KVPool, attn_mixed_batch,
     attn_mixed_batch_workspace_bytes, build_info, dsv_profile_events, KERNEL_PLAN, KERNEL_ROWS,
-    KERNEL_TILES, KERNEL_MERGE, KERNEL_MIXED, kv_append, kv_pack_chunks, kv_unpack_chunks, library_path,
-    load_library,
+    KERNEL_TILES, KERNEL_MERGE, KERNEL_MIXED, KERNEL_STAGE, kv_append, kv_pack_chunks, kv_unpack_chunks,
+    library_path, load_library, attn_mixed_batch_fp8kv, attn_mixed_batch_fp8kv_workspace_bytes,
+    kv_append_fp8, kv_pack_chunks_fp8, kv_unpack_chunks_fp8,
 )

@@ -36,8 +36,10 @@ CHUNK_DTYPE = np.dtype([("seq", "<i4"), ("token_begin", "<i4"), ("num_tokens", "
 assert CHUNK_DTYPE.itemsize == 24
 
 EXPORTS = ("attn_mixed_batch_workspace_bytes", "attn_mixed_batch", "kv_pack_chunks",
-           "kv_unpack_chunks", "kv_append", "dsv_profile_events", "dsv_build_info")
-KERNEL_PLAN, KERNEL_ROWS, KERNEL_TILES, KERNEL_MERGE, KERNEL_MIXED = 0, 1, 2, 3, 4
+           "kv_unpack_chunks", "kv_append", "attn_mixed_batch_fp8kv_workspace_bytes",
+           "attn_mixed_batch_fp8kv", "kv_append_fp8", "kv_pack_chunks_fp8", "kv_unpack_chunks_fp8",
+           "dsv_profile_events", "dsv_build_info")
+KERNEL_PLAN, KERNEL_ROWS, KERNEL_TILES, KERNEL_MERGE, KERNEL_MIXED, KERNEL_STAGE = 0, 1, 2, 3, 4, 5
 
 
 def library_path() -> str:
@@ -67,6 +69,19 @@ def load_library():
     lib.kv_pack_chunks.argtypes = [C.POINTER(_Pool), vp, C.c_int32, vp, vp, C.c_int32, vp, vp]
     lib.kv_unpack_chunks.restype = C.c_int
     lib.kv_unpack_chunks.argtypes = [vp, vp, vp, C.c_int32, C.POINTER(_Pool), vp, C.c_int32, vp]
+    lib.attn_mixed_batch_fp8kv_workspace_bytes.restype = C.c_size_t
+    lib.attn_mixed_batch_fp8kv_workspace_bytes.argtypes = lib.attn_mixed_batch_workspace_bytes.argtypes
+    lib.attn_mixed_batch_fp8kv.restype = C.c_int
+    lib.attn_mixed_batch_fp8kv.argtypes = [vp, vp, C.POINTER(_Pool), C.c_int32, vp, C.c_int32, vp, vp,
+                                           i32p, i32p, C.c_int32, C.c_int32, C.c_float, C.c_float,
+                                           C.c_float, C.c_int32, vp, C.c_size_t, vp]
+    lib.kv_append_fp8.restype = C.c_int
+    lib.kv_append_fp8.argtypes = [vp, vp, C.POINTER(_Pool), C.c_int32, vp, C.c_int32, vp, vp, i32p,
+                                  i32p, C.c_int32, C.c_float, C.c_float, vp]
+    lib.kv_pack_chunks_fp8.restype = C.c_int
+    lib.kv_pack_chunks_fp8.argtypes = lib.kv_pack_chunks.argtypes
+    lib.kv_unpack_chunks_fp8.restype = C.c_int
+    lib.kv_unpack_chunks_fp8.argtypes = lib.kv_unpack_chunks.argtypes
     lib.dsv_profile_events.restype = C.c_int
     lib.dsv_profile_events.argtypes = [C.c_int32, vp, vp]
     lib.dsv_build_info.restype = C.c_char_p
@@ -104,11 +119,14 @@ def _stream_ptr(stream) -> Optional[int]:
 
 
 class KVPool:
-    """A paged KV pool held in two torch tensors ``[L, num_blocks, 16, Hkv, D]`` (bf16, device)."""
+    """A paged KV pool held in two torch tensors ``[L, num_blocks, 16, Hkv, D]`` on the device:
+    2-byte elements (bf16) for the plain entry points, 1-byte elements (E4M3 codes, e.g. uint8)
+    for the ``*_fp8`` / ``*_fp8kv`` ones."""
 
     def __init__(self, k, v):
         assert k.shape == v.shape and k.dim() == 5 and k.is_contiguous() and v.is_contiguous()
-        assert k.element_size() == 2 and v.element_size() == 2
+        assert k.element_size() == v.element_size() and k.element_size() in (1, 2)
+        self.elem_bytes = k.element_size()
         self.k, self.v = k, v
         L, NB, bs, Hkv, D = k.shape
         self.L, self.NB, self.bs, self.Hkv, self.D = L, NB, bs, Hkv, D
@@ -196,3 +214,73 @@ def kv_unpack_chunks(chunk_buf, descs: ChunkDescs, dst: KVPool, dst_block_tables
         dst_block_tables.data_ptr(), int(dst_block_tables.shape[1]), _stream_ptr(stream))
     if rc:
         raise DsvError("kv_unpack_chunks", rc)
+
+
+# ---- 8-bit KV cache variant ------------------------------------------------------------------
+
+def attn_mixed_batch_fp8kv_workspace_bytes(q_offsets_host, ctx_lens_host, num_q_heads, num_kv_heads,
+                                           head_dim) -> int:
+    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
+    return int(load_library().attn_mixed_batch_fp8kv_workspace_bytes(
+        cl.shape[0], _i32_ptr(qo), _i32_ptr(cl), num_q_heads, num_kv_heads, head_dim))
+
+
+def attn_mixed_batch_fp8kv(q, out, pool: KVPool, layer, block_tables, q_offsets, ctx_lens,
+                           q_offsets_host, ctx_lens_host, num_q_heads, softmax_scale, k_scale,
+                           v_scale, workspace, stream=None) -> None:
+    """See ``attn_mixed_batch_fp8kv`` in include/dsv_attn.h; ``pool`` holds 1-byte elements."""
+    import torch
+    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
+    out_dtype = DSV_OUT_F32 if out.dtype == torch.float32 else DSV_OUT_BF16
+    assert pool.elem_bytes == 1
+    assert out.dtype in (torch.float32, torch.bfloat16)
+    assert block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous()
+    assert q_offsets.dtype == torch.int32 and ctx_lens.dtype == torch.int32
+    assert q.is_contiguous() and out.is_contiguous() and q.element_size() == 2
+    assert tuple(q.shape) == tuple(out.shape)
+    rc = load_library().attn_mixed_batch_fp8kv(
+        q.data_ptr(), out.data_ptr(), pool.c, int(layer), block_tables.data_ptr(),
+        int(block_tables.shape[1]), q_offsets.data_ptr(), ctx_lens.data_ptr(), _i32_ptr(qo), _i32_ptr(cl),
+        int(cl.shape[0]), int(num_q_heads), float(softmax_scale), float(k_scale), float(v_scale),
+        out_dtype, workspace.data_ptr(), int(workspace.numel() * workspace.element_size()),
+        _stream_ptr(stream))
+    if rc:
+        raise DsvError("attn_mixed_batch_fp8kv", rc)
+
+
+def kv_append_fp8(k_new, v_new, pool: KVPool, layer, block_tables, q_offsets, ctx_lens,
+                  q_offsets_host, ctx_lens_host, k_scale, v_scale, stream=None) -> None:
+    """See ``kv_append_fp8`` in include/dsv_attn.h: bf16 rows in, E4M3 codes stored."""
+    import torch
+    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
+    assert pool.elem_bytes == 1
+    assert k_new.is_contiguous() and v_new.is_contiguous() and k_new.element_size() == 2
+    assert tuple(k_new.shape) == tuple(v_new.shape)
+    assert block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous()
+    assert q_offsets.dtype == torch.int32 and ctx_lens.dtype == torch.int32
+    rc = load_library().kv_append_fp8(
+        k_new.data_ptr(), v_new.data_ptr(), pool.c, int(layer), block_tables.data_ptr(),
+        int(block_tables.shape[1]), q_offsets.data_ptr(), ctx_lens.data_ptr(), _i32_ptr(qo), _i32_ptr(cl),
+        int(cl.shape[0]), float(k_scale), float(v_scale), _stream_ptr(stream))
+    if rc:
+        raise DsvError("kv_append_fp8", rc)
+
+
+def kv_pack_chunks_fp8(src: KVPool, block_tables, descs: ChunkDescs, chunk_buf, stream=None) -> None:
+    """See ``kv_pack_chunks_fp8`` in include/dsv_attn.h."""
+    assert src.elem_bytes == 1 and block_tables.is_contiguous() and chunk_buf.is_contiguous()
+    rc = load_library().kv_pack_chunks_fp8(
+        src.c, block_tables.data_ptr(), int(block_tables.shape[1]), descs.dev.data_ptr(),
+        descs.host.ctypes.data, descs.n, chunk_buf.data_ptr(), _stream_ptr(stream))
+    if rc:
+        raise DsvError("kv_pack_chunks_fp8", rc)
+
+
+def kv_unpack_chunks_fp8(chunk_buf, descs: ChunkDescs, dst: KVPool, dst_block_tables, stream=None) -> None:
+    """See ``kv_unpack_chunks_fp8`` in include/dsv_attn.h."""
+    assert dst.elem_bytes == 1 and dst_block_tables.is_contiguous() and chunk_buf.is_contiguous()
+    rc = load_library().kv_unpack_chunks_fp8(
+        chunk_buf.data_ptr(), descs.dev.data_ptr(), descs.host.ctypes.data, descs.n, dst.c,
+        dst_block_tables.data_ptr(), int(dst_block_tables.shape[1]), _stream_ptr(stream))
+    if rc:
+        raise DsvError("kv_unpack_chunks_fp8", rc)

@@ -17,7 +17,7 @@ namespace {
 constexpr int kPlanThreads = 1024;
 
 // Benchmark hook: event pairs recorded around individual kernels (see dsv_profile_events).
-thread_local hipEvent_t g_events[5][2] = {};
+thread_local hipEvent_t g_events[6][2] = {};
 
 struct EventScope {
   hipEvent_t stop;
@@ -72,12 +72,19 @@ int validate_batch(int32_t S, const int32_t* qo, const int32_t* cl, int32_t max_
   return DSV_OK;
 }
 
-PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl) {
+PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8) {
   PlanConfig c;
   c.mfma_min_qlen = env_int("DSV_MFMA_MIN_QLEN", 16);
   c.tile_tokens = 64;
-  c.row_nbuf = env_int("DSV_ROW_NBUF", 2);
-  if (c.row_nbuf != 3 && c.row_nbuf != 4) c.row_nbuf = 2;
+  // LDS ring slots per wave of the row kernel.  A slot of 8-bit codes is half the size, so twice
+  // as many keep the same number of bytes in flight.
+  if (kv8) {
+    c.row_nbuf = env_int("DSV_ROW_NBUF", 4);
+    if (c.row_nbuf != 2 && c.row_nbuf != 8) c.row_nbuf = 4;
+  } else {
+    c.row_nbuf = env_int("DSV_ROW_NBUF", 2);
+    if (c.row_nbuf != 3 && c.row_nbuf != 4) c.row_nbuf = 2;
+  }
   c.num_cus = device_cus();
   // Partition size: enough (row, partition) items to fill 256 CUs several times over, but not so
   // small that the partial results written per partition matter next to the KV bytes read.
@@ -116,6 +123,10 @@ PlanCounts count_plan(int32_t S, const int32_t* qo, const int32_t* cl, const Pla
     } else {
       n.tiles += ceil_div(q_len, c.tile_tokens);
       n.tile_pairs += (int64_t)q_len * (cl[i] - q_len) + (int64_t)q_len * (q_len + 1) / 2;
+      const int nblk = ceil_div(cl[i], kBlockSize);
+      n.stage_segs += 1;
+      n.stage_blocks += nblk;
+      if (nblk > n.stage_max_blocks) n.stage_max_blocks = nblk;
     }
   }
   return n;
@@ -125,7 +136,7 @@ PlanCounts count_plan(int32_t S, const int32_t* qo, const int32_t* cl, const Pla
 
 size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
-size_t carve(const PlanCounts& n, int Hq, int D, char* base, WorkLists* w) {
+size_t carve(const PlanCounts& n, int S, int Hq, int Hkv, int D, bool kv8, char* base, WorkLists* w) {
   size_t off = 0;
   auto take = [&](size_t bytes) {
     char* p = base ? base + off : nullptr;
@@ -141,7 +152,16 @@ size_t carve(const PlanCounts& n, int Hq, int D, char* base, WorkLists* w) {
   char* pc = take(items * 4);
   char* p9 = take(items * (size_t)Hq * D * 4);
   char* p10 = take(items * (size_t)Hq * 2 * 4);
+  char *s0 = nullptr, *s1 = nullptr, *s2 = nullptr, *s3 = nullptr, *s4 = nullptr, *s5 = nullptr;
+  if (kv8 && n.tiles) {
+    const size_t blk_bytes = (size_t)kBlockSize * Hkv * D * 2;
+    s0 = take((size_t)n.stage_segs * 4); s1 = take((size_t)S * 4); s2 = take((size_t)n.stage_segs * 4);
+    s3 = take((size_t)n.stage_segs * n.stage_max_blocks * 4);
+    s4 = take((size_t)n.stage_blocks * blk_bytes); s5 = take((size_t)n.stage_blocks * blk_bytes);
+  }
   if (w) {
+    w->stage_seq = (int32_t*)s0; w->stage_rows = (int32_t*)s1; w->stage_blk0 = (int32_t*)s2;
+    w->stage_table = (int32_t*)s3; w->stage_k = (uint16_t*)s4; w->stage_v = (uint16_t*)s5;
     w->row_seq = (int32_t*)p0; w->row_qtok = (int32_t*)p1; w->row_ctx = (int32_t*)p2;
     w->row_item0 = (int32_t*)p3; w->row_nparts = (int32_t*)p4;
     w->item_rec = (int4*)p5;
@@ -193,7 +213,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
                                                             const int32_t* __restrict__ ctx_lens,
                                                             const int32_t* __restrict__ block_tables,
                                                             int32_t max_blocks, int32_t S, PlanConfig c,
-                                                            WorkLists w, int32_t has_tiles) {
+                                                            WorkLists w, int32_t has_tiles,
+                                                            int32_t stage) {
   __shared__ int smem[kPlanThreads];
   __shared__ int tile_slot[kTileBuckets];
   if (threadIdx.x < 64) w.zero_line[threadIdx.x] = 0u;
@@ -222,7 +243,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
     __syncthreads();
   }
 
-  int row_carry = 0, item_carry = 0;
+  int row_carry = 0, item_carry = 0, stage_carry = 0, sblk_carry = 0;
   for (int base = 0; base < S; base += kPlanThreads) {
     const int i = base + (int)threadIdx.x;
     int q0 = 0, q_len = 0, ctx = 0, n_rows = 0, n_items = 0, n_tiles = 0;
@@ -259,6 +280,22 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
     }
     row_carry += tot_rows;
     item_carry += tot_items;
+    if (stage) {
+      // Segments on the MFMA path, in segment order, and the staged blocks of their contexts
+      // (uniform branch: `stage` is a kernel argument).
+      const int is_staged = n_tiles > 0 ? 1 : 0;
+      const int n_sblk = is_staged ? (ctx + kBlockSize - 1) / kBlockSize : 0;
+      int tot_s, tot_b;
+      const int s0 = stage_carry + block_exclusive_scan(is_staged, smem, &tot_s);
+      const int sb0 = sblk_carry + block_exclusive_scan(n_sblk, smem, &tot_b);
+      if (i < S) w.stage_rows[i] = is_staged ? s0 : -1;
+      if (is_staged) {
+        w.stage_seq[s0] = i;
+        w.stage_blk0[s0] = sb0;
+      }
+      stage_carry += tot_s;
+      sblk_carry += tot_b;
+    }
   }
   // Second pass, all threads: the id of each item's first block, so that the row kernel can
   // request its first K/V block as soon as it has read the item record.
@@ -341,7 +378,7 @@ __global__ __launch_bounds__(256) void merge_kernel(AttnArgs a, WorkLists w) {
     }
   }
   if (!h_ok) return;
-  const float inv = 1.0f / l_run;
+  const float inv = a.out_scale / l_run;
   acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
   const int64_t o = ((int64_t)w.row_qtok[r] * a.Hq + h) * D + d4 * 4;
   if (a.out_bf16) {
@@ -354,7 +391,54 @@ __global__ __launch_bounds__(256) void merge_kernel(AttnArgs a, WorkLists w) {
   }
 }
 
+
+// ---- bf16 staging of 8-bit contexts ----------------------------------------------------------
+// With a cache of E4M3 codes the MFMA kernel does not widen K/V itself: every K/V tile is read
+// by many query tiles, so the contexts of the segments it serves are widened once, here, into a
+// private run of bf16 blocks with a block table of its own, and the MFMA kernel runs on that
+// copy unchanged.  The copy is exact (every E4M3 value is a bf16 value); the dequantisation
+// scales are applied to the scores and to the normalised output instead.
+// One workgroup per (block of a staged context): reads 16 bytes of codes per thread and writes
+// 32 bytes of bf16, K then V.
+__global__ __launch_bounds__(256) void stage_kernel(AttnArgs a, WorkLists w, int32_t table_stride) {
+  const int s = blockIdx.y, b = blockIdx.x;
+  const int seq = w.stage_seq[s];
+  const int nblk = (a.ctx_lens[seq] + kBlockSize - 1) / kBlockSize;
+  if (b >= nblk) return;                                   // uniform for the workgroup
+  const int64_t src = a.block_tables[(int64_t)seq * a.max_blocks + b];
+  const int64_t dst = w.stage_blk0[s] + b;
+  if (threadIdx.x == 0) w.stage_table[(int64_t)s * table_stride + b] = (int32_t)dst;
+  const int units = a.Hkv * a.D;                           // 16-byte units of codes per block and tensor
+  const int64_t blk_elems = (int64_t)kBlockSize * a.Hkv * a.D;
+#pragma unroll
+  for (int kv = 0; kv < 2; ++kv) {
+    const uint4* in = reinterpret_cast<const uint4*>(
+        reinterpret_cast<const unsigned char*>(kv ? a.v_pool : a.k_pool) + src * blk_elems);
+    uint4* outp = reinterpret_cast<uint4*>((kv ? w.stage_v : w.stage_k) + dst * blk_elems);
+    for (int u = (int)threadIdx.x; u < units; u += 256) {
+      const uint4 c = in[u];
+      const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
+      uint32_t r[8];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        r[2 * k] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)cw[k], 1.0f, false));
+        r[2 * k + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)cw[k], 1.0f, true));
+      }
+      outp[2 * u] = make_uint4(r[0], r[1], r[2], r[3]);
+      outp[2 * u + 1] = make_uint4(r[4], r[5], r[6], r[7]);
+    }
+  }
+}
+
 }  // namespace
+
+int launch_stage(const AttnArgs& a, const WorkLists& w, const PlanCounts& n, hipStream_t stream) {
+  if (!a.kv8 || n.tiles == 0) return DSV_OK;
+  dim3 grid((unsigned)n.stage_max_blocks, (unsigned)n.stage_segs);
+  if (n.stage_segs > 65535) return DSV_E_UNSUPPORTED;
+  hipLaunchKernelGGL(stage_kernel, grid, dim3(256), 0, stream, a, w, n.stage_max_blocks);
+  return launch_status();
+}
 
 int launch_merge(const AttnArgs& a, const WorkLists& w, const PlanCounts& n, hipStream_t stream) {
   if (n.split_items == 0) return DSV_OK;
@@ -372,24 +456,27 @@ int launch_merge(const AttnArgs& a, const WorkLists& w, const PlanCounts& n, hip
 
 using namespace dsv;
 
-extern "C" size_t attn_mixed_batch_workspace_bytes(int32_t num_seqs, const int32_t* q_offsets_host,
-                                                   const int32_t* ctx_lens_host, int32_t num_q_heads,
-                                                   int32_t num_kv_heads, int32_t head_dim) {
+namespace {
+
+size_t workspace_bytes_for(bool kv8, int32_t num_seqs, const int32_t* q_offsets_host,
+                           const int32_t* ctx_lens_host, int32_t num_q_heads, int32_t num_kv_heads,
+                           int32_t head_dim) {
   if (num_q_heads < 1 || num_kv_heads < 1 || num_q_heads % num_kv_heads) return 0;
   if (head_dim != 64 && head_dim != 128) return 0;
   if (validate_batch(num_seqs, q_offsets_host, ctx_lens_host, -1) != DSV_OK) return 0;
-  const PlanConfig c = choose_plan(num_seqs, q_offsets_host, ctx_lens_host);
+  const PlanConfig c = choose_plan(num_seqs, q_offsets_host, ctx_lens_host, kv8);
   const PlanCounts n = count_plan(num_seqs, q_offsets_host, ctx_lens_host, c);
-  return carve(n, num_q_heads, head_dim, nullptr, nullptr);
+  return carve(n, num_seqs, num_q_heads, num_kv_heads, head_dim, kv8, nullptr, nullptr);
 }
 
-extern "C" int attn_mixed_batch(const void* q, void* out, const dsv_kv_pool* pool, int32_t layer,
-                                const int32_t* block_tables, int32_t max_blocks_per_seq,
-                                const int32_t* q_offsets, const int32_t* ctx_lens,
-                                const int32_t* q_offsets_host, const int32_t* ctx_lens_host,
-                                int32_t num_seqs, int32_t num_q_heads, float softmax_scale,
-                                int32_t out_dtype, void* workspace, size_t workspace_bytes,
-                                void* hip_stream) {
+// Both entry points.  kv8: the pool holds E4M3 codes (one byte per element) with the two
+// dequantisation scales; otherwise bf16 and both scales are 1.
+int run_attention(bool kv8, float k_scale, float v_scale, const void* q, void* out,
+                  const dsv_kv_pool* pool, int32_t layer, const int32_t* block_tables,
+                  int32_t max_blocks_per_seq, const int32_t* q_offsets, const int32_t* ctx_lens,
+                  const int32_t* q_offsets_host, const int32_t* ctx_lens_host, int32_t num_seqs,
+                  int32_t num_q_heads, float softmax_scale, int32_t out_dtype, void* workspace,
+                  size_t workspace_bytes, void* hip_stream) {
   int rc = check_pool(pool);
   if (rc) return rc;
   if (num_seqs < 0) return DSV_E_INVALID;
@@ -399,29 +486,32 @@ extern "C" int attn_mixed_batch(const void* q, void* out, const dsv_kv_pool* poo
   if (num_q_heads < 1 || num_q_heads % pool->num_kv_heads) return DSV_E_INVALID;
   if (out_dtype != DSV_OUT_F32 && out_dtype != DSV_OUT_BF16) return DSV_E_INVALID;
   if (!(softmax_scale >= 0.0f) || isinf(softmax_scale)) return DSV_E_INVALID;
+  if (!(k_scale > 0.0f) || isinf(k_scale) || !(v_scale > 0.0f) || isinf(v_scale)) return DSV_E_INVALID;
   if ((reinterpret_cast<uintptr_t>(q) & 15) || (reinterpret_cast<uintptr_t>(out) & 15) ||
       (reinterpret_cast<uintptr_t>(pool->k_base) & 15) || (reinterpret_cast<uintptr_t>(pool->v_base) & 15) ||
       (reinterpret_cast<uintptr_t>(workspace) & 255))
     return DSV_E_INVALID;
-  if (pool->num_layers > 1 && (pool->layer_stride % 8)) return DSV_E_INVALID;
+  const int elem_bytes = kv8 ? 1 : 2;
+  if (pool->num_layers > 1 && (pool->layer_stride * elem_bytes % 16)) return DSV_E_INVALID;
   rc = validate_batch(num_seqs, q_offsets_host, ctx_lens_host, max_blocks_per_seq);
   if (rc) return rc;
 
-  const PlanConfig cfg = choose_plan(num_seqs, q_offsets_host, ctx_lens_host);
+  const PlanConfig cfg = choose_plan(num_seqs, q_offsets_host, ctx_lens_host, kv8);
   const PlanCounts n = count_plan(num_seqs, q_offsets_host, ctx_lens_host, cfg);
   if (n.items > 0x7fffffffLL || n.tiles > 0x7fffffffLL || n.rows > 0x7fffffffLL ||
-      n.max_parts > 0xffff)
+      n.max_parts > 0xffff || n.stage_blocks > 0x7fffffffLL)
     return DSV_E_UNSUPPORTED;
   WorkLists w;
-  const size_t need = carve(n, num_q_heads, pool->head_dim, static_cast<char*>(workspace), &w);
+  const size_t need = carve(n, num_seqs, num_q_heads, pool->num_kv_heads, pool->head_dim, kv8,
+                            static_cast<char*>(workspace), &w);
   if (workspace_bytes < need) return DSV_E_WORKSPACE;
 
   AttnArgs a;
-  const int64_t layer_off = pool->num_layers > 1 ? (int64_t)layer * pool->layer_stride : 0;
+  const int64_t layer_off = pool->num_layers > 1 ? (int64_t)layer * pool->layer_stride * elem_bytes : 0;
   a.q = static_cast<const uint16_t*>(q);
   a.out = out;
-  a.k_pool = static_cast<const uint16_t*>(pool->k_base) + layer_off;
-  a.v_pool = static_cast<const uint16_t*>(pool->v_base) + layer_off;
+  a.k_pool = reinterpret_cast<const uint16_t*>(static_cast<const unsigned char*>(pool->k_base) + layer_off);
+  a.v_pool = reinterpret_cast<const uint16_t*>(static_cast<const unsigned char*>(pool->v_base) + layer_off);
   a.block_tables = block_tables;
   a.q_offsets = q_offsets;
   a.ctx_lens = ctx_lens;
@@ -430,15 +520,23 @@ extern "C" int attn_mixed_batch(const void* q, void* out, const dsv_kv_pool* poo
   a.Hq = num_q_heads;
   a.Hkv = pool->num_kv_heads;
   a.D = pool->head_dim;
-  a.scale_log2e = softmax_scale * 1.4426950408889634f;
+  a.scale_log2e = kv8 ? softmax_scale * k_scale * 1.4426950408889634f : softmax_scale * 1.4426950408889634f;
   a.out_bf16 = out_dtype == DSV_OUT_BF16;
+  a.out_scale = kv8 ? v_scale : 1.0f;
+  a.kv8 = kv8 ? 1 : 0;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const bool stage = kv8 && n.tiles > 0;
   {
     EventScope ev(DSV_KERNEL_PLAN, stream);
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, q_offsets, ctx_lens,
-                       block_tables, max_blocks_per_seq, num_seqs, cfg, w, n.tiles > 0 ? 1 : 0);
+                       block_tables, max_blocks_per_seq, num_seqs, cfg, w, n.tiles > 0 ? 1 : 0,
+                       stage ? 1 : 0);
     if ((rc = launch_status())) return rc;
+  }
+  if (stage) {
+    EventScope ev(DSV_KERNEL_STAGE, stream);
+    if ((rc = launch_stage(a, w, n, stream))) return rc;
   }
   // A batch with both prefill tiles and row items can run them in one launch.
   // Mixing pays when neither kind of work is a small fraction of the other (measured: a fifth
@@ -473,8 +571,50 @@ extern "C" int attn_mixed_batch(const void* q, void* out, const dsv_kv_pool* poo
   return DSV_OK;
 }
 
+}  // namespace
+
+extern "C" size_t attn_mixed_batch_workspace_bytes(int32_t num_seqs, const int32_t* q_offsets_host,
+                                                   const int32_t* ctx_lens_host, int32_t num_q_heads,
+                                                   int32_t num_kv_heads, int32_t head_dim) {
+  return workspace_bytes_for(false, num_seqs, q_offsets_host, ctx_lens_host, num_q_heads,
+                             num_kv_heads, head_dim);
+}
+
+extern "C" size_t attn_mixed_batch_fp8kv_workspace_bytes(int32_t num_seqs, const int32_t* q_offsets_host,
+                                                         const int32_t* ctx_lens_host,
+                                                         int32_t num_q_heads, int32_t num_kv_heads,
+                                                         int32_t head_dim) {
+  return workspace_bytes_for(true, num_seqs, q_offsets_host, ctx_lens_host, num_q_heads,
+                             num_kv_heads, head_dim);
+}
+
+extern "C" int attn_mixed_batch(const void* q, void* out, const dsv_kv_pool* pool, int32_t layer,
+                                const int32_t* block_tables, int32_t max_blocks_per_seq,
+                                const int32_t* q_offsets, const int32_t* ctx_lens,
+                                const int32_t* q_offsets_host, const int32_t* ctx_lens_host,
+                                int32_t num_seqs, int32_t num_q_heads, float softmax_scale,
+                                int32_t out_dtype, void* workspace, size_t workspace_bytes,
+                                void* hip_stream) {
+  return run_attention(false, 1.0f, 1.0f, q, out, pool, layer, block_tables, max_blocks_per_seq,
+                       q_offsets, ctx_lens, q_offsets_host, ctx_lens_host, num_seqs, num_q_heads,
+                       softmax_scale, out_dtype, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int attn_mixed_batch_fp8kv(const void* q, void* out, const dsv_kv_pool* pool, int32_t layer,
+                                      const int32_t* block_tables, int32_t max_blocks_per_seq,
+                                      const int32_t* q_offsets, const int32_t* ctx_lens,
+                                      const int32_t* q_offsets_host, const int32_t* ctx_lens_host,
+                                      int32_t num_seqs, int32_t num_q_heads, float softmax_scale,
+                                      float k_scale, float v_scale, int32_t out_dtype,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return run_attention(true, k_scale, v_scale, q, out, pool, layer, block_tables,
+                       max_blocks_per_seq, q_offsets, ctx_lens, q_offsets_host, ctx_lens_host,
+                       num_seqs, num_q_heads, softmax_scale, out_dtype, workspace, workspace_bytes,
+                       hip_stream);
+}
+
 extern "C" int dsv_profile_events(int32_t kernel_id, void* start_event, void* stop_event) {
-  if (kernel_id < 0 || kernel_id > 4) return DSV_E_INVALID;
+  if (kernel_id < 0 || kernel_id > 5) return DSV_E_INVALID;
   g_events[kernel_id][0] = static_cast<hipEvent_t>(start_event);
   g_events[kernel_id][1] = static_cast<hipEvent_t>(stop_event);
   return DSV_OK;

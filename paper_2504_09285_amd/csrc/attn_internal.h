@@ -29,6 +29,11 @@ struct PlanCounts {
   int32_t max_parts = 0;
   int64_t row_tokens = 0;  // KV tokens the row path streams (per KV head)
   int64_t tile_pairs = 0;  // causal (query, key) pairs of the MFMA path (per query head)
+  // Filled only for a cache of 8-bit codes: the MFMA path then reads a bf16 copy of the whole
+  // context of every segment it serves.
+  int64_t stage_segs = 0;        // segments on the MFMA path
+  int64_t stage_blocks = 0;      // KV blocks of their contexts, summed
+  int32_t stage_max_blocks = 0;  // largest number of blocks of one of them
 };
 
 // Device-resident work lists, carved out of the caller's workspace.
@@ -46,6 +51,13 @@ struct WorkLists {
   int32_t* item_blk0;      // [items] pool block id of the item's first block
   float*   part_acc;       // [items][Hq][D]  unnormalised partial outputs
   float*   part_ml;        // [items][Hq][2]  running max (log2 domain) and sum
+  // bf16 copy of the MFMA path's contexts (cache of 8-bit codes only, else null)
+  int32_t* stage_seq;      // [stage_segs] segment of each staged context
+  int32_t* stage_rows;     // [num_seqs] index into stage_seq / row of stage_table, or -1
+  int32_t* stage_blk0;     // [stage_segs] first staged block of the context
+  int32_t* stage_table;    // [stage_segs][stage_max_blocks] block table over the staged blocks
+  uint16_t* stage_k;       // [stage_blocks][16][Hkv][D] bf16
+  uint16_t* stage_v;
 };
 
 struct AttnArgs {
@@ -60,12 +72,18 @@ struct AttnArgs {
   int32_t num_seqs;
   int32_t Hq, Hkv, D;
   float scale_log2e;           // softmax_scale * log2(e): scores are kept in the log2 domain
+                               // (times the K dequantisation scale for a cache of 8-bit codes)
   int32_t out_bf16;
+  float out_scale;             // multiplies the normalised output: 1, or the V dequantisation scale
+  int32_t kv8;                 // 0: k_pool/v_pool hold bf16; 1: E4M3 codes, one byte per element
+                               // (same geometry; the row kernel widens them in registers)
 };
 
 int launch_rows(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg,
                 const PlanCounts& n, hipStream_t stream);
 int launch_merge(const AttnArgs& a, const WorkLists& w, const PlanCounts& n, hipStream_t stream);
+// Widens the 8-bit contexts of the MFMA path's segments into the staged bf16 blocks.
+int launch_stage(const AttnArgs& a, const WorkLists& w, const PlanCounts& n, hipStream_t stream);
 int launch_prefill_tiles(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg,
                          const PlanCounts& n, hipStream_t stream);
 // Prefill tiles and row items in one launch (same results as the two launches above).

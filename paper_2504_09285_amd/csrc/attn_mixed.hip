@@ -45,7 +45,7 @@ __global__ __launch_bounds__(512, 2) void mixed_kernel(prefill_impl::TilesParams
     const uint32_t wg = (g - t0) * kGroup + lane_in_group;
     if (wg >= mp.row_wgs) return;
     const uint32_t bx = wg % mp.rows_x, rest = wg / mp.rows_x;
-    rows_impl::rows_body<D, 2>(rp, (int)bx, (int)(rest % mp.rows_y), (int)(rest / mp.rows_y), mp.rows_waves, smem);
+    rows_impl::rows_body<D, 2, false>(rp, (int)bx, (int)(rest % mp.rows_y), (int)(rest / mp.rows_y), mp.rows_waves, smem);
   }
 }
 
@@ -66,7 +66,7 @@ int launch_mixed_t(const prefill_impl::TilesParams& tp, const rows_impl::RowsPar
 }  // namespace
 
 bool mixed_launch_supported(const AttnArgs& a, const PlanConfig& cfg, const PlanCounts& n) {
-  return n.tiles > 0 && n.items > 0 && cfg.row_nbuf == 2 && cfg.tile_tokens == prefill_impl::kTileQ &&
+  return !a.kv8 && n.tiles > 0 && n.items > 0 && cfg.row_nbuf == 2 && cfg.tile_tokens == prefill_impl::kTileQ &&
          cfg.part_tokens <= 64 * kBlockSize && prefill_impl::kThreads == 512 && (a.D == 128 || a.D == 64);
 }
 
@@ -74,7 +74,7 @@ int launch_mixed(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, c
                  hipStream_t stream) {
   if (!mixed_launch_supported(a, cfg, n)) return DSV_E_UNSUPPORTED;
   const int G = a.Hq / a.Hkv;
-  prefill_impl::TilesParams tp{a, w, (int32_t)n.tiles, G};
+  prefill_impl::TilesParams tp{a, w, (int32_t)n.tiles, G, nullptr};
   rows_impl::RowsParams rp{a, w, cfg.part_tokens, G};
   int waves = 1;
   while (waves < a.Hkv && waves < 8) waves <<= 1;
@@ -91,7 +91,7 @@ int launch_mixed(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, c
   mp.tile_groups = (uint32_t)tg;
   mp.total_groups = (uint32_t)(tg + rg);
   mp.rows_waves = waves;
-  const int rows_lds = waves * 2 * (a.D == 128 ? rows_impl::RowGeom<128>::SLOT_BYTES : rows_impl::RowGeom<64>::SLOT_BYTES);
+  const int rows_lds = waves * 2 * (a.D == 128 ? rows_impl::RowGeom<128, 2>::SLOT_BYTES : rows_impl::RowGeom<64, 2>::SLOT_BYTES);
   if (a.D == 128)
     return launch_mixed_t<128>(tp, rp, mp, max(rows_lds, (int)prefill_impl::TileGeom<128>::LDS_BYTES), stream);
   return launch_mixed_t<64>(tp, rp, mp, max(rows_lds, (int)prefill_impl::TileGeom<64>::LDS_BYTES), stream);

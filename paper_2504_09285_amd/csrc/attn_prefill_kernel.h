@@ -74,6 +74,9 @@ struct TilesParams {
   WorkLists w;
   int32_t num_tiles;
   int32_t G;
+  const int32_t* stage_rows;   // null, or [num_seqs]: row of a.block_tables that serves a segment
+                               // (a cache of 8-bit codes is attended through a bf16 copy of the
+                               // spans' contexts with a table of its own)
 };
 
 template <int D>
@@ -206,7 +209,8 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
   const int q_len = a.q_offsets[seq + 1] - q0;
   const int ctx = a.ctx_lens[seq];
   const int prefix = ctx - q_len;
-  const int32_t* table = a.block_tables + (int64_t)seq * a.max_blocks;
+  const int table_row = prm.stage_rows ? prm.stage_rows[seq] : seq;
+  const int32_t* table = a.block_tables + (int64_t)table_row * a.max_blocks;
   const int nblk = (ctx + kBlockSize - 1) / kBlockSize;
   const int kv_end = min(ctx, prefix + j0 + kTileQ);          // exclusive: last visible token + 1
   const int n_tiles = (kv_end + kTileKV - 1) / kTileKV;
@@ -600,7 +604,7 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
   for (int c = 0; c < NH; ++c) {
     const float l_tot = other_half_sum(l_run[c]);
     if (!head_ok[c]) continue;
-    const float inv = 1.0f / l_tot;
+    const float inv = a.out_scale / l_tot;
     const int64_t o_row = ((int64_t)(q0 + jq) * a.Hq + head[c]) * D;
 #pragma unroll
     for (int db = 0; db < DB; ++db)

@@ -5,23 +5,23 @@ namespace dsv {
 namespace {
 using namespace rows_impl;
 
-template <int D, int R>
+template <int D, int R, bool KV8>
 __global__ __launch_bounds__(512) void rows_kernel(RowsParams prm) {
   extern __shared__ __align__(16) unsigned char smem[];
-  rows_body<D, R>(prm, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, (int)(blockDim.x / kWave), smem);
+  rows_body<D, R, KV8>(prm, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, (int)(blockDim.x / kWave), smem);
 }
 
-template <int D, int R>
+template <int D, int R, bool KV8>
 int launch_rows_t(const RowsParams& prm, dim3 grid, int waves, hipStream_t stream) {
-  const int lds = waves * R * RowGeom<D>::SLOT_BYTES;
+  const int lds = waves * R * RowGeom<D, KV8 ? 1 : 2>::SLOT_BYTES;
   static int configured = 0;          // raising the dynamic-LDS limit is idempotent; races are benign
   if (lds > configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(rows_kernel<D, R>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(rows_kernel<D, R, KV8>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
       return DSV_E_LAUNCH;
     configured = lds;
   }
-  hipLaunchKernelGGL((rows_kernel<D, R>), grid, dim3(waves * kWave), lds, stream, prm);
+  hipLaunchKernelGGL((rows_kernel<D, R, KV8>), grid, dim3(waves * kWave), lds, stream, prm);
   return launch_status();
 }
 
@@ -32,14 +32,19 @@ int launch_rows(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, co
   if (cfg.part_tokens > 64 * kBlockSize) return DSV_E_UNSUPPORTED;   // one table vector per partition
   RowsParams prm{a, w, cfg.part_tokens, a.Hq / a.Hkv};
   int waves = 1;
-  const int max_waves = cfg.row_nbuf <= 2 ? 8 : 4;     // waves * slots * 8 KiB must fit in LDS
+  // waves * slots * slot bytes (8 KiB of bf16, 4 KiB of codes) must fit in the 160 KB of LDS
+  const int max_waves = cfg.row_nbuf <= (a.kv8 ? 4 : 2) ? 8 : 4;
   while (waves < a.Hkv && waves < max_waves) waves <<= 1;
   dim3 grid((unsigned)n.items, (unsigned)ceil_div(a.Hkv, waves), (unsigned)ceil_div(prm.G, kRowHeads));
   const int r = cfg.row_nbuf;
-#define DSV_ROWS_CASE(DD, RR) \
-  if (a.D == DD && r == RR) return launch_rows_t<DD, RR>(prm, grid, waves, stream);
-  DSV_ROWS_CASE(128, 2) DSV_ROWS_CASE(128, 3) DSV_ROWS_CASE(128, 4) DSV_ROWS_CASE(128, 6) DSV_ROWS_CASE(128, 8)
-  DSV_ROWS_CASE(64, 2) DSV_ROWS_CASE(64, 3) DSV_ROWS_CASE(64, 4) DSV_ROWS_CASE(64, 6) DSV_ROWS_CASE(64, 8)
+#define DSV_ROWS_CASE(DD, RR, KK) \
+  if (a.D == DD && r == RR && (a.kv8 != 0) == KK) return launch_rows_t<DD, RR, KK>(prm, grid, waves, stream);
+  DSV_ROWS_CASE(128, 2, false) DSV_ROWS_CASE(128, 3, false) DSV_ROWS_CASE(128, 4, false)
+  DSV_ROWS_CASE(128, 6, false) DSV_ROWS_CASE(128, 8, false)
+  DSV_ROWS_CASE(64, 2, false) DSV_ROWS_CASE(64, 3, false) DSV_ROWS_CASE(64, 4, false)
+  DSV_ROWS_CASE(64, 6, false) DSV_ROWS_CASE(64, 8, false)
+  DSV_ROWS_CASE(128, 2, true) DSV_ROWS_CASE(128, 4, true) DSV_ROWS_CASE(128, 8, true)
+  DSV_ROWS_CASE(64, 2, true) DSV_ROWS_CASE(64, 4, true) DSV_ROWS_CASE(64, 8, true)
 #undef DSV_ROWS_CASE
   return DSV_E_UNSUPPORTED;
 }

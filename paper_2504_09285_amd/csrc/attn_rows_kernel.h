@@ -35,6 +35,7 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 typedef __attribute__((address_space(3))) void* lds_void_t;
 typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_t;
 typedef const __attribute__((address_space(1))) void* gbl_void_t;
@@ -53,10 +54,11 @@ struct RowsParams {
   int32_t G;            // query heads per KV head
 };
 
-template <int D>
+// EB = bytes per cached element: 2 (bf16) or 1 (E4M3 codes, widened to bf16 in registers).
+template <int D, int EB>
 struct RowGeom {
-  static constexpr int ROWB = D * 2;              // bytes per token row of one head
-  static constexpr int CPR = D / 8;               // 16-byte chunks per row
+  static constexpr int ROWB = D * EB;             // bytes per token row of one head
+  static constexpr int CPR = ROWB / 16;           // 16-byte chunks per row
   static constexpr int TPI = kWave / CPR;         // token rows per load instruction
   static constexpr int IPB = kBlockSize / TPI;    // load instructions per block, per tensor
   static constexpr int KS = D / 32;               // 16x16x32 k-steps of K Q^T
@@ -64,11 +66,33 @@ struct RowGeom {
   static constexpr int TENSOR_BYTES = kBlockSize * ROWB;
   static constexpr int SLOT_BYTES = 2 * TENSOR_BYTES;
   static constexpr int LOADS_PER_BLOCK = 2 * IPB;
+  static constexpr int ROWS_PER_WRAP = 256 / ROWB;   // token rows before the LDS banks repeat
 };
 
-// Row swizzles: 16-byte chunk c of token row n is stored at chunk position c ^ swz(n).
-template <int D> __device__ __forceinline__ int k_swz(int n) { return n & (RowGeom<D>::CPR - 1); }
-template <int D> __device__ __forceinline__ int v_swz(int n) { return 2 * (n & (RowGeom<D>::CPR / 2 - 1)); }
+// Row swizzles: 16-byte chunk c of token row n is stored at chunk position c ^ swz(n), chosen so
+// that the rows which share LDS banks are read at different chunk positions.
+template <int D, int EB> __device__ __forceinline__ int k_swz(int n) {
+  using Geo = RowGeom<D, EB>;
+  if (EB == 2) return n & (Geo::CPR - 1);
+  return (n / Geo::ROWS_PER_WRAP) & (Geo::CPR - 1);
+}
+template <int D, int EB> __device__ __forceinline__ int v_swz(int n) {
+  using Geo = RowGeom<D, EB>;
+  if (EB == 2) return 2 * (n & (Geo::CPR / 2 - 1));
+  return 2 * ((n / Geo::ROWS_PER_WRAP) & (Geo::CPR / 2 - 1));
+}
+
+// Two E4M3 codes (bytes 0,1 or 2,3 of w) widened to a bf16 pair; exact, every code is a bf16 value.
+template <bool HI>
+__device__ __forceinline__ bf16x2_t widen2(uint32_t w) {
+  return __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)w, 1.0f, HI);
+}
+// Eight codes (two registers) -> eight bf16 in the same order.
+__device__ __forceinline__ bf16x8_t widen8(u32x2_t w) {
+  const bf16x2_t a = widen2<false>(w.x), b = widen2<true>(w.x), c = widen2<false>(w.y), d = widen2<true>(w.y);
+  const bf16x4_t ab = __builtin_shufflevector(a, b, 0, 1, 2, 3), cd = __builtin_shufflevector(c, d, 0, 1, 2, 3);
+  return __builtin_shufflevector(ab, cd, 0, 1, 2, 3, 4, 5, 6, 7);
+}
 
 // max / sum across the four lane groups j (lanes l, l^16, l^32, l^48).
 __device__ __forceinline__ float cross16_max(float x) {
@@ -102,15 +126,48 @@ __device__ __forceinline__ void read_vt4(uint32_t a0, uint32_t a1, uint32_t a2, 
       : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
       : "memory");
 }
+// The K fragments of a block of 8-bit codes (8 bytes per lane and k-step), in assembly for the
+// same reason.
+__device__ __forceinline__ void read_k4(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3,
+                                        u32x2_t& v0, u32x2_t& v1, u32x2_t& v2, u32x2_t& v3) {
+  asm volatile(
+      "ds_read_b64 %0, %4\n\t"
+      "ds_read_b64 %1, %5\n\t"
+      "ds_read_b64 %2, %6\n\t"
+      "ds_read_b64 %3, %7\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3)
+      : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+      : "memory");
+}
+__device__ __forceinline__ void read_k2(uint32_t a0, uint32_t a1, u32x2_t& v0, u32x2_t& v1) {
+  asm volatile(
+      "ds_read_b64 %0, %2\n\t"
+      "ds_read_b64 %1, %3\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(v0), "=&v"(v1)
+      : "v"(a0), "v"(a1)
+      : "memory");
+}
+__device__ __forceinline__ void read_vt2(uint32_t a0, uint32_t a1, s16x4_t& v0, s16x4_t& v1) {
+  asm volatile(
+      "ds_read_b64_tr_b16 %0, %2\n\t"
+      "ds_read_b64_tr_b16 %1, %3\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(v0), "=&v"(v1)
+      : "v"(a0), "v"(a1)
+      : "memory");
+}
 
 // The kernel body as a device function, so that the same code serves the kernel of its own and
 // the launch that mixes row work with prefill tiles.  (bx, by, bz) stand in for the block
 // index, `waves` is the number of waves per workgroup that are given a KV head, `smem` the
 // dynamic LDS.
-template <int D, int R>
+template <int D, int R, bool KV8>
 __device__ __forceinline__ void rows_body(const RowsParams& prm, int bx, int by, int bz, int waves,
                                           unsigned char* smem) {
-  using Geo = RowGeom<D>;
+  constexpr int EB = KV8 ? 1 : 2;
+  using Geo = RowGeom<D, EB>;
   constexpr int ROWB = Geo::ROWB, CPR = Geo::CPR, TPI = Geo::TPI, IPB = Geo::IPB, KS = Geo::KS, DB = Geo::DB;
 
   const AttnArgs& a = prm.a;
@@ -156,20 +213,22 @@ __device__ __forceinline__ void rows_body(const RowsParams& prm, int bx, int by,
   unsigned char* const ring = smem + (size_t)wave * R * Geo::SLOT_BYTES;
   const int ld_row = lane / CPR;                 // token row inside a piece
   const int ld_pos = lane % CPR;                 // chunk position inside the row
-  const uint32_t tok_stride = (uint32_t)a.Hkv * D;          // elements between token slots
-  const int64_t blk_elems = (int64_t)kBlockSize * tok_stride;
-  const uint16_t* const zero_line = reinterpret_cast<const uint16_t*>(prm.w.zero_line);
+  const uint32_t tok_stride = (uint32_t)a.Hkv * ROWB;       // bytes between token slots
+  const int64_t blk_bytes = (int64_t)kBlockSize * tok_stride;
+  const unsigned char* const k_bytes = reinterpret_cast<const unsigned char*>(a.k_pool);
+  const unsigned char* const v_bytes = reinterpret_cast<const unsigned char*>(a.v_pool);
+  const unsigned char* const zero_line = reinterpret_cast<const unsigned char*>(prm.w.zero_line);
   auto issue_block_id = [&](int bid, int b, int slot) {
-    const uint16_t* kb = a.k_pool + (int64_t)bid * blk_elems + (uint32_t)kvh * D;
-    const uint16_t* vb = a.v_pool + (int64_t)bid * blk_elems + (uint32_t)kvh * D;
+    const unsigned char* kb = k_bytes + (int64_t)bid * blk_bytes + (uint32_t)kvh * ROWB;
+    const unsigned char* vb = v_bytes + (int64_t)bid * blk_bytes + (uint32_t)kvh * ROWB;
     unsigned char* ks_base = ring + slot * Geo::SLOT_BYTES;
     unsigned char* vs_base = ks_base + Geo::TENSOR_BYTES;
 #pragma unroll
     for (int i = 0; i < IPB; ++i) {
       const int n = i * TPI + ld_row;            // token slot in the block
-      const uint16_t* kp = kb + (uint32_t)n * tok_stride + ((ld_pos ^ k_swz<D>(n)) * 8);
-      const uint16_t* vp = vb + (uint32_t)n * tok_stride + ((ld_pos ^ v_swz<D>(n)) * 8);
-      if (b * kBlockSize + n >= t1) vp = zero_line + ld_pos * 8;     // beyond the partition: V := 0
+      const unsigned char* kp = kb + (uint32_t)n * tok_stride + ((ld_pos ^ k_swz<D, EB>(n)) * 16);
+      const unsigned char* vp = vb + (uint32_t)n * tok_stride + ((ld_pos ^ v_swz<D, EB>(n)) * 16);
+      if (b * kBlockSize + n >= t1) vp = zero_line + ld_pos * 16;    // beyond the partition: V := 0
       __builtin_amdgcn_global_load_lds((gbl_void_t)kp, (lds_void_t)(ks_base + i * 1024), 16, 0, kStreamOnce);
       __builtin_amdgcn_global_load_lds((gbl_void_t)vp, (lds_void_t)(vs_base + i * 1024), 16, 0, kStreamOnce);
     }
@@ -186,17 +245,25 @@ __device__ __forceinline__ void rows_body(const RowsParams& prm, int bx, int by,
   const float scale = a.scale_log2e;
 
   // LDS read offsets (bytes) inside a slot.
-  // K fragment (A operand, rows = tokens): lane (token qcol, jj) reads dims 32*ks + 8*jj .. +8.
+  // K fragment (A operand, rows = tokens): lane (token qcol, jj) reads dims 32*ks + 8*jj .. +8,
+  // 16 bytes of bf16 or 8 bytes of codes.
   int k_off[KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) k_off[ks] = qcol * ROWB + (((ks * 4 + jj) ^ k_swz<D>(qcol)) * 16);
-  // V^T fragment by transpose read: the 16 lanes of group jj fetch token rows 4jj..4jj+3 x 16 dims.
+  for (int ks = 0; ks < KS; ++ks) {
+    if constexpr (KV8)
+      k_off[ks] = qcol * ROWB + (((ks * 2 + jj / 2) ^ k_swz<D, EB>(qcol)) * 16) + (jj % 2) * 8;
+    else
+      k_off[ks] = qcol * ROWB + (((ks * 4 + jj) ^ k_swz<D, EB>(qcol)) * 16);
+  }
+  // V^T fragment by transpose read: the 16 lanes of group jj fetch token rows 4jj..4jj+3 x 32
+  // bytes, i.e. 16 dims of bf16, or 32 dims of codes (a 16-bit unit is then a pair of dims).
+  constexpr int VT = KV8 ? DB / 2 : DB;                  // transpose reads per block
   const int v_row = jj * 4 + (lane % 16) / 4;
   const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)ring;
-  uint32_t v_off[DB];
+  uint32_t v_off[VT];
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
-    v_off[db] = ring_lds + Geo::TENSOR_BYTES + v_row * ROWB + (((2 * db + (lane % 4) / 2) ^ v_swz<D>(v_row)) * 16) + (lane % 2) * 8;
+  for (int db = 0; db < VT; ++db)
+    v_off[db] = ring_lds + Geo::TENSOR_BYTES + v_row * ROWB + (((2 * db + (lane % 4) / 2) ^ v_swz<D, EB>(v_row)) * 16) + (lane % 2) * 8;
 
   // The first block is requested at once (its id came with the item); the table slice and the
   // query rows are only waited for where they are first used.
@@ -215,10 +282,19 @@ __device__ __forceinline__ void rows_body(const RowsParams& prm, int bx, int by,
 
     // S^T = K Q^T: lane (head qcol, jj) gets tokens 4jj..4jj+3 of the block.
     f32x4_t s = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (KV8) {
+      const uint32_t kb = ring_lds + (uint32_t)slot * Geo::SLOT_BYTES;
+      u32x2_t kc[KS];
+      if constexpr (KS == 4) read_k4(kb + k_off[0], kb + k_off[1], kb + k_off[2], kb + k_off[3], kc[0], kc[1], kc[2], kc[3]);
+      else read_k2(kb + k_off[0], kb + k_off[1], kc[0], kc[1]);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sl + k_off[ks]);
-      s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[ks], s, 0, 0, 0);
+      for (int ks = 0; ks < KS; ++ks) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen8(kc[ks]), qf[ks], s, 0, 0, 0);
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sl + k_off[ks]);
+        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[ks], s, 0, 0, 0);
+      }
     }
     const int tok = b * kBlockSize + jj * 4;
     if (tok + 3 >= t1) {
@@ -244,15 +320,35 @@ __device__ __forceinline__ void rows_body(const RowsParams& prm, int bx, int by,
 
     // O^T = O^T * corr + V^T P^T.
     const uint32_t slot_off = (uint32_t)slot * Geo::SLOT_BYTES;
+    constexpr int VG = VT >= 4 ? 4 : 2;                  // transpose reads issued together
 #pragma unroll
-    for (int d4 = 0; d4 < DB; d4 += 4) {
-      s16x4_t vt[4];
-      read_vt4(v_off[d4] + slot_off, v_off[d4 + 1] + slot_off, v_off[d4 + 2] + slot_off,
-               v_off[d4 + 3] + slot_off, vt[0], vt[1], vt[2], vt[3]);
+    for (int d4 = 0; d4 < VT; d4 += VG) {
+      s16x4_t vt[VG];
+      if constexpr (VG == 4)
+        read_vt4(v_off[d4] + slot_off, v_off[d4 + 1] + slot_off, v_off[d4 + 2] + slot_off,
+                 v_off[d4 + 3] + slot_off, vt[0], vt[1], vt[2], vt[3]);
+      else
+        read_vt2(v_off[d4] + slot_off, v_off[d4 + 1] + slot_off, vt[0], vt[1]);
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        o[d4 + u] *= corr;
-        o[d4 + u] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt[u], __builtin_bit_cast(s16x4_t, pf), o[d4 + u], 0, 0, 0);
+      for (int u = 0; u < VG; ++u) {
+        if constexpr (KV8) {
+          // vt[u]: 16-bit unit e = token 4jj+e, low byte dim 32(d4+u) + 2m, high byte the next
+          // dim (m = lane % 16).  Gather the even-dim and the odd-dim codes of the four tokens
+          // and widen them: two A fragments, rows m <-> dims 32(d4+u) + 2m (+1).
+          const u32x2_t w = __builtin_bit_cast(u32x2_t, vt[u]);
+          const uint32_t ev = __builtin_amdgcn_perm(w.y, w.x, 0x06040200u);
+          const uint32_t od = __builtin_amdgcn_perm(w.y, w.x, 0x07050301u);
+          const bf16x4_t a_ev = __builtin_shufflevector(widen2<false>(ev), widen2<true>(ev), 0, 1, 2, 3);
+          const bf16x4_t a_od = __builtin_shufflevector(widen2<false>(od), widen2<true>(od), 0, 1, 2, 3);
+          const int db = 2 * (d4 + u);
+          o[db] *= corr;
+          o[db + 1] *= corr;
+          o[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, a_ev), __builtin_bit_cast(s16x4_t, pf), o[db], 0, 0, 0);
+          o[db + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, a_od), __builtin_bit_cast(s16x4_t, pf), o[db + 1], 0, 0, 0);
+        } else {
+          o[d4 + u] *= corr;
+          o[d4 + u] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt[u], __builtin_bit_cast(s16x4_t, pf), o[d4 + u], 0, 0, 0);
+        }
       }
     }
   }
@@ -261,27 +357,60 @@ __device__ __forceinline__ void rows_body(const RowsParams& prm, int bx, int by,
   const float l_tot = cross16_sum(l_run);
   if (qcol >= nh) return;
   const int h = h0 + qcol;
+  // Lane (head qcol, jj) holds, for every 16-dim block db, the dims 16db + 4jj + e (bf16 cache),
+  // or, for every 32-dim block j, the dims 32j + 8jj + 2e (+1) in o[2j] (o[2j+1]) (code cache).
   if (nparts == 1) {
-    const float inv = 1.0f / l_tot;
-    const int64_t ob = ((int64_t)qtok * a.Hq + h) * D + jj * 4;
+    const float inv = a.out_scale / l_tot;
+    if constexpr (KV8) {
+      const int64_t ob = ((int64_t)qtok * a.Hq + h) * D + jj * 8;
 #pragma unroll
-    for (int db = 0; db < DB; ++db) {
-      const float x0 = o[db][0] * inv, x1 = o[db][1] * inv, x2 = o[db][2] * inv, x3 = o[db][3] * inv;
-      if (a.out_bf16) {
-        uint2 pk;
-        pk.x = (uint32_t)f32_to_bf16_rne(x0) | ((uint32_t)f32_to_bf16_rne(x1) << 16);
-        pk.y = (uint32_t)f32_to_bf16_rne(x2) | ((uint32_t)f32_to_bf16_rne(x3) << 16);
-        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + ob + db * 16) = pk;
-      } else {
-        *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + ob + db * 16) = make_float4(x0, x1, x2, x3);
+      for (int j = 0; j < DB / 2; ++j) {
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { x[2 * e] = o[2 * j][e] * inv; x[2 * e + 1] = o[2 * j + 1][e] * inv; }
+        if (a.out_bf16) {
+          uint4 pk;
+          pk.x = (uint32_t)f32_to_bf16_rne(x[0]) | ((uint32_t)f32_to_bf16_rne(x[1]) << 16);
+          pk.y = (uint32_t)f32_to_bf16_rne(x[2]) | ((uint32_t)f32_to_bf16_rne(x[3]) << 16);
+          pk.z = (uint32_t)f32_to_bf16_rne(x[4]) | ((uint32_t)f32_to_bf16_rne(x[5]) << 16);
+          pk.w = (uint32_t)f32_to_bf16_rne(x[6]) | ((uint32_t)f32_to_bf16_rne(x[7]) << 16);
+          *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(a.out) + ob + j * 32) = pk;
+        } else {
+          float* dst = reinterpret_cast<float*>(a.out) + ob + j * 32;
+          *reinterpret_cast<float4*>(dst) = make_float4(x[0], x[1], x[2], x[3]);
+          *reinterpret_cast<float4*>(dst + 4) = make_float4(x[4], x[5], x[6], x[7]);
+        }
+      }
+    } else {
+      const int64_t ob = ((int64_t)qtok * a.Hq + h) * D + jj * 4;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const float x0 = o[db][0] * inv, x1 = o[db][1] * inv, x2 = o[db][2] * inv, x3 = o[db][3] * inv;
+        if (a.out_bf16) {
+          uint2 pk;
+          pk.x = (uint32_t)f32_to_bf16_rne(x0) | ((uint32_t)f32_to_bf16_rne(x1) << 16);
+          pk.y = (uint32_t)f32_to_bf16_rne(x2) | ((uint32_t)f32_to_bf16_rne(x3) << 16);
+          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + ob + db * 16) = pk;
+        } else {
+          *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + ob + db * 16) = make_float4(x0, x1, x2, x3);
+        }
       }
     }
   } else {
     const int64_t ph = (int64_t)item * a.Hq + h;
-    float* pa = prm.w.part_acc + ph * D + jj * 4;
+    if constexpr (KV8) {
+      float* pa = prm.w.part_acc + ph * D + jj * 8;
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
-      *reinterpret_cast<float4*>(pa + db * 16) = make_float4(o[db][0], o[db][1], o[db][2], o[db][3]);
+      for (int j = 0; j < DB / 2; ++j) {
+        *reinterpret_cast<float4*>(pa + j * 32) = make_float4(o[2 * j][0], o[2 * j + 1][0], o[2 * j][1], o[2 * j + 1][1]);
+        *reinterpret_cast<float4*>(pa + j * 32 + 4) = make_float4(o[2 * j][2], o[2 * j + 1][2], o[2 * j][3], o[2 * j + 1][3]);
+      }
+    } else {
+      float* pa = prm.w.part_acc + ph * D + jj * 4;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        *reinterpret_cast<float4*>(pa + db * 16) = make_float4(o[db][0], o[db][1], o[db][2], o[db][3]);
+    }
     if (jj == 0) *reinterpret_cast<float2*>(prm.w.part_ml + ph * 2) = make_float2(m_run, l_tot);
   }
 }

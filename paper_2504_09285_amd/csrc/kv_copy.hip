@@ -34,6 +34,7 @@ struct CopyParams {
   int32_t tiles_per_chunk;       // ceil(max num_tokens / tile_tokens)
   int32_t upr;                   // 16-byte units per token row
   int32_t upr_shift;             // log2(upr) or -1
+  int32_t off_shift;             // chunk_offset (elements) -> units: 3 for 2-byte, 4 for 1-byte elements
 };
 
 // PACK = true: pool -> chunk.  PACK = false: chunk -> pool.
@@ -52,7 +53,7 @@ __global__ __launch_bounds__(kCopyThreads) void kv_copy_kernel(CopyParams p) {
   const int ntok = min(p.tile_tokens, d.num_tokens - tok0);
 
   unit_t* pool = ((plane & 1u) ? p.pool_v : p.pool_k) + (int64_t)(plane >> 1) * p.layer_stride_u;
-  unit_t* chunk = p.chunk_buf + (d.chunk_offset >> 3) +
+  unit_t* chunk = p.chunk_buf + (d.chunk_offset >> p.off_shift) +
                  ((int64_t)plane * d.num_tokens + tok0) * p.upr;
   const int32_t* table = p.block_tables + (int64_t)d.seq * p.max_blocks;
 
@@ -86,7 +87,9 @@ __global__ __launch_bounds__(kCopyThreads) void kv_copy_kernel(CopyParams p) {
 
 int run_copy(bool pack, const dsv_kv_pool* pool, const int32_t* block_tables, int32_t max_blocks,
              const dsv_chunk_desc* descs, const dsv_chunk_desc* descs_host, int32_t num_chunks,
-             void* chunk_buf, void* hip_stream) {
+             void* chunk_buf, void* hip_stream, int elem_bytes) {
+  // elem_bytes = 2 (bf16 cache) or 1 (8-bit codes): the copy itself only sees 16-byte units.
+  const int epu = 16 / elem_bytes;                 // elements per unit
   int rc = check_pool(pool);
   if (rc) return rc;
   if (num_chunks < 0 || max_blocks < 1) return DSV_E_INVALID;
@@ -96,7 +99,7 @@ int run_copy(bool pack, const dsv_kv_pool* pool, const int32_t* block_tables, in
       (reinterpret_cast<uintptr_t>(pool->v_base) & 15))
     return DSV_E_INVALID;
   const int64_t row_elems = (int64_t)pool->num_kv_heads * pool->head_dim;   // multiple of 64
-  if (pool->num_layers > 1 && (pool->layer_stride % 8)) return DSV_E_INVALID;
+  if (pool->num_layers > 1 && (pool->layer_stride % epu)) return DSV_E_INVALID;
   if (pool->num_layers > 1 &&
       pool->layer_stride < (int64_t)pool->num_blocks * kBlockSize * row_elems)
     return DSV_E_INVALID;
@@ -104,7 +107,7 @@ int run_copy(bool pack, const dsv_kv_pool* pool, const int32_t* block_tables, in
   for (int c = 0; c < num_chunks; ++c) {
     const dsv_chunk_desc& d = descs_host[c];
     if (d.seq < 0 || d.token_begin < 0 || d.num_tokens < 1 || d.reserved != 0) return DSV_E_INVALID;
-    if (d.chunk_offset < 0 || (d.chunk_offset % 8)) return DSV_E_INVALID;
+    if (d.chunk_offset < 0 || (d.chunk_offset % epu)) return DSV_E_INVALID;
     if (ceil_div((int64_t)d.token_begin + d.num_tokens, kBlockSize) > max_blocks) return DSV_E_INVALID;
     if (d.num_tokens > max_tokens) max_tokens = d.num_tokens;
   }
@@ -114,10 +117,11 @@ int run_copy(bool pack, const dsv_kv_pool* pool, const int32_t* block_tables, in
   p.chunk_buf = static_cast<unit_t*>(chunk_buf);
   p.block_tables = block_tables;
   p.descs = descs;
-  p.layer_stride_u = pool->num_layers > 1 ? pool->layer_stride / 8 : 0;
+  p.layer_stride_u = pool->num_layers > 1 ? pool->layer_stride / epu : 0;
   p.max_blocks = max_blocks;
   p.num_layers = pool->num_layers;
-  p.upr = (int32_t)(row_elems / 8);
+  p.upr = (int32_t)(row_elems / epu);
+  p.off_shift = elem_bytes == 2 ? 3 : 4;
   p.tile_tokens = p.upr >= kTileUnits ? 1 : kTileUnits / p.upr;
   p.tiles_per_chunk = ceil_div(max_tokens, p.tile_tokens);
   p.upr_shift = (p.upr & (p.upr - 1)) == 0 ? __builtin_ctz((unsigned)p.upr) : -1;
@@ -139,7 +143,7 @@ extern "C" int kv_pack_chunks(const dsv_kv_pool* src, const int32_t* block_table
                               const dsv_chunk_desc* descs_host, int32_t num_chunks,
                               void* chunk_buf, void* hip_stream) {
   return dsv::run_copy(true, src, block_tables, max_blocks_per_seq, descs, descs_host, num_chunks,
-                       chunk_buf, hip_stream);
+                       chunk_buf, hip_stream, 2);
 }
 
 extern "C" int kv_unpack_chunks(const void* chunk_buf, const dsv_chunk_desc* descs,
@@ -147,5 +151,21 @@ extern "C" int kv_unpack_chunks(const void* chunk_buf, const dsv_chunk_desc* des
                                 const dsv_kv_pool* dst, const int32_t* dst_block_tables,
                                 int32_t max_blocks_per_seq, void* hip_stream) {
   return dsv::run_copy(false, dst, dst_block_tables, max_blocks_per_seq, descs, descs_host,
-                       num_chunks, const_cast<void*>(chunk_buf), hip_stream);
+                       num_chunks, const_cast<void*>(chunk_buf), hip_stream, 2);
+}
+
+extern "C" int kv_pack_chunks_fp8(const dsv_kv_pool* src, const int32_t* block_tables,
+                                  int32_t max_blocks_per_seq, const dsv_chunk_desc* descs,
+                                  const dsv_chunk_desc* descs_host, int32_t num_chunks,
+                                  void* chunk_buf, void* hip_stream) {
+  return dsv::run_copy(true, src, block_tables, max_blocks_per_seq, descs, descs_host, num_chunks,
+                       chunk_buf, hip_stream, 1);
+}
+
+extern "C" int kv_unpack_chunks_fp8(const void* chunk_buf, const dsv_chunk_desc* descs,
+                                    const dsv_chunk_desc* descs_host, int32_t num_chunks,
+                                    const dsv_kv_pool* dst, const int32_t* dst_block_tables,
+                                    int32_t max_blocks_per_seq, void* hip_stream) {
+  return dsv::run_copy(false, dst, dst_block_tables, max_blocks_per_seq, descs, descs_host,
+                       num_chunks, const_cast<void*>(chunk_buf), hip_stream, 1);
 }

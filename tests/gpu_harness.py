@@ -67,3 +67,43 @@ class DeviceHandoff:
 
     def unpack(self, stream=None):
         dsv.kv_unpack_chunks(self.chunk_buf, self.descs, self.dst, self.dst_tables, stream=stream)
+
+
+def dev_u8(u8: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(u8, dtype=np.uint8)).cuda()
+
+
+class DeviceBatchFp8:
+    """Device copy of a workloads.AttnBatch whose single-layer pools hold E4M3 codes (uint8)."""
+
+    def __init__(self, b, k_pool=None, v_pool=None):
+        self.b = b
+        self.q = dev_bf16(b.q)
+        self.pool = dsv.KVPool(dev_u8((b.k_pool if k_pool is None else k_pool)[None]),
+                               dev_u8((b.v_pool if v_pool is None else v_pool)[None]))
+        self.block_tables = torch.from_numpy(np.ascontiguousarray(b.block_tables, dtype=np.int32)).cuda()
+        self.q_offsets = torch.from_numpy(b.q_offsets).cuda()
+        self.ctx_lens = torch.from_numpy(b.ctx_lens).cuda()
+        nbytes = dsv.attn_mixed_batch_fp8kv_workspace_bytes(b.q_offsets, b.ctx_lens, b.Hq, b.Hkv, b.D)
+        assert nbytes > 0
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+
+    def run(self, out_dtype=torch.float32, stream=None, fill=None, k_scale=None, v_scale=None):
+        b = self.b
+        out = torch.empty(self.q.shape, dtype=out_dtype, device="cuda")
+        if fill is not None:
+            out.fill_(fill)
+        dsv.attn_mixed_batch_fp8kv(self.q, out, self.pool, 0, self.block_tables, self.q_offsets,
+                                   self.ctx_lens, b.q_offsets, b.ctx_lens, b.Hq, b.scale,
+                                   b.meta["k_scale"] if k_scale is None else k_scale,
+                                   b.meta["v_scale"] if v_scale is None else v_scale,
+                                   self.workspace, stream=stream)
+        return out
+
+
+def run_attention_fp8kv(b, out_dtype=torch.float32, **over) -> np.ndarray:
+    out = DeviceBatchFp8(b, **over).run(out_dtype, fill=float("nan"))
+    torch.cuda.synchronize()
+    if out_dtype == torch.bfloat16:
+        return host_u16(out)
+    return out.cpu().numpy()
