@@ -114,6 +114,8 @@ def upload(b):
 
 def attn_step(d):
     import paper_2504_09285_amd as dsv
+    if getattr(d, "step", None) is not None:
+        return d.step()
     b = d.b
     dsv.attn_mixed_batch(d.q, d.out, d.pool, 0, d.block_tables, d.q_offsets, d.ctx_lens,
                          b.q_offsets, b.ctx_lens, b.Hq, b.scale, d.workspace)
@@ -242,6 +244,69 @@ def bench_handoff(h, steps, warmup, hev):
         out[name] = {"ms": ms, "GB/s": gbs, "frac_hbm_peak": gbs / HBM_PEAK_GBS}
     out["payload_bytes"] = h.payload_bytes
     out["workload"] = h.name
+    return out
+
+
+def bench_fp8kv(steps, warmup, hev):
+    """Second workload: the same shapes on a cache of 8-bit (E4M3) codes.  Decode streams half
+    the bytes per token, so tokens/s should double at the same GB/s; prefill spans pay for a bf16
+    copy of their contexts (the "stage" kernel); chunks are half the size."""
+    import torch
+    import paper_2504_09285_amd as dsv
+    from workloads import gen
+    out = {}
+    ids = [dsv.KERNEL_ROWS, dsv.KERNEL_TILES, dsv.KERNEL_MERGE, dsv.KERNEL_PLAN, dsv.KERNEL_STAGE]
+    for b in (gen.config2_fp8kv(), gen.config3_fp8kv()):
+        d = argparse.Namespace()
+        d.b = b
+        d.q = torch.from_numpy(np.ascontiguousarray(b.q).view(np.int16)).cuda().view(torch.bfloat16)
+        d.pool = dsv.KVPool(torch.from_numpy(b.k_pool[None]).cuda(), torch.from_numpy(b.v_pool[None]).cuda())
+        d.block_tables = torch.from_numpy(b.block_tables).cuda()
+        d.q_offsets, d.ctx_lens = torch.from_numpy(b.q_offsets).cuda(), torch.from_numpy(b.ctx_lens).cuda()
+        nbytes = dsv.attn_mixed_batch_fp8kv_workspace_bytes(b.q_offsets, b.ctx_lens, b.Hq, b.Hkv, b.D)
+        d.workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        d.out = torch.empty(d.q.shape, dtype=torch.bfloat16, device="cuda")
+        d.step = lambda d=d, b=b: dsv.attn_mixed_batch_fp8kv(
+            d.q, d.out, d.pool, 0, d.block_tables, d.q_offsets, d.ctx_lens, b.q_offsets, b.ctx_lens, b.Hq,
+            b.scale, b.meta["k_scale"], b.meta["v_scale"], d.workspace)
+        sec, pk = time_attention(d, steps, warmup, ids, hev)
+        r = {"ms_per_step": sec * 1e3, "tokens_per_s": b.total_q / sec, "workspace_bytes": int(nbytes),
+             "kernel_ms": {"rows": pk[dsv.KERNEL_ROWS], "tiles": pk[dsv.KERNEL_TILES], "merge": pk[dsv.KERNEL_MERGE],
+                           "plan": pk[dsv.KERNEL_PLAN], "stage": pk[dsv.KERNEL_STAGE]}}
+        dec = b.q_lens == 1
+        ctx = b.ctx_lens[dec].astype(np.int64)
+        kv_bytes = int(ctx.sum()) * 2 * b.Hkv * b.D + int(dec.sum()) * b.Hq * b.D * 4 + 4 * int(((ctx + 15) // 16).sum())
+        if pk[dsv.KERNEL_ROWS]:
+            gbs = kv_bytes / (pk[dsv.KERNEL_ROWS] * 1e-3) / 1e9
+            r["decode"] = {"algorithmic_bytes": kv_bytes, "GB/s": gbs, "frac_hbm_peak": gbs / HBM_PEAK_GBS}
+        if pk[dsv.KERNEL_TILES]:
+            tf = prefill_flops(b) / (pk[dsv.KERNEL_TILES] * 1e-3) / 1e12
+            r["prefill"] = {"TFLOP/s": tf, "frac_mfma_peak": tf / MFMA_BF16_PEAK_TFLOPS}
+        out[b.name] = r
+        del d
+    h = gen.config5_handoff_fp8kv(layers=4)
+    src = dsv.KVPool(torch.from_numpy(h.src_k).cuda(), torch.from_numpy(h.src_v).cuda())
+    dst = dsv.KVPool(torch.from_numpy(h.dst_k).cuda(), torch.from_numpy(h.dst_v).cuda())
+    st, dt = torch.from_numpy(h.src_tables).cuda(), torch.from_numpy(h.dst_tables).cuda()
+    descs = dsv.ChunkDescs(h.chunks)
+    buf = torch.empty(h.chunk_elems, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream or None
+    ho = {"payload_bytes": h.payload_bytes}
+    for name, fn in (("pack", lambda: dsv.kv_pack_chunks_fp8(src, st, descs, buf)),
+                     ("unpack", lambda: dsv.kv_unpack_chunks_fp8(buf, descs, dst, dt))):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        evs = [(hev.create(), hev.create()) for _ in range(10)]
+        for a, e in evs:
+            hev.record(a, stream)
+            fn()
+            hev.record(e, stream)
+        torch.cuda.synchronize()
+        ms = float(np.mean([hev.elapsed_ms(a, e) for a, e in evs]))
+        gbs = 2 * h.payload_bytes / (ms * 1e-3) / 1e9
+        ho[name] = {"ms": ms, "GB/s": gbs, "frac_hbm_peak": gbs / HBM_PEAK_GBS}
+    out["handoff_c5_4layers_fp8kv"] = ho
     return out
 
 
@@ -445,6 +510,7 @@ def main():
             del d3
         extras["kv_append_c3"] = bench_append(gen.config3(threads=threads), 20, 3, hev)
         extras["c4_micro_request"] = bench_config4(threads, 10, 2, hev)
+        extras["fp8kv"] = bench_fp8kv(20, 3, hev)
         # Chunk-pipelined hand-off (paper section 4.3): transfer of chunk k next to computation of k+1.
         from paper_2504_09285_amd.chunk_pipeline import measure as measure_chunk_pipeline
         extras["chunk_pipelined_handoff"] = measure_chunk_pipeline(8192, 512, 8)

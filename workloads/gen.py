@@ -220,10 +220,11 @@ class Handoff:
     dst_tables: np.ndarray
     chunks: np.ndarray         # [C, 4] i64: seq, token_begin, num_tokens, chunk_offset (elements)
     chunk_elems: int           # total elements of the chunk buffer
+    elem_bytes: int = 2        # 2: bf16 bits (uint16 arrays); 1: E4M3 codes (uint8 arrays)
 
     @property
     def payload_bytes(self) -> int:
-        return int(self.chunks[:, 2].sum()) * 2 * self.L * self.Hkv * self.D * 2
+        return int(self.chunks[:, 2].sum()) * 2 * self.L * self.Hkv * self.D * self.elem_bytes
 
 
 def make_chunks(ranges: Sequence[Tuple[int, int, int]], chunk_tokens: int, L: int, Hkv: int,
@@ -346,3 +347,40 @@ def config5_handoff(shrink: int = 1, layers: int = 32, threads: int = 8) -> Hand
     tok = 8192 // shrink
     return make_handoff("c5_handoff", seed, layers, 8, 128, [tok] * n_req,
                         [(r, 0, tok) for r in range(n_req)], 256, threads=threads)
+
+
+# ---- the 8-bit KV variant of the same shapes (second workload) -----------------------------------
+
+def config2_fp8kv(shrink: int = 1) -> AttnBatch:
+    """Config 2's batch (same seed, same contexts) on a cache of E4M3 codes."""
+    seed = seed_for(2)
+    n = max(256 // shrink, 8)
+    ctx = lognormal_lengths(seed, n, 1024.0 / shrink, 0.8, max(64 // shrink, 1), 8192 // shrink)
+    return make_batch_fp8kv("c2_decode_heavy_fp8kv", seed, 32, 8, 128, [(1, int(c)) for c in ctx],
+                            meta={"shrink": shrink})
+
+
+def config3_fp8kv(shrink: int = 1) -> AttnBatch:
+    """Config 3's batch (same seed, same segments) on a cache of E4M3 codes."""
+    seed = seed_for(3)
+    ql = 2048 // shrink
+    segs = [(ql, ql + p // shrink) for p in (0, 512, 1024, 4096)]
+    ctx = lognormal_lengths(seed, 16, 2048.0 / shrink, 0.8, max(64 // shrink, 1), 16384 // shrink)
+    segs += [(1, int(c)) for c in ctx]
+    return make_batch_fp8kv("c3_prefill_heavy_fp8kv", seed, 32, 8, 128, segs, meta={"shrink": shrink})
+
+
+def config5_handoff_fp8kv(shrink: int = 1, layers: int = 32) -> Handoff:
+    """Config 5's hand-off (8 requests x 8192 tokens, 256-token chunks) with 1-byte elements:
+    half the payload.  Offsets in ``chunks`` count elements, i.e. bytes."""
+    seed = seed_for(5)
+    n_req = max(8 // shrink, 2)
+    tok = 8192 // shrink
+    req = [tok] * n_req
+    src_tables, nb_s = build_block_tables(seed, TID_SRC_PERM, req, 0.10)
+    dst_tables, nb_d = build_block_tables(seed, TID_DST_PERM, req, 0.10)
+    shp_s, shp_d = (layers, nb_s, BLOCK_SIZE, 8, 128), (layers, nb_d, BLOCK_SIZE, 8, 128)
+    chunks, n_el = make_chunks([(r, 0, tok) for r in range(n_req)], 256, layers, 8, 128)
+    return Handoff("c5_handoff_fp8kv", layers, 8, 128, e4m3_codes(seed, 41, shp_s), e4m3_codes(seed, 42, shp_s),
+                   src_tables, e4m3_codes(seed, 43, shp_d), e4m3_codes(seed, 44, shp_d), dst_tables,
+                   chunks, n_el, elem_bytes=1)
