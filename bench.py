@@ -448,6 +448,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--full-extras", action="store_true", help="config 5 at full context lengths (16 GB of KV)")
+    ap.add_argument("--fp8kv-only", action="store_true",
+                    help="run only the second workload (8-bit KV cache) and print its results")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy, 10 times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -469,6 +471,9 @@ def main():
     dsv.load_library()
     threads = min(16, os.cpu_count() or 8)
     hev = HipEvents()
+    if args.fp8kv_only:
+        print(json.dumps({"fp8kv": bench_fp8kv(args.steps, args.warmup, hev)}))
+        return
 
     b = make_workload(args.workload, threads)
     res, d = bench_attention(b, args.steps, args.warmup, hev)

@@ -80,3 +80,29 @@ def test_null_and_unsupported_arguments_return_codes_without_gpu(lib):
     assert lib.kv_pack_chunks(C.byref(pool), None, 1, None, None, 0, None, None) == 0     # no-op
     assert lib.attn_mixed_batch(None, None, C.byref(pool), 0, None, 1, None, None, None, None, 0, 32,
                                 0.1, 0, None, 0, None) == 0                               # no-op
+
+
+def test_fp8kv_entry_points_check_scales_and_workspace_before_any_gpu_work(lib):
+    pool = binding._Pool(4096, 4096, 0, 1, 4, 16, 8, 128)
+    qo = np.array([0, 1], np.int32)
+    cl = np.array([5], np.int32)
+    p = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+    fake = 4096                                            # non-null, 16-byte aligned, never dereferenced
+    call = lambda ks, vs, ws_bytes: lib.attn_mixed_batch_fp8kv(
+        fake, fake, C.byref(pool), 0, fake, 1, fake, fake, p(qo), p(cl), 1, 32, 0.1, ks, vs, 0,
+        fake * 4, ws_bytes, None)
+    assert call(0.0, 1.0, 0) == -1
+    assert call(1.0, float("inf"), 0) == -1
+    assert call(float("nan"), 1.0, 0) == -1
+    assert call(0.5, 0.5, 0) == -3                          # valid arguments, workspace too small
+    assert lib.kv_append_fp8(fake, fake, C.byref(pool), 0, fake, 1, fake, fake, p(qo), p(cl), 1,
+                             0.0, 1.0, None) == -1
+    assert lib.kv_append_fp8(fake, fake, C.byref(pool), 0, fake, 1, fake, fake, p(qo), p(cl), 0,
+                             1.0, 1.0, None) == 0           # empty batch: no-op
+    f8 = dsv.attn_mixed_batch_fp8kv_workspace_bytes
+    f16 = dsv.attn_mixed_batch_workspace_bytes
+    assert f8([0, 1, 3], [10, 20], 32, 8, 128) == f16([0, 1, 3], [10, 20], 32, 8, 128)   # no span of 16+
+    grow = f8([0, 64], [640], 32, 8, 128) - f16([0, 64], [640], 32, 8, 128)
+    assert grow >= 640 * 4 * 8 * 128                        # the bf16 copy of the span's context
+    assert lib.kv_pack_chunks_fp8(C.byref(pool), None, 1, None, None, 0, None, None) == 0
+    assert lib.kv_pack_chunks_fp8(C.byref(pool), None, 1, None, None, 1, None, None) == -1
