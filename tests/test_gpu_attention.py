@@ -247,6 +247,21 @@ def test_mixed_launch_equals_the_two_kernels_apart(monkeypatch):
         assert np.abs(one - oracle_out(b)).max() <= TOL
 
 
+def _many_segments():
+    """2,600 segments: the planner's scans run three passes of 1,024 with carries between them,
+    and prefill spans (tile work) sit in the second and third pass."""
+    rng = np.random.default_rng(11)
+    segs = [(1, int(c)) for c in rng.integers(1, 180, 2600)]
+    for i, s in {5: (20, 50), 1030: (70, 200), 1500: (3, 90), 2047: (64, 64), 2300: (130, 131), 2599: (7, 7)}.items():
+        segs[i] = s
+    return segs
+
+
+def test_more_segments_than_one_planner_pass():
+    b = gen.make_batch("many", 91, 8, 2, 64, _many_segments())
+    check(b)
+
+
 def test_config3_prefill_heavy_shrunk():
     check(gen.config3(shrink=8))
 

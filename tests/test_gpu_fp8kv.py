@@ -55,6 +55,16 @@ def test_prefill_spans_read_the_staged_copy(Hq, Hkv, D):
     check(b)
 
 
+def test_more_segments_than_one_planner_pass():
+    """2,600 segments with prefill spans in the planner's second and third pass of 1,024: the
+    staged segments' indices and block offsets carry across passes."""
+    rng = np.random.default_rng(11)
+    segs = [(1, int(c)) for c in rng.integers(1, 180, 2600)]
+    for i, s in {5: (20, 50), 1030: (70, 200), 1500: (3, 90), 2047: (64, 64), 2300: (130, 131), 2599: (7, 7)}.items():
+        segs[i] = s
+    check(gen.make_batch_fp8kv("f8many", 4350, 8, 2, 64, segs))
+
+
 def test_only_prefill_spans_and_bf16_output():
     import torch
     from gpu_harness import run_attention_fp8kv
