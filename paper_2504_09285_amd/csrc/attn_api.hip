@@ -76,13 +76,12 @@ PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8
   PlanConfig c;
   c.mfma_min_qlen = env_int("DSV_MFMA_MIN_QLEN", 16);
   c.tile_tokens = 64;
-  // LDS ring slots per wave of the row kernel.  A slot of 8-bit codes is half the size, so twice
-  // as many keep the same number of bytes in flight.
+  // LDS ring slots per wave of the row kernel.  (8-bit codes: a slot is half the size; two and
+  // four slots measured the same, two keep the mixed launch available.)
+  c.row_nbuf = env_int("DSV_ROW_NBUF", 2);
   if (kv8) {
-    c.row_nbuf = env_int("DSV_ROW_NBUF", 4);
-    if (c.row_nbuf != 2 && c.row_nbuf != 8) c.row_nbuf = 4;
+    if (c.row_nbuf != 4 && c.row_nbuf != 8) c.row_nbuf = 2;
   } else {
-    c.row_nbuf = env_int("DSV_ROW_NBUF", 2);
     if (c.row_nbuf != 3 && c.row_nbuf != 4) c.row_nbuf = 2;
   }
   c.num_cus = device_cus();
@@ -548,7 +547,7 @@ int run_attention(bool kv8, float k_scale, float v_scale, const void* q, void* o
   // matrix-core work at 0.9 PFLOP/s.  DSV_MIXED_LAUNCH=1 / 0 forces the choice.
   bool mix = mixed_launch_supported(a, cfg, n);
   if (mix) {
-    const double t_rows = (double)n.row_tokens * a.Hkv * a.D * 4.0 / 5.5e12;
+    const double t_rows = (double)n.row_tokens * a.Hkv * a.D * (kv8 ? 2.0 : 4.0) / 5.5e12;
     const double t_tiles = (double)n.tile_pairs * a.Hq * a.D * 4.0 / 0.9e15;
     mix = t_rows >= 0.25 * t_tiles && t_tiles >= 0.25 * t_rows;
     const int forced = env_int("DSV_MIXED_LAUNCH", -1);

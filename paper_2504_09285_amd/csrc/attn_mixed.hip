@@ -27,7 +27,7 @@ struct MixParams {
   int32_t rows_waves;
 };
 
-template <int D>
+template <int D, bool KV8>
 __global__ __launch_bounds__(512, 2) void mixed_kernel(prefill_impl::TilesParams tp,
                                                        rows_impl::RowsParams rp, MixParams mp) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -45,28 +45,28 @@ __global__ __launch_bounds__(512, 2) void mixed_kernel(prefill_impl::TilesParams
     const uint32_t wg = (g - t0) * kGroup + lane_in_group;
     if (wg >= mp.row_wgs) return;
     const uint32_t bx = wg % mp.rows_x, rest = wg / mp.rows_x;
-    rows_impl::rows_body<D, 2, false>(rp, (int)bx, (int)(rest % mp.rows_y), (int)(rest / mp.rows_y), mp.rows_waves, smem);
+    rows_impl::rows_body<D, 2, KV8>(rp, (int)bx, (int)(rest % mp.rows_y), (int)(rest / mp.rows_y), mp.rows_waves, smem);
   }
 }
 
-template <int D>
+template <int D, bool KV8>
 int launch_mixed_t(const prefill_impl::TilesParams& tp, const rows_impl::RowsParams& rp,
                    const MixParams& mp, int lds, hipStream_t stream) {
   static int configured = 0;          // raising the dynamic-LDS limit is idempotent; races are benign
   if (lds > configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(mixed_kernel<D>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(mixed_kernel<D, KV8>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
       return DSV_E_LAUNCH;
     configured = lds;
   }
-  hipLaunchKernelGGL((mixed_kernel<D>), dim3(mp.total_groups * kGroup), dim3(512), lds, stream, tp, rp, mp);
+  hipLaunchKernelGGL((mixed_kernel<D, KV8>), dim3(mp.total_groups * kGroup), dim3(512), lds, stream, tp, rp, mp);
   return launch_status();
 }
 
 }  // namespace
 
 bool mixed_launch_supported(const AttnArgs& a, const PlanConfig& cfg, const PlanCounts& n) {
-  return !a.kv8 && n.tiles > 0 && n.items > 0 && cfg.row_nbuf == 2 && cfg.tile_tokens == prefill_impl::kTileQ &&
+  return n.tiles > 0 && n.items > 0 && cfg.row_nbuf == 2 && cfg.tile_tokens == prefill_impl::kTileQ &&
          cfg.part_tokens <= 64 * kBlockSize && prefill_impl::kThreads == 512 && (a.D == 128 || a.D == 64);
 }
 
@@ -74,7 +74,7 @@ int launch_mixed(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, c
                  hipStream_t stream) {
   if (!mixed_launch_supported(a, cfg, n)) return DSV_E_UNSUPPORTED;
   const int G = a.Hq / a.Hkv;
-  prefill_impl::TilesParams tp{a, w, (int32_t)n.tiles, G, nullptr};
+  const prefill_impl::TilesParams tp = prefill_impl::make_tiles_params(a, w, n);
   rows_impl::RowsParams rp{a, w, cfg.part_tokens, G};
   int waves = 1;
   while (waves < a.Hkv && waves < 8) waves <<= 1;
@@ -91,10 +91,15 @@ int launch_mixed(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, c
   mp.tile_groups = (uint32_t)tg;
   mp.total_groups = (uint32_t)(tg + rg);
   mp.rows_waves = waves;
-  const int rows_lds = waves * 2 * (a.D == 128 ? rows_impl::RowGeom<128, 2>::SLOT_BYTES : rows_impl::RowGeom<64, 2>::SLOT_BYTES);
-  if (a.D == 128)
-    return launch_mixed_t<128>(tp, rp, mp, max(rows_lds, (int)prefill_impl::TileGeom<128>::LDS_BYTES), stream);
-  return launch_mixed_t<64>(tp, rp, mp, max(rows_lds, (int)prefill_impl::TileGeom<64>::LDS_BYTES), stream);
+  const int slot = a.D == 128 ? (a.kv8 ? rows_impl::RowGeom<128, 1>::SLOT_BYTES : rows_impl::RowGeom<128, 2>::SLOT_BYTES)
+                              : (a.kv8 ? rows_impl::RowGeom<64, 1>::SLOT_BYTES : rows_impl::RowGeom<64, 2>::SLOT_BYTES);
+  const int rows_lds = waves * 2 * slot;
+  if (a.D == 128) {
+    const int lds = max(rows_lds, (int)prefill_impl::TileGeom<128>::LDS_BYTES);
+    return a.kv8 ? launch_mixed_t<128, true>(tp, rp, mp, lds, stream) : launch_mixed_t<128, false>(tp, rp, mp, lds, stream);
+  }
+  const int lds = max(rows_lds, (int)prefill_impl::TileGeom<64>::LDS_BYTES);
+  return a.kv8 ? launch_mixed_t<64, true>(tp, rp, mp, lds, stream) : launch_mixed_t<64, false>(tp, rp, mp, lds, stream);
 }
 
 }  // namespace dsv

@@ -29,16 +29,7 @@ int launch_t(const TilesParams& prm, dim3 grid, hipStream_t stream) {
 int launch_prefill_tiles(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg,
                          const PlanCounts& n, hipStream_t stream) {
   if (cfg.tile_tokens != kTileQ) return DSV_E_UNSUPPORTED;
-  TilesParams prm{a, w, (int32_t)n.tiles, a.Hq / a.Hkv, nullptr};
-  if (a.kv8) {
-    // A cache of 8-bit codes is attended through the staged bf16 copy of the spans' contexts.
-    prm.a.k_pool = w.stage_k;
-    prm.a.v_pool = w.stage_v;
-    prm.a.block_tables = w.stage_table;
-    prm.a.max_blocks = n.stage_max_blocks;
-    prm.a.kv8 = 0;
-    prm.stage_rows = w.stage_rows;
-  }
+  const TilesParams prm = make_tiles_params(a, w, n);
   dim3 grid((unsigned)(n.tiles * a.Hkv), 1u, (unsigned)ceil_div(prm.G, 4));
   if (a.D == 128) return launch_t<128>(prm, grid, stream);
   if (a.D == 64) return launch_t<64>(prm, grid, stream);

@@ -79,6 +79,21 @@ struct TilesParams {
                                // spans' contexts with a table of its own)
 };
 
+// Parameters of a launch over the tile list.  A cache of 8-bit codes is attended through the
+// staged bf16 copy of the spans' contexts and its own block table.
+inline TilesParams make_tiles_params(const AttnArgs& a, const WorkLists& w, const PlanCounts& n) {
+  TilesParams prm{a, w, (int32_t)n.tiles, a.Hq / a.Hkv, nullptr};
+  if (a.kv8) {
+    prm.a.k_pool = w.stage_k;
+    prm.a.v_pool = w.stage_v;
+    prm.a.block_tables = w.stage_table;
+    prm.a.max_blocks = n.stage_max_blocks;
+    prm.a.kv8 = 0;
+    prm.stage_rows = w.stage_rows;
+  }
+  return prm;
+}
+
 template <int D>
 struct TileGeom {
   static constexpr int KS = D / 16;          // MFMA k-steps of K Q^T

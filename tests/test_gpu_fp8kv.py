@@ -65,6 +65,25 @@ def test_more_segments_than_one_planner_pass():
     check(gen.make_batch_fp8kv("f8many", 4350, 8, 2, 64, segs))
 
 
+def test_mixed_launch_equals_the_two_kernels_apart(monkeypatch):
+    """Prefill tiles (on the staged copy) and row items (on the codes) in one launch: forced on,
+    forced off and left to the library give bit-equal outputs, and they match the oracle."""
+    from gpu_harness import run_attention_fp8kv
+    for Hq, Hkv, D, segs in [(32, 8, 128, [(300, 420), (1, 900), (64, 64), (1, 17), (3, 200), (1, 5000)]),
+                             (16, 2, 64, [(70, 70), (1, 33), (2, 40)]),
+                             (64, 8, 128, [(129, 300), (1, 2500)])]:
+        b = gen.make_batch_fp8kv("f8mixed", 4360, Hq, Hkv, D, segs)
+        monkeypatch.setenv("DSV_MIXED_LAUNCH", "1")
+        one = run_attention_fp8kv(b)
+        monkeypatch.setenv("DSV_MIXED_LAUNCH", "0")
+        two = run_attention_fp8kv(b)
+        monkeypatch.delenv("DSV_MIXED_LAUNCH", raising=False)
+        auto = run_attention_fp8kv(b)
+        np.testing.assert_array_equal(one, two)
+        np.testing.assert_array_equal(auto, two)
+        assert np.abs(one - oracle_out(b)).max() <= TOL
+
+
 def test_only_prefill_spans_and_bf16_output():
     import torch
     from gpu_harness import run_attention_fp8kv
