@@ -54,6 +54,10 @@ int launch_mixed_t(const prefill_impl::TilesParams& tp, const rows_impl::RowsPar
                    const MixParams& mp, int lds, hipStream_t stream) {
   static int configured = 0;          // raising the dynamic-LDS limit is idempotent; races are benign
   if (lds > configured) {
+    hipFuncAttributes fa;               // no static LDS: the tile body's ring must start at LDS address 0
+    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(mixed_kernel<D, KV8>)) != hipSuccess ||
+        fa.sharedSizeBytes != 0)
+      return DSV_E_LAUNCH;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(mixed_kernel<D, KV8>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
       return DSV_E_LAUNCH;

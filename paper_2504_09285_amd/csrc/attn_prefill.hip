@@ -15,6 +15,12 @@ template <int D>
 int launch_t(const TilesParams& prm, dim3 grid, hipStream_t stream) {
   static bool configured = false;       // raising the dynamic-LDS limit is idempotent; races are benign
   if (!configured) {
+    // The kernel steps through its LDS ring by address bits: the ring must start at LDS
+    // address 0, i.e. the kernel must have no static LDS in front of the dynamic part.
+    hipFuncAttributes fa;
+    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(prefill_tiles_kernel<D>)) != hipSuccess ||
+        fa.sharedSizeBytes != 0)
+      return DSV_E_LAUNCH;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_tiles_kernel<D>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, TileGeom<D>::LDS_BYTES) != hipSuccess)
       return DSV_E_LAUNCH;

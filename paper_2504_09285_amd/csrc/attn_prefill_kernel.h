@@ -13,7 +13,9 @@
 //
 // K/V tiles of 64 tokens (four 16-token blocks gathered through the block table, half a block
 // per wave) go straight from global memory into a ring of four LDS buffers with direct loads;
-// tile t+3 is requested while tile t is used.  One workgroup barrier per tile.
+// tile t+3 is requested while tile t is used.  One workgroup barrier per tile.  The ring starts
+// at LDS address 0 (the kernel owns no static LDS; the launchers check), so the fragment read
+// addresses step from buffer to buffer by an XOR of two address bits.
 //
 // The products are computed transposed, S^T = K Q^T and O^T = V^T P^T, with the 32x32x16 MFMA:
 //   - the query row is the MFMA column, so a lane owns one query row for the whole kernel: row
@@ -104,13 +106,22 @@ struct TileGeom {
   static constexpr int PPB = kBlockSize / RPP;       // pieces per 16-token block
   static constexpr int TENSOR_BYTES = kTileKV * ROWB;
   static constexpr int TILE_BYTES = 2 * TENSOR_BYTES;
-  static constexpr int LDS_BYTES = kRing * TILE_BYTES;
+  static constexpr int RING_BYTES = kRing * TILE_BYTES;
+  static constexpr int LDS_BYTES = RING_BYTES + 16;  // the ring, then the workgroup's overflow flag
   static constexpr int PPW = PPB / kWavesPerBlock;   // pieces per wave
   static constexpr int LOADS = 2 * PPW;      // direct loads per wave per tile (its share of a block of K and of V)
 };
 
 template <int CPR> __device__ __forceinline__ int k_swz(int row) { return row & (CPR - 1); }
-template <int CPR> __device__ __forceinline__ int v_swz(int row) { return 2 * (row & (CPR / 2 - 1)); }
+// V: a transpose read covers 8 token rows x 64 bytes, and the LDS serves 32 lanes (4 rows x 64
+// bytes = all 64 banks) per cycle, so rows that share banks must sit in different 64-byte
+// groups: bits 2.. of the chunk index are swizzled by the row (measured with 8 waves reading:
+// 2.8 cycles per read against 4.0 with a swizzle that only separates 32-byte pairs).
+template <int CPR> __device__ __forceinline__ int v_swz(int row) {
+  constexpr int GPR = CPR / 4;      // 64-byte groups per row
+  constexpr int RW = 16 / CPR;      // rows per 256 bytes (one pass over the banks)
+  return (4 * ((row / RW) % GPR)) ^ (2 * ((row >> 2) & 1));
+}
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   const f32x2_t v = {lo, hi};
@@ -126,15 +137,17 @@ __device__ __forceinline__ void wait_vmcnt() {
 // back (lds_issue4_*), waits (lds_wait) and then passes every result through
 // lds_ready4(): an empty asm that redefines the registers, so that no consumer can be scheduled
 // ahead of the wait while the read results are still in flight.
+// (OFF: byte offset carried in the instruction.)
+template <int OFF>
 __device__ __forceinline__ void lds_issue4_b128(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3,
                                                 u32x4_t& v0, u32x4_t& v1, u32x4_t& v2, u32x4_t& v3) {
   asm volatile(
-      "ds_read_b128 %0, %4\n\t"
-      "ds_read_b128 %1, %5\n\t"
-      "ds_read_b128 %2, %6\n\t"
-      "ds_read_b128 %3, %7"
+      "ds_read_b128 %0, %4 offset:%8\n\t"
+      "ds_read_b128 %1, %5 offset:%8\n\t"
+      "ds_read_b128 %2, %6 offset:%8\n\t"
+      "ds_read_b128 %3, %7 offset:%8"
       : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3)
-      : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+      : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "n"(OFF)
       : "memory");
 }
 // Two addresses, each read at byte offsets OFF and OFF + STEP (immediates of the instruction).
@@ -337,24 +350,47 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
   bool any_corr;
   u32x4_t kf[KS];
   u32x2_t vf0[2][DB], vf1[2][DB];          // V^T fragments [k16][db]: tokens +0..3 and +8..11
-  auto issue_k = [&](int s) __attribute__((always_inline)) {
-    const uint32_t kbuf = (uint32_t)((s / 2) % kRing) * Geo::TILE_BYTES + (uint32_t)(s & 1) * (32 * ROWB);
+  // Fragment addresses of the tile being read, K and V separately (the K reads run a tile ahead
+  // of the V reads).  They are absolute LDS addresses, and the ring starts at LDS address 0 and
+  // has four tile buffers, so stepping to the next buffer (0 -> 1 -> 2 -> 3 -> 0) is an XOR of the
+  // two address bits above a tile with 1 or 3: one instruction per address register and tile,
+  // where adding a buffer offset at every use cost one per register and sub-tile.  The offset of
+  // the sub-tile inside the tile rides in the read instructions.
+  static_assert(kRing == 4 && (Geo::TILE_BYTES & (Geo::TILE_BYTES - 1)) == 0, "XOR stepping of the ring");
+  uint32_t k_adr[KS], v_adr[DB];
+  auto ring_step = [&](int tile) __attribute__((always_inline)) {
+    return (uint32_t)((tile & 1) ? 3 * Geo::TILE_BYTES : Geo::TILE_BYTES);
+  };
+  // K fragments of sub-tile s (its parity given as a constant); after the odd sub-tile the
+  // addresses move on to the next tile.
+  auto issue_k = [&](int s, auto odd_c) __attribute__((always_inline)) {
+    constexpr int ODD = decltype(odd_c)::value;
 #pragma unroll
     for (int g4 = 0; g4 < KS; g4 += 4)
-      lds_issue4_b128(k_off[g4] + kbuf, k_off[g4 + 1] + kbuf, k_off[g4 + 2] + kbuf, k_off[g4 + 3] + kbuf,
-                      kf[g4], kf[g4 + 1], kf[g4 + 2], kf[g4 + 3]);
+      lds_issue4_b128<ODD * 32 * ROWB>(k_adr[g4], k_adr[g4 + 1], k_adr[g4 + 2], k_adr[g4 + 3],
+                                       kf[g4], kf[g4 + 1], kf[g4 + 2], kf[g4 + 3]);
+    if constexpr (ODD) {
+      const uint32_t x = ring_step(s >> 1);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) k_adr[ks] ^= x;
+    }
   };
   auto ready_k = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int g4 = 0; g4 < KS; g4 += 4) lds_ready4(kf[g4], kf[g4 + 1], kf[g4 + 2], kf[g4 + 3]);
   };
-  auto issue_v = [&](int sv, auto k16_c) __attribute__((always_inline)) {
+  auto issue_v = [&](int sv, auto odd_c, auto k16_c) __attribute__((always_inline)) {
+    constexpr int ODD = decltype(odd_c)::value;
     constexpr int k16 = decltype(k16_c)::value;
-    const uint32_t vbuf = (uint32_t)((sv / 2) % kRing) * Geo::TILE_BYTES + (uint32_t)(sv & 1) * (32 * ROWB);
 #pragma unroll
     for (int d2 = 0; d2 < DB; d2 += 2)
-      lds_issue4_tr<k16 * 16 * ROWB, 8 * ROWB>(v_off[d2] + vbuf, v_off[d2 + 1] + vbuf, vf0[k16][d2], vf1[k16][d2],
-                                               vf0[k16][d2 + 1], vf1[k16][d2 + 1]);
+      lds_issue4_tr<ODD * 32 * ROWB + k16 * 16 * ROWB, 8 * ROWB>(v_adr[d2], v_adr[d2 + 1], vf0[k16][d2], vf1[k16][d2],
+                                                                 vf0[k16][d2 + 1], vf1[k16][d2 + 1]);
+    if constexpr (ODD && k16 == 1) {
+      const uint32_t x = ring_step(sv >> 1);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) v_adr[db] ^= x;
+    }
   };
   auto ready_v = [&](int k16) __attribute__((always_inline)) {
 #pragma unroll
@@ -466,7 +502,7 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
     // served first throughout and then idles at the tile barrier while the other finishes.
     if (tg) __builtin_amdgcn_s_setprio(CUR); else __builtin_amdgcn_s_setprio(CUR ^ 1);
     if constexpr (with_pv) {
-      issue_v(s - 1, std::integral_constant<int, 0>{});
+      issue_v(s - 1, std::integral_constant<int, CUR ^ 1>{}, std::integral_constant<int, 0>{});
       lds_wait<2 * DB>();                // the K fragments (older than these 2*DB reads) are in
     } else {
       lds_wait<0>();
@@ -493,7 +529,7 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
     // reads cannot move above that group, and so anchors what follows it behind the group.
     asm volatile("" : "+v"(kf[KS - 1]));
     if constexpr (with_pv) {
-      issue_v(s - 1, std::integral_constant<int, 1>{});
+      issue_v(s - 1, std::integral_constant<int, CUR ^ 1>{}, std::integral_constant<int, 1>{});
       lds_wait<2 * DB>();                // first half of V^T in
       ready_v(0);
       pv(pfb[CUR ^ 1], 0);
@@ -502,9 +538,9 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
     if constexpr (CUR == 0) {
       lds_wait<0>();                     // this wave's last read of tile u-1 is complete
       tile_sync();
-      issue_k(s + 2);
+      issue_k(s + 2, std::integral_constant<int, CUR>{});
     } else {
-      issue_k(s + 2);
+      issue_k(s + 2, std::integral_constant<int, CUR>{});
       lds_wait<KS>();                    // second half of V^T in (the K reads may be in flight)
     }
     if constexpr (with_pv) {
@@ -532,7 +568,9 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
 
   using i0 = std::integral_constant<int, 0>;
   using i1 = std::integral_constant<int, 1>;
-  __shared__ int wg_overflow;
+  // (The flag lives behind the ring in the dynamic LDS: the kernel must own no static LDS, so
+  // that the ring starts at LDS address 0; the launchers check that.)
+  volatile int& wg_overflow = *reinterpret_cast<volatile int*>(smem + Geo::RING_BYTES);
   if (tid == 0) wg_overflow = 0;
   // One pass over the KV tiles of this work item, in fast or robust mode.
   auto attend = [&](auto robust_c) __attribute__((always_inline)) {
@@ -546,6 +584,10 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
       l_run[c] = 0.f;
     }
     any_corr = false;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) k_adr[ks] = k_off[ks];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) v_adr[db] = v_off[db];
     // ---- prologue: tiles 0..2 requested, tile 0 awaited ----
     issue_tile(0, block_id(0));
     issue_tile(1, block_id(1));
@@ -581,11 +623,11 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
       ++u_sync;
     };
     auto no_sync = []() __attribute__((always_inline)) {};
-    issue_k(0);
+    issue_k(0, i0{});
     lds_wait<0>();
     ready_k();
     qk(scb[0]);
-    issue_k(1);
+    issue_k(1, i1{});
     stage(0, i0{}, std::false_type{}, robust_c, next_tile);
     stage(1, i1{}, std::true_type{}, robust_c, no_sync);
     for (int u = 1; u < n_tiles; ++u) {
@@ -599,8 +641,8 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
     if constexpr (decltype(robust_c)::value) {
       if (__any(any_corr)) rescale(corr);
     }
-    issue_v(NS - 1, i0{});
-    issue_v(NS - 1, i1{});
+    issue_v(NS - 1, i1{}, i0{});           // NS - 1 is odd: the second sub-tile of the last tile
+    issue_v(NS - 1, i1{}, i1{});
     lds_wait<0>();
     ready_v(0);
     ready_v(1);
