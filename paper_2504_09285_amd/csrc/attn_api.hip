@@ -59,6 +59,18 @@ __host__ __device__ inline int parts_of(int ctx_eff, const PlanConfig& c) {
   return (ctx_eff + c.part_tokens - 1) / c.part_tokens;
 }
 
+// KV tiles the t-th query tile of a span visits: its last row sees tokens [0, prefix + 64(t+1)).
+__host__ __device__ inline int kv_tiles_of(int ctx, int q_len, int t, const PlanConfig& c) {
+  const int kv_end = min(ctx, ctx - q_len + (t + 1) * c.tile_tokens);
+  return (kv_end + c.tile_tokens - 1) / c.tile_tokens;
+}
+// Context partitions of a query tile that visits n_kv KV tiles.  With base = n_kv / P and
+// rem = n_kv % P, partition p of P covers base + (p < rem) KV tiles from p * base + min(p, rem):
+// sizes differ by at most one, none is empty, the shorter ones (diagonal included) come last.
+__host__ __device__ inline int tile_parts_of(int n_kv, const PlanConfig& c) {
+  return c.tile_part_tiles > 0 ? (n_kv + c.tile_part_tiles - 1) / c.tile_part_tiles : 1;
+}
+
 int validate_batch(int32_t S, const int32_t* qo, const int32_t* cl, int32_t max_blocks) {
   if (S < 0) return DSV_E_INVALID;
   if (S == 0) return DSV_OK;
@@ -72,7 +84,7 @@ int validate_batch(int32_t S, const int32_t* qo, const int32_t* cl, int32_t max_
   return DSV_OK;
 }
 
-PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8) {
+PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8, int wgs_per_tile) {
   PlanConfig c;
   c.mfma_min_qlen = env_int("DSV_MFMA_MIN_QLEN", 16);
   c.tile_tokens = 64;
@@ -106,6 +118,38 @@ PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8
   if (forced >= 16) part = forced / 16 * 16;
   if (part > 1024) part = 1024;                 // the row kernel keeps one 64-entry table vector
   c.part_tokens = (int32_t)part;
+  // Query tiles are cut along the context only when there are too few of them to fill the
+  // device (a short span on a long prefix: 8 query tiles x 8 KV heads would occupy a quarter of
+  // the compute units for the whole step).  Then the partitions are sized for about three
+  // workgroups per compute unit, and never below 16 KV tiles (1024 tokens), so that the
+  // partials a partition writes (64 tokens x 4 heads x D floats) stay small next to the K/V it
+  // reads.  DSV_TILE_PART_TILES forces a size (tests), -1 turns cutting off.
+  c.tile_part_tiles = 0;
+  int64_t kv_visits = 0, largest = 0;
+  for (int i = 0; i < S; ++i) {
+    const int q_len = qo[i + 1] - qo[i];
+    if (q_len < c.mfma_min_qlen) continue;
+    const int nt = ceil_div(q_len, c.tile_tokens);
+    for (int t = 0; t < nt; ++t) {
+      const int n_kv = kv_tiles_of(cl[i], q_len, t, c);
+      kv_visits += n_kv;
+      if (n_kv > largest) largest = n_kv;
+    }
+  }
+  // Uncut, the step lasts at least as long as its largest query tile, and at least its share of
+  // all KV tile visits; cutting pays when the former is well above the latter (measured: 512
+  // tokens on 131,072 cached ones 2.8 -> 1.3 ms, 64 on 16,384 0.38 -> 0.08 ms; 2,048 on 65,536,
+  // which already has one equal workgroup per compute unit, gets 13 % slower and is left alone).
+  const int64_t per_cu = (kv_visits * wgs_per_tile + c.num_cus - 1) / c.num_cus;
+  if (largest > 16 && 2 * largest > 3 * per_cu) {
+    int64_t t = (per_cu + 2) / 3;
+    if (t < 16) t = 16;
+    if (t > 0x3fffffff) t = 0x3fffffff;
+    c.tile_part_tiles = (int32_t)t;
+  }
+  const int forced_t = env_int("DSV_TILE_PART_TILES", 0);
+  if (forced_t > 0) c.tile_part_tiles = forced_t;
+  if (forced_t < 0) c.tile_part_tiles = 0;
   return c;
 }
 
@@ -123,7 +167,16 @@ PlanCounts count_plan(int32_t S, const int32_t* qo, const int32_t* cl, const Pla
         if (np > n.max_parts) n.max_parts = np;
       }
     } else {
-      n.tiles += ceil_div(q_len, c.tile_tokens);
+      const int nt = ceil_div(q_len, c.tile_tokens);
+      for (int t = 0; t < nt; ++t) {
+        const int np = tile_parts_of(kv_tiles_of(cl[i], q_len, t, c), c);
+        n.tiles += np;
+        if (np > 1) {
+          n.split_qtiles += 1;
+          n.tile_split_items += (int64_t)min(c.tile_tokens, q_len - t * c.tile_tokens) * np;
+        }
+        if (np > n.max_parts) n.max_parts = np;
+      }
       n.tile_pairs += (int64_t)q_len * (cl[i] - q_len) + (int64_t)q_len * (q_len + 1) / 2;
       const int nblk = ceil_div(cl[i], kBlockSize);
       n.stage_segs += 1;
@@ -150,10 +203,13 @@ size_t carve(const PlanCounts& n, int S, int Hq, int Hkv, int D, bool kv8, char*
   char* p3 = take(rows * 4); char* p4 = take(rows * 4);
   char* p5 = take(items * 16);
   char* p7 = take(tiles * 4); char* p8 = take(tiles * 4);
+  char* p7b = take(tiles * 4); char* p7c = take(tiles * 4);
+  char* p7d = take((size_t)n.split_qtiles * 16);
   char* pz = take(256);
   char* pc = take(items * 4);
-  char* p9 = take(items * (size_t)Hq * D * 4);
-  char* p10 = take(items * (size_t)Hq * 2 * 4);
+  const size_t partials = items + (size_t)n.tile_split_items;    // row items first, then cut q-tiles
+  char* p9 = take(partials * (size_t)Hq * D * 4);
+  char* p10 = take(partials * (size_t)Hq * 2 * 4);
   char *s0 = nullptr, *s1 = nullptr, *s2 = nullptr, *s3 = nullptr, *s4 = nullptr, *s5 = nullptr;
   if (kv8 && n.tiles) {
     const size_t blk_bytes = (size_t)kBlockSize * Hkv * D * 2;
@@ -168,6 +224,7 @@ size_t carve(const PlanCounts& n, int S, int Hq, int Hkv, int D, bool kv8, char*
     w->row_item0 = (int32_t*)p3; w->row_nparts = (int32_t*)p4;
     w->item_rec = (int4*)p5;
     w->tile_seq = (int32_t*)p7; w->tile_q0 = (int32_t*)p8;
+    w->tile_part = (int32_t*)p7b; w->tile_item0 = (int32_t*)p7c; w->split_rec = (int4*)p7d;
     w->zero_line = (uint32_t*)pz;
     w->item_blk0 = (int32_t*)pc;
     w->part_acc = (float*)p9; w->part_ml = (float*)p10;
@@ -205,36 +262,67 @@ __device__ int block_exclusive_scan(int v, int* smem, int* total) {
 
 // Sort key of a tile: bucket 0 holds the tiles with the most KV tiles to visit.
 constexpr int kTileBuckets = 4 * kPlanThreads;
-__device__ __forceinline__ int tile_bucket(int ctx, int q_len, int t, const PlanConfig& c) {
-  const int kv_end = min(ctx, ctx - q_len + (t + 1) * c.tile_tokens);
-  const int n = (kv_end + c.tile_tokens - 1) / c.tile_tokens;
-  return kTileBuckets - 1 - min(n, kTileBuckets - 1);
+__device__ __forceinline__ int tile_bucket(int kv_tiles) {
+  return kTileBuckets - 1 - min(kv_tiles, kTileBuckets - 1);
 }
-
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __restrict__ q_offsets,
                                                             const int32_t* __restrict__ ctx_lens,
                                                             const int32_t* __restrict__ block_tables,
                                                             int32_t max_blocks, int32_t S, PlanConfig c,
                                                             WorkLists w, int32_t has_tiles,
-                                                            int32_t stage) {
+                                                            int32_t stage, int32_t row_items) {
   __shared__ int smem[kPlanThreads];
   __shared__ int tile_slot[kTileBuckets];
+  __shared__ int split_count, split_items;      // cut q-tiles and their partials handed out so far
+  __shared__ int tseg_n;                        // segments with tile work, listed for the
+  __shared__ int tseg_list[kPlanThreads];       // cooperative passes (has_tiles == 2)
+  if (threadIdx.x == 0) { split_count = 0; split_items = 0; tseg_n = 0; }
   if (threadIdx.x < 64) w.zero_line[threadIdx.x] = 0u;
 
   // Tiles are listed heaviest first (most KV tiles to visit), so that the MFMA kernel's
   // workgroups, dispatched in list order, leave no long tile for the end: a counting sort on
   // the KV tile count.  The order of equal keys is left to the atomics; it affects nothing but
   // the dispatch order.
-  // A batch the host found no tile in (has_tiles == 0, uniform) skips the sort.
+  // has_tiles (uniform): 0 = the host found no tile, the sort is skipped; 2 = at most
+  // kPlanThreads segments hold tiles: they are listed first and all threads then share the
+  // query tiles of one listed segment after the other (a long span's tiles are not one thread's
+  // serial loop); 1 = more such segments than the list holds: each thread walks the query tiles
+  // of its own segments.
   for (int b = (int)threadIdx.x; has_tiles && b < kTileBuckets; b += kPlanThreads) tile_slot[b] = 0;
   __syncthreads();
-  for (int i = (int)threadIdx.x; has_tiles && i < S; i += kPlanThreads) {
-    const int q_len = q_offsets[i + 1] - q_offsets[i], ctx = ctx_lens[i];
-    if (q_len > 0 && !on_row_path(q_len, c)) {
-      const int n_tiles = (q_len + c.tile_tokens - 1) / c.tile_tokens;
-      for (int t = 0; t < n_tiles; ++t) atomicAdd(&tile_slot[tile_bucket(ctx, q_len, t, c)], 1);
+  if (has_tiles == 2) {
+    for (int i = (int)threadIdx.x; i < S; i += kPlanThreads) {
+      const int q_len = q_offsets[i + 1] - q_offsets[i];
+      if (q_len > 0 && !on_row_path(q_len, c)) tseg_list[atomicAdd(&tseg_n, 1)] = i;
     }
+    __syncthreads();
   }
+  // fn(segment, q_len, ctx, q0, query tile) for every query tile of the batch, spread over the threads.
+  auto for_each_query_tile = [&](auto&& fn) {
+    if (has_tiles == 2) {
+      const int n_list = tseg_n;
+      for (int k = 0; k < n_list; ++k) {
+        const int i = tseg_list[k];
+        const int q0 = q_offsets[i], q_len = q_offsets[i + 1] - q0, ctx = ctx_lens[i];
+        const int n_tiles = (q_len + c.tile_tokens - 1) / c.tile_tokens;
+        for (int t = (int)threadIdx.x; t < n_tiles; t += kPlanThreads) fn(i, q_len, ctx, t);
+      }
+    } else if (has_tiles == 1) {
+      for (int i = (int)threadIdx.x; i < S; i += kPlanThreads) {
+        const int q0 = q_offsets[i], q_len = q_offsets[i + 1] - q0, ctx = ctx_lens[i];
+        if (q_len > 0 && !on_row_path(q_len, c)) {
+          const int n_tiles = (q_len + c.tile_tokens - 1) / c.tile_tokens;
+          for (int t = 0; t < n_tiles; ++t) fn(i, q_len, ctx, t);
+        }
+      }
+    }
+  };
+  for_each_query_tile([&](int, int q_len, int ctx, int t) {
+    const int n_kv = kv_tiles_of(ctx, q_len, t, c), P = tile_parts_of(n_kv, c);
+    const int base_kv = n_kv / P, rem = n_kv - base_kv * P;
+    if (rem) atomicAdd(&tile_slot[tile_bucket(base_kv + 1)], rem);
+    atomicAdd(&tile_slot[tile_bucket(base_kv)], P - rem);
+  });
   __syncthreads();
   if (has_tiles) {
     constexpr int kPer = kTileBuckets / kPlanThreads;
@@ -244,6 +332,29 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
     for (int k = 0; k < kPer; ++k) { tile_slot[threadIdx.x * kPer + k] = ex; ex += cnt[k]; }
     __syncthreads();
   }
+
+  // Placement: every query tile takes list positions for its partitions (two sizes at most).
+  for_each_query_tile([&](int i, int q_len, int ctx, int t) {
+    const int n_kv = kv_tiles_of(ctx, q_len, t, c), P = tile_parts_of(n_kv, c);
+    int first_partial = -1;
+    if (P > 1) {
+      // A cut q-tile: its partials (one per query token and partition) sit behind the row
+      // path's items; the order in which q-tiles take their ranges does not matter.
+      const int ntok = min(c.tile_tokens, q_len - t * c.tile_tokens);
+      first_partial = row_items + atomicAdd(&split_items, ntok * P);
+      w.split_rec[atomicAdd(&split_count, 1)] = make_int4(i, t * c.tile_tokens, P, first_partial);
+    }
+    const int base_kv = n_kv / P, rem = n_kv - base_kv * P;
+    const int pos_long = rem ? atomicAdd(&tile_slot[tile_bucket(base_kv + 1)], rem) : 0;
+    const int pos_short = atomicAdd(&tile_slot[tile_bucket(base_kv)], P - rem);
+    for (int pp = 0; pp < P; ++pp) {
+      const int pos = pp < rem ? pos_long + pp : pos_short + (pp - rem);
+      w.tile_seq[pos] = i;
+      w.tile_q0[pos] = t * c.tile_tokens;
+      w.tile_part[pos] = pp | (P << 16);
+      w.tile_item0[pos] = first_partial;
+    }
+  });
 
   int row_carry = 0, item_carry = 0, stage_carry = 0, sblk_carry = 0;
   for (int base = 0; base < S; base += kPlanThreads) {
@@ -274,11 +385,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
       w.row_nparts[r] = np;
       for (int p = 0; p < np; ++p) w.item_rec[item0 + p] = make_int4(i, q0 + j, ctx_eff, p | (np << 16));
       item0 += np;
-    }
-    for (int t = 0; t < n_tiles; ++t) {
-      const int pos = atomicAdd(&tile_slot[tile_bucket(ctx, q_len, t, c)], 1);
-      w.tile_seq[pos] = i;
-      w.tile_q0[pos] = t * c.tile_tokens;
     }
     row_carry += tot_rows;
     item_carry += tot_items;
@@ -318,20 +424,34 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
 // in flight per thread, so the kernel is not a chain of dependent memory round trips.
 constexpr int kMergeChunk = 64;
 
-template <int D>
+// TILES = false: blockIdx.x is a row of the row path.  TILES = true: blockIdx.x / 64 is a cut
+// q-tile of the MFMA path and blockIdx.x % 64 the query token in it.
+template <int D, bool TILES>
 __global__ __launch_bounds__(256) void merge_kernel(AttnArgs a, WorkLists w) {
   constexpr int kThreadsPerHead = D / 4;
   constexpr int kHeadsPerBlock = 256 / kThreadsPerHead;
   __shared__ float s_m[kHeadsPerBlock][kMergeChunk];
   __shared__ float s_l[kHeadsPerBlock][kMergeChunk];
-  const int r = blockIdx.x;
-  const int np = w.row_nparts[r];
-  if (np <= 1) return;                                   // uniform for the workgroup
+  int np, item0, qtok;
+  if constexpr (TILES) {
+    const int4 rec = w.split_rec[blockIdx.x / 64];       // {seq, q0 of the tile, partitions, first partial}
+    const int j = (int)blockIdx.x % 64;
+    const int q_begin = a.q_offsets[rec.x];
+    if (rec.y + j >= a.q_offsets[rec.x + 1] - q_begin) return;   // ragged last tile (uniform)
+    np = rec.z;
+    item0 = rec.w + j * np;
+    qtok = q_begin + rec.y + j;
+  } else {
+    const int r = blockIdx.x;
+    np = w.row_nparts[r];
+    if (np <= 1) return;                                 // uniform for the workgroup
+    item0 = w.row_item0[r];
+    qtok = w.row_qtok[r];
+  }
   const int hl = (int)threadIdx.x / kThreadsPerHead;     // head within the block
   const int h = blockIdx.y * kHeadsPerBlock + hl;
   const bool h_ok = h < a.Hq;
   const int d4 = (int)threadIdx.x % kThreadsPerHead;
-  const int item0 = w.row_item0[r];
   const float2* ml = reinterpret_cast<const float2*>(w.part_ml);
   const float4* pa = reinterpret_cast<const float4*>(w.part_acc);
 
@@ -382,7 +502,7 @@ __global__ __launch_bounds__(256) void merge_kernel(AttnArgs a, WorkLists w) {
   if (!h_ok) return;
   const float inv = a.out_scale / l_run;
   acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
-  const int64_t o = ((int64_t)w.row_qtok[r] * a.Hq + h) * D + d4 * 4;
+  const int64_t o = ((int64_t)qtok * a.Hq + h) * D + d4 * 4;
   if (a.out_bf16) {
     ushort4 ob;
     ob.x = f32_to_bf16_rne(acc.x); ob.y = f32_to_bf16_rne(acc.y);
@@ -443,15 +563,21 @@ int launch_stage(const AttnArgs& a, const WorkLists& w, const PlanCounts& n, hip
 }
 
 int launch_merge(const AttnArgs& a, const WorkLists& w, const PlanCounts& n, hipStream_t stream) {
-  if (n.split_items == 0) return DSV_OK;
-  if (a.D == 128) {
-    dim3 grid((unsigned)n.rows, (unsigned)ceil_div(a.Hq, 8));
-    hipLaunchKernelGGL(merge_kernel<128>, grid, dim3(256), 0, stream, a, w);
-  } else {
-    dim3 grid((unsigned)n.rows, (unsigned)ceil_div(a.Hq, 16));
-    hipLaunchKernelGGL(merge_kernel<64>, grid, dim3(256), 0, stream, a, w);
+  const unsigned gy = (unsigned)ceil_div(a.Hq, a.D == 128 ? 8 : 16);
+  if (n.split_items) {
+    dim3 grid((unsigned)n.rows, gy);
+    if (a.D == 128) hipLaunchKernelGGL((merge_kernel<128, false>), grid, dim3(256), 0, stream, a, w);
+    else hipLaunchKernelGGL((merge_kernel<64, false>), grid, dim3(256), 0, stream, a, w);
+    if (launch_status()) return DSV_E_LAUNCH;
   }
-  return launch_status();
+  if (n.split_qtiles) {
+    if (n.split_qtiles * 64 > 0x7fffffffLL) return DSV_E_UNSUPPORTED;
+    dim3 grid((unsigned)(n.split_qtiles * 64), gy);
+    if (a.D == 128) hipLaunchKernelGGL((merge_kernel<128, true>), grid, dim3(256), 0, stream, a, w);
+    else hipLaunchKernelGGL((merge_kernel<64, true>), grid, dim3(256), 0, stream, a, w);
+    if (launch_status()) return DSV_E_LAUNCH;
+  }
+  return DSV_OK;
 }
 
 }  // namespace dsv
@@ -466,7 +592,8 @@ size_t workspace_bytes_for(bool kv8, int32_t num_seqs, const int32_t* q_offsets_
   if (num_q_heads < 1 || num_kv_heads < 1 || num_q_heads % num_kv_heads) return 0;
   if (head_dim != 64 && head_dim != 128) return 0;
   if (validate_batch(num_seqs, q_offsets_host, ctx_lens_host, -1) != DSV_OK) return 0;
-  const PlanConfig c = choose_plan(num_seqs, q_offsets_host, ctx_lens_host, kv8);
+  const PlanConfig c = choose_plan(num_seqs, q_offsets_host, ctx_lens_host, kv8,
+                                   num_kv_heads * ceil_div(num_q_heads / num_kv_heads, 4));
   const PlanCounts n = count_plan(num_seqs, q_offsets_host, ctx_lens_host, c);
   return carve(n, num_seqs, num_q_heads, num_kv_heads, head_dim, kv8, nullptr, nullptr);
 }
@@ -498,10 +625,12 @@ int run_attention(bool kv8, float k_scale, float v_scale, const void* q, void* o
   rc = validate_batch(num_seqs, q_offsets_host, ctx_lens_host, max_blocks_per_seq);
   if (rc) return rc;
 
-  const PlanConfig cfg = choose_plan(num_seqs, q_offsets_host, ctx_lens_host, kv8);
+  const PlanConfig cfg = choose_plan(num_seqs, q_offsets_host, ctx_lens_host, kv8,
+                                     pool->num_kv_heads * ceil_div(num_q_heads / pool->num_kv_heads, 4));
   const PlanCounts n = count_plan(num_seqs, q_offsets_host, ctx_lens_host, cfg);
   if (n.items > 0x7fffffffLL || n.tiles > 0x7fffffffLL || n.rows > 0x7fffffffLL ||
-      n.max_parts > 0xffff || n.stage_blocks > 0x7fffffffLL)
+      n.max_parts > 0x7fff || n.stage_blocks > 0x7fffffffLL ||
+      n.items + n.tile_split_items > 0x7fffffffLL)
     return DSV_E_UNSUPPORTED;
   WorkLists w;
   const size_t need = carve(n, num_seqs, num_q_heads, pool->num_kv_heads, pool->head_dim, kv8,
@@ -523,6 +652,9 @@ int run_attention(bool kv8, float k_scale, float v_scale, const void* q, void* o
   a.Hkv = pool->num_kv_heads;
   a.D = pool->head_dim;
   a.scale_log2e = kv8 ? softmax_scale * k_scale * 1.4426950408889634f : softmax_scale * 1.4426950408889634f;
+  // A scale of exactly zero (uniform weights) would turn masked scores, -inf, into NaN when it
+  // multiplies them; a scale too small to move any finite score does the same job.
+  if (a.scale_log2e == 0.0f) a.scale_log2e = 1e-30f;
   a.out_bf16 = out_dtype == DSV_OUT_BF16;
   a.out_scale = kv8 ? v_scale : 1.0f;
   a.kv8 = kv8 ? 1 : 0;
@@ -532,8 +664,8 @@ int run_attention(bool kv8, float k_scale, float v_scale, const void* q, void* o
   {
     EventScope ev(DSV_KERNEL_PLAN, stream);
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, q_offsets, ctx_lens,
-                       block_tables, max_blocks_per_seq, num_seqs, cfg, w, n.tiles > 0 ? 1 : 0,
-                       stage ? 1 : 0);
+                       block_tables, max_blocks_per_seq, num_seqs, cfg, w, n.tiles == 0 ? 0 : (n.stage_segs <= kPlanThreads ? 2 : 1),
+                       stage ? 1 : 0, (int32_t)n.items);
     if ((rc = launch_status())) return rc;
   }
   if (stage) {
@@ -566,7 +698,7 @@ int run_attention(bool kv8, float k_scale, float v_scale, const void* q, void* o
       if ((rc = launch_rows(a, w, cfg, n, stream))) return rc;
     }
   }
-  if (n.split_items) {
+  if (n.split_items || n.split_qtiles) {
     EventScope ev(DSV_KERNEL_MERGE, stream);
     if ((rc = launch_merge(a, w, n, stream))) return rc;
   }

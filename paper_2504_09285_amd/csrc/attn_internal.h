@@ -12,20 +12,27 @@ namespace dsv {
 //    shorter than mfma_min_qlen tokens.  A row with one partition writes its output directly;
 //    otherwise each partition writes an unnormalised partial and a merge kernel combines them.
 //  * "tile" work: tile_tokens consecutive query tokens of a long prefill span for one KV head,
-//    processed by the MFMA kernel.
+//    processed by the MFMA kernel.  When the batch holds too few query tiles to fill the device
+//    (a short span on a long prefix), a query tile's context is cut into tile_part_tiles-sized
+//    partitions as well: each partition is a work item that writes unnormalised partials, and a
+//    merge kernel combines them (same arithmetic as for split rows).
 struct PlanConfig {
   int32_t part_tokens;     // multiple of 16
   int32_t mfma_min_qlen;   // spans with q_len >= this go to the MFMA kernel
   int32_t tile_tokens;     // query tokens per MFMA tile
   int32_t row_nbuf;        // LDS ring slots (blocks) per wave of the row kernel: 2, 3, 4, 6 or 8
   int32_t num_cus;         // compute units of the device (sizes the persistent grid)
+  int32_t tile_part_tiles; // 0: query tiles are never cut along the context; else a query tile
+                           // that visits n KV tiles is cut into ceil(n / tile_part_tiles) partitions
 };
 
 struct PlanCounts {
   int64_t rows = 0;        // query tokens on the row path
   int64_t items = 0;       // (row, partition) work items
   int64_t split_items = 0; // items belonging to rows with more than one partition
-  int64_t tiles = 0;       // (span, q-tile) work items of the MFMA path
+  int64_t tiles = 0;       // (span, q-tile, context partition) work items of the MFMA path
+  int64_t split_qtiles = 0;   // q-tiles cut into more than one partition
+  int64_t tile_split_items = 0;  // (query token, partition) partials of those q-tiles
   int32_t max_parts = 0;
   int64_t row_tokens = 0;  // KV tokens the row path streams (per KV head)
   int64_t tile_pairs = 0;  // causal (query, key) pairs of the MFMA path (per query head)
@@ -47,6 +54,11 @@ struct WorkLists {
                            // (row, partition) work item needs, in one 16-byte scalar read
   int32_t* tile_seq;       // [tiles]
   int32_t* tile_q0;        // [tiles] first new-token index j of the tile
+  int32_t* tile_part;      // [tiles] partition | partitions << 16
+  int32_t* tile_item0;     // [tiles] cut q-tiles: first partial of the q-tile (token j of the tile,
+                           // partition p -> item tile_item0 + j * partitions + p), counted
+                           // after the row path's items; -1 for uncut q-tiles
+  int4*    split_rec;      // [split_qtiles] {seq, q0 of the tile, partitions, first partial}
   uint32_t* zero_line;     // 256 bytes of zeros (stands in for V rows that must not be read)
   int32_t* item_blk0;      // [items] pool block id of the item's first block
   float*   part_acc;       // [items][Hq][D]  unnormalised partial outputs

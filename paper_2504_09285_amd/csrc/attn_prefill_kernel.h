@@ -241,12 +241,21 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
   const int32_t* table = a.block_tables + (int64_t)table_row * a.max_blocks;
   const int nblk = (ctx + kBlockSize - 1) / kBlockSize;
   const int kv_end = min(ctx, prefix + j0 + kTileQ);          // exclusive: last visible token + 1
-  const int n_tiles = (kv_end + kTileKV - 1) / kTileKV;
+  // The work item covers KV tiles [t_first, t_first + n_tiles) of the n_kv the query tile
+  // visits: all of them, or one of several nearly equal partitions whose results a merge kernel
+  // combines.  Tile and sub-tile indices below are relative to t_first.
+  const int n_kv = (kv_end + kTileKV - 1) / kTileKV;
+  const int part_rec = prm.w.tile_part[tile];
+  const int part = part_rec & 0xffff, nparts = part_rec >> 16;
+  const int base_kv = n_kv / nparts, rem_kv = n_kv - base_kv * nparts;
+  const int t_first = part * base_kv + min(part, rem_kv);
+  const int n_tiles = base_kv + (part < rem_kv ? 1 : 0);
+  const int pos0 = t_first * kTileKV;                          // position of the partition's first token
   const int NS = 2 * n_tiles;                                  // 32-token sub-tiles
 
   // Query fragments: B operand of S^T = K Q^T; lane (jrow, hh) holds dims 16*ks + 8*hh .. +8.
   const int jq = j0 + 32 * tg + jrow;    // new-token index of this lane's query row
-  const int p_j = prefix + jq;           // its absolute position
+  const int p_j = prefix + jq - pos0;    // its position, counted from the partition's first token
   bool head_ok[NH];
   int head[NH];
   uint4 qf[NH][KS];
@@ -293,11 +302,11 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
   // needs a branch; whether the block exists is decided when the id is used, so nothing waits
   // for the load here.
   auto block_id = [&](int t) __attribute__((always_inline)) -> int {
-    const int b = t * (kTileKV / kBlockSize) + blk_in_tile;
+    const int b = (t_first + t) * (kTileKV / kBlockSize) + blk_in_tile;
     return ctable[min(b, nblk - 1)];
   };
   auto issue_tile = [&](int t, int bid) __attribute__((always_inline)) {
-    const int b = t * (kTileKV / kBlockSize) + blk_in_tile;
+    const int b = (t_first + t) * (kTileKV / kBlockSize) + blk_in_tile;
     unsigned char* kdst = smem + (t % kRing) * Geo::TILE_BYTES + blk_in_tile * (kBlockSize * ROWB) +
                           half * (PPW) * 1024;
     unsigned char* vdst = kdst + Geo::TENSOR_BYTES;
@@ -445,7 +454,9 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
 #pragma unroll
         for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[c][r]);
         mx = other_half_max(mx);
-        const float m_cand = mx * scale;
+        // (Clamped: a row may see no token of a context partition's first sub-tile, or of the
+        // whole partition; its sum and accumulators then stay zero.)
+        const float m_cand = fmaxf(mx * scale, kMinusBig);
         const float m_new = (first || m_cand > m_run[c] + kMaxSlack) ? m_cand : m_run[c];
         if constexpr (robust && !first) {
           corr[c] = __builtin_amdgcn_exp2f(m_run[c] - m_new);
@@ -510,7 +521,7 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
     ready_k();
     // Only sub-tiles that reach past some row's own position need the causal mask (a
     // wave-uniform branch, so the unmasked path pays one scalar compare).
-    if (s * 32 + 31 > prefix + j0 + 32 * tg) {
+    if (s * 32 + 31 > prefix + j0 + 32 * tg - pos0) {
 #pragma unroll
       for (int c = 0; c < NH; ++c)
 #pragma unroll
@@ -657,10 +668,26 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
   __syncthreads();
   if (wg_overflow) attend(std::true_type{});
 
+  // A cut q-tile writes unnormalised partials (accumulators, and the reference / sum pair per
+  // row and head) for the merge kernel; token j of the tile, partition p -> partial
+  // first + j * partitions + p.
+  const int first_partial = nparts > 1 ? prm.w.tile_item0[tile] : -1;
 #pragma unroll
   for (int c = 0; c < NH; ++c) {
     const float l_tot = other_half_sum(l_run[c]);
     if (!head_ok[c]) continue;
+    if (nparts > 1) {
+      const int64_t ph = ((int64_t)first_partial + (int64_t)(jq - j0) * nparts + part) * a.Hq + head[c];
+      float* pa = prm.w.part_acc + ph * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int aa = 0; aa < 4; ++aa)
+          *reinterpret_cast<float4*>(pa + db * 32 + aa * 8 + hh * 4) =
+              make_float4(o[c][db][aa * 4 + 0], o[c][db][aa * 4 + 1], o[c][db][aa * 4 + 2], o[c][db][aa * 4 + 3]);
+      if (hh == 0) *reinterpret_cast<float2*>(prm.w.part_ml + ph * 2) = make_float2(m_run[c], l_tot);
+      continue;
+    }
     const float inv = a.out_scale / l_tot;
     const int64_t o_row = ((int64_t)(q0 + jq) * a.Hq + head[c]) * D;
 #pragma unroll

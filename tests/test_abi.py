@@ -106,3 +106,16 @@ def test_fp8kv_entry_points_check_scales_and_workspace_before_any_gpu_work(lib):
     assert grow >= 640 * 4 * 8 * 128                        # the bf16 copy of the span's context
     assert lib.kv_pack_chunks_fp8(C.byref(pool), None, 1, None, None, 0, None, None) == 0
     assert lib.kv_pack_chunks_fp8(C.byref(pool), None, 1, None, None, 1, None, None) == -1
+
+
+def test_workspace_holds_partials_when_query_tiles_are_cut(lib, monkeypatch):
+    f = dsv.attn_mixed_batch_workspace_bytes
+    monkeypatch.delenv("DSV_TILE_PART_TILES", raising=False)
+    cut = f([0, 128], [20128], 32, 8, 128)              # 2 query tiles on 20,000 cached tokens: cut
+    monkeypatch.setenv("DSV_TILE_PART_TILES", "-1")
+    uncut = f([0, 128], [20128], 32, 8, 128)
+    assert cut - uncut >= 128 * 2 * 32 * 128 * 4        # at least two partials per token and head
+    monkeypatch.delenv("DSV_TILE_PART_TILES", raising=False)
+    assert f([0, 2048], [2048], 32, 8, 128) == pytest.approx(f([0, 2048], [2048], 32, 8, 128))
+    monkeypatch.setenv("DSV_TILE_PART_TILES", "-1")
+    assert f([0, 2048] * 1, [2048], 32, 8, 128) > 0

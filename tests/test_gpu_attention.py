@@ -1,6 +1,8 @@
 """GPU parity of attn_mixed_batch against the fp64 CPU oracle, element by element on the same
 seeded inputs, through the C ABI.  Tolerance: max abs error <= 1e-2 on the fp32 output (bf16
 inputs, fp32 accumulation); the bf16 output must be the round-to-nearest-even of the fp32 one."""
+import os
+
 import numpy as np
 import pytest
 
@@ -260,6 +262,51 @@ def _many_segments():
 def test_more_segments_than_one_planner_pass():
     b = gen.make_batch("many", 91, 8, 2, 64, _many_segments())
     check(b)
+
+
+@pytest.mark.parametrize("part_tiles", [1, 2, 3, 5])
+def test_query_tiles_cut_along_the_context_forced(monkeypatch, part_tiles):
+    """DSV_TILE_PART_TILES forces every query tile's context into partitions of that many KV
+    tiles (production only cuts when query tiles are scarce, and never below 16): partials +
+    merge must reproduce the oracle on spans with and without prefix, ragged tails, partitions
+    of one tile, and rows that see nothing of their last partition."""
+    monkeypatch.setenv("DSV_TILE_PART_TILES", str(part_tiles))
+    segs = [(16, 16), (1, 90), (64, 64), (65, 130), (100, 1000), (3, 40), (130, 131), (17, 600),
+            (1, 2000), (200, 777)]
+    for Hq, Hkv, D in [(32, 8, 128), (4, 1, 64), (6, 2, 128)]:
+        check(gen.make_batch("cut", 93 + part_tiles, Hq, Hkv, D, segs))
+
+
+def test_short_span_on_a_long_prefix_is_cut_by_the_library():
+    """Two query tiles on 20,000 cached tokens: 16 workgroups uncut; the library cuts the context
+    so that the device is filled, and the result matches the oracle (all rows)."""
+    import paper_2504_09285_amd as dsv
+    b = gen.make_batch("long_prefix", 94, 32, 8, 128, [(128, 20128), (1, 300)])
+    cut = dsv.attn_mixed_batch_workspace_bytes(b.q_offsets, b.ctx_lens, b.Hq, b.Hkv, b.D)
+    os.environ["DSV_TILE_PART_TILES"] = "-1"
+    try:
+        uncut = dsv.attn_mixed_batch_workspace_bytes(b.q_offsets, b.ctx_lens, b.Hq, b.Hkv, b.D)
+    finally:
+        del os.environ["DSV_TILE_PART_TILES"]
+    assert cut > uncut                  # partials of the cut q-tiles
+    check(b)
+
+
+def test_scale_zero_gives_the_mean_of_the_visible_values():
+    """softmax_scale = 0: uniform weights over the causal context (masked scores must not turn
+    into NaN when multiplied by a zero scale)."""
+    b = gen.make_batch("scale0", 95, 8, 2, 128, [(70, 100), (1, 50), (5, 5), (1, 600)])
+    b.scale = 0.0
+    check(b)
+
+
+def test_more_prefill_spans_than_the_planner_lists():
+    """1,100 spans of 16-20 tokens: more segments with tile work than the planner's cooperative
+    list holds, so every thread walks the query tiles of its own segments."""
+    rng = np.random.default_rng(12)
+    segs = [(int(q), int(q + p)) for q, p in zip(rng.integers(16, 21, 1100), rng.integers(0, 60, 1100))]
+    segs += [(1, 100), (3, 50)]
+    check(gen.make_batch("many_spans", 96, 4, 1, 64, segs))
 
 
 def test_config3_prefill_heavy_shrunk():

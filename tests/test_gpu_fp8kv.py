@@ -84,6 +84,13 @@ def test_mixed_launch_equals_the_two_kernels_apart(monkeypatch):
         assert np.abs(one - oracle_out(b)).max() <= TOL
 
 
+def test_query_tiles_cut_along_the_context_forced(monkeypatch):
+    """Context partitions of the query tiles on the staged copy of an 8-bit cache."""
+    monkeypatch.setenv("DSV_TILE_PART_TILES", "2")
+    segs = [(64, 64), (65, 130), (100, 1000), (3, 40), (130, 131), (1, 2000)]
+    check(gen.make_batch_fp8kv("f8cut", 4370, 16, 2, 128, segs))
+
+
 def test_only_prefill_spans_and_bf16_output():
     import torch
     from gpu_harness import run_attention_fp8kv
