@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5] [--no-extras]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|lp] [--no-extras]
                     [--no-cpu-baseline]
 
 A step is one attn_mixed_batch call (plan + attention kernels + merge) over one seeded synthetic
@@ -436,6 +436,8 @@ def make_workload(name, threads):
         return gen.config4(threads=threads)[0]
     if name == "c5":
         return gen.config5_attention(threads=threads)
+    if name == "lp":
+        return gen.long_prefix_chunk(threads=threads)
     raise SystemExit("unknown workload " + name)
 
 
@@ -444,7 +446,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5", "lp"])
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--full-extras", action="store_true", help="config 5 at full context lengths (16 GB of KV)")
@@ -487,7 +489,7 @@ def main():
                    "kv_tokens": int(b.ctx_lens.sum()), "out_dtype": "bf16"},
         "kernel_ms": res["kernel_ms"],
     }
-    if "prefill" in res and (args.workload == "c3"):
+    if "prefill" in res and (args.workload in ("c3", "lp")):
         p = res["prefill"]
         line["roofline"] = {"bound": "mfma", "achieved": p["TFLOP/s"], "peak": MFMA_BF16_PEAK_TFLOPS,
                             "unit": "TFLOP/s", "frac": p["frac_mfma_peak"], "traffic": None,
@@ -516,6 +518,10 @@ def main():
         extras["kv_append_c3"] = bench_append(gen.config3(threads=threads), 20, 3, hev)
         extras["c4_micro_request"] = bench_config4(threads, 10, 2, hev)
         extras["fp8kv"] = bench_fp8kv(20, 3, hev)
+        # A 512-token chunk on a 130,560-token prefix: eight query tiles, cut along the context.
+        rl, dl = bench_attention(gen.long_prefix_chunk(threads=threads), 10, 2, hev)
+        extras["long_prefix_chunk"] = {k: rl[k] for k in ("ms_per_step", "tokens_per_s", "kernel_ms", "prefill") if k in rl}
+        del dl
         # Chunk-pipelined hand-off (paper section 4.3): transfer of chunk k next to computation of k+1.
         from paper_2504_09285_amd.chunk_pipeline import measure as measure_chunk_pipeline
         extras["chunk_pipelined_handoff"] = measure_chunk_pipeline(8192, 512, 8)

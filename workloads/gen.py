@@ -384,3 +384,11 @@ def config5_handoff_fp8kv(shrink: int = 1, layers: int = 32) -> Handoff:
     return Handoff("c5_handoff_fp8kv", layers, 8, 128, e4m3_codes(seed, 41, shp_s), e4m3_codes(seed, 42, shp_s),
                    src_tables, e4m3_codes(seed, 43, shp_d), e4m3_codes(seed, 44, shp_d), dst_tables,
                    chunks, n_el, elem_bytes=1)
+
+
+def long_prefix_chunk(q_len: int = 512, prefix: int = 131072 - 512, threads: int = 8) -> AttnBatch:
+    """One chunk of a chunked prefill late in a long prompt (or the second span of a micro-request
+    split near the end): q_len new tokens on a long cached prefix, nothing else in the batch.
+    Few query tiles, each with a very long context."""
+    return make_batch("long_prefix_chunk", seed_for(6), 32, 8, 128, [(q_len, prefix + q_len)],
+                      threads=threads, meta={"q_len": q_len, "prefix": prefix})
