@@ -515,6 +515,14 @@ def main():
             r3, d3 = bench_attention(gen.config3(threads=threads), 10, 2, hev)
             extras["c3_prefill_heavy"] = {k: r3[k] for k in ("ms_per_step", "tokens_per_s", "mixed_launch_ms", "ms_per_step_kernels_apart", "kernel_ms", "prefill", "decode") if k in r3}
             del d3
+        keys = ("ms_per_step", "tokens_per_s", "mixed_launch_ms", "ms_per_step_kernels_apart", "kernel_ms", "prefill", "decode")
+        r1, d1 = bench_attention(gen.config1()[0], 20, 3, hev)          # the tiny case: launch-bound
+        extras["c1_tiny"] = {k: r1[k] for k in keys if k in r1}
+        del d1
+        if args.workload != "c5":
+            r5, d5 = bench_attention(gen.config5_attention(threads=threads), 10, 2, hev)   # full contexts, one layer
+            extras["c5_long_context"] = {k: r5[k] for k in keys if k in r5}
+            del d5
         extras["kv_append_c3"] = bench_append(gen.config3(threads=threads), 20, 3, hev)
         extras["c4_micro_request"] = bench_config4(threads, 10, 2, hev)
         extras["fp8kv"] = bench_fp8kv(20, 3, hev)
