@@ -1,0 +1,71 @@
+"""Seeded random mixed batches against the oracle: head geometries (also group sizes that are not
+powers of two), head_dim 64 and 128, decodes, short spans, long spans with and without prefix in
+any order, and the library's tuning knobs (partition sizes of rows and of query tiles, mixed
+launch on or off) drawn at random as well.  bf16 cache and 8-bit cache.  Tolerance as for the
+fixed cases: max abs error <= 1e-2 on the fp32 output."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import gen
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-2
+
+
+def random_case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    Hkv = int(rng.choice([1, 2, 3, 8]))
+    G = int(rng.choice([1, 2, 4, 5, 8, 16]))
+    D = int(rng.choice([64, 128]))
+    segs = []
+    for _ in range(int(rng.integers(1, 11))):
+        kind = rng.integers(0, 4)
+        if kind == 0:
+            segs.append((1, int(rng.integers(1, 1500))))
+        elif kind == 1:
+            q = int(rng.integers(2, 16))
+            segs.append((q, q + int(rng.integers(0, 600))))
+        elif kind == 2:
+            q = int(rng.integers(16, 200))
+            segs.append((q, q))
+        else:
+            q = int(rng.integers(16, 200))
+            segs.append((q, q + int(rng.integers(1, 1200))))
+    env = {}
+    if rng.random() < 0.5:
+        env["DSV_TILE_PART_TILES"] = str(int(rng.choice([1, 2, 3, 7])))
+    if rng.random() < 0.5:
+        env["DSV_PART_TOKENS"] = str(int(rng.choice([16, 64, 256])))
+    if rng.random() < 0.6:
+        env["DSV_MIXED_LAUNCH"] = str(int(rng.integers(0, 2)))
+    return Hkv * G, Hkv, D, segs, env
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_batch_bf16_cache(monkeypatch, seed):
+    from gpu_harness import run_attention
+    Hq, Hkv, D, segs, env = random_case(seed)
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    b = gen.make_batch("rnd%d" % seed, 7000 + seed, Hq, Hkv, D, segs)
+    got = run_attention(b)
+    ref = oracle.attn_mixed_batch(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens, b.scale)
+    assert np.isfinite(got).all(), (Hq, Hkv, D, segs, env)
+    err = np.abs(got - ref).max()
+    assert err <= TOL, (err, Hq, Hkv, D, segs, env)
+
+
+@pytest.mark.parametrize("seed", range(24, 40))
+def test_random_batch_8bit_cache(monkeypatch, seed):
+    from gpu_harness import run_attention_fp8kv
+    Hq, Hkv, D, segs, env = random_case(seed)
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    b = gen.make_batch_fp8kv("rnd8_%d" % seed, 7000 + seed, Hq, Hkv, D, segs)
+    got = run_attention_fp8kv(b)
+    ref = oracle.attn_mixed_batch_fp8kv(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens,
+                                        b.scale, b.meta["k_scale"], b.meta["v_scale"])
+    assert np.isfinite(got).all(), (Hq, Hkv, D, segs, env)
+    err = np.abs(got - ref).max()
+    assert err <= TOL, (err, Hq, Hkv, D, segs, env)
