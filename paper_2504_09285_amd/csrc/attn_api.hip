@@ -52,8 +52,9 @@ int device_cus() {
 
 // ---- plan: counts --------------------------------------------------------------------------
 
-__host__ __device__ inline bool on_row_path(int q_len, const PlanConfig& c) {
-  return q_len < c.mfma_min_qlen;
+__host__ __device__ inline bool on_row_path(int q_len, int ctx, const PlanConfig& c) {
+  if (q_len >= c.mfma_min_qlen) return false;
+  return q_len < 2 || ctx < c.mfma_long_ctx;
 }
 __host__ __device__ inline int parts_of(int ctx_eff, const PlanConfig& c) {
   return (ctx_eff + c.part_tokens - 1) / c.part_tokens;
@@ -86,7 +87,19 @@ int validate_batch(int32_t S, const int32_t* qo, const int32_t* cl, int32_t max_
 
 PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8, int wgs_per_tile) {
   PlanConfig c;
-  c.mfma_min_qlen = env_int("DSV_MFMA_MIN_QLEN", 16);
+  // Which spans take the row path.  It streams the context once per query token, the MFMA path
+  // once per span (with mostly empty query tiles), so beyond a few tokens the MFMA path wins
+  // whatever the context; measured (32/8 heads, D=128): 4 tokens x 64 spans on 2,048 cached tokens
+  // 0.42 -> 0.21 ms, 15 tokens 1.26 -> 0.22 ms, 8 tokens on 32,768 0.27 -> 0.10 ms; with 2 or 3
+  // tokens it only pays on long contexts, where the tile kernel's fixed cost per work item
+  // disappears.  DSV_MFMA_MIN_QLEN forces one threshold for all contexts.
+  // (8-bit cache: the MFMA path first widens the span's whole context into the staged copy, and
+  // the row path streams half the bytes, so the threshold sits higher: measured, spans of 8
+  // tokens are about even and 15 tokens win only on long contexts or many spans.)
+  c.mfma_min_qlen = kv8 ? 16 : 4;
+  c.mfma_long_ctx = kv8 ? 0x7fffffff : 1024;
+  const int forced_q = env_int("DSV_MFMA_MIN_QLEN", 0);
+  if (forced_q > 0) { c.mfma_min_qlen = forced_q; c.mfma_long_ctx = 0x7fffffff; }
   c.tile_tokens = 64;
   // LDS ring slots per wave of the row kernel.  (8-bit codes: a slot is half the size; two and
   // four slots measured the same, two keep the mixed launch available.)
@@ -102,7 +115,7 @@ PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8
   int64_t row_tokens = 0;
   for (int i = 0; i < S; ++i) {
     const int q_len = qo[i + 1] - qo[i];
-    if (q_len >= c.mfma_min_qlen) continue;
+    if (!on_row_path(q_len, cl[i], c)) continue;
     const int64_t prefix = cl[i] - q_len;
     row_tokens += (int64_t)q_len * prefix + (int64_t)q_len * (q_len + 1) / 2;
   }
@@ -128,7 +141,7 @@ PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8
   int64_t kv_visits = 0, largest = 0;
   for (int i = 0; i < S; ++i) {
     const int q_len = qo[i + 1] - qo[i];
-    if (q_len < c.mfma_min_qlen) continue;
+    if (on_row_path(q_len, cl[i], c)) continue;
     const int nt = ceil_div(q_len, c.tile_tokens);
     for (int t = 0; t < nt; ++t) {
       const int n_kv = kv_tiles_of(cl[i], q_len, t, c);
@@ -157,7 +170,7 @@ PlanCounts count_plan(int32_t S, const int32_t* qo, const int32_t* cl, const Pla
   PlanCounts n;
   for (int i = 0; i < S; ++i) {
     const int q_len = qo[i + 1] - qo[i];
-    if (on_row_path(q_len, c)) {
+    if (on_row_path(q_len, cl[i], c)) {
       n.rows += q_len;
       for (int j = 0; j < q_len; ++j) {
         n.row_tokens += cl[i] - q_len + j + 1;
@@ -293,7 +306,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
   if (has_tiles == 2) {
     for (int i = (int)threadIdx.x; i < S; i += kPlanThreads) {
       const int q_len = q_offsets[i + 1] - q_offsets[i];
-      if (q_len > 0 && !on_row_path(q_len, c)) tseg_list[atomicAdd(&tseg_n, 1)] = i;
+      if (q_len > 0 && !on_row_path(q_len, ctx_lens[i], c)) tseg_list[atomicAdd(&tseg_n, 1)] = i;
     }
     __syncthreads();
   }
@@ -310,7 +323,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
     } else if (has_tiles == 1) {
       for (int i = (int)threadIdx.x; i < S; i += kPlanThreads) {
         const int q0 = q_offsets[i], q_len = q_offsets[i + 1] - q0, ctx = ctx_lens[i];
-        if (q_len > 0 && !on_row_path(q_len, c)) {
+        if (q_len > 0 && !on_row_path(q_len, ctx, c)) {
           const int n_tiles = (q_len + c.tile_tokens - 1) / c.tile_tokens;
           for (int t = 0; t < n_tiles; ++t) fn(i, q_len, ctx, t);
         }
@@ -364,7 +377,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
       q0 = q_offsets[i];
       q_len = q_offsets[i + 1] - q0;
       ctx = ctx_lens[i];
-      if (on_row_path(q_len, c)) {
+      if (on_row_path(q_len, ctx, c)) {
         n_rows = q_len;
         for (int j = 0; j < q_len; ++j) n_items += parts_of(ctx - q_len + j + 1, c);
       } else {

@@ -54,6 +54,17 @@ def test_decode_ragged_contexts(Hq, Hkv, D):
     check(b)
 
 
+@pytest.mark.parametrize("min_qlen", ["2", "16", "300"])
+def test_short_and_long_spans_on_either_path(monkeypatch, min_qlen):
+    """DSV_MFMA_MIN_QLEN moves the boundary between the row path (one pass over the context per
+    query token) and the matrix-core path: spans of 2-15 tokens on both, and spans of up to 299
+    tokens on the row path."""
+    monkeypatch.setenv("DSV_MFMA_MIN_QLEN", min_qlen)
+    segs = [(2, 2), (3, 50), (15, 15), (7, 1300), (1, 1), (12, 1500), (2, 2048), (1, 777), (40, 90), (299, 320)]
+    for Hq, Hkv, D in [(32, 8, 128), (4, 1, 64)]:
+        check(gen.make_batch("either", 97, Hq, Hkv, D, segs))
+
+
 def test_short_prefill_spans_mixed_with_decodes():
     """Sub-block prefill pieces (1..15 tokens) resuming on prefixes, interleaved with decodes in
     arbitrary order (Alg. 2 emits partial prefill requests next to all decodes)."""

@@ -39,6 +39,8 @@ def random_case(seed):
         env["DSV_PART_TOKENS"] = str(int(rng.choice([16, 64, 256])))
     if rng.random() < 0.6:
         env["DSV_MIXED_LAUNCH"] = str(int(rng.integers(0, 2)))
+    if rng.random() < 0.5:
+        env["DSV_MFMA_MIN_QLEN"] = str(int(rng.choice([2, 16, 64])))
     return Hkv * G, Hkv, D, segs, env
 
 
