@@ -212,7 +212,7 @@ size_t carve(const PlanCounts& n, int S, int Hq, int Hkv, int D, bool kv8, char*
     return p;
   };
   const size_t rows = (size_t)n.rows, items = (size_t)n.items, tiles = (size_t)n.tiles;
-  char* p0 = take(rows * 4); char* p1 = take(rows * 4); char* p2 = take(rows * 4);
+  char* p1 = take(rows * 4);
   char* p3 = take(rows * 4); char* p4 = take(rows * 4);
   char* p5 = take(items * 16);
   char* p7 = take(tiles * 4); char* p8 = take(tiles * 4);
@@ -233,7 +233,7 @@ size_t carve(const PlanCounts& n, int S, int Hq, int Hkv, int D, bool kv8, char*
   if (w) {
     w->stage_seq = (int32_t*)s0; w->stage_rows = (int32_t*)s1; w->stage_blk0 = (int32_t*)s2;
     w->stage_table = (int32_t*)s3; w->stage_k = (uint16_t*)s4; w->stage_v = (uint16_t*)s5;
-    w->row_seq = (int32_t*)p0; w->row_qtok = (int32_t*)p1; w->row_ctx = (int32_t*)p2;
+    w->row_qtok = (int32_t*)p1;
     w->row_item0 = (int32_t*)p3; w->row_nparts = (int32_t*)p4;
     w->item_rec = (int4*)p5;
     w->tile_seq = (int32_t*)p7; w->tile_q0 = (int32_t*)p8;
@@ -391,9 +391,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
       const int ctx_eff = ctx - q_len + j + 1;
       const int np = parts_of(ctx_eff, c);
       const int r = row0 + j;
-      w.row_seq[r] = i;
       w.row_qtok[r] = q0 + j;
-      w.row_ctx[r] = ctx_eff;
       w.row_item0[r] = item0;
       w.row_nparts[r] = np;
       for (int p = 0; p < np; ++p) w.item_rec[item0 + p] = make_int4(i, q0 + j, ctx_eff, p | (np << 16));

@@ -48,9 +48,7 @@ struct PlanCounts {
 
 // Device-resident work lists, carved out of the caller's workspace.
 struct WorkLists {
-  int32_t* row_seq;        // [rows] segment of the row
   int32_t* row_qtok;       // [rows] index of the query token in q / out
-  int32_t* row_ctx;        // [rows] number of KV tokens the row attends to (p+1)
   int32_t* row_item0;      // [rows] first item of the row
   int32_t* row_nparts;     // [rows]
   int4*    item_rec;       // [items]: {seq, qtok, ctx, part | nparts << 16}: everything a
