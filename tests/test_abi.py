@@ -119,3 +119,14 @@ def test_workspace_holds_partials_when_query_tiles_are_cut(lib, monkeypatch):
     assert f([0, 2048], [2048], 32, 8, 128) == pytest.approx(f([0, 2048], [2048], 32, 8, 128))
     monkeypatch.setenv("DSV_TILE_PART_TILES", "-1")
     assert f([0, 2048] * 1, [2048], 32, 8, 128) > 0
+
+
+def test_empty_batches_are_no_ops_on_every_attention_and_append_entry_point(lib):
+    pool = binding._Pool(4096, 4096, 0, 1, 4, 16, 8, 128)
+    assert lib.attn_mixed_batch(None, None, C.byref(pool), 0, None, 1, None, None, None, None, 0, 32,
+                                0.1, 0, None, 0, None) == 0
+    assert lib.attn_mixed_batch_fp8kv(None, None, C.byref(pool), 0, None, 1, None, None, None, None, 0, 32,
+                                      0.1, 0.5, 0.5, 0, None, 0, None) == 0
+    assert lib.kv_append(None, None, C.byref(pool), 0, None, 1, None, None, None, None, 0, None) == 0
+    assert lib.kv_unpack_chunks_fp8(None, None, None, 0, C.byref(pool), None, 1, None) == 0
+    assert dsv.attn_mixed_batch_workspace_bytes([0], [], 32, 8, 128) > 0      # lists only, no partials
