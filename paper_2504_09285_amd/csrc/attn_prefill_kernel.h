@@ -256,6 +256,8 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
   // Query fragments: B operand of S^T = K Q^T; lane (jrow, hh) holds dims 16*ks + 8*hh .. +8.
   const int jq = j0 + 32 * tg + jrow;    // new-token index of this lane's query row
   const int p_j = prefix + jq - pos0;    // its position, counted from the partition's first token
+  // (wave-uniform) Does any of this wave's 32 query rows, for any of its heads, exist?
+  const bool wave_has_rows = j0 + 32 * tg < q_len && bz * 4 + hp * NH < prm.G;
   bool head_ok[NH];
   int head[NH];
   uint4 qf[NH][KS];
@@ -634,6 +636,15 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
       ++u_sync;
     };
     auto no_sync = []() __attribute__((always_inline)) {};
+    if (!wave_has_rows) {
+      // All 32 query rows of this wave lie beyond the span (a short span, or the ragged last tile
+      // of one), or its query head beyond the group: the wave only fetches its share of every
+      // tile and keeps the barriers - the one above and one per tile, as in the stages below -
+      // and leaves the SIMD to the wave that has rows.
+      for (int u = 0; u < n_tiles; ++u) next_tile();
+      wait_vmcnt<0>();
+      return;
+    }
     issue_k(0, i0{});
     lds_wait<0>();
     ready_k();
