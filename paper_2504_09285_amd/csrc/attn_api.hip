@@ -54,7 +54,7 @@ int device_cus() {
 
 __host__ __device__ inline bool on_row_path(int q_len, int ctx, const PlanConfig& c) {
   if (q_len >= c.mfma_min_qlen) return false;
-  return q_len < 2 || ctx < c.mfma_long_ctx;
+  return q_len < 2 || (int64_t)q_len * ctx < c.mfma_min_work;
 }
 __host__ __device__ inline int parts_of(int ctx_eff, const PlanConfig& c) {
   return (ctx_eff + c.part_tokens - 1) / c.part_tokens;
@@ -88,18 +88,18 @@ int validate_batch(int32_t S, const int32_t* qo, const int32_t* cl, int32_t max_
 PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8, int wgs_per_tile) {
   PlanConfig c;
   // Which spans take the row path.  It streams the context once per query token, the MFMA path
-  // once per span (with mostly empty query tiles), so beyond a few tokens the MFMA path wins
-  // whatever the context; measured (32/8 heads, D=128): 4 tokens x 64 spans on 2,048 cached tokens
-  // 0.42 -> 0.21 ms, 15 tokens 1.26 -> 0.22 ms, 8 tokens on 32,768 0.27 -> 0.10 ms; with 2 or 3
-  // tokens it only pays on long contexts, where the tile kernel's fixed cost per work item
-  // disappears.  DSV_MFMA_MIN_QLEN forces one threshold for all contexts.
+  // once per span (with mostly empty query tiles, whose idle waves step aside) at a fixed cost
+  // of about 10 us per work item, so the MFMA path wins once a span's q_len * ctx_len passes
+  // about 1,200 tokens; measured (32/8 heads, D=128, 64 spans): 4 tokens on 2,048 cached ones
+  // 0.42 -> 0.18 ms, 15 tokens 1.26 -> 0.19 ms, 4 tokens on 128 cached ones 0.05 ms on the row
+  // path against 0.10 on the other.  DSV_MFMA_MIN_QLEN forces a plain length threshold.
   // (8-bit cache: the MFMA path first widens the span's whole context into the staged copy, and
-  // the row path streams half the bytes, so the threshold sits higher: measured, spans of 8
+  // the row path streams half the bytes: plain threshold of 16 tokens; measured, spans of 8
   // tokens are about even and 15 tokens win only on long contexts or many spans.)
-  c.mfma_min_qlen = kv8 ? 16 : 4;
-  c.mfma_long_ctx = kv8 ? 0x7fffffff : 1024;
+  c.mfma_min_qlen = 16;
+  c.mfma_min_work = kv8 ? 0x7fffffff : 1200;
   const int forced_q = env_int("DSV_MFMA_MIN_QLEN", 0);
-  if (forced_q > 0) { c.mfma_min_qlen = forced_q; c.mfma_long_ctx = 0x7fffffff; }
+  if (forced_q > 0) { c.mfma_min_qlen = forced_q; c.mfma_min_work = 0x7fffffff; }
   c.tile_tokens = 64;
   // LDS ring slots per wave of the row kernel.  (8-bit codes: a slot is half the size; two and
   // four slots measured the same, two keep the mixed launch available.)

@@ -8,10 +8,9 @@ namespace dsv {
 // workspace) and on the device (to fill the work lists), from q_offsets / ctx_lens alone.
 //
 //  * "row" work: one query token against its causal context, cut along the context into
-//    partitions of part_tokens tokens (split-K).  Used for decodes and for the shortest
-//    prefill spans (fewer than mfma_min_qlen tokens; on contexts of mfma_long_ctx tokens and
-//    more, only single tokens): the row path streams the context once per query token, the
-//    MFMA path once per span.  A row with one partition writes its output directly;
+//    partitions of part_tokens tokens (split-K).  Used for decodes and for the smallest
+//    prefill spans (fewer than mfma_min_qlen tokens and q_len * ctx_len below mfma_min_work):
+//    the row path streams the context once per query token, the MFMA path once per span.  A row with one partition writes its output directly;
 //    otherwise each partition writes an unnormalised partial and a merge kernel combines them.
 //  * "tile" work: tile_tokens consecutive query tokens of a long prefill span for one KV head,
 //    processed by the MFMA kernel.  When the batch holds too few query tiles to fill the device
@@ -21,7 +20,7 @@ namespace dsv {
 struct PlanConfig {
   int32_t part_tokens;     // multiple of 16
   int32_t mfma_min_qlen;   // spans with q_len >= this go to the MFMA kernel
-  int32_t mfma_long_ctx;   // on a context of at least this many tokens, spans of 2 tokens and more do
+  int32_t mfma_min_work;   // ... and so do shorter spans of 2+ tokens with q_len * ctx_len >= this
   int32_t tile_tokens;     // query tokens per MFMA tile
   int32_t row_nbuf;        // LDS ring slots (blocks) per wave of the row kernel: 2, 3, 4, 6 or 8
   int32_t num_cus;         // compute units of the device (sizes the persistent grid)
