@@ -223,8 +223,13 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
   const int lane = tid % kWave;
   const int jrow = lane % 32;            // query row of the wave (MFMA column) / token row of a K sub-tile
   const int hh = lane / 32;
-  const int tg = wave / kHeadWaves;      // which 32 query tokens of the tile
-  const int hp = wave % kHeadWaves;      // which NH query heads of the group of four
+  // Wave w runs on SIMD w % 4.  With four query heads per KV head, SIMD s hosts both halves of
+  // the query tile for head s.  With one or two heads per KV head most head slots are empty
+  // (their waves only fetch tiles): the waves that have rows are then spread over the SIMDs
+  // instead of sharing SIMD 0 (and 1).
+  const bool few_heads = prm.G - bz * 4 <= 2;
+  const int tg = few_heads ? wave % 2 : wave / kHeadWaves;          // which 32 query tokens of the tile
+  const int hp = few_heads ? wave / 2 : wave % kHeadWaves;          // which query head of the group of four
 
   // Workgroups are dispatched in index order (bx) and dealt round-robin to the eight XCDs: the
   // KV head is the fastest index, so the heaviest tiles (the list is sorted) of every head start
