@@ -218,6 +218,7 @@ __device__ __forceinline__ void rows_body(const RowsParams& prm, int bx, int by,
   const unsigned char* const k_bytes = reinterpret_cast<const unsigned char*>(a.k_pool);
   const unsigned char* const v_bytes = reinterpret_cast<const unsigned char*>(a.v_pool);
   const unsigned char* const zero_line = reinterpret_cast<const unsigned char*>(prm.w.zero_line);
+  const int blast = b1 - 1;
   auto issue_block_id = [&](int bid, int b, int slot) {
     const unsigned char* kb = k_bytes + (int64_t)bid * blk_bytes + (uint32_t)kvh * ROWB;
     const unsigned char* vb = v_bytes + (int64_t)bid * blk_bytes + (uint32_t)kvh * ROWB;
@@ -229,12 +230,13 @@ __device__ __forceinline__ void rows_body(const RowsParams& prm, int bx, int by,
       const unsigned char* kp = kb + (uint32_t)n * tok_stride + ((ld_pos ^ k_swz<D, EB>(n)) * 16);
       const unsigned char* vp = vb + (uint32_t)n * tok_stride + ((ld_pos ^ v_swz<D, EB>(n)) * 16);
       if (b * kBlockSize + n >= t1) vp = zero_line + ld_pos * 16;    // beyond the partition: V := 0
+      if (b > blast) kp = zero_line + ld_pos * 16;                   // a refill nobody reads (see the loop)
       __builtin_amdgcn_global_load_lds((gbl_void_t)kp, (lds_void_t)(ks_base + i * 1024), 16, 0, kStreamOnce);
       __builtin_amdgcn_global_load_lds((gbl_void_t)vp, (lds_void_t)(vs_base + i * 1024), 16, 0, kStreamOnce);
     }
   };
   auto issue_block = [&](int b, int slot) {
-    issue_block_id(__builtin_amdgcn_readlane(tab_vec, b - b0), b, slot);
+    issue_block_id(__builtin_amdgcn_readlane(tab_vec, min(b, blast) - b0), b, slot);
   };
 
   // ---- per-lane state: lane (qcol, jj) owns head qcol; O^T rows are dims 16*db + 4*jj + e ----
@@ -267,16 +269,17 @@ __device__ __forceinline__ void rows_body(const RowsParams& prm, int bx, int by,
 
   // The first block is requested at once (its id came with the item); the table slice and the
   // query rows are only waited for where they are first used.
-  const int blast = b1 - 1;
   issue_block_id(bid0, b0, 0);
 #pragma unroll
-  for (int u = 1; u + 1 < R; ++u) issue_block(min(b0 + u, blast), u);
+  for (int u = 1; u + 1 < R; ++u) issue_block(b0 + u, u);
 
   for (int b = b0; b < b1; ++b) {
     const int slot = (b - b0) % R;
     // Refill the slot consumed in the previous step (unconditionally, so that the number of
     // loads in flight is static), then wait until only the R-1 younger blocks are outstanding.
-    issue_block(min(b + R - 1, blast), (b - b0 + R - 1) % R);
+    // Past the partition's last block the refill is never consumed: it reads the zero line (a
+    // cached 256 bytes) instead of fetching the last block from HBM once more.
+    issue_block(b + R - 1, (b - b0 + R - 1) % R);
     wait_vmcnt<(R - 1) * Geo::LOADS_PER_BLOCK>();
     const unsigned char* sl = ring + slot * Geo::SLOT_BYTES;
 
