@@ -119,12 +119,11 @@ PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8
     const int64_t prefix = cl[i] - q_len;
     row_tokens += (int64_t)q_len * prefix + (int64_t)q_len * (q_len + 1) / 2;
   }
-  // (Measured: about 1100 items, i.e. 320 tokens for 0.36M streamed tokens; 1024 tokens for
-  // a million and more.)
-  // With 8-bit codes a block takes half as long to stream, so the fixed cost of starting an item
-  // and of splitting a row weighs twice as much: about 350 items (measured on the same batch:
-  // 1024-token partitions 0.138 ms, 320-token ones 0.151 ms).
-  int64_t part = (row_tokens / (kv8 ? 350 : 1120) + 15) / 16 * 16;
+  // Measured with the items dispatched longest first (the plan kernel's order): about 1.9 items
+  // per compute unit.  Config 2 (0.36M streamed tokens): 736-token partitions 0.253 ms per step,
+  // 336 tokens 0.277, 1024 tokens 0.258; the same optimum on 8-bit codes (0.145 ms); config 4's
+  // decodes (0.74M tokens) and longer batches run best at the cap of 1024.
+  int64_t part = (row_tokens * 10 / ((int64_t)c.num_cus * 19) + 15) / 16 * 16;
   if (part < 256) part = 256;
   if (part > 1024) part = 1024;
   const int forced = env_int("DSV_PART_TOKENS", 0);
@@ -220,6 +219,7 @@ size_t carve(const PlanCounts& n, int S, int Hq, int Hkv, int D, bool kv8, char*
   char* p7d = take((size_t)n.split_qtiles * 16);
   char* pz = take(256);
   char* pc = take(items * 4);
+  char* po = take(items * 4);
   const size_t partials = items + (size_t)n.tile_split_items;    // row items first, then cut q-tiles
   char* p9 = take(partials * (size_t)Hq * D * 4);
   char* p10 = take(partials * (size_t)Hq * 2 * 4);
@@ -240,6 +240,7 @@ size_t carve(const PlanCounts& n, int S, int Hq, int Hkv, int D, bool kv8, char*
     w->tile_part = (int32_t*)p7b; w->tile_item0 = (int32_t*)p7c; w->split_rec = (int4*)p7d;
     w->zero_line = (uint32_t*)pz;
     w->item_blk0 = (int32_t*)pc;
+    w->item_order = (int32_t*)po;
     w->part_acc = (float*)p9; w->part_ml = (float*)p10;
   }
   return off + 256;
@@ -273,6 +274,7 @@ __device__ int block_exclusive_scan(int v, int* smem, int* total) {
   return before + incl - v;
 }
 
+constexpr int kOrderBins = 64;                 // a row item streams 1..64 blocks (part_tokens <= 1024)
 // Sort key of a tile: bucket 0 holds the tiles with the most KV tiles to visit.
 constexpr int kTileBuckets = 4 * kPlanThreads;
 __device__ __forceinline__ int tile_bucket(int kv_tiles) {
@@ -289,6 +291,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
   __shared__ int split_count, split_items;      // cut q-tiles and their partials handed out so far
   __shared__ int tseg_n;                        // segments with tile work, listed for the
   __shared__ int tseg_list[kPlanThreads];       // cooperative passes (has_tiles == 2)
+  __shared__ int order_slot[kOrderBins + 1];    // row items by block count (bin kOrderBins - blocks)
   if (threadIdx.x == 0) { split_count = 0; split_items = 0; tseg_n = 0; }
   if (threadIdx.x < 64) w.zero_line[threadIdx.x] = 0u;
 
@@ -418,11 +421,60 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
   }
   // Second pass, all threads: the id of each item's first block, so that the row kernel can
   // request its first K/V block as soon as it has read the item record.
+  // The same pass lists the items in dispatch order, those with the most blocks first (counting
+  // sort by block count, at most 64), so that the row kernel's workgroups, dispatched in list
+  // order, end with the short last partitions of the rows instead of with whatever the last
+  // segments hold.  Most items are full partitions: a wave counts and places those with one
+  // atomic per wave.  The order of equal keys is left to the atomics; it affects nothing but the
+  // dispatch order.
+  if (threadIdx.x <= kOrderBins) order_slot[threadIdx.x] = 0;
   __syncthreads();
-  for (int it = (int)threadIdx.x; it < item_carry; it += kPlanThreads) {
-    const int4 rec = w.item_rec[it];
-    const int b0 = (rec.w & 0xffff) * c.part_tokens / kBlockSize;
-    w.item_blk0[it] = block_tables[(int64_t)rec.x * max_blocks + b0];
+  const int full_blocks = c.part_tokens / kBlockSize;
+  auto blocks_of = [&](const int4& rec) {
+    const int part = rec.w & 0xffff;
+    const int t1 = min(rec.z, (part + 1) * c.part_tokens);
+    return (t1 + kBlockSize - 1) / kBlockSize - part * full_blocks;       // 1 .. full_blocks
+  };
+  // take(bin, valid): a position counter of the bin, one atomic per wave for the full-size bin.
+  auto take = [&](int nb, bool valid) {
+    const bool full = valid && nb == full_blocks;
+    const unsigned long long m = __ballot(full);
+    int pos = 0;
+    if (full) {
+      const int lane = (int)threadIdx.x & 63;
+      const int lead = __ffsll((long long)m) - 1;
+      if (lane == lead) pos = atomicAdd(&order_slot[kOrderBins - nb], __popcll(m));
+      pos = __shfl(pos, lead, 64) + __popcll(m & ((1ull << lane) - 1ull));
+    } else if (valid) {
+      pos = atomicAdd(&order_slot[kOrderBins - nb], 1);
+    }
+    return pos;
+  };
+  const int item_iters = (item_carry + kPlanThreads - 1) / kPlanThreads;   // uniform trip count
+  for (int k = 0; k < item_iters; ++k) {
+    const int it = k * kPlanThreads + (int)threadIdx.x;
+    const bool valid = it < item_carry;
+    int nb = 0;
+    if (valid) {
+      const int4 rec = w.item_rec[it];
+      const int b0 = (rec.w & 0xffff) * full_blocks;
+      w.item_blk0[it] = block_tables[(int64_t)rec.x * max_blocks + b0];
+      nb = blocks_of(rec);
+    }
+    take(nb, valid);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {                        // bins in order of falling block count
+    int run = 0;
+    for (int b = 0; b <= kOrderBins; ++b) { const int n = order_slot[b]; order_slot[b] = run; run += n; }
+  }
+  __syncthreads();
+  for (int k = 0; k < item_iters; ++k) {
+    const int it = k * kPlanThreads + (int)threadIdx.x;
+    const bool valid = it < item_carry;
+    const int nb = valid ? blocks_of(w.item_rec[it]) : 0;
+    const int pos = take(nb, valid);
+    if (valid) w.item_order[pos] = it;
   }
 }
 

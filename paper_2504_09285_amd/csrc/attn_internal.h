@@ -61,6 +61,7 @@ struct WorkLists {
   int4*    split_rec;      // [split_qtiles] {seq, q0 of the tile, partitions, first partial}
   uint32_t* zero_line;     // 256 bytes of zeros (stands in for V rows that must not be read)
   int32_t* item_blk0;      // [items] pool block id of the item's first block
+  int32_t* item_order;     // [items] the items in dispatch order: most blocks to stream first
   float*   part_acc;       // [items][Hq][D]  unnormalised partial outputs
   float*   part_ml;        // [items][Hq][2]  running max (log2 domain) and sum
   // bf16 copy of the MFMA path's contexts (cache of 8-bit codes only, else null)

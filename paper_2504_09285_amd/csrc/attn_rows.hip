@@ -34,7 +34,9 @@ int launch_rows(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, co
   int waves = 1;
   // waves * slots * slot bytes (8 KiB of bf16, 4 KiB of codes) must fit in the 160 KB of LDS
   const int max_waves = cfg.row_nbuf <= (a.kv8 ? 4 : 2) ? 8 : 4;
-  while (waves < a.Hkv && waves < max_waves) waves <<= 1;
+  int cap = max_waves;
+  if (const char* e = getenv("DSV_ROW_WAVES")) cap = min(max_waves, max(1, atoi(e)));
+  while (waves < a.Hkv && waves < cap) waves <<= 1;
   dim3 grid((unsigned)n.items, (unsigned)ceil_div(a.Hkv, waves), (unsigned)ceil_div(prm.G, kRowHeads));
   const int r = cfg.row_nbuf;
 #define DSV_ROWS_CASE(DD, RR, KK) \

@@ -178,7 +178,7 @@ __device__ __forceinline__ void rows_body(const RowsParams& prm, int bx, int by,
   const int h0 = kvh * prm.G + bz * kRowHeads;   // first query head of this wave
   const int nh = min(kRowHeads, prm.G - bz * kRowHeads);
 
-  const int item = bx;
+  const int item = prm.w.item_order[bx];         // workgroups are dispatched longest item first
   const int4 rec = prm.w.item_rec[item];         // {seq, qtok, ctx, part | nparts << 16}
   const int bid0 = prm.w.item_blk0[item];        // id of the partition's first block
   const int qtok = rec.y;
