@@ -29,7 +29,7 @@ sys.path.insert(0, ROOT)
 METRIC = "mixed-batch attention tokens/s; decode HBM GB/s & prefill MFMA util vs peak"
 # HBM bytes per rows_kernel launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the
 # counter reads for a plain 1 GiB copy (profiles/rows_kernel_c2_decode_heavy.md).
-MEASURED_TRAFFIC_BYTES = {"c2_decode_heavy": 1.554e9}
+MEASURED_TRAFFIC_BYTES = {"c2_decode_heavy": 1.495e9}
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
