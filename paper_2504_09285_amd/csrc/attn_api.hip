@@ -736,15 +736,15 @@ int run_attention(bool kv8, float k_scale, float v_scale, const void* q, void* o
     if ((rc = launch_stage(a, w, n, stream))) return rc;
   }
   // A batch with both prefill tiles and row items can run them in one launch.
-  // Mixing pays when neither kind of work is a small fraction of the other (measured: a fifth
-  // faster on config 4, a few percent slower on config 3 where the decodes are 1/8 of the
-  // step), so it is chosen from rough time estimates: streamed bytes at 5.5 TB/s against
-  // matrix-core work at 0.9 PFLOP/s.  DSV_MIXED_LAUNCH=1 / 0 forces the choice.
+  // Mixing pays when neither kind of work is a tiny fraction of the other (measured: 14 % faster
+  // on config 4, 3 % on config 3 where the decodes are 1/8 of the step), so it is chosen from
+  // rough time estimates: streamed bytes at 5.5 TB/s against matrix-core work at 0.9 PFLOP/s,
+  // ratio at least 1/10 both ways.  DSV_MIXED_LAUNCH=1 / 0 forces the choice.
   bool mix = mixed_launch_supported(a, cfg, n);
   if (mix) {
     const double t_rows = (double)n.row_tokens * a.Hkv * a.D * (kv8 ? 2.0 : 4.0) / 5.5e12;
     const double t_tiles = (double)n.tile_pairs * a.Hq * a.D * 4.0 / 0.9e15;
-    mix = t_rows >= 0.25 * t_tiles && t_tiles >= 0.25 * t_rows;
+    mix = t_rows >= 0.1 * t_tiles && t_tiles >= 0.1 * t_rows;
     const int forced = env_int("DSV_MIXED_LAUNCH", -1);
     if (forced >= 0) mix = forced != 0;
   }

@@ -90,8 +90,12 @@ def test_sweep_fills_the_table_and_the_budget_holds_on_the_gpu():
     for d in (8, 64):
         lat = [e[(p, 1024, d)] for p in (0, 512, 1024, 2048)]
         assert all(b > a * 0.9 for a, b in zip(lat, lat[1:])), lat          # grows with plen (10% noise margin)
-    slo = 0.5 * (e[(512, 1024, 64)] + e[(1024, 1024, 64)])
+    # A target between the 1024- and the 2048-token entries (the latter has three times the
+    # causal pairs, so the two are well apart; 512 against 1024 tokens can be within the noise).
+    lo, hi = e[(1024, 1024, 64)], e[(2048, 1024, 64)]
+    assert hi > 1.1 * lo, (lo, hi)
+    slo = 0.5 * (lo + hi)
     b = compose_batch([PrefillRequest(0, 4000)], [(i, 1000) for i in range(64)], slo, t)
-    assert b.budget == 512 and b.plen == 512
+    assert b.budget == 1024 and b.plen == 1024
     fresh = sweep(ProfileTable(plen_step=512), plens=(b.plen,), ctxs=(1024,), dnums=(64,), steps=5)
     assert list(fresh.entries().values())[0] <= slo * 1.25
