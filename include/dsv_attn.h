@@ -11,6 +11,13 @@
  *     memory and keeps no pointer after the call returns.
  *   - All GPU work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the
  *     default stream).  Calls never synchronise.  Host arrays are consumed before return.
+ *   - Stream capture: a call made while `hip_stream` is being captured into a HIP graph
+ *     records kernel launches only (no allocation, no synchronisation, no memset node; the
+ *     work lists are cleared by the library's own kernels), so it may be captured and
+ *     replayed.  A replay reads every device buffer afresh; what the host derived from the
+ *     host-side arrays (grid sizes, workspace layout) is frozen, so a graph is valid for
+ *     batches with the same host-side arrays.  Make one call outside the capture first (the
+ *     first call on a device configures the kernels).
  *   - Return value: DSV_OK (0) or a negative DSV_E_* code.  Arguments are checked before any
  *     GPU work: with DSV_E_INVALID, DSV_E_UNSUPPORTED or DSV_E_WORKSPACE nothing has been
  *     enqueued.  DSV_E_LAUNCH means HIP refused a launch part-way; outputs are then undefined.
