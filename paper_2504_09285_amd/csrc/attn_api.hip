@@ -124,7 +124,13 @@ PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8
   // 336 tokens 0.277, 1024 tokens 0.258; the same optimum on 8-bit codes (0.145 ms); config 4's
   // decodes (0.74M tokens) and longer batches run best at the cap of 1024.
   int64_t part = (row_tokens * 10 / ((int64_t)c.num_cus * 19) + 15) / 16 * 16;
-  if (part < 256) part = 256;
+  // A small batch is latency-bound: one item per compute unit (a compute unit alone streams
+  // about 30 GB/s, so a 256-token item lasts 35 us), down to 128 tokens.  Measured, 32/8 heads:
+  // 8 decodes on 1,024 tokens 30 -> 23 us per step, 64 on 300 tokens 34 -> 28 us, one on 8,192
+  // tokens 34 -> 30 us; 64-token partitions are slower again (more partials than streaming).
+  const int64_t one_each = (row_tokens / c.num_cus + 15) / 16 * 16;
+  const int64_t floor_part = one_each < 128 ? 128 : (one_each < 256 ? one_each : 256);
+  if (part < floor_part) part = floor_part;
   if (part > 1024) part = 1024;
   const int forced = env_int("DSV_PART_TOKENS", 0);
   if (forced >= 16) part = forced / 16 * 16;
