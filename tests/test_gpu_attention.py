@@ -347,6 +347,34 @@ def test_config3_prefill_heavy_full_sampled_rows():
         assert err <= TOL, (i, j, h, err)
 
 
+def test_thousands_of_row_items_of_every_length(monkeypatch):
+    """400 decodes and short spans with contexts of 1 to 3,000 tokens, cut into 256-token
+    partitions: about 2,500 row items of 1 to 16 blocks (several passes of the plan kernel's item
+    loop, every bin of the dispatch order in use), listed longest first.  Every item must be
+    processed exactly once whatever the order: sampled rows against the oracle, all rows finite."""
+    from gpu_harness import run_attention
+    monkeypatch.setenv("DSV_PART_TOKENS", "256")
+    rng = np.random.default_rng(11)
+    segs = [(1, int(c)) for c in rng.integers(1, 3000, 380)]
+    segs += [(int(q), int(q) + int(c)) for q, c in zip(rng.integers(2, 9, 20), rng.integers(0, 100, 20))]
+    order = rng.permutation(len(segs))
+    segs = [segs[k] for k in order]
+    b = gen.make_batch("many_items", 68, 16, 2, 128, segs)
+    got = run_attention(b)
+    assert np.isfinite(got).all()
+    rows = [(int(i), 0, int(rng.integers(b.Hq))) for i in rng.choice(b.num_seqs, 120, replace=False)]
+    shortest, longest = int(np.argmin(b.ctx_lens)), int(np.argmax(b.ctx_lens))
+    rows += [(shortest, 0, 0), (longest, 0, b.Hq - 1)]
+    for i in range(b.num_seqs):
+        q_len = int(b.q_offsets[i + 1] - b.q_offsets[i])
+        if q_len > 1:
+            rows.append((i, q_len - 1, int(rng.integers(b.Hq))))
+    ref = oracle.attn_rows(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens, b.scale, rows)
+    for r, (i, j, h) in enumerate(rows):
+        err = np.abs(got[b.q_offsets[i] + j, h] - ref[r]).max()
+        assert err <= TOL, (i, j, h, err)
+
+
 def test_long_prefill_on_a_long_prefix_sampled_rows():
     """A 8,192-token span resuming on a 24,576-token prefix (ctx 32,768: 512 KV tiles for the last
     query tile), an unaligned one (ctx 20,011) and a few decodes, 64/8 heads: many tiles per work
