@@ -110,8 +110,9 @@ PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8
     if (c.row_nbuf != 3 && c.row_nbuf != 4) c.row_nbuf = 2;
   }
   c.num_cus = device_cus();
-  // Partition size: enough (row, partition) items to fill 256 CUs several times over, but not so
-  // small that the partial results written per partition matter next to the KV bytes read.
+  // Partition size: enough (row, partition) items to keep every compute unit streaming to the
+  // end of the launch, but not so small that starting an item and the partial results written
+  // per partition matter next to the KV bytes read.
   int64_t row_tokens = 0;
   for (int i = 0; i < S; ++i) {
     const int q_len = qo[i + 1] - qo[i];
