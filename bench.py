@@ -530,7 +530,7 @@ def main():
         extras["handoff_c5_4layers"] = bench_handoff(h, 10, 2, hev)
         del h
         if args.workload != "c3":
-            r3, d3 = bench_attention(gen.config3(threads=threads), 10, 2, hev)
+            r3, d3 = bench_attention(gen.config3(threads=threads), 40, 5, hev)
             extras["c3_prefill_heavy"] = {k: r3[k] for k in ("ms_per_step", "tokens_per_s", "mixed_launch_ms", "ms_per_step_kernels_apart", "kernel_ms", "prefill", "decode") if k in r3}
             del d3
         keys = ("ms_per_step", "tokens_per_s", "mixed_launch_ms", "ms_per_step_kernels_apart", "kernel_ms", "prefill", "decode")
@@ -538,14 +538,14 @@ def main():
         extras["c1_tiny"] = {k: r1[k] for k in keys if k in r1}
         del d1
         if args.workload != "c5":
-            r5, d5 = bench_attention(gen.config5_attention(threads=threads), 10, 2, hev)   # full contexts, one layer
+            r5, d5 = bench_attention(gen.config5_attention(threads=threads), 20, 3, hev)   # full contexts, one layer
             extras["c5_long_context"] = {k: r5[k] for k in keys if k in r5}
             del d5
         extras["kv_append_c3"] = bench_append(gen.config3(threads=threads), 20, 3, hev)
-        extras["c4_micro_request"] = bench_config4(threads, 10, 2, hev)
+        extras["c4_micro_request"] = bench_config4(threads, 40, 5, hev)
         extras["fp8kv"] = bench_fp8kv(20, 3, hev)
         # A 512-token chunk on a 130,560-token prefix: eight query tiles, cut along the context.
-        rl, dl = bench_attention(gen.long_prefix_chunk(threads=threads), 10, 2, hev)
+        rl, dl = bench_attention(gen.long_prefix_chunk(threads=threads), 30, 5, hev)
         extras["long_prefix_chunk"] = {k: rl[k] for k in ("ms_per_step", "tokens_per_s", "kernel_ms", "prefill") if k in rl}
         del dl
         # Chunk-pipelined hand-off (paper section 4.3): transfer of chunk k next to computation of k+1.

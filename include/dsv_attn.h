@@ -232,10 +232,9 @@ int kv_unpack_chunks_fp8(const void* chunk_buf, const dsv_chunk_desc* descs,
 #define DSV_KERNEL_ROWS   1   /* single-token attention split along the context (decodes) */
 #define DSV_KERNEL_TILES  2   /* MFMA attention of long prefill spans                     */
 #define DSV_KERNEL_MERGE  3   /* combination of context partitions                        */
-#define DSV_KERNEL_MIXED  4   /* rows and tiles in one launch: what a batch holding         */
-                              /* comparable amounts of both kinds of work runs instead of  */
-                              /* ids 1 and 2 (environment DSV_MIXED_LAUNCH=0 / 1 forces    */
-                              /* the two launches / the single one)                        */
+#define DSV_KERNEL_MIXED  4   /* rows and tiles in one launch: what a batch holding both  */
+                              /* kinds of work runs instead of ids 1 and 2 (environment    */
+                              /* DSV_MIXED_LAUNCH=0 keeps them in launches of their own)   */
 #define DSV_KERNEL_STAGE  5   /* bf16 copy of the prefill spans' contexts (8-bit cache only)  */
 int dsv_profile_events(int32_t kernel_id, void* start_event, void* stop_event);
 

@@ -179,7 +179,6 @@ PlanCounts count_plan(int32_t S, const int32_t* qo, const int32_t* cl, const Pla
     if (on_row_path(q_len, cl[i], c)) {
       n.rows += q_len;
       for (int j = 0; j < q_len; ++j) {
-        n.row_tokens += cl[i] - q_len + j + 1;
         const int np = parts_of(cl[i] - q_len + j + 1, c);
         n.items += np;
         if (np > 1) n.split_items += np;
@@ -196,7 +195,6 @@ PlanCounts count_plan(int32_t S, const int32_t* qo, const int32_t* cl, const Pla
         }
         if (np > n.max_parts) n.max_parts = np;
       }
-      n.tile_pairs += (int64_t)q_len * (cl[i] - q_len) + (int64_t)q_len * (q_len + 1) / 2;
       const int nblk = ceil_div(cl[i], kBlockSize);
       n.stage_segs += 1;
       n.stage_blocks += nblk;
@@ -742,19 +740,14 @@ int run_attention(bool kv8, float k_scale, float v_scale, const void* q, void* o
     EventScope ev(DSV_KERNEL_STAGE, stream);
     if ((rc = launch_stage(a, w, n, stream))) return rc;
   }
-  // A batch with both prefill tiles and row items can run them in one launch.
-  // Mixing pays when neither kind of work is a tiny fraction of the other (measured: 14 % faster
-  // on config 4, 3 % on config 3 where the decodes are 1/8 of the step), so it is chosen from
-  // rough time estimates: streamed bytes at 5.5 TB/s against matrix-core work at 0.9 PFLOP/s,
-  // ratio at least 1/10 both ways.  DSV_MIXED_LAUNCH=1 / 0 forces the choice.
+  // A batch with both prefill tiles and row items runs them in one launch: some compute units
+  // stream KV for the rows while the others run the spans' MFMAs, and one launch gap goes.
+  // Measured over the batch shapes a local scheduler emits (one span of 64-4,096 tokens, 4-256
+  // decodes on 1,024 or 8,192 tokens, 32/8 heads): up to 20 % faster than the two kernels one
+  // after the other where one side is small (a 512-token span with 16 decodes: 67 -> 55 us), 14 %
+  // on config 4, 3 % on config 3, never more than 1 % slower.  DSV_MIXED_LAUNCH=0 keeps them apart.
   bool mix = mixed_launch_supported(a, cfg, n);
-  if (mix) {
-    const double t_rows = (double)n.row_tokens * a.Hkv * a.D * (kv8 ? 2.0 : 4.0) / 5.5e12;
-    const double t_tiles = (double)n.tile_pairs * a.Hq * a.D * 4.0 / 0.9e15;
-    mix = t_rows >= 0.1 * t_tiles && t_tiles >= 0.1 * t_rows;
-    const int forced = env_int("DSV_MIXED_LAUNCH", -1);
-    if (forced >= 0) mix = forced != 0;
-  }
+  if (mix && env_int("DSV_MIXED_LAUNCH", 1) == 0) mix = false;
   if (mix) {
     EventScope ev(DSV_KERNEL_MIXED, stream);
     if ((rc = launch_mixed(a, w, cfg, n, stream))) return rc;

@@ -36,8 +36,6 @@ struct PlanCounts {
   int64_t split_qtiles = 0;   // q-tiles cut into more than one partition
   int64_t tile_split_items = 0;  // (query token, partition) partials of those q-tiles
   int32_t max_parts = 0;
-  int64_t row_tokens = 0;  // KV tokens the row path streams (per KV head)
-  int64_t tile_pairs = 0;  // causal (query, key) pairs of the MFMA path (per query head)
   // Filled only for a cache of 8-bit codes: the MFMA path then reads a bf16 copy of the whole
   // context of every segment it serves.
   int64_t stage_segs = 0;        // segments on the MFMA path
