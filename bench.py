@@ -201,6 +201,32 @@ def bench_attention(b, steps, warmup, hev):
     return res, d
 
 
+def bench_shared_plan(d, layers, iterations, warmup):
+    """A serving iteration runs one batch through every layer: one attn_mixed_batch_plan, then one
+    planned call per layer (the same single-layer pool stands in for every layer: the KV does not
+    fit any cache, so each call streams it from HBM).  Wall time per layer call, plan included."""
+    import torch
+    import paper_2504_09285_amd as dsv
+    b = d.b
+
+    def iteration():
+        plan = dsv.attn_mixed_batch_plan(d.block_tables, d.q_offsets, d.ctx_lens, b.q_offsets, b.ctx_lens,
+                                         b.Hq, b.Hkv, b.D, d.workspace)
+        for _ in range(layers):
+            dsv.attn_mixed_batch_planned(plan, d.q, d.out, d.pool, 0, d.block_tables, d.q_offsets, d.ctx_lens,
+                                         b.q_offsets, b.ctx_lens, b.Hq, b.scale, d.workspace)
+    for _ in range(warmup):
+        iteration()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(iterations):
+        iteration()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / (iterations * layers)
+    return {"workload": b.name, "layers_per_plan": layers, "ms_per_layer_call": sec * 1e3,
+            "tokens_per_s": b.total_q / sec}
+
+
 def bench_append(b, steps, warmup, hev):
     """kv_append of the batch's new tokens (the step before attention): read once, written once."""
     import torch
@@ -526,6 +552,9 @@ def main():
     if not args.no_extras:
         from workloads import gen
         extras = {}
+        if args.workload == "c2":
+            # the same batch with the work lists built once per 32 layer calls
+            extras["c2_one_plan_per_32_layers"] = bench_shared_plan(d, 32, 6, 1)
         h = gen.config5_handoff(layers=4, threads=threads)     # 8 x 8192 tokens, 256-token chunks, 4 of 32 layers
         extras["handoff_c5_4layers"] = bench_handoff(h, 10, 2, hev)
         del h

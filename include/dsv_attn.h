@@ -222,6 +222,52 @@ int kv_unpack_chunks_fp8(const void* chunk_buf, const dsv_chunk_desc* descs,
                          int32_t max_blocks_per_seq, void* hip_stream);
 
 /*
+ * ---- One plan for all layers of a step ---------------------------------------------------
+ * A serving iteration runs the same batch through every layer of the model (paper sections
+ * 2.1 and 4.2: a batch is formed once per iteration), and the work lists attn_mixed_batch
+ * derives from the batch (which span takes which path, context partitions, tile order) do not
+ * depend on the layer.  attn_mixed_batch_plan builds them once into `workspace`;
+ * attn_mixed_batch_planned / attn_mixed_batch_fp8kv_planned then run the step of one layer on
+ * those lists: the same result as attn_mixed_batch, without its list-building kernel.
+ *
+ *   plan      host memory, caller-owned, written by attn_mixed_batch_plan, read by the planned
+ *             calls.  It records what the lists depend on; a planned call whose arguments differ
+ *             (host arrays by content; workspace, block_tables, q_offsets, ctx_lens by address;
+ *             sequence and head counts, head_dim, max_blocks_per_seq, element size, the tuning
+ *             knobs of the environment) returns DSV_E_INVALID and enqueues nothing.
+ *   kv_elem_bytes  2 for a bf16 cache (planned calls: attn_mixed_batch_planned), 1 for E4M3 codes
+ *             (attn_mixed_batch_fp8kv_planned); workspace size as for the respective full call.
+ *   The planned calls must be enqueued after the plan call on the same stream (or ordered
+ *   behind it by the caller).  Between them nothing else may write the workspace, and the
+ *   contents of block_tables, q_offsets and ctx_lens must not change.  The calls of successive
+ *   layers share the partial-result area of the workspace, so they must not overlap in time
+ *   (one stream, or ordered by the caller).  All other arguments, the result and the error
+ *   codes are those of attn_mixed_batch / attn_mixed_batch_fp8kv.  num_seqs == 0: no work.
+ */
+typedef struct { uint64_t opaque[16]; } dsv_attn_plan;
+int attn_mixed_batch_plan(dsv_attn_plan* plan, const int32_t* block_tables,
+                          int32_t max_blocks_per_seq, const int32_t* q_offsets,
+                          const int32_t* ctx_lens, const int32_t* q_offsets_host,
+                          const int32_t* ctx_lens_host, int32_t num_seqs, int32_t num_q_heads,
+                          int32_t num_kv_heads, int32_t head_dim, int32_t kv_elem_bytes,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+int attn_mixed_batch_planned(const dsv_attn_plan* plan, const void* q, void* out,
+                             const dsv_kv_pool* pool, int32_t layer, const int32_t* block_tables,
+                             int32_t max_blocks_per_seq, const int32_t* q_offsets,
+                             const int32_t* ctx_lens, const int32_t* q_offsets_host,
+                             const int32_t* ctx_lens_host, int32_t num_seqs, int32_t num_q_heads,
+                             float softmax_scale, int32_t out_dtype, void* workspace,
+                             size_t workspace_bytes, void* hip_stream);
+int attn_mixed_batch_fp8kv_planned(const dsv_attn_plan* plan, const void* q, void* out,
+                                   const dsv_kv_pool* pool, int32_t layer,
+                                   const int32_t* block_tables, int32_t max_blocks_per_seq,
+                                   const int32_t* q_offsets, const int32_t* ctx_lens,
+                                   const int32_t* q_offsets_host, const int32_t* ctx_lens_host,
+                                   int32_t num_seqs, int32_t num_q_heads, float softmax_scale,
+                                   float k_scale, float v_scale, int32_t out_dtype, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream);
+
+/*
  * Profiling aid for benchmarks (not needed for correct use).  Until cleared with NULLs, every
  * later attn_mixed_batch call made by the calling host thread records `start_event` on its
  * stream immediately before, and `stop_event` immediately after, the launch of the named

@@ -9,5 +9,6 @@ from .binding import (  # noqa: F401
     attn_mixed_batch_workspace_bytes, build_info, dsv_profile_events, KERNEL_PLAN, KERNEL_ROWS,
     KERNEL_TILES, KERNEL_MERGE, KERNEL_MIXED, KERNEL_STAGE, kv_append, kv_pack_chunks, kv_unpack_chunks,
     library_path, load_library, attn_mixed_batch_fp8kv, attn_mixed_batch_fp8kv_workspace_bytes,
-    kv_append_fp8, kv_pack_chunks_fp8, kv_unpack_chunks_fp8,
+    kv_append_fp8, kv_pack_chunks_fp8, kv_unpack_chunks_fp8, AttnPlan, attn_mixed_batch_plan,
+    attn_mixed_batch_planned, attn_mixed_batch_fp8kv_planned,
 )

@@ -31,6 +31,17 @@ class _Pool(C.Structure):
                 ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32)]
 
 
+class _Plan(C.Structure):
+    _fields_ = [("opaque", C.c_uint64 * 16)]
+
+
+class AttnPlan:
+    """Host-side record of ``attn_mixed_batch_plan`` (``dsv_attn_plan``), handed to the planned calls."""
+
+    def __init__(self):
+        self.c = _Plan()
+
+
 CHUNK_DTYPE = np.dtype([("seq", "<i4"), ("token_begin", "<i4"), ("num_tokens", "<i4"),
                         ("reserved", "<i4"), ("chunk_offset", "<i8")])
 assert CHUNK_DTYPE.itemsize == 24
@@ -38,6 +49,7 @@ assert CHUNK_DTYPE.itemsize == 24
 EXPORTS = ("attn_mixed_batch_workspace_bytes", "attn_mixed_batch", "kv_pack_chunks",
            "kv_unpack_chunks", "kv_append", "attn_mixed_batch_fp8kv_workspace_bytes",
            "attn_mixed_batch_fp8kv", "kv_append_fp8", "kv_pack_chunks_fp8", "kv_unpack_chunks_fp8",
+           "attn_mixed_batch_plan", "attn_mixed_batch_planned", "attn_mixed_batch_fp8kv_planned",
            "dsv_profile_events", "dsv_build_info")
 KERNEL_PLAN, KERNEL_ROWS, KERNEL_TILES, KERNEL_MERGE, KERNEL_MIXED, KERNEL_STAGE = 0, 1, 2, 3, 4, 5
 
@@ -75,6 +87,13 @@ def load_library():
     lib.attn_mixed_batch_fp8kv.argtypes = [vp, vp, C.POINTER(_Pool), C.c_int32, vp, C.c_int32, vp, vp,
                                            i32p, i32p, C.c_int32, C.c_int32, C.c_float, C.c_float,
                                            C.c_float, C.c_int32, vp, C.c_size_t, vp]
+    lib.attn_mixed_batch_plan.restype = C.c_int
+    lib.attn_mixed_batch_plan.argtypes = [C.POINTER(_Plan), vp, C.c_int32, vp, vp, i32p, i32p, C.c_int32,
+                                          C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, C.c_size_t, vp]
+    lib.attn_mixed_batch_planned.restype = C.c_int
+    lib.attn_mixed_batch_planned.argtypes = [C.POINTER(_Plan)] + lib.attn_mixed_batch.argtypes
+    lib.attn_mixed_batch_fp8kv_planned.restype = C.c_int
+    lib.attn_mixed_batch_fp8kv_planned.argtypes = [C.POINTER(_Plan)] + lib.attn_mixed_batch_fp8kv.argtypes
     lib.kv_append_fp8.restype = C.c_int
     lib.kv_append_fp8.argtypes = [vp, vp, C.POINTER(_Pool), C.c_int32, vp, C.c_int32, vp, vp, i32p,
                                   i32p, C.c_int32, C.c_float, C.c_float, vp]
@@ -177,6 +196,70 @@ def attn_mixed_batch(q, out, pool: KVPool, layer, block_tables, q_offsets, ctx_l
         workspace.data_ptr(), int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
     if rc:
         raise DsvError("attn_mixed_batch", rc)
+
+
+def attn_mixed_batch_plan(block_tables, q_offsets, ctx_lens, q_offsets_host, ctx_lens_host,
+                          num_q_heads, num_kv_heads, head_dim, workspace, kv_elem_bytes=2,
+                          stream=None) -> AttnPlan:
+    """See ``attn_mixed_batch_plan`` in include/dsv_attn.h: the work lists of a batch, built once
+    into ``workspace`` for the planned calls of every layer."""
+    import torch
+    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
+    assert block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous()
+    assert q_offsets.dtype == torch.int32 and ctx_lens.dtype == torch.int32
+    plan = AttnPlan()
+    rc = load_library().attn_mixed_batch_plan(
+        C.byref(plan.c), block_tables.data_ptr(), int(block_tables.shape[1]), q_offsets.data_ptr(),
+        ctx_lens.data_ptr(), _i32_ptr(qo), _i32_ptr(cl), int(cl.shape[0]), int(num_q_heads),
+        int(num_kv_heads), int(head_dim), int(kv_elem_bytes), workspace.data_ptr(),
+        int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
+    if rc:
+        raise DsvError("attn_mixed_batch_plan", rc)
+    return plan
+
+
+def attn_mixed_batch_planned(plan: AttnPlan, q, out, pool: KVPool, layer, block_tables, q_offsets,
+                             ctx_lens, q_offsets_host, ctx_lens_host, num_q_heads, softmax_scale,
+                             workspace, stream=None) -> None:
+    """See ``attn_mixed_batch_planned`` in include/dsv_attn.h."""
+    import torch
+    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
+    out_dtype = DSV_OUT_F32 if out.dtype == torch.float32 else DSV_OUT_BF16
+    assert out.dtype in (torch.float32, torch.bfloat16)
+    assert block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous()
+    assert q_offsets.dtype == torch.int32 and ctx_lens.dtype == torch.int32
+    assert q.is_contiguous() and out.is_contiguous() and q.element_size() == 2
+    assert tuple(q.shape) == tuple(out.shape)
+    rc = load_library().attn_mixed_batch_planned(
+        C.byref(plan.c), q.data_ptr(), out.data_ptr(), pool.c, int(layer), block_tables.data_ptr(),
+        int(block_tables.shape[1]), q_offsets.data_ptr(), ctx_lens.data_ptr(), _i32_ptr(qo), _i32_ptr(cl),
+        int(cl.shape[0]), int(num_q_heads), float(softmax_scale), out_dtype,
+        workspace.data_ptr(), int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
+    if rc:
+        raise DsvError("attn_mixed_batch_planned", rc)
+
+
+def attn_mixed_batch_fp8kv_planned(plan: AttnPlan, q, out, pool: KVPool, layer, block_tables,
+                                   q_offsets, ctx_lens, q_offsets_host, ctx_lens_host, num_q_heads,
+                                   softmax_scale, k_scale, v_scale, workspace, stream=None) -> None:
+    """See ``attn_mixed_batch_fp8kv_planned`` in include/dsv_attn.h; ``pool`` holds 1-byte elements."""
+    import torch
+    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
+    out_dtype = DSV_OUT_F32 if out.dtype == torch.float32 else DSV_OUT_BF16
+    assert pool.elem_bytes == 1
+    assert out.dtype in (torch.float32, torch.bfloat16)
+    assert block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous()
+    assert q_offsets.dtype == torch.int32 and ctx_lens.dtype == torch.int32
+    assert q.is_contiguous() and out.is_contiguous() and q.element_size() == 2
+    assert tuple(q.shape) == tuple(out.shape)
+    rc = load_library().attn_mixed_batch_fp8kv_planned(
+        C.byref(plan.c), q.data_ptr(), out.data_ptr(), pool.c, int(layer), block_tables.data_ptr(),
+        int(block_tables.shape[1]), q_offsets.data_ptr(), ctx_lens.data_ptr(), _i32_ptr(qo), _i32_ptr(cl),
+        int(cl.shape[0]), int(num_q_heads), float(softmax_scale), float(k_scale), float(v_scale),
+        out_dtype, workspace.data_ptr(), int(workspace.numel() * workspace.element_size()),
+        _stream_ptr(stream))
+    if rc:
+        raise DsvError("attn_mixed_batch_fp8kv_planned", rc)
 
 
 def kv_append(k_new, v_new, pool: KVPool, layer, block_tables, q_offsets, ctx_lens, q_offsets_host,

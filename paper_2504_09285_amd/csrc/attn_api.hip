@@ -8,6 +8,7 @@
 // from host memory.
 #include <math.h>
 #include <stdlib.h>
+#include <string.h>
 
 #include "attn_internal.h"
 
@@ -666,9 +667,48 @@ size_t workspace_bytes_for(bool kv8, int32_t num_seqs, const int32_t* q_offsets_
   return carve(n, num_seqs, num_q_heads, num_kv_heads, head_dim, kv8, nullptr, nullptr);
 }
 
-// Both entry points.  kv8: the pool holds E4M3 codes (one byte per element) with the two
-// dequantisation scales; otherwise bf16 and both scales are 1.
-int run_attention(bool kv8, float k_scale, float v_scale, const void* q, void* out,
+// What a call does: the whole step, the work lists only, or the step on lists a plan call left
+// in the workspace (one plan per batch serves every layer of the model).
+enum class Phase { kPlanAndRun, kPlanOnly, kRunPlanned };
+
+// Host-side record of a plan call, kept in the caller's dsv_attn_plan: everything the lists in
+// the workspace depend on, so that a planned call made with anything else is refused.
+struct PlanStamp {
+  uint64_t magic, lists_hash;
+  const void *workspace, *block_tables, *q_offsets, *ctx_lens;
+  int32_t num_seqs, Hq, Hkv, D, kv8, max_blocks;
+  int32_t part_tokens, mfma_min_qlen, mfma_min_work, tile_tokens, tile_part_tiles, num_cus;
+};
+static_assert(sizeof(PlanStamp) <= sizeof(dsv_attn_plan), "dsv_attn_plan too small");
+constexpr uint64_t kPlanMagic = 0x6473765f706c616eull;
+
+uint64_t hash_lists(const int32_t* qo, const int32_t* cl, int32_t S) {
+  uint64_t h = 0xcbf29ce484222325ull;                            // FNV-1a over both arrays
+  auto mix = [&](uint32_t v) { h = (h ^ v) * 0x100000001b3ull; };
+  for (int i = 0; i <= S; ++i) mix((uint32_t)qo[i]);
+  for (int i = 0; i < S; ++i) mix((uint32_t)cl[i]);
+  return h;
+}
+
+PlanStamp make_stamp(const PlanConfig& c, bool kv8, const void* workspace, const int32_t* block_tables,
+                     int32_t max_blocks, const int32_t* q_offsets, const int32_t* ctx_lens,
+                     const int32_t* qo_host, const int32_t* cl_host, int32_t S, int32_t Hq, int32_t Hkv,
+                     int32_t D) {
+  PlanStamp st;
+  memset(&st, 0, sizeof st);
+  st.magic = kPlanMagic;
+  st.lists_hash = hash_lists(qo_host, cl_host, S);
+  st.workspace = workspace; st.block_tables = block_tables; st.q_offsets = q_offsets; st.ctx_lens = ctx_lens;
+  st.num_seqs = S; st.Hq = Hq; st.Hkv = Hkv; st.D = D; st.kv8 = kv8 ? 1 : 0; st.max_blocks = max_blocks;
+  st.part_tokens = c.part_tokens; st.mfma_min_qlen = c.mfma_min_qlen; st.mfma_min_work = c.mfma_min_work;
+  st.tile_tokens = c.tile_tokens; st.tile_part_tiles = c.tile_part_tiles; st.num_cus = c.num_cus;
+  return st;
+}
+
+// All attention entry points.  kv8: the pool holds E4M3 codes (one byte per element) with the two
+// dequantisation scales; otherwise bf16 and both scales are 1.  In a plan-only call q, out and the
+// pool's base pointers are not looked at.
+int run_attention(Phase phase, dsv_attn_plan* plan, bool kv8, float k_scale, float v_scale, const void* q, void* out,
                   const dsv_kv_pool* pool, int32_t layer, const int32_t* block_tables,
                   int32_t max_blocks_per_seq, const int32_t* q_offsets, const int32_t* ctx_lens,
                   const int32_t* q_offsets_host, const int32_t* ctx_lens_host, int32_t num_seqs,
@@ -677,17 +717,22 @@ int run_attention(bool kv8, float k_scale, float v_scale, const void* q, void* o
   int rc = check_pool(pool);
   if (rc) return rc;
   if (num_seqs < 0) return DSV_E_INVALID;
-  if (num_seqs == 0) return DSV_OK;
-  if (!q || !out || !block_tables || !q_offsets || !ctx_lens || !workspace) return DSV_E_INVALID;
+  if (phase != Phase::kPlanAndRun && !plan) return DSV_E_INVALID;
+  if (num_seqs == 0) {
+    if (phase == Phase::kPlanOnly) memset(plan, 0, sizeof *plan);    // no lists: a planned call of
+    return DSV_OK;                                                 // an empty batch does nothing either
+  }
+  const bool data = phase != Phase::kPlanOnly;
+  if ((data && (!q || !out)) || !block_tables || !q_offsets || !ctx_lens || !workspace) return DSV_E_INVALID;
   if (layer < 0 || layer >= pool->num_layers || max_blocks_per_seq < 1) return DSV_E_INVALID;
   if (num_q_heads < 1 || num_q_heads % pool->num_kv_heads) return DSV_E_INVALID;
   if (out_dtype != DSV_OUT_F32 && out_dtype != DSV_OUT_BF16) return DSV_E_INVALID;
   if (!(softmax_scale >= 0.0f) || isinf(softmax_scale)) return DSV_E_INVALID;
   if (!(k_scale > 0.0f) || isinf(k_scale) || !(v_scale > 0.0f) || isinf(v_scale)) return DSV_E_INVALID;
-  if ((reinterpret_cast<uintptr_t>(q) & 15) || (reinterpret_cast<uintptr_t>(out) & 15) ||
-      (reinterpret_cast<uintptr_t>(pool->k_base) & 15) || (reinterpret_cast<uintptr_t>(pool->v_base) & 15) ||
-      (reinterpret_cast<uintptr_t>(workspace) & 255))
+  if (data && ((reinterpret_cast<uintptr_t>(q) & 15) || (reinterpret_cast<uintptr_t>(out) & 15) ||
+               (reinterpret_cast<uintptr_t>(pool->k_base) & 15) || (reinterpret_cast<uintptr_t>(pool->v_base) & 15)))
     return DSV_E_INVALID;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return DSV_E_INVALID;
   const int elem_bytes = kv8 ? 1 : 2;
   if (pool->num_layers > 1 && (pool->layer_stride * elem_bytes % 16)) return DSV_E_INVALID;
   rc = validate_batch(num_seqs, q_offsets_host, ctx_lens_host, max_blocks_per_seq);
@@ -704,6 +749,16 @@ int run_attention(bool kv8, float k_scale, float v_scale, const void* q, void* o
   const size_t need = carve(n, num_seqs, num_q_heads, pool->num_kv_heads, pool->head_dim, kv8,
                             static_cast<char*>(workspace), &w);
   if (workspace_bytes < need) return DSV_E_WORKSPACE;
+  const PlanStamp stamp = make_stamp(cfg, kv8, workspace, block_tables, max_blocks_per_seq, q_offsets, ctx_lens,
+                                     q_offsets_host, ctx_lens_host, num_seqs, num_q_heads,
+                                     pool->num_kv_heads, pool->head_dim);
+  if (phase == Phase::kRunPlanned) {
+    // The lists in the workspace are only as good as the plan call that wrote them: same batch
+    // arrays (host copies by content, device arrays by address), same geometry, same knobs.
+    PlanStamp made;
+    memcpy(&made, plan, sizeof made);
+    if (memcmp(&made, &stamp, sizeof stamp) != 0) return DSV_E_INVALID;
+  }
 
   AttnArgs a;
   const int64_t layer_off = pool->num_layers > 1 ? (int64_t)layer * pool->layer_stride * elem_bytes : 0;
@@ -729,12 +784,17 @@ int run_attention(bool kv8, float k_scale, float v_scale, const void* q, void* o
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const bool stage = kv8 && n.tiles > 0;
-  {
+  if (phase != Phase::kRunPlanned) {
     EventScope ev(DSV_KERNEL_PLAN, stream);
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, q_offsets, ctx_lens,
                        block_tables, max_blocks_per_seq, num_seqs, cfg, w, n.tiles == 0 ? 0 : (n.stage_segs <= kPlanThreads ? 2 : 1),
                        stage ? 1 : 0, (int32_t)n.items);
     if ((rc = launch_status())) return rc;
+  }
+  if (phase == Phase::kPlanOnly) {
+    memset(plan, 0, sizeof *plan);
+    memcpy(plan, &stamp, sizeof stamp);
+    return DSV_OK;
   }
   if (stage) {
     EventScope ev(DSV_KERNEL_STAGE, stream);
@@ -792,9 +852,9 @@ extern "C" int attn_mixed_batch(const void* q, void* out, const dsv_kv_pool* poo
                                 int32_t num_seqs, int32_t num_q_heads, float softmax_scale,
                                 int32_t out_dtype, void* workspace, size_t workspace_bytes,
                                 void* hip_stream) {
-  return run_attention(false, 1.0f, 1.0f, q, out, pool, layer, block_tables, max_blocks_per_seq,
-                       q_offsets, ctx_lens, q_offsets_host, ctx_lens_host, num_seqs, num_q_heads,
-                       softmax_scale, out_dtype, workspace, workspace_bytes, hip_stream);
+  return run_attention(Phase::kPlanAndRun, nullptr, false, 1.0f, 1.0f, q, out, pool, layer, block_tables,
+                       max_blocks_per_seq, q_offsets, ctx_lens, q_offsets_host, ctx_lens_host, num_seqs,
+                       num_q_heads, softmax_scale, out_dtype, workspace, workspace_bytes, hip_stream);
 }
 
 extern "C" int attn_mixed_batch_fp8kv(const void* q, void* out, const dsv_kv_pool* pool, int32_t layer,
@@ -804,10 +864,58 @@ extern "C" int attn_mixed_batch_fp8kv(const void* q, void* out, const dsv_kv_poo
                                       int32_t num_seqs, int32_t num_q_heads, float softmax_scale,
                                       float k_scale, float v_scale, int32_t out_dtype,
                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
-  return run_attention(true, k_scale, v_scale, q, out, pool, layer, block_tables,
+  return run_attention(Phase::kPlanAndRun, nullptr, true, k_scale, v_scale, q, out, pool, layer, block_tables,
                        max_blocks_per_seq, q_offsets, ctx_lens, q_offsets_host, ctx_lens_host,
                        num_seqs, num_q_heads, softmax_scale, out_dtype, workspace, workspace_bytes,
                        hip_stream);
+}
+
+extern "C" int attn_mixed_batch_plan(dsv_attn_plan* plan, const int32_t* block_tables,
+                                     int32_t max_blocks_per_seq, const int32_t* q_offsets,
+                                     const int32_t* ctx_lens, const int32_t* q_offsets_host,
+                                     const int32_t* ctx_lens_host, int32_t num_seqs,
+                                     int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim,
+                                     int32_t kv_elem_bytes, void* workspace, size_t workspace_bytes,
+                                     void* hip_stream) {
+  if (kv_elem_bytes != 1 && kv_elem_bytes != 2) return DSV_E_INVALID;
+  // Geometry only: the plan does not touch K/V (the base pointers below are never dereferenced).
+  dsv_kv_pool geo;
+  geo.k_base = &geo; geo.v_base = &geo;
+  geo.layer_stride = 0; geo.num_layers = 1; geo.num_blocks = 1; geo.block_size = kBlockSize;
+  geo.num_kv_heads = num_kv_heads; geo.head_dim = head_dim;
+  return run_attention(Phase::kPlanOnly, plan, kv_elem_bytes == 1, 1.0f, 1.0f, nullptr, nullptr, &geo, 0,
+                       block_tables, max_blocks_per_seq, q_offsets, ctx_lens, q_offsets_host,
+                       ctx_lens_host, num_seqs, num_q_heads, 1.0f, DSV_OUT_BF16, workspace,
+                       workspace_bytes, hip_stream);
+}
+
+extern "C" int attn_mixed_batch_planned(const dsv_attn_plan* plan, const void* q, void* out,
+                                        const dsv_kv_pool* pool, int32_t layer,
+                                        const int32_t* block_tables, int32_t max_blocks_per_seq,
+                                        const int32_t* q_offsets, const int32_t* ctx_lens,
+                                        const int32_t* q_offsets_host, const int32_t* ctx_lens_host,
+                                        int32_t num_seqs, int32_t num_q_heads, float softmax_scale,
+                                        int32_t out_dtype, void* workspace, size_t workspace_bytes,
+                                        void* hip_stream) {
+  return run_attention(Phase::kRunPlanned, const_cast<dsv_attn_plan*>(plan), false, 1.0f, 1.0f, q, out, pool,
+                       layer, block_tables, max_blocks_per_seq, q_offsets, ctx_lens, q_offsets_host,
+                       ctx_lens_host, num_seqs, num_q_heads, softmax_scale, out_dtype, workspace,
+                       workspace_bytes, hip_stream);
+}
+
+extern "C" int attn_mixed_batch_fp8kv_planned(const dsv_attn_plan* plan, const void* q, void* out,
+                                              const dsv_kv_pool* pool, int32_t layer,
+                                              const int32_t* block_tables, int32_t max_blocks_per_seq,
+                                              const int32_t* q_offsets, const int32_t* ctx_lens,
+                                              const int32_t* q_offsets_host,
+                                              const int32_t* ctx_lens_host, int32_t num_seqs,
+                                              int32_t num_q_heads, float softmax_scale, float k_scale,
+                                              float v_scale, int32_t out_dtype, void* workspace,
+                                              size_t workspace_bytes, void* hip_stream) {
+  return run_attention(Phase::kRunPlanned, const_cast<dsv_attn_plan*>(plan), true, k_scale, v_scale, q, out,
+                       pool, layer, block_tables, max_blocks_per_seq, q_offsets, ctx_lens,
+                       q_offsets_host, ctx_lens_host, num_seqs, num_q_heads, softmax_scale, out_dtype,
+                       workspace, workspace_bytes, hip_stream);
 }
 
 extern "C" int dsv_profile_events(int32_t kernel_id, void* start_event, void* stop_event) {

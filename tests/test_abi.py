@@ -130,3 +130,34 @@ def test_empty_batches_are_no_ops_on_every_attention_and_append_entry_point(lib)
     assert lib.kv_append(None, None, C.byref(pool), 0, None, 1, None, None, None, None, 0, None) == 0
     assert lib.kv_unpack_chunks_fp8(None, None, None, 0, C.byref(pool), None, 1, None) == 0
     assert dsv.attn_mixed_batch_workspace_bytes([0], [], 32, 8, 128) > 0      # lists only, no partials
+
+
+def test_plan_entry_points_check_their_arguments_before_any_gpu_work(lib):
+    """attn_mixed_batch_plan / *_planned: bad arguments and a plan record that does not match the
+    call are refused on the host (nothing here reaches a launch, so no GPU is needed)."""
+    pool = binding._Pool(4096, 4096, 0, 1, 4, 16, 8, 128)
+    qo = np.array([0, 1], np.int32)
+    cl = np.array([5], np.int32)
+    p = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+    fake = 4096                                            # non-null, aligned, never dereferenced
+    plan = binding._Plan()
+    f = lib.attn_mixed_batch_plan
+    assert f(None, fake, 1, fake, fake, p(qo), p(cl), 1, 32, 8, 128, 2, fake, 1 << 30, None) == -1   # no plan record
+    assert f(C.byref(plan), fake, 1, fake, fake, p(qo), p(cl), 1, 32, 8, 128, 3, fake, 1 << 30, None) == -1  # element size
+    assert f(C.byref(plan), fake, 1, fake, fake, p(qo), p(cl), 1, 32, 8, 96, 2, fake, 1 << 30, None) == -2   # head_dim
+    assert f(C.byref(plan), fake, 1, fake, fake, p(qo), p(cl), 1, 32, 8, 128, 2, None, 1 << 30, None) == -1  # no workspace
+    assert f(C.byref(plan), fake, 1, fake, fake, p(qo), p(cl), 1, 32, 8, 128, 2, fake, 16, None) == -3       # too small
+    assert f(C.byref(plan), None, 1, None, None, None, None, 0, 32, 8, 128, 2, None, 0, None) == 0           # empty batch
+    need = dsv.attn_mixed_batch_workspace_bytes(qo, cl, 32, 8, 128)
+    # a record that no plan call filled: the planned calls refuse it
+    rc = lib.attn_mixed_batch_planned(C.byref(plan), fake, fake, C.byref(pool), 0, fake, 1, fake, fake, p(qo), p(cl),
+                                      1, 32, 0.1, 0, fake, need, None)
+    assert rc == -1
+    rc = lib.attn_mixed_batch_fp8kv_planned(C.byref(plan), fake, fake, C.byref(pool), 0, fake, 1, fake, fake, p(qo),
+                                            p(cl), 1, 32, 0.1, 0.5, 0.5, 0,
+                                            fake, dsv.attn_mixed_batch_fp8kv_workspace_bytes(qo, cl, 32, 8, 128), None)
+    assert rc == -1
+    assert lib.attn_mixed_batch_planned(None, fake, fake, C.byref(pool), 0, fake, 1, fake, fake, p(qo), p(cl),
+                                        1, 32, 0.1, 0, fake, need, None) == -1
+    assert lib.attn_mixed_batch_planned(C.byref(plan), None, None, C.byref(pool), 0, None, 1, None, None, None, None,
+                                        0, 32, 0.1, 0, None, 0, None) == 0                                   # empty batch
