@@ -18,6 +18,9 @@
  *     host-side arrays (grid sizes, workspace layout) is frozen, so a graph is valid for
  *     batches with the same host-side arrays.  Make one call outside the capture first (the
  *     first call on a device configures the kernels).
+ *   - A call that enqueues work first clears the calling thread's HIP last-error state
+ *     (hipGetLastError), so that an error left by an earlier, unrelated HIP call is not
+ *     reported as DSV_E_LAUNCH.
  *   - Return value: DSV_OK (0) or a negative DSV_E_* code.  Arguments are checked before any
  *     GPU work: with DSV_E_INVALID, DSV_E_UNSUPPORTED or DSV_E_WORKSPACE nothing has been
  *     enqueued.  DSV_E_LAUNCH means HIP refused a launch part-way; outputs are then undefined.

@@ -66,6 +66,14 @@ def load_library():
     if not os.path.exists(_LIB_PATH):
         raise RuntimeError("libdsv_attn.so is not built: run `python -m paper_2504_09285_amd.build` "
                            "(there is no fallback path)")
+    # torch ships a HIP runtime of its own (same soname as the system's, different file).  Tensors
+    # and streams come from torch, so its runtime has to be the one this library binds to: loaded
+    # first, it satisfies the library's dependency; loaded second, the process would hold two
+    # runtimes that do not know each other's allocations, and every launch would fail.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(_LIB_PATH)
     i32p, vp = C.POINTER(C.c_int32), C.c_void_p
     lib.attn_mixed_batch_workspace_bytes.restype = C.c_size_t

@@ -783,6 +783,7 @@ int run_attention(Phase phase, dsv_attn_plan* plan, bool kv8, float k_scale, flo
   a.kv8 = kv8 ? 1 : 0;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  begin_gpu_work();
   const bool stage = kv8 && n.tiles > 0;
   if (phase != Phase::kRunPlanned) {
     EventScope ev(DSV_KERNEL_PLAN, stream);

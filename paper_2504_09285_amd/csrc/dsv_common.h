@@ -29,6 +29,11 @@ __host__ __device__ inline uint16_t f32_to_bf16_rne(float x) {
   return (uint16_t)(u >> 16);
 }
 
+// Called by every entry point before its first launch: an error that an earlier HIP call of this
+// host thread left behind (the caller's, or another library's) must not be taken for a failed
+// launch of ours by launch_status() below.
+inline void begin_gpu_work() { (void)hipGetLastError(); }
+
 inline int launch_status() {
   return hipGetLastError() == hipSuccess ? DSV_OK : DSV_E_LAUNCH;
 }

@@ -215,6 +215,7 @@ extern "C" int kv_append(const void* k_new, const void* v_new, const dsv_kv_pool
   if (rc <= 0) return rc;
   const int64_t grid = ((int64_t)p.total_q + p.tile_tokens - 1) / p.tile_tokens;
   if (grid > 0x7fffffffLL) return DSV_E_UNSUPPORTED;
+  begin_gpu_work();
   hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)grid, 2u), dim3(kAppendThreads), 0,
                      static_cast<hipStream_t>(hip_stream), p);
   return launch_status();
@@ -235,6 +236,7 @@ extern "C" int kv_append_fp8(const void* k_new, const void* v_new, const dsv_kv_
   q.v_scale = v_scale;
   const int64_t grid = ((int64_t)q.p.total_q + q.p.tile_tokens - 1) / q.p.tile_tokens;
   if (grid > 0x7fffffffLL) return DSV_E_UNSUPPORTED;
+  begin_gpu_work();
   hipLaunchKernelGGL(kv_append_fp8_kernel, dim3((unsigned)grid, 2u), dim3(kAppendThreads), 0,
                      static_cast<hipStream_t>(hip_stream), q);
   return launch_status();

@@ -128,6 +128,7 @@ int run_copy(bool pack, const dsv_kv_pool* pool, const int32_t* block_tables, in
   const int64_t grid = (int64_t)num_chunks * 2 * pool->num_layers * p.tiles_per_chunk;
   if (grid > 0x7fffffffLL) return DSV_E_UNSUPPORTED;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  begin_gpu_work();
   if (pack)
     hipLaunchKernelGGL(kv_copy_kernel<true>, dim3((unsigned)grid), dim3(kCopyThreads), 0, stream, p);
   else

@@ -107,3 +107,12 @@ def run_attention_fp8kv(b, out_dtype=torch.float32, **over) -> np.ndarray:
     if out_dtype == torch.bfloat16:
         return host_u16(out)
     return out.cpu().numpy()
+
+
+def loaded_hip_runtime():
+    """The HIP runtime already in this process (torch's), for tests that call it directly."""
+    import ctypes
+    for line in open("/proc/self/maps"):
+        if "libamdhip64" in line:
+            return ctypes.CDLL(line.split()[-1])
+    raise RuntimeError("no HIP runtime loaded")

@@ -161,3 +161,15 @@ def test_plan_entry_points_check_their_arguments_before_any_gpu_work(lib):
                                         1, 32, 0.1, 0, fake, need, None) == -1
     assert lib.attn_mixed_batch_planned(C.byref(plan), None, None, C.byref(pool), 0, None, 1, None, None, None, None,
                                         0, 32, 0.1, 0, None, 0, None) == 0                                   # empty batch
+
+
+def test_loading_the_library_first_leaves_one_hip_runtime_in_the_process():
+    """torch ships a HIP runtime of its own.  Whatever is imported first, the process must end up
+    with a single libamdhip64 mapped: two runtimes do not know each other's allocations."""
+    import subprocess
+    import sys
+    code = ("import paper_2504_09285_amd as dsv; dsv.load_library(); import torch; "
+            "paths = {l.split()[-1] for l in open('/proc/self/maps') if 'libamdhip64' in l}; "
+            "assert len(paths) == 1, paths; print('one runtime')")
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, cwd=ROOT)
+    assert r.returncode == 0 and "one runtime" in r.stdout, r.stderr[-2000:]

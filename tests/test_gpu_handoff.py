@@ -106,3 +106,52 @@ def test_config5_handoff_full_size():
     for l in range(h.L):
         assert np.array_equal(host_u16(d.dst.k[l]), h.dst_k[l]), l
         assert np.array_equal(host_u16(d.dst.v[l]), h.dst_v[l]), l
+
+
+def test_an_error_left_by_an_unrelated_hip_call_is_not_reported_as_a_failed_launch():
+    """The calling thread's HIP last-error state may hold an error from a call that has nothing to
+    do with this library (here: the elapsed time of two events that were never recorded, a
+    host-side error).  Every entry point must still do its work and return success."""
+    import ctypes as C
+
+    import torch
+
+    import paper_2504_09285_amd as dsv
+    from gpu_harness import DeviceBatch, DeviceHandoff, host_u16, loaded_hip_runtime
+    hip = loaded_hip_runtime()
+    hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+    hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+    hip.hipEventDestroy.argtypes = [C.c_void_p]
+    e0, e1 = C.c_void_p(), C.c_void_p()
+    assert hip.hipEventCreate(C.byref(e0)) == 0 and hip.hipEventCreate(C.byref(e1)) == 0
+
+    def leave_an_error():
+        ms = C.c_float()
+        assert hip.hipEventElapsedTime(C.byref(ms), e0, e1) != 0
+
+    b, h = gen.config1()
+    d = DeviceHandoff(h)
+    torch.cuda.synchronize()
+    leave_an_error()
+    d.pack()
+    leave_an_error()
+    d.unpack()
+    db = DeviceBatch(b)
+    k_new = db.q[:, :b.Hkv].contiguous()         # (torch's own launches do not survive a planted error)
+    out = torch.empty(db.q.shape, dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    leave_an_error()
+    dsv.attn_mixed_batch(db.q, out, db.pool, 0, db.block_tables, db.q_offsets, db.ctx_lens, b.q_offsets,
+                         b.ctx_lens, b.Hq, b.scale, db.workspace)
+    leave_an_error()
+    dsv.kv_append(k_new, k_new, db.pool, 0, db.block_tables, db.q_offsets, db.ctx_lens, b.q_offsets,
+                  b.ctx_lens)
+    hip.hipGetLastError()                        # leave the thread clean for torch
+    torch.cuda.synchronize()
+    buf, dk, dv = oracle_handoff(h)
+    np.testing.assert_array_equal(host_u16(d.chunk_buf), buf)
+    np.testing.assert_array_equal(host_u16(d.dst.k), dk)
+    ref = oracle.attn_mixed_batch(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens, b.scale)
+    assert np.abs(out.cpu().numpy() - ref).max() <= 1e-2
+    hip.hipEventDestroy(e0)
+    hip.hipEventDestroy(e1)
