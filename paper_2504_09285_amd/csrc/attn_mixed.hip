@@ -40,7 +40,9 @@ __global__ __launch_bounds__(512, 2) void mixed_kernel(prefill_impl::TilesParams
   if (t1 != t0) {
     const uint32_t wg = t0 * kGroup + lane_in_group;
     if (wg >= mp.tile_wgs) return;                               // uniform for the workgroup
-    prefill_impl::prefill_tiles_body<D>(tp, (int)(wg % mp.tiles_x), (int)(wg / mp.tiles_x), smem);
+    int bx, bz;
+    prefill_impl::tile_work_item(wg, tp.a.Hkv, tp.G, bx, bz);
+    prefill_impl::prefill_tiles_body<D>(tp, bx, bz, smem);
   } else {
     const uint32_t wg = (g - t0) * kGroup + lane_in_group;
     if (wg >= mp.row_wgs) return;

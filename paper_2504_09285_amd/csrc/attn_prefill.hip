@@ -8,7 +8,9 @@ using namespace prefill_impl;
 template <int D>
 __global__ __launch_bounds__(kThreads, kThreads / 256) void prefill_tiles_kernel(TilesParams prm) {
   extern __shared__ __align__(16) unsigned char smem[];
-  prefill_tiles_body<D>(prm, (int)blockIdx.x, (int)blockIdx.z, smem);
+  int bx, bz;
+  tile_work_item(blockIdx.x, prm.a.Hkv, prm.G, bx, bz);
+  prefill_tiles_body<D>(prm, bx, bz, smem);
 }
 
 template <int D>
@@ -36,7 +38,9 @@ int launch_prefill_tiles(const AttnArgs& a, const WorkLists& w, const PlanConfig
                          const PlanCounts& n, hipStream_t stream) {
   if (cfg.tile_tokens != kTileQ) return DSV_E_UNSUPPORTED;
   const TilesParams prm = make_tiles_params(a, w, n);
-  dim3 grid((unsigned)(n.tiles * a.Hkv), 1u, (unsigned)ceil_div(prm.G, 4));
+  const int64_t wgs = n.tiles * a.Hkv * ceil_div(prm.G, 4);
+  if (wgs > 0x7fffffffLL) return DSV_E_UNSUPPORTED;
+  dim3 grid((unsigned)wgs);
   if (a.D == 128) return launch_t<128>(prm, grid, stream);
   if (a.D == 64) return launch_t<64>(prm, grid, stream);
   return DSV_E_UNSUPPORTED;

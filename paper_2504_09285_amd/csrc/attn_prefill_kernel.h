@@ -207,6 +207,18 @@ __device__ __forceinline__ float other_half_sum(float x) {
   return lo + hi;
 }
 
+// Work item of the wg-th prefill workgroup.  The tile list is sorted heaviest first and
+// workgroups are dispatched in index order, so the groups of four query heads of one (tile, KV
+// head) follow each other (all head groups of the heavy tiles start before any light tile),
+// while the KV head stays the fastest index: with eight KV heads, eight consecutive workgroups
+// go to the eight XCDs and KV head k always lands on XCD k.
+__device__ __forceinline__ void tile_work_item(uint32_t wg, int Hkv, int G, int& bx, int& bz) {
+  const uint32_t nbz = (uint32_t)(G + 3) / 4;
+  const uint32_t kvh = wg % (uint32_t)Hkv, r = wg / (uint32_t)Hkv;
+  bz = (int)(r % nbz);
+  bx = (int)((r / nbz) * (uint32_t)Hkv + kvh);
+}
+
 // The kernel body as a device function, so that the same code serves the kernel of its own and
 // the launch that mixes prefill tiles with row work.  bx = tile * Hkv + KV head and bz = group
 // of four query heads stand in for the block index; `smem` is the dynamic LDS (LDS_BYTES).
