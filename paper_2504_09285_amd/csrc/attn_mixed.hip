@@ -46,8 +46,9 @@ __global__ __launch_bounds__(512, 2) void mixed_kernel(prefill_impl::TilesParams
   } else {
     const uint32_t wg = (g - t0) * kGroup + lane_in_group;
     if (wg >= mp.row_wgs) return;
-    const uint32_t bx = wg % mp.rows_x, rest = wg / mp.rows_x;
-    rows_impl::rows_body<D, 2, KV8>(rp, (int)bx, (int)(rest % mp.rows_y), (int)(rest / mp.rows_y), mp.rows_waves, smem);
+    int bx, by, bz;
+    rows_impl::row_work_item(wg, rp.gy, rp.G, bx, by, bz);
+    rows_impl::rows_body<D, 2, KV8>(rp, bx, by, bz, mp.rows_waves, smem);
   }
 }
 
@@ -81,7 +82,7 @@ int launch_mixed(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, c
   if (!mixed_launch_supported(a, cfg, n)) return DSV_E_UNSUPPORTED;
   const int G = a.Hq / a.Hkv;
   const prefill_impl::TilesParams tp = prefill_impl::make_tiles_params(a, w, n);
-  rows_impl::RowsParams rp{a, w, cfg.part_tokens, G};
+  rows_impl::RowsParams rp{a, w, cfg.part_tokens, G, 1};
   int waves = 1;
   while (waves < a.Hkv && waves < 8) waves <<= 1;
   MixParams mp;
@@ -89,6 +90,7 @@ int launch_mixed(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, c
   const int64_t tile_wgs = (int64_t)mp.tiles_x * ceil_div(G, 4);
   mp.rows_x = (uint32_t)n.items;
   mp.rows_y = (uint32_t)ceil_div(a.Hkv, waves);
+  rp.gy = (int32_t)mp.rows_y;
   const int64_t row_wgs = (int64_t)n.items * mp.rows_y * ceil_div(G, rows_impl::kRowHeads);
   const int64_t tg = ceil_div(tile_wgs, (int64_t)kGroup), rg = ceil_div(row_wgs, (int64_t)kGroup);
   if ((tg + rg) * kGroup > 0x7fffffffLL) return DSV_E_UNSUPPORTED;

@@ -8,7 +8,9 @@ using namespace rows_impl;
 template <int D, int R, bool KV8>
 __global__ __launch_bounds__(512) void rows_kernel(RowsParams prm) {
   extern __shared__ __align__(16) unsigned char smem[];
-  rows_body<D, R, KV8>(prm, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, (int)(blockDim.x / kWave), smem);
+  int bx, by, bz;
+  row_work_item(blockIdx.x, prm.gy, prm.G, bx, by, bz);
+  rows_body<D, R, KV8>(prm, bx, by, bz, (int)(blockDim.x / kWave), smem);
 }
 
 template <int D, int R, bool KV8>
@@ -30,14 +32,17 @@ int launch_rows_t(const RowsParams& prm, dim3 grid, int waves, hipStream_t strea
 int launch_rows(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, const PlanCounts& n,
                 hipStream_t stream) {
   if (cfg.part_tokens > 64 * kBlockSize) return DSV_E_UNSUPPORTED;   // one table vector per partition
-  RowsParams prm{a, w, cfg.part_tokens, a.Hq / a.Hkv};
+  RowsParams prm{a, w, cfg.part_tokens, a.Hq / a.Hkv, 1};
   int waves = 1;
   // waves * slots * slot bytes (8 KiB of bf16, 4 KiB of codes) must fit in the 160 KB of LDS
   const int max_waves = cfg.row_nbuf <= (a.kv8 ? 4 : 2) ? 8 : 4;
   int cap = max_waves;
   if (const char* e = getenv("DSV_ROW_WAVES")) cap = min(max_waves, max(1, atoi(e)));
   while (waves < a.Hkv && waves < cap) waves <<= 1;
-  dim3 grid((unsigned)n.items, (unsigned)ceil_div(a.Hkv, waves), (unsigned)ceil_div(prm.G, kRowHeads));
+  prm.gy = ceil_div(a.Hkv, waves);
+  const int64_t wgs = n.items * prm.gy * ceil_div(prm.G, kRowHeads);
+  if (wgs > 0x7fffffffLL) return DSV_E_UNSUPPORTED;
+  dim3 grid((unsigned)wgs);
   const int r = cfg.row_nbuf;
 #define DSV_ROWS_CASE(DD, RR, KK) \
   if (a.D == DD && r == RR && (a.kv8 != 0) == KK) return launch_rows_t<DD, RR, KK>(prm, grid, waves, stream);

@@ -52,7 +52,18 @@ struct RowsParams {
   WorkLists w;
   int32_t part_tokens;
   int32_t G;            // query heads per KV head
+  int32_t gy;           // workgroups per item along the KV heads (a workgroup covers `waves` of them)
 };
+
+// Work item of the wg-th row workgroup: the workgroups of one item (KV head groups, and groups of
+// kRowHeads query heads per KV head) follow each other, so the longest-first order of the items holds
+// for the whole launch.
+__device__ __forceinline__ void row_work_item(uint32_t wg, int gy, int G, int& bx, int& by, int& bz) {
+  const uint32_t per_item = (uint32_t)gy * (uint32_t)((G + kRowHeads - 1) / kRowHeads), sub = wg % per_item;
+  bx = (int)(wg / per_item);
+  by = (int)(sub % (uint32_t)gy);
+  bz = (int)(sub / (uint32_t)gy);
+}
 
 // EB = bytes per cached element: 2 (bf16) or 1 (E4M3 codes, widened to bf16 in registers).
 template <int D, int EB>
