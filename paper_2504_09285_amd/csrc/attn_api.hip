@@ -86,7 +86,8 @@ int validate_batch(int32_t S, const int32_t* qo, const int32_t* cl, int32_t max_
   return DSV_OK;
 }
 
-PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8, int wgs_per_tile) {
+PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8, int Hkv, int G) {
+  const int wgs_per_tile = Hkv * ceil_div(G, 4);
   PlanConfig c;
   // Which spans take the row path.  It streams the context once per query token, the MFMA path
   // once per span (with mostly empty query tiles, whose idle waves step aside) at a fixed cost
@@ -121,19 +122,49 @@ PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8
     const int64_t prefix = cl[i] - q_len;
     row_tokens += (int64_t)q_len * prefix + (int64_t)q_len * (q_len + 1) / 2;
   }
-  // Measured with the items dispatched longest first (the plan kernel's order): about 1.9 items
-  // per compute unit.  Config 2 (0.36M streamed tokens): 736-token partitions 0.253 ms per step,
-  // 336 tokens 0.277, 1024 tokens 0.258; the same optimum on 8-bit codes (0.145 ms); config 4's
-  // decodes (0.74M tokens) and longer batches run best at the cap of 1024.
-  int64_t part = (row_tokens * 10 / ((int64_t)c.num_cus * 19) + 15) / 16 * 16;
-  // A small batch is latency-bound: one item per compute unit (a compute unit alone streams
-  // about 30 GB/s, so a 256-token item lasts 35 us), down to 128 tokens.  Measured, 32/8 heads:
-  // 8 decodes on 1,024 tokens 30 -> 23 us per step, 64 on 300 tokens 34 -> 28 us, one on 8,192
-  // tokens 34 -> 30 us; 64-token partitions are slower again (more partials than streaming).
-  const int64_t one_each = (row_tokens / c.num_cus + 15) / 16 * 16;
-  const int64_t floor_part = one_each < 128 ? 128 : (one_each < 256 ? one_each : 256);
-  if (part < floor_part) part = floor_part;
-  if (part > 1024) part = 1024;
+  // Items stream side by side, one workgroup of up to eight waves (KV heads, or groups of 16
+  // query heads) to a compute unit; `conc` items fill the device.  With the items dispatched longest first (the plan
+  // kernel's order) the fewest, largest items that still keep every compute unit busy are
+  // fastest, measured on decode batches of 32/8 heads with contexts of 200-2,600 tokens:
+  //   0.13M streamed tokens: 640-token partitions (260 items) 96 us per step, 272 tokens 104 us,
+  //                          1,024 tokens (180 items) 109 us;
+  //   0.22M: 1,024 tokens (300 items) 150 us, 448 tokens 158 us;
+  //   0.36M (config 2): 736 tokens (630 items, 2.5 per compute unit) 0.253 ms, 1,024 tokens (476)
+  //                          0.258, 336 tokens 0.277; the same optimum on 8-bit codes;
+  //   0.55M and more (config 4's decodes, config 5): the cap of 1,024 tokens.
+  // So: with at least 1.5 conc items at the cap, 1.9 items per slot; with at least conc items at
+  // the cap, the cap; otherwise the smallest partition whose items all start at once (at most
+  // conc of them), down to 128 tokens.  A few items more than conc is the worst case: config 3's
+  // 16 decodes (64k tokens) take 47 us in 257 items of 256 tokens or 208 of 320, and 62 us in
+  // 274 items of 240.  (A small batch is latency-bound: 8 decodes on 1,024 tokens 30 -> 23 us per
+  // step with 128-token instead of 256-token partitions; 64-token partitions are slower again.)
+  auto items_at = [&](int64_t p) {
+    int64_t n = 0;
+    for (int i = 0; i < S; ++i) {
+      const int q_len = qo[i + 1] - qo[i];
+      if (!on_row_path(q_len, cl[i], c)) continue;
+      for (int j = 0; j < q_len; ++j) n += (cl[i] - q_len + j + p) / p;        // ceil((ctx_eff) / p)
+    }
+    return n;
+  };
+  // (Fewer than eight KV heads: a workgroup is smaller and several share a compute unit, but the
+  // measured optimum follows the number of workgroups: 2,048 decodes with one KV head run 3 %
+  // faster with the partitions a count of one item per compute unit gives.)
+  const int64_t conc = max((int64_t)1, (int64_t)c.num_cus * 8 / max((int64_t)8, (int64_t)Hkv * ceil_div(G, 16)));
+  const int64_t n_cap = items_at(1024);
+  int64_t part = 1024;
+  if (n_cap * 2 >= conc * 3) {
+    part = (row_tokens * 10 / (conc * 19) + 15) / 16 * 16;
+    if (part > 1024) part = 1024;
+    if (part < 128) part = 128;
+  } else if (n_cap < conc) {
+    int64_t lo = 128 / 16, hi = 1024 / 16;       // smallest multiple of 16 with items_at <= conc
+    while (lo < hi) {
+      const int64_t mid = (lo + hi) / 2;
+      if (items_at(mid * 16) <= conc) hi = mid; else lo = mid + 1;
+    }
+    part = lo * 16;
+  }
   const int forced = env_int("DSV_PART_TOKENS", 0);
   if (forced >= 16) part = forced / 16 * 16;
   if (part > 1024) part = 1024;                 // the row kernel keeps one 64-entry table vector
@@ -661,8 +692,8 @@ size_t workspace_bytes_for(bool kv8, int32_t num_seqs, const int32_t* q_offsets_
   if (num_q_heads < 1 || num_kv_heads < 1 || num_q_heads % num_kv_heads) return 0;
   if (head_dim != 64 && head_dim != 128) return 0;
   if (validate_batch(num_seqs, q_offsets_host, ctx_lens_host, -1) != DSV_OK) return 0;
-  const PlanConfig c = choose_plan(num_seqs, q_offsets_host, ctx_lens_host, kv8,
-                                   num_kv_heads * ceil_div(num_q_heads / num_kv_heads, 4));
+  const PlanConfig c = choose_plan(num_seqs, q_offsets_host, ctx_lens_host, kv8, num_kv_heads,
+                                   num_q_heads / num_kv_heads);
   const PlanCounts n = count_plan(num_seqs, q_offsets_host, ctx_lens_host, c);
   return carve(n, num_seqs, num_q_heads, num_kv_heads, head_dim, kv8, nullptr, nullptr);
 }
@@ -738,8 +769,8 @@ int run_attention(Phase phase, dsv_attn_plan* plan, bool kv8, float k_scale, flo
   rc = validate_batch(num_seqs, q_offsets_host, ctx_lens_host, max_blocks_per_seq);
   if (rc) return rc;
 
-  const PlanConfig cfg = choose_plan(num_seqs, q_offsets_host, ctx_lens_host, kv8,
-                                     pool->num_kv_heads * ceil_div(num_q_heads / pool->num_kv_heads, 4));
+  const PlanConfig cfg = choose_plan(num_seqs, q_offsets_host, ctx_lens_host, kv8, pool->num_kv_heads,
+                                     num_q_heads / pool->num_kv_heads);
   const PlanCounts n = count_plan(num_seqs, q_offsets_host, ctx_lens_host, cfg);
   if (n.items > 0x7fffffffLL || n.tiles > 0x7fffffffLL || n.rows > 0x7fffffffLL ||
       n.max_parts > 0x7fff || n.stage_blocks > 0x7fffffffLL ||
