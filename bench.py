@@ -227,6 +227,20 @@ def bench_shared_plan(d, layers, iterations, warmup):
             "tokens_per_s": b.total_q / sec}
 
 
+def settle_runtime():
+    """The HIP runtime stalls the host once per process, for about 70 ms, somewhere around its
+    thousandth kernel launch (measured on this image: 18 us per call before and after, 714 us per
+    call over one block of 100 calls).  Long steps hide it behind queued work; short ones (config
+    1, the profile table) would carry it into whichever timed region it falls.  A few hundred
+    untimed calls on a tiny batch take the process past it before anything is timed."""
+    import torch
+    from workloads import gen
+    d = upload(gen.make_batch("settle", 1, 8, 2, 64, [(1, 40), (20, 30), (1, 300)]))
+    for _ in range(500):
+        attn_step(d)
+    torch.cuda.synchronize()
+
+
 def bench_append(b, steps, warmup, hev):
     """kv_append of the batch's new tokens (the step before attention): read once, written once."""
     import torch
@@ -517,6 +531,7 @@ def main():
     dsv.load_library()
     threads = min(16, os.cpu_count() or 8)
     hev = HipEvents()
+    settle_runtime()
     if args.fp8kv_only:
         print(json.dumps({"fp8kv": bench_fp8kv(args.steps, args.warmup, hev)}))
         return
