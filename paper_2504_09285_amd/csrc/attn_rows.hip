@@ -47,9 +47,7 @@ int launch_rows(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, co
 #define DSV_ROWS_CASE(DD, RR, KK) \
   if (a.D == DD && r == RR && (a.kv8 != 0) == KK) return launch_rows_t<DD, RR, KK>(prm, grid, waves, stream);
   DSV_ROWS_CASE(128, 2, false) DSV_ROWS_CASE(128, 3, false) DSV_ROWS_CASE(128, 4, false)
-  DSV_ROWS_CASE(128, 6, false) DSV_ROWS_CASE(128, 8, false)
   DSV_ROWS_CASE(64, 2, false) DSV_ROWS_CASE(64, 3, false) DSV_ROWS_CASE(64, 4, false)
-  DSV_ROWS_CASE(64, 6, false) DSV_ROWS_CASE(64, 8, false)
   DSV_ROWS_CASE(128, 2, true) DSV_ROWS_CASE(128, 4, true) DSV_ROWS_CASE(128, 8, true)
   DSV_ROWS_CASE(64, 2, true) DSV_ROWS_CASE(64, 4, true) DSV_ROWS_CASE(64, 8, true)
 #undef DSV_ROWS_CASE

@@ -495,3 +495,20 @@ def test_config5_long_context_full_sampled_rows():
     far = int(np.argmax(b.block_tables.max(axis=1)))          # the sequence owning the highest block id
     rows.append((far, 0, 3))
     _sampled_rows_check(b, rows, got)
+
+
+@pytest.mark.parametrize("nbuf", ["3", "4"])
+def test_deeper_lds_rings_of_the_row_kernel(monkeypatch, nbuf):
+    """DSV_ROW_NBUF selects three or four LDS ring slots per wave (four waves per workgroup instead
+    of eight, two workgroups per item with eight KV heads; tiles and rows then run in launches of
+    their own).  Contexts shorter than the ring, of exactly one block, ragged, and split rows."""
+    from gpu_harness import run_attention
+    monkeypatch.setenv("DSV_ROW_NBUF", nbuf)
+    monkeypatch.setenv("DSV_PART_TOKENS", "128")
+    segs = [(1, 1), (1, 16), (1, 17), (1, 33), (1, 48), (1, 130), (1, 700), (1, 1025), (3, 40), (70, 90), (1, 64)]
+    for Hq, Hkv, D in ((32, 8, 128), (12, 3, 64)):
+        b = gen.make_batch("ring%s_%d" % (nbuf, D), 71, Hq, Hkv, D, segs)
+        got = run_attention(b)
+        ref = oracle.attn_mixed_batch(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens, b.scale)
+        assert np.isfinite(got).all()
+        assert np.abs(got - ref).max() <= TOL

@@ -274,3 +274,19 @@ def test_pack_and_unpack_of_codes_are_byte_exact(L, Hkv, D, chunk_tokens):
     np.testing.assert_array_equal(dst.k.cpu().numpy().view(np.uint16), want_dk)
     np.testing.assert_array_equal(dst.v.cpu().numpy().view(np.uint16), want_dv)
     assert (want_dk != as16(dst_k)).any()
+
+
+@pytest.mark.parametrize("nbuf", ["4", "8"])
+def test_deeper_lds_rings_of_the_row_kernel_8bit(monkeypatch, nbuf):
+    """DSV_ROW_NBUF on the 8-bit cache: four slots (eight waves) or eight slots (four waves) per wave."""
+    from gpu_harness import run_attention_fp8kv
+    monkeypatch.setenv("DSV_ROW_NBUF", nbuf)
+    monkeypatch.setenv("DSV_PART_TOKENS", "128")
+    segs = [(1, 1), (1, 16), (1, 17), (1, 33), (1, 48), (1, 130), (1, 700), (1, 1025), (3, 40), (70, 90), (1, 64)]
+    for Hq, Hkv, D in ((32, 8, 128), (12, 3, 64)):
+        b = gen.make_batch_fp8kv("ring8_%s_%d" % (nbuf, D), 72, Hq, Hkv, D, segs)
+        got = run_attention_fp8kv(b)
+        ref = oracle.attn_mixed_batch_fp8kv(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens,
+                                            b.scale, b.meta["k_scale"], b.meta["v_scale"])
+        assert np.isfinite(got).all()
+        assert np.abs(got - ref).max() <= TOL
