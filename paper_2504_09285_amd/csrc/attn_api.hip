@@ -64,7 +64,7 @@ __host__ __device__ inline int parts_of(int ctx_eff, const PlanConfig& c) {
 // KV tiles the t-th query tile of a span visits: its last row sees tokens [0, prefix + 64(t+1)).
 __host__ __device__ inline int kv_tiles_of(int ctx, int q_len, int t, const PlanConfig& c) {
   const int kv_end = min(ctx, ctx - q_len + (t + 1) * c.tile_tokens);
-  return (kv_end + c.tile_tokens - 1) / c.tile_tokens;
+  return (kv_end + 63) / 64;                     // KV tiles are 64 tokens whatever the query tile
 }
 // Context partitions of a query tile that visits n_kv KV tiles.  With base = n_kv / P and
 // rem = n_kv % P, partition p of P covers base + (p < rem) KV tiles from p * base + min(p, rem):
@@ -87,8 +87,18 @@ int validate_batch(int32_t S, const int32_t* qo, const int32_t* cl, int32_t max_
 }
 
 PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8, int Hkv, int G) {
-  const int wgs_per_tile = Hkv * ceil_div(G, 4);
   PlanConfig c;
+  // Query heads per KV head that do not fill groups of four (5, 6, 7, 9, ...; Qwen-2.5's 40/8
+  // heads) would leave most waves of the last group's work items without rows.  Then a work
+  // item takes the (token, head) pairs of all heads of a group of up to eight for fewer tokens:
+  // 256 rows = 51 tokens x 5 heads, 42 x 6, 36 x 7, 32 x 8, each lane addressing its own head.
+  c.flat_heads = 0;
+  c.head_groups = ceil_div(G, 4);
+  if (G > 4 && G % 4 != 0) {
+    c.head_groups = ceil_div(G, 8);
+    c.flat_heads = ceil_div(G, c.head_groups);
+  }
+  const int wgs_per_tile = Hkv * c.head_groups;
   // Which spans take the row path.  It streams the context once per query token, the MFMA path
   // once per span (with mostly empty query tiles, whose idle waves step aside) at a fixed cost
   // of about 10 us per work item, so the MFMA path wins once a span's q_len * ctx_len passes
@@ -102,7 +112,7 @@ PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8
   c.mfma_min_work = kv8 ? 0x7fffffff : 1200;
   const int forced_q = env_int("DSV_MFMA_MIN_QLEN", 0);
   if (forced_q > 0) { c.mfma_min_qlen = forced_q; c.mfma_min_work = 0x7fffffff; }
-  c.tile_tokens = 64;
+  c.tile_tokens = c.flat_heads ? 256 / c.flat_heads : 64;
   // LDS ring slots per wave of the row kernel.  (8-bit codes: a slot is half the size; two and
   // four slots measured the same, two keep the mixed launch available.)
   c.row_nbuf = env_int("DSV_ROW_NBUF", 2);
@@ -527,7 +537,7 @@ constexpr int kMergeChunk = 64;
 // TILES = false: blockIdx.x is a row of the row path.  TILES = true: blockIdx.x / 64 is a cut
 // q-tile of the MFMA path and blockIdx.x % 64 the query token in it.
 template <int D, bool TILES>
-__global__ __launch_bounds__(256) void merge_kernel(AttnArgs a, WorkLists w) {
+__global__ __launch_bounds__(256) void merge_kernel(AttnArgs a, WorkLists w, int tile_q) {
   constexpr int kThreadsPerHead = D / 4;
   constexpr int kHeadsPerBlock = 256 / kThreadsPerHead;
   __shared__ float s_m[kHeadsPerBlock][kMergeChunk];
@@ -536,6 +546,7 @@ __global__ __launch_bounds__(256) void merge_kernel(AttnArgs a, WorkLists w) {
   if constexpr (TILES) {
     const int4 rec = w.split_rec[blockIdx.x / 64];       // {seq, q0 of the tile, partitions, first partial}
     const int j = (int)blockIdx.x % 64;
+    if (j >= tile_q) return;                             // a q-tile holds tile_q <= 64 tokens (uniform)
     const int q_begin = a.q_offsets[rec.x];
     if (rec.y + j >= a.q_offsets[rec.x + 1] - q_begin) return;   // ragged last tile (uniform)
     np = rec.z;
@@ -662,19 +673,20 @@ int launch_stage(const AttnArgs& a, const WorkLists& w, const PlanCounts& n, hip
   return launch_status();
 }
 
-int launch_merge(const AttnArgs& a, const WorkLists& w, const PlanCounts& n, hipStream_t stream) {
+int launch_merge(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, const PlanCounts& n,
+                 hipStream_t stream) {
   const unsigned gy = (unsigned)ceil_div(a.Hq, a.D == 128 ? 8 : 16);
   if (n.split_items) {
     dim3 grid((unsigned)n.rows, gy);
-    if (a.D == 128) hipLaunchKernelGGL((merge_kernel<128, false>), grid, dim3(256), 0, stream, a, w);
-    else hipLaunchKernelGGL((merge_kernel<64, false>), grid, dim3(256), 0, stream, a, w);
+    if (a.D == 128) hipLaunchKernelGGL((merge_kernel<128, false>), grid, dim3(256), 0, stream, a, w, cfg.tile_tokens);
+    else hipLaunchKernelGGL((merge_kernel<64, false>), grid, dim3(256), 0, stream, a, w, cfg.tile_tokens);
     if (launch_status()) return DSV_E_LAUNCH;
   }
   if (n.split_qtiles) {
     if (n.split_qtiles * 64 > 0x7fffffffLL) return DSV_E_UNSUPPORTED;
     dim3 grid((unsigned)(n.split_qtiles * 64), gy);
-    if (a.D == 128) hipLaunchKernelGGL((merge_kernel<128, true>), grid, dim3(256), 0, stream, a, w);
-    else hipLaunchKernelGGL((merge_kernel<64, true>), grid, dim3(256), 0, stream, a, w);
+    if (a.D == 128) hipLaunchKernelGGL((merge_kernel<128, true>), grid, dim3(256), 0, stream, a, w, cfg.tile_tokens);
+    else hipLaunchKernelGGL((merge_kernel<64, true>), grid, dim3(256), 0, stream, a, w, cfg.tile_tokens);
     if (launch_status()) return DSV_E_LAUNCH;
   }
   return DSV_OK;
@@ -709,6 +721,7 @@ struct PlanStamp {
   const void *workspace, *block_tables, *q_offsets, *ctx_lens;
   int32_t num_seqs, Hq, Hkv, D, kv8, max_blocks;
   int32_t part_tokens, mfma_min_qlen, mfma_min_work, tile_tokens, tile_part_tiles, num_cus;
+  int32_t flat_heads, head_groups;
 };
 static_assert(sizeof(PlanStamp) <= sizeof(dsv_attn_plan), "dsv_attn_plan too small");
 constexpr uint64_t kPlanMagic = 0x6473765f706c616eull;
@@ -732,6 +745,7 @@ PlanStamp make_stamp(const PlanConfig& c, bool kv8, const void* workspace, const
   st.workspace = workspace; st.block_tables = block_tables; st.q_offsets = q_offsets; st.ctx_lens = ctx_lens;
   st.num_seqs = S; st.Hq = Hq; st.Hkv = Hkv; st.D = D; st.kv8 = kv8 ? 1 : 0; st.max_blocks = max_blocks;
   st.part_tokens = c.part_tokens; st.mfma_min_qlen = c.mfma_min_qlen; st.mfma_min_work = c.mfma_min_work;
+  st.flat_heads = c.flat_heads; st.head_groups = c.head_groups;
   st.tile_tokens = c.tile_tokens; st.tile_part_tiles = c.tile_part_tiles; st.num_cus = c.num_cus;
   return st;
 }
@@ -855,7 +869,7 @@ int run_attention(Phase phase, dsv_attn_plan* plan, bool kv8, float k_scale, flo
   }
   if (n.split_items || n.split_qtiles) {
     EventScope ev(DSV_KERNEL_MERGE, stream);
-    if ((rc = launch_merge(a, w, n, stream))) return rc;
+    if ((rc = launch_merge(a, w, cfg, n, stream))) return rc;
   }
   return DSV_OK;
 }

@@ -21,7 +21,10 @@ struct PlanConfig {
   int32_t part_tokens;     // multiple of 16
   int32_t mfma_min_qlen;   // spans with q_len >= this go to the MFMA kernel
   int32_t mfma_min_work;   // ... and so do shorter spans of 2+ tokens with q_len * ctx_len >= this
-  int32_t tile_tokens;     // query tokens per MFMA tile
+  int32_t tile_tokens;     // query tokens per MFMA work item
+  int32_t flat_heads;      // 0: a work item is 64 tokens x 4 query heads; h > 0: its 256 rows are
+                           // the (token, head) pairs of tile_tokens = 256 / h tokens and h heads
+  int32_t head_groups;     // work items per (query tile, KV head)
   int32_t row_nbuf;        // LDS ring slots (blocks) per wave of the row kernel: 2, 3, 4, 6 or 8
   int32_t num_cus;         // compute units of the device (sizes the persistent grid)
   int32_t tile_part_tiles; // 0: query tiles are never cut along the context; else a query tile
@@ -92,7 +95,8 @@ struct AttnArgs {
 
 int launch_rows(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg,
                 const PlanCounts& n, hipStream_t stream);
-int launch_merge(const AttnArgs& a, const WorkLists& w, const PlanCounts& n, hipStream_t stream);
+int launch_merge(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, const PlanCounts& n,
+                 hipStream_t stream);
 // Widens the 8-bit contexts of the MFMA path's segments into the staged bf16 blocks.
 int launch_stage(const AttnArgs& a, const WorkLists& w, const PlanCounts& n, hipStream_t stream);
 int launch_prefill_tiles(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg,

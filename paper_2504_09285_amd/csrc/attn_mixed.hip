@@ -41,7 +41,7 @@ __global__ __launch_bounds__(512, 2) void mixed_kernel(prefill_impl::TilesParams
     const uint32_t wg = t0 * kGroup + lane_in_group;
     if (wg >= mp.tile_wgs) return;                               // uniform for the workgroup
     int bx, bz;
-    prefill_impl::tile_work_item(wg, tp.a.Hkv, tp.G, bx, bz);
+    prefill_impl::tile_work_item(wg, tp.a.Hkv, tp.head_groups, bx, bz);
     prefill_impl::prefill_tiles_body<D>(tp, bx, bz, smem);
   } else {
     const uint32_t wg = (g - t0) * kGroup + lane_in_group;
@@ -73,7 +73,7 @@ int launch_mixed_t(const prefill_impl::TilesParams& tp, const rows_impl::RowsPar
 }  // namespace
 
 bool mixed_launch_supported(const AttnArgs& a, const PlanConfig& cfg, const PlanCounts& n) {
-  return n.tiles > 0 && n.items > 0 && cfg.row_nbuf == 2 && cfg.tile_tokens == prefill_impl::kTileQ &&
+  return n.tiles > 0 && n.items > 0 && cfg.row_nbuf == 2 && cfg.tile_tokens >= 32 && cfg.tile_tokens <= prefill_impl::kTileQ &&
          cfg.part_tokens <= 64 * kBlockSize && prefill_impl::kThreads == 512 && (a.D == 128 || a.D == 64);
 }
 
@@ -81,13 +81,13 @@ int launch_mixed(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, c
                  hipStream_t stream) {
   if (!mixed_launch_supported(a, cfg, n)) return DSV_E_UNSUPPORTED;
   const int G = a.Hq / a.Hkv;
-  const prefill_impl::TilesParams tp = prefill_impl::make_tiles_params(a, w, n);
+  const prefill_impl::TilesParams tp = prefill_impl::make_tiles_params(a, w, cfg, n);
   rows_impl::RowsParams rp{a, w, cfg.part_tokens, G, 1};
   int waves = 1;
   while (waves < a.Hkv && waves < 8) waves <<= 1;
   MixParams mp;
   mp.tiles_x = (uint32_t)(n.tiles * a.Hkv);
-  const int64_t tile_wgs = (int64_t)mp.tiles_x * ceil_div(G, 4);
+  const int64_t tile_wgs = (int64_t)mp.tiles_x * cfg.head_groups;
   mp.rows_x = (uint32_t)n.items;
   mp.rows_y = (uint32_t)ceil_div(a.Hkv, waves);
   rp.gy = (int32_t)mp.rows_y;

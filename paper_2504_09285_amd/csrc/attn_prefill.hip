@@ -9,7 +9,7 @@ template <int D>
 __global__ __launch_bounds__(kThreads, kThreads / 256) void prefill_tiles_kernel(TilesParams prm) {
   extern __shared__ __align__(16) unsigned char smem[];
   int bx, bz;
-  tile_work_item(blockIdx.x, prm.a.Hkv, prm.G, bx, bz);
+  tile_work_item(blockIdx.x, prm.a.Hkv, prm.head_groups, bx, bz);
   prefill_tiles_body<D>(prm, bx, bz, smem);
 }
 
@@ -36,9 +36,9 @@ int launch_t(const TilesParams& prm, dim3 grid, hipStream_t stream) {
 
 int launch_prefill_tiles(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg,
                          const PlanCounts& n, hipStream_t stream) {
-  if (cfg.tile_tokens != kTileQ) return DSV_E_UNSUPPORTED;
-  const TilesParams prm = make_tiles_params(a, w, n);
-  const int64_t wgs = n.tiles * a.Hkv * ceil_div(prm.G, 4);
+  if (cfg.tile_tokens < 32 || cfg.tile_tokens > kTileQ) return DSV_E_UNSUPPORTED;
+  const TilesParams prm = make_tiles_params(a, w, cfg, n);
+  const int64_t wgs = n.tiles * a.Hkv * cfg.head_groups;
   if (wgs > 0x7fffffffLL) return DSV_E_UNSUPPORTED;
   dim3 grid((unsigned)wgs);
   if (a.D == 128) return launch_t<128>(prm, grid, stream);

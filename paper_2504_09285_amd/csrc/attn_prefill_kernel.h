@@ -79,12 +79,16 @@ struct TilesParams {
   const int32_t* stage_rows;   // null, or [num_seqs]: row of a.block_tables that serves a segment
                                // (a cache of 8-bit codes is attended through a bf16 copy of the
                                // spans' contexts with a table of its own)
+  int32_t tile_q;              // query tokens per work item (64, or 256 / flat_heads)
+  int32_t flat_heads;          // see PlanConfig
+  int32_t head_groups;
 };
 
 // Parameters of a launch over the tile list.  A cache of 8-bit codes is attended through the
 // staged bf16 copy of the spans' contexts and its own block table.
-inline TilesParams make_tiles_params(const AttnArgs& a, const WorkLists& w, const PlanCounts& n) {
-  TilesParams prm{a, w, (int32_t)n.tiles, a.Hq / a.Hkv, nullptr};
+inline TilesParams make_tiles_params(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg,
+                                     const PlanCounts& n) {
+  TilesParams prm{a, w, (int32_t)n.tiles, a.Hq / a.Hkv, nullptr, cfg.tile_tokens, cfg.flat_heads, cfg.head_groups};
   if (a.kv8) {
     prm.a.k_pool = w.stage_k;
     prm.a.v_pool = w.stage_v;
@@ -208,12 +212,12 @@ __device__ __forceinline__ float other_half_sum(float x) {
 }
 
 // Work item of the wg-th prefill workgroup.  The tile list is sorted heaviest first and
-// workgroups are dispatched in index order, so the groups of four query heads of one (tile, KV
+// workgroups are dispatched in index order, so the groups of query heads of one (tile, KV
 // head) follow each other (all head groups of the heavy tiles start before any light tile),
 // while the KV head stays the fastest index: with eight KV heads, eight consecutive workgroups
 // go to the eight XCDs and KV head k always lands on XCD k.
-__device__ __forceinline__ void tile_work_item(uint32_t wg, int Hkv, int G, int& bx, int& bz) {
-  const uint32_t nbz = (uint32_t)(G + 3) / 4;
+__device__ __forceinline__ void tile_work_item(uint32_t wg, int Hkv, int head_groups, int& bx, int& bz) {
+  const uint32_t nbz = (uint32_t)head_groups;
   const uint32_t kvh = wg % (uint32_t)Hkv, r = wg / (uint32_t)Hkv;
   bz = (int)(r % nbz);
   bx = (int)((r / nbz) * (uint32_t)Hkv + kvh);
@@ -242,6 +246,14 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
   const bool few_heads = prm.G - bz * 4 <= 2;
   const int tg = few_heads ? wave % 2 : wave / kHeadWaves;          // which 32 query tokens of the tile
   const int hp = few_heads ? wave / 2 : wave % kHeadWaves;          // which query head of the group of four
+  // Flat rows (head groups that are not four heads): row r = 32 * wave + jrow of the work item is
+  // the pair (token j0 + r / gh, head bz * gh + r % gh) of a group of gh heads; rows
+  // tile_q * gh .. 255 do not exist.  Everything below that is per query row (its token's
+  // position, its head's rows of Q and of the output) is per lane already.
+  const int gh = prm.flat_heads;
+  const bool flat = gh > 0;
+  const int row_in_item = 32 * wave + jrow;
+  const int wave_first_tok = flat ? (32 * wave) / gh : 32 * tg;     // first query token of the wave, from j0
 
   // Workgroups are dispatched in index order (bx) and dealt round-robin to the eight XCDs: the
   // KV head is the fastest index, so the heaviest tiles (the list is sorted) of every head start
@@ -257,7 +269,7 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
   const int table_row = prm.stage_rows ? prm.stage_rows[seq] : seq;
   const int32_t* table = a.block_tables + (int64_t)table_row * a.max_blocks;
   const int nblk = (ctx + kBlockSize - 1) / kBlockSize;
-  const int kv_end = min(ctx, prefix + j0 + kTileQ);          // exclusive: last visible token + 1
+  const int kv_end = min(ctx, prefix + j0 + prm.tile_q);      // exclusive: last visible token + 1
   // The work item covers KV tiles [t_first, t_first + n_tiles) of the n_kv the query tile
   // visits: all of them, or one of several nearly equal partitions whose results a merge kernel
   // combines.  Tile and sub-tile indices below are relative to t_first.
@@ -271,17 +283,18 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
   const int NS = 2 * n_tiles;                                  // 32-token sub-tiles
 
   // Query fragments: B operand of S^T = K Q^T; lane (jrow, hh) holds dims 16*ks + 8*hh .. +8.
-  const int jq = j0 + 32 * tg + jrow;    // new-token index of this lane's query row
+  const int jq = flat ? j0 + row_in_item / gh : j0 + 32 * tg + jrow;    // new-token index of this lane's query row
   const int p_j = prefix + jq - pos0;    // its position, counted from the partition's first token
   // (wave-uniform) Does any of this wave's 32 query rows, for any of its heads, exist?
-  const bool wave_has_rows = j0 + 32 * tg < q_len && bz * 4 + hp * NH < prm.G;
+  const bool wave_has_rows = flat ? (j0 + wave_first_tok < q_len && 32 * wave < prm.tile_q * gh)
+                                  : (j0 + 32 * tg < q_len && bz * 4 + hp * NH < prm.G);
   bool head_ok[NH];
   int head[NH];
   uint4 qf[NH][KS];
 #pragma unroll
   for (int c = 0; c < NH; ++c) {
-    const int hsub = bz * 4 + hp * NH + c;
-    head_ok[c] = hsub < prm.G && jq < q_len;
+    const int hsub = flat ? bz * gh + row_in_item % gh : bz * 4 + hp * NH + c;
+    head_ok[c] = hsub < prm.G && jq < q_len && (!flat || row_in_item < prm.tile_q * gh);
     head[c] = kvh * prm.G + (hsub < prm.G ? hsub : 0);
     const int64_t off = ((int64_t)(q0 + (jq < q_len ? jq : 0)) * a.Hq + head[c]) * D + hh * 8;
 #pragma unroll
@@ -530,7 +543,7 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
     // The two waves of a SIMD (the two halves of the query tile, same head) take turns at the
     // higher issue priority, stage by stage: left to the default arbitration the older wave is
     // served first throughout and then idles at the tile barrier while the other finishes.
-    if (tg) __builtin_amdgcn_s_setprio(CUR); else __builtin_amdgcn_s_setprio(CUR ^ 1);
+    if (flat ? wave / 4 : tg) __builtin_amdgcn_s_setprio(CUR); else __builtin_amdgcn_s_setprio(CUR ^ 1);
     if constexpr (with_pv) {
       issue_v(s - 1, std::integral_constant<int, CUR ^ 1>{}, std::integral_constant<int, 0>{});
       lds_wait<2 * DB>();                // the K fragments (older than these 2*DB reads) are in
@@ -540,7 +553,7 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
     ready_k();
     // Only sub-tiles that reach past some row's own position need the causal mask (a
     // wave-uniform branch, so the unmasked path pays one scalar compare).
-    if (s * 32 + 31 > prefix + j0 + 32 * tg - pos0) {
+    if (s * 32 + 31 > prefix + j0 + wave_first_tok - pos0) {
 #pragma unroll
       for (int c = 0; c < NH; ++c)
 #pragma unroll

@@ -512,3 +512,23 @@ def test_deeper_lds_rings_of_the_row_kernel(monkeypatch, nbuf):
         ref = oracle.attn_mixed_batch(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens, b.scale)
         assert np.isfinite(got).all()
         assert np.abs(got - ref).max() <= TOL
+
+
+@pytest.mark.parametrize("G,Hkv,D,cut", [(5, 8, 128, None), (5, 2, 64, "2"), (6, 1, 128, None), (7, 2, 128, "3"),
+                                         (9, 1, 64, None), (10, 2, 128, "1"), (3, 3, 128, None), (13, 1, 128, None)])
+def test_head_groups_that_are_not_four_heads(monkeypatch, G, Hkv, D, cut):
+    """Query heads per KV head that do not fill groups of four (the paper's Qwen-2.5 models have
+    40 query and 8 KV heads): a work item of the MFMA path then takes (token, head) pairs of a
+    group of up to eight heads for fewer tokens (51 x 5, 42 x 6, 36 x 7, 32 x 8), so query tiles
+    are not 64 tokens long.  Spans shorter and longer than a tile, with and without prefix,
+    ragged ends, decodes in between; with and without query tiles cut along the context."""
+    from gpu_harness import run_attention
+    if cut is not None:
+        monkeypatch.setenv("DSV_TILE_PART_TILES", cut)
+    segs = [(200, 200), (1, 300), (51, 51), (52, 700), (36, 36), (17, 17), (130, 1000), (1, 40), (32, 95), (64, 64)]
+    b = gen.make_batch("flat%d_%d" % (G, D), 90 + G, G * Hkv, Hkv, D, segs)
+    got = run_attention(b)
+    ref = oracle.attn_mixed_batch(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens, b.scale)
+    assert np.isfinite(got).all()
+    err = np.abs(got - ref)
+    assert err.max() <= TOL, (err.max(), np.unravel_index(err.argmax(), err.shape))
