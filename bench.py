@@ -578,6 +578,11 @@ def main():
             extras["c3_prefill_heavy"] = {k: r3[k] for k in ("ms_per_step", "tokens_per_s", "mixed_launch_ms", "ms_per_step_kernels_apart", "kernel_ms", "prefill", "decode") if k in r3}
             del d3
         keys = ("ms_per_step", "tokens_per_s", "mixed_launch_ms", "ms_per_step_kernels_apart", "kernel_ms", "prefill", "decode")
+        # config 3's segments with the head counts of the models the paper serves (Qwen-2.5-14B/32B:
+        # 40 query heads on 8 KV heads, five per KV head)
+        rq, dq = bench_attention(gen.config3_heads(40, 8, threads=threads), 30, 5, hev)
+        extras["c3_segments_40q_8kv_heads"] = {k: rq[k] for k in keys if k in rq}
+        del dq
         r1, d1 = bench_attention(gen.config1()[0], 20, 3, hev)          # the tiny case: launch-bound
         extras["c1_tiny"] = {k: r1[k] for k in keys if k in r1}
         del d1

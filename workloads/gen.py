@@ -299,6 +299,18 @@ def config3(shrink: int = 1, threads: int = 8) -> AttnBatch:
                       meta={"shrink": shrink})
 
 
+def config3_heads(num_q_heads: int, num_kv_heads: int, threads: int = 8) -> AttnBatch:
+    """Config 3's segments (same seed) with another head geometry, e.g. 40 query and 8 KV heads:
+    Qwen-2.5-14B/32B, the models the paper serves, whose five query heads per KV head do not fill
+    groups of four."""
+    seed = seed_for(3)
+    segs = [(2048, 2048 + p) for p in (0, 512, 1024, 4096)]
+    ctx = lognormal_lengths(seed, 16, 2048.0, 0.8, 64, 16384)
+    segs += [(1, int(c)) for c in ctx]
+    return make_batch("c3_prefill_heavy_%dq_%dkv" % (num_q_heads, num_kv_heads), seed, num_q_heads,
+                      num_kv_heads, 128, segs, threads=threads)
+
+
 @dataclass
 class SplitRequest:
     """Config 4's split prompt: request tokens live under table row 0 (segment A's table);
