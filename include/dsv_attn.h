@@ -39,7 +39,7 @@ extern "C" {
 
 #define DSV_OK              0
 #define DSV_E_INVALID      -1   /* null pointer, bad length, chunk outside its table, ...   */
-#define DSV_E_UNSUPPORTED  -2   /* head_dim not 64/128, block_size not 16, group too large   */
+#define DSV_E_UNSUPPORTED  -2   /* head_dim not 64/128, block_size not 16, counts past 2^31 */
 #define DSV_E_WORKSPACE    -3   /* workspace smaller than attn_mixed_batch_workspace_bytes() */
 #define DSV_E_LAUNCH       -4   /* HIP reported an error while enqueueing                    */
 
