@@ -271,6 +271,35 @@ int attn_mixed_batch_fp8kv_planned(const dsv_attn_plan* plan, const void* q, voi
                                    size_t workspace_bytes, void* hip_stream);
 
 /*
+ * ---- attn_mixed_batch without a workspace argument -------------------------------------------
+ * For callers that cannot allocate device memory or bring a workspace: code that runs under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same computation and
+ * the same kernels as attn_mixed_batch (same arguments, result and error codes, minus the two
+ * workspace arguments); the work lists and split-context partials live in a fixed array of
+ * DSV_STATIC_SCRATCH_BYTES in device memory that the library itself owns (part of its code object:
+ * every GPU the library is used on holds one copy until the process ends).  The call allocates
+ * nothing, frees nothing and calls no allocating routine.
+ *   - A batch whose attn_mixed_batch_workspace_bytes() exceeds DSV_STATIC_SCRATCH_BYTES is
+ *     refused with DSV_E_WORKSPACE before anything is enqueued (64 MiB hold each of the five
+ *     benchmark configurations; the largest, 64 decodes on 16K-128K contexts, needs 56 MiB).
+ *   - All calls on one GPU share that GPU's array, and the array keeps the previous call's
+ *     contents (nothing in it needs to start at zero: every call rewrites what it reads).  Calls
+ *     that overlap in time on one GPU - two streams, two host threads - race on it and give
+ *     undefined results; calls on one stream, or ordered by the caller, are safe.
+ *   - The first call on a device looks the array's address up (no allocation); make it outside
+ *     stream capture, as for every entry point.
+ * attn_mixed_batch_static_max_bytes() returns DSV_STATIC_SCRATCH_BYTES as built.
+ */
+#define DSV_STATIC_SCRATCH_BYTES (64u << 20)
+size_t attn_mixed_batch_static_max_bytes(void);
+int attn_mixed_batch_static(const void* q, void* out, const dsv_kv_pool* pool, int32_t layer,
+                            const int32_t* block_tables, int32_t max_blocks_per_seq,
+                            const int32_t* q_offsets, const int32_t* ctx_lens,
+                            const int32_t* q_offsets_host, const int32_t* ctx_lens_host,
+                            int32_t num_seqs, int32_t num_q_heads, float softmax_scale,
+                            int32_t out_dtype, void* hip_stream);
+
+/*
  * Profiling aid for benchmarks (not needed for correct use).  Until cleared with NULLs, every
  * later attn_mixed_batch call made by the calling host thread records `start_event` on its
  * stream immediately before, and `stop_event` immediately after, the launch of the named

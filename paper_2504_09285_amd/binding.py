@@ -50,6 +50,7 @@ EXPORTS = ("attn_mixed_batch_workspace_bytes", "attn_mixed_batch", "kv_pack_chun
            "kv_unpack_chunks", "kv_append", "attn_mixed_batch_fp8kv_workspace_bytes",
            "attn_mixed_batch_fp8kv", "kv_append_fp8", "kv_pack_chunks_fp8", "kv_unpack_chunks_fp8",
            "attn_mixed_batch_plan", "attn_mixed_batch_planned", "attn_mixed_batch_fp8kv_planned",
+           "attn_mixed_batch_static", "attn_mixed_batch_static_max_bytes",
            "dsv_profile_events", "dsv_build_info")
 KERNEL_PLAN, KERNEL_ROWS, KERNEL_TILES, KERNEL_MERGE, KERNEL_MIXED, KERNEL_STAGE = 0, 1, 2, 3, 4, 5
 
@@ -109,6 +110,11 @@ def load_library():
     lib.kv_pack_chunks_fp8.argtypes = lib.kv_pack_chunks.argtypes
     lib.kv_unpack_chunks_fp8.restype = C.c_int
     lib.kv_unpack_chunks_fp8.argtypes = lib.kv_unpack_chunks.argtypes
+    lib.attn_mixed_batch_static.restype = C.c_int
+    lib.attn_mixed_batch_static.argtypes = [vp, vp, C.POINTER(_Pool), C.c_int32, vp, C.c_int32, vp, vp,
+                                            i32p, i32p, C.c_int32, C.c_int32, C.c_float, C.c_int32, vp]
+    lib.attn_mixed_batch_static_max_bytes.restype = C.c_size_t
+    lib.attn_mixed_batch_static_max_bytes.argtypes = []
     lib.dsv_profile_events.restype = C.c_int
     lib.dsv_profile_events.argtypes = [C.c_int32, vp, vp]
     lib.dsv_build_info.restype = C.c_char_p
@@ -204,6 +210,29 @@ def attn_mixed_batch(q, out, pool: KVPool, layer, block_tables, q_offsets, ctx_l
         workspace.data_ptr(), int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
     if rc:
         raise DsvError("attn_mixed_batch", rc)
+
+
+def attn_mixed_batch_static_max_bytes() -> int:
+    return int(load_library().attn_mixed_batch_static_max_bytes())
+
+
+def attn_mixed_batch_static(q, out, pool: KVPool, layer, block_tables, q_offsets, ctx_lens,
+                            q_offsets_host, ctx_lens_host, num_q_heads, softmax_scale, stream=None) -> None:
+    """See ``attn_mixed_batch_static`` in include/dsv_attn.h: no workspace argument, nothing allocated."""
+    import torch
+    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
+    out_dtype = DSV_OUT_F32 if out.dtype == torch.float32 else DSV_OUT_BF16
+    assert out.dtype in (torch.float32, torch.bfloat16)
+    assert block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous()
+    assert q_offsets.dtype == torch.int32 and ctx_lens.dtype == torch.int32
+    assert q.is_contiguous() and out.is_contiguous() and q.element_size() == 2
+    assert tuple(q.shape) == tuple(out.shape)
+    rc = load_library().attn_mixed_batch_static(
+        q.data_ptr(), out.data_ptr(), pool.c, int(layer), block_tables.data_ptr(),
+        int(block_tables.shape[1]), q_offsets.data_ptr(), ctx_lens.data_ptr(), _i32_ptr(qo), _i32_ptr(cl),
+        int(cl.shape[0]), int(num_q_heads), float(softmax_scale), out_dtype, _stream_ptr(stream))
+    if rc:
+        raise DsvError("attn_mixed_batch_static", rc)
 
 
 def attn_mixed_batch_plan(block_tables, q_offsets, ctx_lens, q_offsets_host, ctx_lens_host,

@@ -7,6 +7,7 @@
 // a small planning kernel on the same stream, so a call never synchronises and never copies
 // from host memory.
 #include <math.h>
+#include <atomic>
 #include <stdlib.h>
 #include <string.h>
 
@@ -962,6 +963,65 @@ extern "C" int attn_mixed_batch_fp8kv_planned(const dsv_attn_plan* plan, const v
                        pool, layer, block_tables, max_blocks_per_seq, q_offsets, ctx_lens,
                        q_offsets_host, ctx_lens_host, num_seqs, num_q_heads, softmax_scale, out_dtype,
                        workspace, workspace_bytes, hip_stream);
+}
+
+// ---- the entry point that allocates nothing --------------------------------------------------
+// attn_mixed_batch for callers that cannot bring a workspace: the work lists and split-context
+// partials live in a fixed array in device memory that belongs to the library.  Each device the
+// library's code object is loaded on holds its own copy of the array at its own address; in host
+// code the array's name is only a handle for hipGetSymbolAddress, never a device pointer.
+namespace {
+
+constexpr size_t kStaticScratchBytes = (size_t)DSV_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];      // device address of `scratch`, per device
+
+// Device address of the scratch array on the current device (looked up once per device).
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return DSV_E_LAUNCH; }
+  if (dev < 0 || dev >= kMaxDevices) return DSV_E_UNSUPPORTED;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return DSV_E_LAUNCH;
+    }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // every thread finds the same address
+  }
+  *out = p;
+  return DSV_OK;
+}
+
+}  // namespace
+
+extern "C" size_t attn_mixed_batch_static_max_bytes(void) { return kStaticScratchBytes; }
+
+extern "C" int attn_mixed_batch_static(const void* q, void* out, const dsv_kv_pool* pool, int32_t layer,
+                                       const int32_t* block_tables, int32_t max_blocks_per_seq,
+                                       const int32_t* q_offsets, const int32_t* ctx_lens,
+                                       const int32_t* q_offsets_host, const int32_t* ctx_lens_host,
+                                       int32_t num_seqs, int32_t num_q_heads, float softmax_scale,
+                                       int32_t out_dtype, void* hip_stream) {
+  int rc = check_pool(pool);
+  if (rc) return rc;
+  if (num_seqs < 0) return DSV_E_INVALID;
+  if (num_seqs == 0) return DSV_OK;
+  if (num_q_heads < 1 || num_q_heads % pool->num_kv_heads) return DSV_E_INVALID;
+  // The batch must fit the fixed array: refused here, before anything is enqueued.
+  const size_t need = workspace_bytes_for(false, num_seqs, q_offsets_host, ctx_lens_host, num_q_heads,
+                                          pool->num_kv_heads, pool->head_dim);
+  if (need == 0) return DSV_E_INVALID;
+  if (need > kStaticScratchBytes) return DSV_E_WORKSPACE;
+  void* ptr = nullptr;
+  if ((rc = static_scratch(&ptr))) return rc;
+  // Nothing in the array has to start at zero: the plan kernel writes every list, the zero line
+  // included, and the attention kernels write every partial the merge kernel reads.
+  return run_attention(Phase::kPlanAndRun, nullptr, false, 1.0f, 1.0f, q, out, pool, layer, block_tables,
+                       max_blocks_per_seq, q_offsets, ctx_lens, q_offsets_host, ctx_lens_host, num_seqs,
+                       num_q_heads, softmax_scale, out_dtype, ptr, kStaticScratchBytes, hip_stream);
 }
 
 extern "C" int dsv_profile_events(int32_t kernel_id, void* start_event, void* stop_event) {

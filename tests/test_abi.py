@@ -173,3 +173,25 @@ def test_loading_the_library_first_leaves_one_hip_runtime_in_the_process():
             "assert len(paths) == 1, paths; print('one runtime')")
     r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, cwd=ROOT)
     assert r.returncode == 0 and "one runtime" in r.stdout, r.stderr[-2000:]
+
+
+def test_static_entry_point_refuses_oversized_and_invalid_batches_on_the_host(lib):
+    """attn_mixed_batch_static checks the batch against its fixed array before any GPU call, so the
+    refusal needs no GPU: too large -> DSV_E_WORKSPACE, invalid -> DSV_E_INVALID, empty -> no-op."""
+    assert dsv.attn_mixed_batch_static_max_bytes() == 64 << 20
+    pool = binding._Pool(0x1000, 0x2000, 0, 1, 4, 16, 8, 128)
+    n = 96
+    qo = np.arange(n + 1, dtype=np.int32)
+    cl = np.full(n, 32768, np.int32)
+    i32p = C.POINTER(C.c_int32)
+
+    def call(qo, cl, n, Hq=64):
+        return lib.attn_mixed_batch_static(0x3000, 0x4000, C.byref(pool), 0, 0x5000, 4096, 0x6000, 0x7000,
+                                           qo.ctypes.data_as(i32p), cl.ctypes.data_as(i32p), n, Hq, 0.1, 0, None)
+    assert dsv.attn_mixed_batch_workspace_bytes(qo, cl, 64, 8, 128) > 64 << 20
+    assert call(qo, cl, n) == -3
+    assert call(qo, cl, 0) == 0
+    assert call(qo, cl, n, Hq=60) == -1
+    bad = cl.copy()
+    bad[3] = 0
+    assert call(qo, bad, n) == -1
