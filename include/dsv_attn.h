@@ -5,7 +5,11 @@
  * instances.
  *
  * Conventions for every entry point
- *   - Plain C, no exceptions, no global state that outlives a call, thread-compatible.
+ *   - Plain C, no exceptions, thread-compatible.  State the library keeps between calls, all
+ *     of it host-side and none of it derived from a caller's buffers: a per-process cache of the
+ *     device's compute-unit count, one flag per kernel saying that its dynamic-LDS limit has been
+ *     raised, the per-device address of the fixed array of attn_mixed_batch_static, and, per host
+ *     thread, the event handles set with dsv_profile_events (until cleared).
  *   - "device" pointers are HIP device memory on the current device; "host" pointers are
  *     ordinary host memory.  All buffers are caller-owned; the library allocates no device
  *     memory and keeps no pointer after the call returns.
@@ -16,8 +20,10 @@
  *     work lists are cleared by the library's own kernels), so it may be captured and
  *     replayed.  A replay reads every device buffer afresh; what the host derived from the
  *     host-side arrays (grid sizes, workspace layout) is frozen, so a graph is valid for
- *     batches with the same host-side arrays.  Make one call outside the capture first (the
- *     first call on a device configures the kernels).
+ *     batches with the same host-side arrays.  Make one call of the same entry point, with the
+ *     same head geometry and cache element size, outside the capture first: the first launch of
+ *     each kernel variant raises that kernel's dynamic-LDS limit (once, to the largest value any
+ *     batch can need), which is not a capturable operation.
  *   - A call that enqueues work first clears the calling thread's HIP last-error state
  *     (hipGetLastError), so that an error left by an earlier, unrelated HIP call is not
  *     reported as DSV_E_LAUNCH.
@@ -25,7 +31,8 @@
  *     GPU work: with DSV_E_INVALID, DSV_E_UNSUPPORTED or DSV_E_WORKSPACE nothing has been
  *     enqueued.  DSV_E_LAUNCH means HIP refused a launch part-way; outputs are then undefined.
  *   - bf16 = upper 16 bits of IEEE-754 binary32, stored as uint16.
- *   - Block-table entries are trusted (not range-checked against num_blocks).
+ *   - Block-table entries are trusted (not range-checked against num_blocks);
+ *     dsv_check_block_tables() checks a table on request.
  */
 #ifndef DSV_ATTN_H
 #define DSV_ATTN_H
@@ -80,9 +87,11 @@ typedef struct {
 } dsv_chunk_desc;
 
 /*
- * Bytes of device workspace attn_mixed_batch needs for this batch (split-context partial
- * results and work lists).  Arguments as in attn_mixed_batch.  Returns 0 if the batch is
- * invalid.
+ * Bytes of device workspace attn_mixed_batch needs for this batch: the work lists of the batch
+ * plan (paper section 4.2, Alg. 2: a batch is formed on the host before each iteration; its
+ * decode tokens and prefill spans become the kernels' work items) and the partial results of
+ * contexts split across workgroups.  Arguments as in attn_mixed_batch; host pointers only, no GPU
+ * call.  Returns 0 if the batch is invalid.
  */
 size_t attn_mixed_batch_workspace_bytes(int32_t num_seqs, const int32_t* q_offsets_host,
                                         const int32_t* ctx_lens_host, int32_t num_q_heads,
@@ -298,6 +307,28 @@ int attn_mixed_batch_static(const void* q, void* out, const dsv_kv_pool* pool, i
                             const int32_t* q_offsets_host, const int32_t* ctx_lens_host,
                             int32_t num_seqs, int32_t num_q_heads, float softmax_scale,
                             int32_t out_dtype, void* hip_stream);
+
+/*
+ * Opt-in check of block-table entries.  Every other entry point trusts the table (paper sections
+ * 2.1 and 4.3: KV lives in blocks, and the receiver of a hand-off chooses their placement): an
+ * entry outside [0, num_blocks) makes a kernel read or write outside the pool.  This call checks,
+ * on the device, the entries a batch or a hand-off will use: for row i the first
+ * ceil(tokens_per_seq[i] / 16) entries.  A row that needs more entries than max_blocks_per_seq,
+ * or has a negative token count, counts as one offence at its first entry.
+ *   block_tables    device, int32 [num_seqs][max_blocks_per_seq]
+ *   tokens_per_seq  device, int32 [num_seqs]: ctx_lens of attn_mixed_batch / kv_append, or the
+ *                   number of tokens a hand-off touches in each row
+ *   num_blocks      blocks in the pool (dsv_kv_pool.num_blocks)
+ *   result          device, int32[2], written by the call: [0] = number of offending entries
+ *                   (0: the table is safe to use), [1] = smallest flat index
+ *                   row * max_blocks_per_seq + column among them, 0x7fffffff if there is none
+ * Enqueues two small kernels on hip_stream and returns; the host reads `result` when it wants
+ * to (after synchronising with the stream).  No workspace, no allocation, capturable.
+ * num_seqs == 0 writes {0, 0x7fffffff}.  More than 65535 rows: DSV_E_UNSUPPORTED.
+ */
+int dsv_check_block_tables(const int32_t* block_tables, int32_t max_blocks_per_seq,
+                           const int32_t* tokens_per_seq, int32_t num_seqs, int32_t num_blocks,
+                           int32_t* result, void* hip_stream);
 
 /*
  * Profiling aid for benchmarks (not needed for correct use).  Until cleared with NULLs, every

@@ -19,6 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "oracle.c")
 _SRCS = [_SRC, os.path.join(_HERE, "oracle_fp8.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
+_SAN_LIB = os.path.join(_HERE, "liboracle_san.so")
 _lock = threading.Lock()
 _lib = None
 
@@ -36,6 +37,20 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized() -> str:
+    """The same two sources with AddressSanitizer and UndefinedBehaviorSanitizer (host code only),
+    into liboracle_san.so.  A process that loads it must have been started with the sanitizer
+    runtime preloaded: ``tests/test_oracle_sanitized.py`` runs the pin tests that way, in a child
+    process with ORACLE_LIB pointing here."""
+    tmp = _SAN_LIB + ".tmp%d" % os.getpid()
+    subprocess.check_call(
+        ["gcc", "-O1", "-g", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
+         "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer",
+         "-o", tmp] + _SRCS + ["-lm"])
+    os.replace(tmp, _SAN_LIB)
+    return _SAN_LIB
+
+
 _i32p = np.ctypeslib.ndpointer(np.int32, flags="C_CONTIGUOUS")
 _i64p = np.ctypeslib.ndpointer(np.int64, flags="C_CONTIGUOUS")
 _u16p = np.ctypeslib.ndpointer(np.uint16, flags="C_CONTIGUOUS")
@@ -49,7 +64,8 @@ def _load():
     global _lib
     with _lock:
         if _lib is None:
-            lib = ctypes.CDLL(build())
+            # ORACLE_LIB: a library built elsewhere from the same sources (the sanitizer build)
+            lib = ctypes.CDLL(os.environ.get("ORACLE_LIB") or build())
             attn_common = [_u16p, _u16p, _u16p, _i32p, _c.c_int32, _i32p, _i32p,
                            _c.c_int32, _c.c_int32, _c.c_int32, _c.c_int32, _c.c_int32, _c.c_double]
             lib.oracle_attn_mixed_batch.argtypes = attn_common + [_f64p]

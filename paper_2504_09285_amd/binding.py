@@ -51,7 +51,7 @@ EXPORTS = ("attn_mixed_batch_workspace_bytes", "attn_mixed_batch", "kv_pack_chun
            "attn_mixed_batch_fp8kv", "kv_append_fp8", "kv_pack_chunks_fp8", "kv_unpack_chunks_fp8",
            "attn_mixed_batch_plan", "attn_mixed_batch_planned", "attn_mixed_batch_fp8kv_planned",
            "attn_mixed_batch_static", "attn_mixed_batch_static_max_bytes",
-           "dsv_profile_events", "dsv_build_info")
+           "dsv_check_block_tables", "dsv_profile_events", "dsv_build_info")
 KERNEL_PLAN, KERNEL_ROWS, KERNEL_TILES, KERNEL_MERGE, KERNEL_MIXED, KERNEL_STAGE = 0, 1, 2, 3, 4, 5
 
 
@@ -115,6 +115,8 @@ def load_library():
                                             i32p, i32p, C.c_int32, C.c_int32, C.c_float, C.c_int32, vp]
     lib.attn_mixed_batch_static_max_bytes.restype = C.c_size_t
     lib.attn_mixed_batch_static_max_bytes.argtypes = []
+    lib.dsv_check_block_tables.restype = C.c_int
+    lib.dsv_check_block_tables.argtypes = [vp, C.c_int32, vp, C.c_int32, C.c_int32, vp, vp]
     lib.dsv_profile_events.restype = C.c_int
     lib.dsv_profile_events.argtypes = [C.c_int32, vp, vp]
     lib.dsv_build_info.restype = C.c_char_p
@@ -184,9 +186,76 @@ class ChunkDescs:
         self.dev = torch.from_numpy(raw).to(device)
 
 
+def _require(cond, what: str) -> None:
+    if not cond:
+        raise ValueError("dsv binding: " + what)
+
+
+def _nbytes(t) -> int:
+    return int(t.numel() * t.element_size())
+
+
+def _batch_lists(q_offsets_host, ctx_lens_host, block_tables, q_offsets, ctx_lens):
+    """Host lists as int32 arrays, checked against each other and against the device arrays: the C
+    ABI carries no lengths for these, so a mismatch would send a kernel outside a buffer."""
+    import torch
+    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
+    _require(qo.ndim == 1 and cl.ndim == 1 and qo.shape[0] == cl.shape[0] + 1,
+             "q_offsets_host needs one entry more than ctx_lens_host")
+    _require(block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous(),
+             "block_tables must be a contiguous int32 [num_seqs, max_blocks] tensor")
+    _require(block_tables.shape[0] >= cl.shape[0], "block_tables has fewer rows than the batch has segments")
+    _require(q_offsets.dtype == torch.int32 and q_offsets.is_contiguous() and q_offsets.numel() >= qo.shape[0],
+             "q_offsets (device) must be int32 with num_seqs + 1 entries")
+    _require(ctx_lens.dtype == torch.int32 and ctx_lens.is_contiguous() and ctx_lens.numel() >= cl.shape[0],
+             "ctx_lens (device) must be int32 with num_seqs entries")
+    return qo, cl
+
+
+def _attn_tensors(q, out, pool: "KVPool", num_q_heads, qo, elem_bytes):
+    import torch
+    _require(pool.elem_bytes == elem_bytes, "the pool's element size does not fit this entry point")
+    _require(out.dtype in (torch.float32, torch.bfloat16), "out must be float32 or bfloat16")
+    _require(q.is_contiguous() and out.is_contiguous() and q.element_size() == 2, "q must be contiguous bf16")
+    total_q = int(qo[-1]) - int(qo[0])               # (offsets that do not start at 0: the library refuses them)
+    want = (total_q, int(num_q_heads), pool.D)
+    _require(tuple(q.shape) == want, "q must have shape [total_q, num_q_heads, head_dim] = %r" % (want,))
+    _require(tuple(out.shape) == want, "out must have the shape of q")
+    return DSV_OUT_F32 if out.dtype == torch.float32 else DSV_OUT_BF16
+
+
+def _new_kv_tensors(k_new, v_new, pool: "KVPool", qo, elem_bytes):
+    _require(pool.elem_bytes == elem_bytes, "the pool's element size does not fit this entry point")
+    _require(k_new.is_contiguous() and v_new.is_contiguous() and k_new.element_size() == 2 and
+             v_new.element_size() == 2, "k_new / v_new must be contiguous bf16")
+    want = (int(qo[-1]) - int(qo[0]), pool.Hkv, pool.D)
+    _require(tuple(k_new.shape) == want and tuple(v_new.shape) == want,
+             "k_new / v_new must have shape [total_q, num_kv_heads, head_dim] = %r" % (want,))
+
+
+def _copy_tensors(pool: "KVPool", block_tables, descs: "ChunkDescs", chunk_buf, elem_bytes):
+    """Hand-off arguments: the table's dtype and row count, and that every chunk lies inside
+    chunk_buf (the C ABI has no buffer length)."""
+    import torch
+    _require(pool.elem_bytes == elem_bytes, "the pool's element size does not fit this entry point")
+    _require(block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous(),
+             "block_tables must be a contiguous int32 [rows, max_blocks] tensor")
+    _require(chunk_buf.is_contiguous(), "chunk_buf must be contiguous")
+    if descs.n:
+        h = descs.host
+        _require(int(h["seq"].min()) >= 0 and int(h["seq"].max()) < block_tables.shape[0],
+                 "a chunk names a row the block table does not have")
+        per_tok = 2 * pool.L * pool.Hkv * pool.D                       # elements per token of a chunk
+        end = (h["chunk_offset"] + h["num_tokens"].astype(np.int64) * per_tok) * elem_bytes
+        _require(int(h["chunk_offset"].min()) >= 0 and int(end.max()) <= _nbytes(chunk_buf),
+                 "a chunk reaches past the end of chunk_buf")
+        _require(_nbytes(descs.dev) >= descs.n * CHUNK_DTYPE.itemsize, "device copy of the descriptors too short")
+
+
 def attn_mixed_batch_workspace_bytes(q_offsets_host, ctx_lens_host, num_q_heads, num_kv_heads,
                                      head_dim) -> int:
     qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
+    _require(qo.shape[0] == cl.shape[0] + 1, "q_offsets_host needs one entry more than ctx_lens_host")
     return int(load_library().attn_mixed_batch_workspace_bytes(
         cl.shape[0], _i32_ptr(qo), _i32_ptr(cl), num_q_heads, num_kv_heads, head_dim))
 
@@ -195,19 +264,13 @@ def attn_mixed_batch(q, out, pool: KVPool, layer, block_tables, q_offsets, ctx_l
                      q_offsets_host, ctx_lens_host, num_q_heads, softmax_scale, workspace,
                      stream=None) -> None:
     """See ``attn_mixed_batch`` in include/dsv_attn.h.  ``out`` dtype selects fp32 or bf16."""
-    import torch
-    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
-    out_dtype = DSV_OUT_F32 if out.dtype == torch.float32 else DSV_OUT_BF16
-    assert out.dtype in (torch.float32, torch.bfloat16)
-    assert block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous()
-    assert q_offsets.dtype == torch.int32 and ctx_lens.dtype == torch.int32
-    assert q.is_contiguous() and out.is_contiguous() and q.element_size() == 2
-    assert tuple(q.shape) == tuple(out.shape)
+    qo, cl = _batch_lists(q_offsets_host, ctx_lens_host, block_tables, q_offsets, ctx_lens)
+    out_dtype = _attn_tensors(q, out, pool, num_q_heads, qo, 2)
     rc = load_library().attn_mixed_batch(
         q.data_ptr(), out.data_ptr(), pool.c, int(layer), block_tables.data_ptr(),
         int(block_tables.shape[1]), q_offsets.data_ptr(), ctx_lens.data_ptr(), _i32_ptr(qo), _i32_ptr(cl),
         int(cl.shape[0]), int(num_q_heads), float(softmax_scale), out_dtype,
-        workspace.data_ptr(), int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
+        workspace.data_ptr(), _nbytes(workspace), _stream_ptr(stream))
     if rc:
         raise DsvError("attn_mixed_batch", rc)
 
@@ -219,14 +282,8 @@ def attn_mixed_batch_static_max_bytes() -> int:
 def attn_mixed_batch_static(q, out, pool: KVPool, layer, block_tables, q_offsets, ctx_lens,
                             q_offsets_host, ctx_lens_host, num_q_heads, softmax_scale, stream=None) -> None:
     """See ``attn_mixed_batch_static`` in include/dsv_attn.h: no workspace argument, nothing allocated."""
-    import torch
-    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
-    out_dtype = DSV_OUT_F32 if out.dtype == torch.float32 else DSV_OUT_BF16
-    assert out.dtype in (torch.float32, torch.bfloat16)
-    assert block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous()
-    assert q_offsets.dtype == torch.int32 and ctx_lens.dtype == torch.int32
-    assert q.is_contiguous() and out.is_contiguous() and q.element_size() == 2
-    assert tuple(q.shape) == tuple(out.shape)
+    qo, cl = _batch_lists(q_offsets_host, ctx_lens_host, block_tables, q_offsets, ctx_lens)
+    out_dtype = _attn_tensors(q, out, pool, num_q_heads, qo, 2)
     rc = load_library().attn_mixed_batch_static(
         q.data_ptr(), out.data_ptr(), pool.c, int(layer), block_tables.data_ptr(),
         int(block_tables.shape[1]), q_offsets.data_ptr(), ctx_lens.data_ptr(), _i32_ptr(qo), _i32_ptr(cl),
@@ -240,16 +297,13 @@ def attn_mixed_batch_plan(block_tables, q_offsets, ctx_lens, q_offsets_host, ctx
                           stream=None) -> AttnPlan:
     """See ``attn_mixed_batch_plan`` in include/dsv_attn.h: the work lists of a batch, built once
     into ``workspace`` for the planned calls of every layer."""
-    import torch
-    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
-    assert block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous()
-    assert q_offsets.dtype == torch.int32 and ctx_lens.dtype == torch.int32
+    qo, cl = _batch_lists(q_offsets_host, ctx_lens_host, block_tables, q_offsets, ctx_lens)
     plan = AttnPlan()
     rc = load_library().attn_mixed_batch_plan(
         C.byref(plan.c), block_tables.data_ptr(), int(block_tables.shape[1]), q_offsets.data_ptr(),
         ctx_lens.data_ptr(), _i32_ptr(qo), _i32_ptr(cl), int(cl.shape[0]), int(num_q_heads),
         int(num_kv_heads), int(head_dim), int(kv_elem_bytes), workspace.data_ptr(),
-        int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
+        _nbytes(workspace), _stream_ptr(stream))
     if rc:
         raise DsvError("attn_mixed_batch_plan", rc)
     return plan
@@ -259,19 +313,13 @@ def attn_mixed_batch_planned(plan: AttnPlan, q, out, pool: KVPool, layer, block_
                              ctx_lens, q_offsets_host, ctx_lens_host, num_q_heads, softmax_scale,
                              workspace, stream=None) -> None:
     """See ``attn_mixed_batch_planned`` in include/dsv_attn.h."""
-    import torch
-    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
-    out_dtype = DSV_OUT_F32 if out.dtype == torch.float32 else DSV_OUT_BF16
-    assert out.dtype in (torch.float32, torch.bfloat16)
-    assert block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous()
-    assert q_offsets.dtype == torch.int32 and ctx_lens.dtype == torch.int32
-    assert q.is_contiguous() and out.is_contiguous() and q.element_size() == 2
-    assert tuple(q.shape) == tuple(out.shape)
+    qo, cl = _batch_lists(q_offsets_host, ctx_lens_host, block_tables, q_offsets, ctx_lens)
+    out_dtype = _attn_tensors(q, out, pool, num_q_heads, qo, 2)
     rc = load_library().attn_mixed_batch_planned(
         C.byref(plan.c), q.data_ptr(), out.data_ptr(), pool.c, int(layer), block_tables.data_ptr(),
         int(block_tables.shape[1]), q_offsets.data_ptr(), ctx_lens.data_ptr(), _i32_ptr(qo), _i32_ptr(cl),
         int(cl.shape[0]), int(num_q_heads), float(softmax_scale), out_dtype,
-        workspace.data_ptr(), int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
+        workspace.data_ptr(), _nbytes(workspace), _stream_ptr(stream))
     if rc:
         raise DsvError("attn_mixed_batch_planned", rc)
 
@@ -280,21 +328,13 @@ def attn_mixed_batch_fp8kv_planned(plan: AttnPlan, q, out, pool: KVPool, layer, 
                                    q_offsets, ctx_lens, q_offsets_host, ctx_lens_host, num_q_heads,
                                    softmax_scale, k_scale, v_scale, workspace, stream=None) -> None:
     """See ``attn_mixed_batch_fp8kv_planned`` in include/dsv_attn.h; ``pool`` holds 1-byte elements."""
-    import torch
-    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
-    out_dtype = DSV_OUT_F32 if out.dtype == torch.float32 else DSV_OUT_BF16
-    assert pool.elem_bytes == 1
-    assert out.dtype in (torch.float32, torch.bfloat16)
-    assert block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous()
-    assert q_offsets.dtype == torch.int32 and ctx_lens.dtype == torch.int32
-    assert q.is_contiguous() and out.is_contiguous() and q.element_size() == 2
-    assert tuple(q.shape) == tuple(out.shape)
+    qo, cl = _batch_lists(q_offsets_host, ctx_lens_host, block_tables, q_offsets, ctx_lens)
+    out_dtype = _attn_tensors(q, out, pool, num_q_heads, qo, 1)
     rc = load_library().attn_mixed_batch_fp8kv_planned(
         C.byref(plan.c), q.data_ptr(), out.data_ptr(), pool.c, int(layer), block_tables.data_ptr(),
         int(block_tables.shape[1]), q_offsets.data_ptr(), ctx_lens.data_ptr(), _i32_ptr(qo), _i32_ptr(cl),
         int(cl.shape[0]), int(num_q_heads), float(softmax_scale), float(k_scale), float(v_scale),
-        out_dtype, workspace.data_ptr(), int(workspace.numel() * workspace.element_size()),
-        _stream_ptr(stream))
+        out_dtype, workspace.data_ptr(), _nbytes(workspace), _stream_ptr(stream))
     if rc:
         raise DsvError("attn_mixed_batch_fp8kv_planned", rc)
 
@@ -302,12 +342,8 @@ def attn_mixed_batch_fp8kv_planned(plan: AttnPlan, q, out, pool: KVPool, layer, 
 def kv_append(k_new, v_new, pool: KVPool, layer, block_tables, q_offsets, ctx_lens, q_offsets_host,
               ctx_lens_host, stream=None) -> None:
     """See ``kv_append`` in include/dsv_attn.h."""
-    import torch
-    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
-    assert k_new.is_contiguous() and v_new.is_contiguous() and k_new.element_size() == 2
-    assert tuple(k_new.shape) == tuple(v_new.shape)
-    assert block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous()
-    assert q_offsets.dtype == torch.int32 and ctx_lens.dtype == torch.int32
+    qo, cl = _batch_lists(q_offsets_host, ctx_lens_host, block_tables, q_offsets, ctx_lens)
+    _new_kv_tensors(k_new, v_new, pool, qo, 2)
     rc = load_library().kv_append(
         k_new.data_ptr(), v_new.data_ptr(), pool.c, int(layer), block_tables.data_ptr(),
         int(block_tables.shape[1]), q_offsets.data_ptr(), ctx_lens.data_ptr(), _i32_ptr(qo), _i32_ptr(cl),
@@ -318,7 +354,7 @@ def kv_append(k_new, v_new, pool: KVPool, layer, block_tables, q_offsets, ctx_le
 
 def kv_pack_chunks(src: KVPool, block_tables, descs: ChunkDescs, chunk_buf, stream=None) -> None:
     """See ``kv_pack_chunks`` in include/dsv_attn.h."""
-    assert block_tables.is_contiguous() and chunk_buf.is_contiguous()
+    _copy_tensors(src, block_tables, descs, chunk_buf, 2)
     rc = load_library().kv_pack_chunks(
         src.c, block_tables.data_ptr(), int(block_tables.shape[1]), descs.dev.data_ptr(),
         descs.host.ctypes.data, descs.n, chunk_buf.data_ptr(), _stream_ptr(stream))
@@ -328,7 +364,7 @@ def kv_pack_chunks(src: KVPool, block_tables, descs: ChunkDescs, chunk_buf, stre
 
 def kv_unpack_chunks(chunk_buf, descs: ChunkDescs, dst: KVPool, dst_block_tables, stream=None) -> None:
     """See ``kv_unpack_chunks`` in include/dsv_attn.h."""
-    assert dst_block_tables.is_contiguous() and chunk_buf.is_contiguous()
+    _copy_tensors(dst, dst_block_tables, descs, chunk_buf, 2)
     rc = load_library().kv_unpack_chunks(
         chunk_buf.data_ptr(), descs.dev.data_ptr(), descs.host.ctypes.data, descs.n, dst.c,
         dst_block_tables.data_ptr(), int(dst_block_tables.shape[1]), _stream_ptr(stream))
@@ -336,11 +372,29 @@ def kv_unpack_chunks(chunk_buf, descs: ChunkDescs, dst: KVPool, dst_block_tables
         raise DsvError("kv_unpack_chunks", rc)
 
 
+def dsv_check_block_tables(block_tables, tokens_per_seq, num_blocks, result, stream=None) -> None:
+    """See ``dsv_check_block_tables`` in include/dsv_attn.h.  ``result``: int32 device tensor of two
+    entries, written by the call; read it after synchronising with the stream."""
+    import torch
+    _require(block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous(),
+             "block_tables must be a contiguous int32 [num_seqs, max_blocks] tensor")
+    _require(tokens_per_seq.dtype == torch.int32 and tokens_per_seq.is_contiguous() and
+             tokens_per_seq.numel() == block_tables.shape[0], "tokens_per_seq must be int32 [num_seqs]")
+    _require(result.dtype == torch.int32 and result.is_contiguous() and result.numel() >= 2,
+             "result must be an int32 tensor of two entries")
+    rc = load_library().dsv_check_block_tables(
+        block_tables.data_ptr(), int(block_tables.shape[1]), tokens_per_seq.data_ptr(),
+        int(block_tables.shape[0]), int(num_blocks), result.data_ptr(), _stream_ptr(stream))
+    if rc:
+        raise DsvError("dsv_check_block_tables", rc)
+
+
 # ---- 8-bit KV cache variant ------------------------------------------------------------------
 
 def attn_mixed_batch_fp8kv_workspace_bytes(q_offsets_host, ctx_lens_host, num_q_heads, num_kv_heads,
                                            head_dim) -> int:
     qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
+    _require(qo.shape[0] == cl.shape[0] + 1, "q_offsets_host needs one entry more than ctx_lens_host")
     return int(load_library().attn_mixed_batch_fp8kv_workspace_bytes(
         cl.shape[0], _i32_ptr(qo), _i32_ptr(cl), num_q_heads, num_kv_heads, head_dim))
 
@@ -349,21 +403,13 @@ def attn_mixed_batch_fp8kv(q, out, pool: KVPool, layer, block_tables, q_offsets,
                            q_offsets_host, ctx_lens_host, num_q_heads, softmax_scale, k_scale,
                            v_scale, workspace, stream=None) -> None:
     """See ``attn_mixed_batch_fp8kv`` in include/dsv_attn.h; ``pool`` holds 1-byte elements."""
-    import torch
-    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
-    out_dtype = DSV_OUT_F32 if out.dtype == torch.float32 else DSV_OUT_BF16
-    assert pool.elem_bytes == 1
-    assert out.dtype in (torch.float32, torch.bfloat16)
-    assert block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous()
-    assert q_offsets.dtype == torch.int32 and ctx_lens.dtype == torch.int32
-    assert q.is_contiguous() and out.is_contiguous() and q.element_size() == 2
-    assert tuple(q.shape) == tuple(out.shape)
+    qo, cl = _batch_lists(q_offsets_host, ctx_lens_host, block_tables, q_offsets, ctx_lens)
+    out_dtype = _attn_tensors(q, out, pool, num_q_heads, qo, 1)
     rc = load_library().attn_mixed_batch_fp8kv(
         q.data_ptr(), out.data_ptr(), pool.c, int(layer), block_tables.data_ptr(),
         int(block_tables.shape[1]), q_offsets.data_ptr(), ctx_lens.data_ptr(), _i32_ptr(qo), _i32_ptr(cl),
         int(cl.shape[0]), int(num_q_heads), float(softmax_scale), float(k_scale), float(v_scale),
-        out_dtype, workspace.data_ptr(), int(workspace.numel() * workspace.element_size()),
-        _stream_ptr(stream))
+        out_dtype, workspace.data_ptr(), _nbytes(workspace), _stream_ptr(stream))
     if rc:
         raise DsvError("attn_mixed_batch_fp8kv", rc)
 
@@ -371,13 +417,8 @@ def attn_mixed_batch_fp8kv(q, out, pool: KVPool, layer, block_tables, q_offsets,
 def kv_append_fp8(k_new, v_new, pool: KVPool, layer, block_tables, q_offsets, ctx_lens,
                   q_offsets_host, ctx_lens_host, k_scale, v_scale, stream=None) -> None:
     """See ``kv_append_fp8`` in include/dsv_attn.h: bf16 rows in, E4M3 codes stored."""
-    import torch
-    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
-    assert pool.elem_bytes == 1
-    assert k_new.is_contiguous() and v_new.is_contiguous() and k_new.element_size() == 2
-    assert tuple(k_new.shape) == tuple(v_new.shape)
-    assert block_tables.dtype == torch.int32 and block_tables.dim() == 2 and block_tables.is_contiguous()
-    assert q_offsets.dtype == torch.int32 and ctx_lens.dtype == torch.int32
+    qo, cl = _batch_lists(q_offsets_host, ctx_lens_host, block_tables, q_offsets, ctx_lens)
+    _new_kv_tensors(k_new, v_new, pool, qo, 1)
     rc = load_library().kv_append_fp8(
         k_new.data_ptr(), v_new.data_ptr(), pool.c, int(layer), block_tables.data_ptr(),
         int(block_tables.shape[1]), q_offsets.data_ptr(), ctx_lens.data_ptr(), _i32_ptr(qo), _i32_ptr(cl),
@@ -388,7 +429,7 @@ def kv_append_fp8(k_new, v_new, pool: KVPool, layer, block_tables, q_offsets, ct
 
 def kv_pack_chunks_fp8(src: KVPool, block_tables, descs: ChunkDescs, chunk_buf, stream=None) -> None:
     """See ``kv_pack_chunks_fp8`` in include/dsv_attn.h."""
-    assert src.elem_bytes == 1 and block_tables.is_contiguous() and chunk_buf.is_contiguous()
+    _copy_tensors(src, block_tables, descs, chunk_buf, 1)
     rc = load_library().kv_pack_chunks_fp8(
         src.c, block_tables.data_ptr(), int(block_tables.shape[1]), descs.dev.data_ptr(),
         descs.host.ctypes.data, descs.n, chunk_buf.data_ptr(), _stream_ptr(stream))
@@ -398,7 +439,7 @@ def kv_pack_chunks_fp8(src: KVPool, block_tables, descs: ChunkDescs, chunk_buf, 
 
 def kv_unpack_chunks_fp8(chunk_buf, descs: ChunkDescs, dst: KVPool, dst_block_tables, stream=None) -> None:
     """See ``kv_unpack_chunks_fp8`` in include/dsv_attn.h."""
-    assert dst.elem_bytes == 1 and dst_block_tables.is_contiguous() and chunk_buf.is_contiguous()
+    _copy_tensors(dst, dst_block_tables, descs, chunk_buf, 1)
     rc = load_library().kv_unpack_chunks_fp8(
         chunk_buf.data_ptr(), descs.dev.data_ptr(), descs.host.ctypes.data, descs.n, dst.c,
         dst_block_tables.data_ptr(), int(dst_block_tables.shape[1]), _stream_ptr(stream))

@@ -55,16 +55,22 @@ __global__ __launch_bounds__(512, 2) void mixed_kernel(prefill_impl::TilesParams
 template <int D, bool KV8>
 int launch_mixed_t(const prefill_impl::TilesParams& tp, const rows_impl::RowsParams& rp,
                    const MixParams& mp, int lds, hipStream_t stream) {
-  static int configured = 0;          // raising the dynamic-LDS limit is idempotent; races are benign
-  if (lds > configured) {
+  // Raised once, to the most either body can ask for (eight row waves with two ring slots each,
+  // or the tile ring), so that no later call has to touch the kernel's attributes again.
+  constexpr int kRowsMax = 8 * 2 * rows_impl::RowGeom<D, KV8 ? 1 : 2>::SLOT_BYTES;
+  constexpr int kMaxLds = kRowsMax > (int)prefill_impl::TileGeom<D>::LDS_BYTES ? kRowsMax
+                                                                              : (int)prefill_impl::TileGeom<D>::LDS_BYTES;
+  static bool configured = false;     // idempotent; a race between two first calls is benign
+  if (lds > kMaxLds) return DSV_E_UNSUPPORTED;
+  if (!configured) {
     hipFuncAttributes fa;               // no static LDS: the tile body's ring must start at LDS address 0
     if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(mixed_kernel<D, KV8>)) != hipSuccess ||
         fa.sharedSizeBytes != 0)
       return DSV_E_LAUNCH;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(mixed_kernel<D, KV8>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds) != hipSuccess)
       return DSV_E_LAUNCH;
-    configured = lds;
+    configured = true;
   }
   hipLaunchKernelGGL((mixed_kernel<D, KV8>), dim3(mp.total_groups * kGroup), dim3(512), lds, stream, tp, rp, mp);
   return launch_status();

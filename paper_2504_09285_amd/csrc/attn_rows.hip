@@ -16,12 +16,19 @@ __global__ __launch_bounds__(512) void rows_kernel(RowsParams prm) {
 template <int D, int R, bool KV8>
 int launch_rows_t(const RowsParams& prm, dim3 grid, int waves, hipStream_t stream) {
   const int lds = waves * R * RowGeom<D, KV8 ? 1 : 2>::SLOT_BYTES;
-  static int configured = 0;          // raising the dynamic-LDS limit is idempotent; races are benign
-  if (lds > configured) {
+  // The dynamic-LDS limit is raised once per instantiation, to the most any geometry can ask for
+  // (eight waves' rings), so that no later call - one inside a stream capture, with more KV heads
+  // than the first call had - has to touch the kernel's attributes again.
+  constexpr int kMaxLds = 8 * R * RowGeom<D, KV8 ? 1 : 2>::SLOT_BYTES <= 160 * 1024
+                              ? 8 * R * RowGeom<D, KV8 ? 1 : 2>::SLOT_BYTES
+                              : 4 * R * RowGeom<D, KV8 ? 1 : 2>::SLOT_BYTES;
+  static bool configured = false;     // idempotent; a race between two first calls is benign
+  if (lds > kMaxLds) return DSV_E_UNSUPPORTED;
+  if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(rows_kernel<D, R, KV8>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds) != hipSuccess)
       return DSV_E_LAUNCH;
-    configured = lds;
+    configured = true;
   }
   hipLaunchKernelGGL((rows_kernel<D, R, KV8>), grid, dim3(waves * kWave), lds, stream, prm);
   return launch_status();

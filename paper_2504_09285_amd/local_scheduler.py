@@ -95,27 +95,23 @@ class Batch:
 
 
 def compose_batch(prefill_queue: Sequence[PrefillRequest], decode_queue: Sequence[Tuple[int, int]],
-                  slo_ms: float, table: ProfileTable, previous: Optional[Tuple[int, int, int, float]] = None) -> Batch:
-    """Algorithm 2.  ``decode_queue`` holds (request id, context length); ``previous`` is the last
-    batch's (plen, ctx, dnum, time_ms), recorded into the table first.  Every decode joins the
-    batch; prefill requests then join in arrival order, each with min(its tokens, remaining
-    budget) tokens, until the budget is used up.  The queues are not modified."""
-    if previous is not None:
-        table.record(*previous)
-    b = Batch()
-    b.decodes = [rid for rid, _ in decode_queue]
-    b.dnum = len(b.decodes)
-    b.ctx = int(round(sum(c for _, c in decode_queue) / b.dnum)) if b.dnum else 0
-    m = b.budget = table.max_prefill_allowed(slo_ms, b.ctx, b.dnum)
-    for r in prefill_queue:
-        if m <= 0:
-            break
-        t = min(int(r.tokens), m)
-        if t > 0:
-            b.prefills.append((r.rid, t))
-            m -= t
-    b.plen = b.budget - m
-    return b
+                  slo_ms: float, table: ProfileTable) -> Batch:
+    """Batch composition of section 4.2, Alg. 2.  ``decode_queue`` holds (request id, context
+    length).  Every decode joins the batch; the table then gives the prefill token budget for
+    those decodes under the latency target, and the prefill queue is cut at that budget in
+    arrival order: a request gets whatever of the budget the requests ahead of it have left, at
+    most its own remaining tokens.  The caller feeds the previous batch's measured latency to
+    ``table.record`` before composing the next one.  The queues are not modified."""
+    import numpy as np
+    dnum = len(decode_queue)
+    ctx = int(round(sum(c for _, c in decode_queue) / dnum)) if dnum else 0
+    budget = table.max_prefill_allowed(slo_ms, ctx, dnum)
+    want = np.maximum(np.asarray([r.tokens for r in prefill_queue], dtype=np.int64), 0)
+    ahead = np.cumsum(want) - want                       # tokens asked for by the requests in front
+    grant = np.clip(budget - ahead, 0, want)
+    picks = [(prefill_queue[i].rid, int(grant[i])) for i in np.flatnonzero(grant > 0)]
+    return Batch(decodes=[rid for rid, _ in decode_queue], prefills=picks, ctx=ctx, dnum=dnum,
+                 plen=int(grant.sum()), budget=budget)
 
 
 def sweep(table: ProfileTable, plens: Sequence[int], ctxs: Sequence[int], dnums: Sequence[int],
@@ -123,12 +119,12 @@ def sweep(table: ProfileTable, plens: Sequence[int], ctxs: Sequence[int], dnums:
           seed: int = 92858) -> ProfileTable:
     """Fills ``table`` by timing ``attn_mixed_batch`` on the GPU for every (plen, ctx, dnum) of the
     grid: one prefill span of plen tokens on an empty prefix plus dnum decodes of context ctx,
-    synthetic N(0,1) data.  The latency recorded is the median of ``steps`` timed calls."""
+    synthetic N(0,1) data.  The latency recorded is the GPU time per call of ``steps`` calls queued
+    back to back (events on the stream), median of three repetitions."""
     import numpy as np
     import torch
 
     from . import binding as dsv
-    import time
 
     g = torch.Generator(device="cuda")
     g.manual_seed(seed)
@@ -163,12 +159,19 @@ def sweep(table: ProfileTable, plens: Sequence[int], ctxs: Sequence[int], dnums:
                 call = lambda: dsv.attn_mixed_batch(q, out, pool, 0, bt, qo, cl, q_off, ctx_lens, Hq,
                                                     1.0 / float(np.sqrt(D)), ws)
                 call()
+                call()
                 torch.cuda.synchronize()
-                times = []
-                for _ in range(steps):
-                    t0 = time.perf_counter()
-                    call()
+                # GPU time of a step, read on the device's own clock: `steps` calls queued back to
+                # back between two events.  (Host wall time around a synchronised call sits on a
+                # floor of tens of microseconds that hides the differences between small batches.)
+                reps = []
+                for _ in range(3):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(steps):
+                        call()
+                    e1.record()
                     torch.cuda.synchronize()
-                    times.append((time.perf_counter() - t0) * 1e3)
-                table.record(plen, ctx, dnum, float(np.median(times)))
+                    reps.append(e0.elapsed_time(e1) / steps)
+                table.record(plen, ctx, dnum, float(np.median(reps)))
     return table

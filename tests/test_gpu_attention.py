@@ -154,11 +154,18 @@ def test_invalid_arguments_are_refused():
     call()
     for kw, code in [(dict(ctx_lens_host=np.array([40, 1], np.int32)), -1),      # ctx < q_len
                      (dict(ctx_lens_host=np.array([40, 4000], np.int32)), -1),   # table too short
-                     (dict(layer=1), -1), (dict(num_q_heads=7), -1),
+                     (dict(layer=1), -1),
+                     (dict(num_q_heads=7, q=d.q[:, :7].contiguous(), out=out[:, :7].contiguous()), -1),   # 7 % 2
                      (dict(workspace=d.workspace[:256]), -3)]:
         with pytest.raises(dsv.DsvError) as e:
             call(**kw)
         assert e.value.code == code
+    # What the C ABI cannot see (it carries no tensor shapes) the binding refuses before the call.
+    for kw in [dict(num_q_heads=7), dict(q=d.q[:2].contiguous()), dict(out=out[:, :4].contiguous()),
+               dict(q_offsets_host=np.array([0, 1, 3, 4], np.int32)),
+               dict(block_tables=d.block_tables.to(torch.int64)), dict(block_tables=d.block_tables[:1].contiguous())]:
+        with pytest.raises(ValueError):
+            call(**kw)
 
 
 # ------------------------------------------------------------------ long prefill spans (MFMA path)
@@ -495,6 +502,69 @@ def test_config5_long_context_full_sampled_rows():
     far = int(np.argmax(b.block_tables.max(axis=1)))          # the sequence owning the highest block id
     rows.append((far, 0, 3))
     _sampled_rows_check(b, rows, got)
+
+
+# ------------------------------------------------------------------ full size, every output
+def _all_outputs_check(b, got):
+    ref = oracle.attn_mixed_batch(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens, b.scale)
+    assert got.shape == ref.shape and np.isfinite(got).all()
+    err = np.abs(got - ref)
+    assert err.max() <= TOL, (float(err.max()), np.unravel_index(int(err.argmax()), err.shape))
+    return ref
+
+
+@pytest.mark.timeout(900)
+def test_config3_prefill_heavy_full_every_output():
+    """Config 3 at its stated size, in the launch configuration bench.py times: every one of the
+    8,208 x 32 output rows against the oracle (about 330 GFLOP of fp64 on the host cores)."""
+    from gpu_harness import run_attention
+    b = gen.config3(threads=16)
+    assert b.total_q == 8208 and b.Hq == 32 and b.ctx_lens[:4].tolist() == [2048, 2560, 3072, 6144]
+    _all_outputs_check(b, run_attention(b))
+
+
+@pytest.mark.timeout(900)
+def test_config4_micro_request_full_every_output():
+    """Config 4 at its stated size: the prompt's first k tokens reach the second span's table through
+    GPU pack/unpack in 64-token chunks, then one mixed batch (two spans + 128 decodes, 64/8 heads).
+    Every output against the oracle, and the two spans together against the unsplit prompt."""
+    import torch
+    import paper_2504_09285_amd as dsv
+    from gpu_harness import DeviceBatch, host_u16
+    b, sp = _config4_inputs(1)
+    assert b.Hq == 64 and sp.total == 4096 and b.num_seqs == 130 and b.total_q == 4224
+    d = DeviceBatch(b)
+    descs = dsv.ChunkDescs(sp.chunks)
+    buf = torch.zeros(sp.chunk_elems, dtype=torch.bfloat16, device="cuda")
+    dsv.kv_pack_chunks(d.pool, d.block_tables[0:1].contiguous(), descs, buf)
+    dsv.kv_unpack_chunks(buf, descs, d.pool, d.block_tables[1:2].contiguous())
+    got = d.run(fill=float("nan")).cpu().numpy()
+    kp, vp = b.k_pool[None].copy(), b.v_pool[None].copy()
+    obuf = np.zeros(sp.chunk_elems, np.uint16)
+    oracle.kv_pack_chunks(kp, vp, b.block_tables[0:1], sp.chunks, obuf)
+    oracle.kv_unpack_chunks(obuf, sp.chunks, kp, vp, b.block_tables[1:2])
+    np.testing.assert_array_equal(host_u16(buf), obuf)
+    np.testing.assert_array_equal(host_u16(d.pool.k), kp)
+    np.testing.assert_array_equal(host_u16(d.pool.v), vp)
+    moved = gen.AttnBatch(b.name, b.Hq, b.Hkv, b.D, b.scale, b.q, kp[0], vp[0], b.block_tables,
+                          b.q_offsets, b.ctx_lens)
+    ref = _all_outputs_check(moved, got)
+    unsplit = gen.AttnBatch("unsplit", b.Hq, b.Hkv, b.D, b.scale, b.q[:sp.total], kp[0], vp[0],
+                            b.block_tables[0:1], np.array([0, sp.total], np.int32),
+                            np.array([sp.total], np.int32))
+    ref_unsplit = oracle_out(unsplit)
+    assert np.abs(got[:sp.total] - ref_unsplit).max() <= TOL
+    assert np.abs(ref[:sp.total] - ref_unsplit).max() <= 1e-12      # the oracle's own split invariant
+
+
+@pytest.mark.timeout(900)
+def test_config5_long_context_full_every_output():
+    """Config 5's attention at its stated size (64 decodes on 16K-128K contexts, a pool of 0.24M
+    blocks whose offsets pass 2^32 elements): all 64 x 32 output rows against the oracle."""
+    from gpu_harness import run_attention
+    b = gen.config5_attention(threads=16)
+    assert b.num_seqs == 64 and int(b.k_pool.size) > 2 ** 31
+    _all_outputs_check(b, run_attention(b))
 
 
 @pytest.mark.parametrize("nbuf", ["3", "4"])

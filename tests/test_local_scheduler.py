@@ -42,7 +42,7 @@ def test_hand_worked_compositions():
         assert b.plen == sum(t for _, t in picks) <= m
 
 
-def test_previous_batch_is_recorded_before_the_budget_is_read():
+def test_recording_the_previous_batch_moves_the_next_budget():
     recs, _ = load_cases()
     t = table_from(recs)
     dq = [(i, 1000) for i in range(8)]
@@ -50,7 +50,8 @@ def test_previous_batch_is_recorded_before_the_budget_is_read():
     # The last batch (1024 prefill tokens, 8 decodes at 1024) ran much faster than the table said:
     # three such records pull the bucket's mean under the target.
     for _ in range(3):
-        b = compose_batch([PrefillRequest(0, 5000)], dq, 30.0, t, previous=(1024, 1000, 8, 20.0))
+        t.record(1024, 1000, 8, 20.0)
+        b = compose_batch([PrefillRequest(0, 5000)], dq, 30.0, t)
     assert b.budget == 1024 and b.prefills == [(0, 1024)]
 
 
