@@ -347,6 +347,24 @@ int dsv_check_block_tables(const int32_t* block_tables, int32_t max_blocks_per_s
 #define DSV_KERNEL_STAGE  5   /* bf16 copy of the prefill spans' contexts (8-bit cache only)  */
 int dsv_profile_events(int32_t kernel_id, void* start_event, void* stop_event);
 
+/*
+ * Calibration aids for benchmarks (nothing on the hot path calls them): what this GPU delivers on
+ * the plainest HBM streaming and matrix-core loops, with the launch shape and memory hints of the
+ * product kernels, to be reported next to the nominal peaks.
+ *   dsv_calib_hbm   mode 0: read `bytes` from src (dst: any valid 16 bytes, normally untouched);
+ *                   mode 1: write `bytes` to dst (src ignored); mode 2: copy src -> dst.
+ *                   One workgroup of 256 threads per 16 KiB, four 16-byte nontemporal accesses per
+ *                   thread in one round: kv_copy_kernel without the block table.  Device pointers,
+ *                   16-byte aligned; bytes a positive multiple of 16.
+ *   dsv_calib_mfma  a register-resident loop of bf16 32x32x16 MFMAs, eight independent
+ *                   accumulators per wave, two waves per SIMD (the prefill kernel's occupancy),
+ *                   four workgroups per compute unit; *flops_out (host, may be NULL) receives the
+ *                   floating-point operations one launch performs.  sink: device, 4 bytes.
+ * Both enqueue one kernel on hip_stream and return; errors as for the other entry points.
+ */
+int dsv_calib_hbm(int32_t mode, void* dst, const void* src, size_t bytes, void* hip_stream);
+int dsv_calib_mfma(int32_t iters, void* sink, double* flops_out, void* hip_stream);
+
 /* Library build identification: a static string, e.g. "dsv_attn gfx950 <date>". */
 const char* dsv_build_info(void);
 

@@ -51,7 +51,7 @@ EXPORTS = ("attn_mixed_batch_workspace_bytes", "attn_mixed_batch", "kv_pack_chun
            "attn_mixed_batch_fp8kv", "kv_append_fp8", "kv_pack_chunks_fp8", "kv_unpack_chunks_fp8",
            "attn_mixed_batch_plan", "attn_mixed_batch_planned", "attn_mixed_batch_fp8kv_planned",
            "attn_mixed_batch_static", "attn_mixed_batch_static_max_bytes",
-           "dsv_check_block_tables", "dsv_profile_events", "dsv_build_info")
+           "dsv_check_block_tables", "dsv_calib_hbm", "dsv_calib_mfma", "dsv_profile_events", "dsv_build_info")
 KERNEL_PLAN, KERNEL_ROWS, KERNEL_TILES, KERNEL_MERGE, KERNEL_MIXED, KERNEL_STAGE = 0, 1, 2, 3, 4, 5
 
 
@@ -117,6 +117,10 @@ def load_library():
     lib.attn_mixed_batch_static_max_bytes.argtypes = []
     lib.dsv_check_block_tables.restype = C.c_int
     lib.dsv_check_block_tables.argtypes = [vp, C.c_int32, vp, C.c_int32, C.c_int32, vp, vp]
+    lib.dsv_calib_hbm.restype = C.c_int
+    lib.dsv_calib_hbm.argtypes = [C.c_int32, vp, vp, C.c_size_t, vp]
+    lib.dsv_calib_mfma.restype = C.c_int
+    lib.dsv_calib_mfma.argtypes = [C.c_int32, vp, C.POINTER(C.c_double), vp]
     lib.dsv_profile_events.restype = C.c_int
     lib.dsv_profile_events.argtypes = [C.c_int32, vp, vp]
     lib.dsv_build_info.restype = C.c_char_p
@@ -387,6 +391,25 @@ def dsv_check_block_tables(block_tables, tokens_per_seq, num_blocks, result, str
         int(block_tables.shape[0]), int(num_blocks), result.data_ptr(), _stream_ptr(stream))
     if rc:
         raise DsvError("dsv_check_block_tables", rc)
+
+
+def dsv_calib_hbm(mode: int, dst, src, nbytes: int, stream=None) -> None:
+    """See ``dsv_calib_hbm`` in include/dsv_attn.h (0 read, 1 write, 2 copy)."""
+    _require(_nbytes(dst) >= (nbytes if mode else 16) and (mode == 1 or _nbytes(src) >= nbytes),
+             "calibration buffers shorter than the byte count")
+    rc = load_library().dsv_calib_hbm(int(mode), dst.data_ptr(), 0 if mode == 1 else src.data_ptr(),
+                                      int(nbytes), _stream_ptr(stream))
+    if rc:
+        raise DsvError("dsv_calib_hbm", rc)
+
+
+def dsv_calib_mfma(iters: int, sink, stream=None) -> float:
+    """See ``dsv_calib_mfma`` in include/dsv_attn.h; returns the flops of the launch."""
+    flops = C.c_double()
+    rc = load_library().dsv_calib_mfma(int(iters), sink.data_ptr(), C.byref(flops), _stream_ptr(stream))
+    if rc:
+        raise DsvError("dsv_calib_mfma", rc)
+    return float(flops.value)
 
 
 # ---- 8-bit KV cache variant ------------------------------------------------------------------

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libdsv_attn.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["kv_copy.hip", "kv_append.hip", "attn_api.hip", "attn_rows.hip", "attn_prefill.hip", "attn_mixed.hip", "table_check.hip"]
+SOURCES = ["kv_copy.hip", "kv_append.hip", "attn_api.hip", "attn_rows.hip", "attn_prefill.hip", "attn_mixed.hip", "table_check.hip", "calib.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", INCLUDE, "-I", CSRC]

@@ -1,0 +1,106 @@
+// Calibration kernels: what this GPU delivers on the plainest possible HBM streaming and
+// matrix-core loops, measured with the same launch shapes and memory hints the product kernels
+// use.  A benchmark reports them next to the nominal peaks (HBM 8 TB/s, bf16 MFMA 2.5 PFLOP/s),
+// so that a kernel's distance from what the hardware can reach is visible beside its distance
+// from the data-sheet number.  Nothing on the hot path calls these.
+#include "dsv_common.h"
+
+namespace dsv {
+namespace {
+
+typedef uint32_t unit_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+constexpr int kThreads = 256;
+constexpr int kUnits = kThreads * 4;          // 16 KiB per workgroup, one round: as kv_copy_kernel
+
+// MODE 0: read only (the values are folded into a word that is never stored unless it takes an
+// impossible value), 1: write only, 2: copy.  Nontemporal loads and stores, as in kv_copy_kernel.
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void hbm_kernel(const unit_t* __restrict__ src, unit_t* __restrict__ dst,
+                                                       uint64_t units) {
+  const uint64_t u0 = (uint64_t)blockIdx.x * kUnits + threadIdx.x;
+  unit_t v[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const uint64_t u = u0 + (uint64_t)k * kThreads;
+    if (MODE != 1) v[k] = u < units ? __builtin_nontemporal_load(&src[u]) : unit_t{0u, 0u, 0u, 0u};
+    else v[k] = unit_t{(uint32_t)u, 1u, 2u, 3u};
+  }
+  if (MODE == 0) {
+    const unit_t x = v[0] ^ v[1] ^ v[2] ^ v[3];
+    if (x.x == 0x9e3779b9u && x.y == 0x7f4a7c15u && x.z == 0x85ebca6bu && x.w == 0xc2b2ae35u) dst[0] = x;
+    return;
+  }
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const uint64_t u = u0 + (uint64_t)k * kThreads;
+    if (u < units) __builtin_nontemporal_store(v[k], &dst[u]);
+  }
+}
+
+// Register-resident MFMA loop: every wave keeps eight independent 32x32 accumulators and issues
+// bf16 32x32x16 MFMAs on them back to back; 512 threads per workgroup = two waves per SIMD, the
+// occupancy of the prefill kernel.  Operands are made from the lane id so nothing is constant-folded.
+constexpr int kMfmaPerIter = 8;
+__global__ __launch_bounds__(512, 2) void mfma_kernel(float* sink, int iters) {
+  f32x16_t acc[kMfmaPerIter];
+#pragma unroll
+  for (int i = 0; i < kMfmaPerIter; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  bf16x8_t a, b;
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    a[r] = (__bf16)(float)((threadIdx.x + r) & 3);
+    b[r] = (__bf16)(float)((threadIdx.x * 3 + r) & 1);
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < kMfmaPerIter; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < kMfmaPerIter; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
+  if (s == -1.0f) sink[0] = s;                   // never true: sums of non-negative products
+}
+
+}  // namespace
+}  // namespace dsv
+
+extern "C" int dsv_calib_hbm(int32_t mode, void* dst, const void* src, size_t bytes, void* hip_stream) {
+  using namespace dsv;
+  if (mode < 0 || mode > 2 || !dst || (mode != 1 && !src) || bytes == 0 || (bytes & 15)) return DSV_E_INVALID;
+  if ((reinterpret_cast<uintptr_t>(dst) & 15) || (reinterpret_cast<uintptr_t>(src) & 15)) return DSV_E_INVALID;
+  const uint64_t units = bytes / 16;
+  const uint64_t grid = (units + kUnits - 1) / kUnits;
+  if (grid > 0x7fffffffull) return DSV_E_UNSUPPORTED;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const unit_t* s = static_cast<const unit_t*>(src);
+  unit_t* d = static_cast<unit_t*>(dst);
+  begin_gpu_work();
+  if (mode == 0) hipLaunchKernelGGL(hbm_kernel<0>, dim3((unsigned)grid), dim3(kThreads), 0, stream, s, d, units);
+  else if (mode == 1) hipLaunchKernelGGL(hbm_kernel<1>, dim3((unsigned)grid), dim3(kThreads), 0, stream, s, d, units);
+  else hipLaunchKernelGGL(hbm_kernel<2>, dim3((unsigned)grid), dim3(kThreads), 0, stream, s, d, units);
+  return launch_status();
+}
+
+extern "C" int dsv_calib_mfma(int32_t iters, void* sink, double* flops_out, void* hip_stream) {
+  using namespace dsv;
+  if (iters < 1 || !sink) return DSV_E_INVALID;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
+    (void)hipGetLastError();
+    return DSV_E_LAUNCH;
+  }
+  const int grid = cus * 4;                      // four rounds of one workgroup per compute unit
+  if (flops_out) *flops_out = (double)grid * 8 /*waves*/ * iters * kMfmaPerIter * (2.0 * 32 * 32 * 16);
+  begin_gpu_work();
+  hipLaunchKernelGGL(mfma_kernel, dim3((unsigned)grid), dim3(512), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<float*>(sink), iters);
+  return launch_status();
+}
