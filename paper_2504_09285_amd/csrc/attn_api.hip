@@ -74,6 +74,16 @@ __host__ __device__ inline int tile_parts_of(int n_kv, const PlanConfig& c) {
   return c.tile_part_tiles > 0 ? (n_kv + c.tile_part_tiles - 1) / c.tile_part_tiles : 1;
 }
 
+// How the plan kernel walks the query tiles (its has_tiles argument).  Sharing one segment's
+// tiles among all threads, segment after segment, pays when a segment has more query tiles than
+// there are such segments (a few long spans: config 3's four spans of 32 tiles); with many short
+// spans it would be a serial walk over the segments (1,024 spans of one tile each: 0.95 ms
+// against 0.02 ms), and each thread takes whole segments instead.
+int tile_list_mode(const PlanCounts& n) {
+  if (n.tiles == 0) return 0;
+  return (n.stage_segs <= kPlanThreads && n.stage_segs <= n.max_qtiles) ? 2 : 1;
+}
+
 int validate_batch(int32_t S, const int32_t* qo, const int32_t* cl, int32_t max_blocks) {
   if (S < 0) return DSV_E_INVALID;
   if (S == 0) return DSV_OK;
@@ -229,6 +239,7 @@ PlanCounts count_plan(int32_t S, const int32_t* qo, const int32_t* cl, const Pla
       }
     } else {
       const int nt = ceil_div(q_len, c.tile_tokens);
+      if (nt > n.max_qtiles) n.max_qtiles = nt;
       for (int t = 0; t < nt; ++t) {
         const int np = tile_parts_of(kv_tiles_of(cl[i], q_len, t, c), c);
         n.tiles += np;
@@ -265,6 +276,8 @@ size_t carve(const PlanCounts& n, int S, int Hq, int Hkv, int D, bool kv8, char*
   char* p7 = take(tiles * 4); char* p8 = take(tiles * 4);
   char* p7b = take(tiles * 4); char* p7c = take(tiles * 4);
   char* p7d = take((size_t)n.split_qtiles * 16);
+  char* p7e = take(tiles * 32);
+  char* p7f = take(64 * 4);
   char* pz = take(256);
   char* pc = take(items * 4);
   char* po = take(items * 4);
@@ -286,6 +299,7 @@ size_t carve(const PlanCounts& n, int S, int Hq, int Hkv, int D, bool kv8, char*
     w->item_rec = (int4*)p5;
     w->tile_seq = (int32_t*)p7; w->tile_q0 = (int32_t*)p8;
     w->tile_part = (int32_t*)p7b; w->tile_item0 = (int32_t*)p7c; w->split_rec = (int4*)p7d;
+    w->tile_rec = (int4*)p7e; w->tile_ctr = (int32_t*)p7f;
     w->zero_line = (uint32_t*)pz;
     w->item_blk0 = (int32_t*)pc;
     w->item_order = (int32_t*)po;
@@ -342,6 +356,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
   __shared__ int order_slot[kOrderBins + 1];    // row items by block count (bin kOrderBins - blocks)
   if (threadIdx.x == 0) { split_count = 0; split_items = 0; tseg_n = 0; }
   if (threadIdx.x < 64) w.zero_line[threadIdx.x] = 0u;
+  if (threadIdx.x < 64) w.tile_ctr[threadIdx.x] = 0;
 
   // Tiles are listed heaviest first (most KV tiles to visit), so that the MFMA kernel's
   // workgroups, dispatched in list order, leave no long tile for the end: a counting sort on
@@ -397,29 +412,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
     __syncthreads();
   }
 
-  // Placement: every query tile takes list positions for its partitions (two sizes at most).
-  for_each_query_tile([&](int i, int q_len, int ctx, int t) {
-    const int n_kv = kv_tiles_of(ctx, q_len, t, c), P = tile_parts_of(n_kv, c);
-    int first_partial = -1;
-    if (P > 1) {
-      // A cut q-tile: its partials (one per query token and partition) sit behind the row
-      // path's items; the order in which q-tiles take their ranges does not matter.
-      const int ntok = min(c.tile_tokens, q_len - t * c.tile_tokens);
-      first_partial = row_items + atomicAdd(&split_items, ntok * P);
-      w.split_rec[atomicAdd(&split_count, 1)] = make_int4(i, t * c.tile_tokens, P, first_partial);
-    }
-    const int base_kv = n_kv / P, rem = n_kv - base_kv * P;
-    const int pos_long = rem ? atomicAdd(&tile_slot[tile_bucket(base_kv + 1)], rem) : 0;
-    const int pos_short = atomicAdd(&tile_slot[tile_bucket(base_kv)], P - rem);
-    for (int pp = 0; pp < P; ++pp) {
-      const int pos = pp < rem ? pos_long + pp : pos_short + (pp - rem);
-      w.tile_seq[pos] = i;
-      w.tile_q0[pos] = t * c.tile_tokens;
-      w.tile_part[pos] = pp | (P << 16);
-      w.tile_item0[pos] = first_partial;
-    }
-  });
-
   int row_carry = 0, item_carry = 0, stage_carry = 0, sblk_carry = 0;
   for (int base = 0; base < S; base += kPlanThreads) {
     const int i = base + (int)threadIdx.x;
@@ -467,6 +459,34 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
       sblk_carry += tot_b;
     }
   }
+  // Placement: every query tile takes list positions for its partitions (two sizes at most).
+  // (After the segment loop above: a record names the block-table row that serves its segment,
+  // which for a cache of 8-bit codes is the staged row assigned there.)
+  __syncthreads();
+  for_each_query_tile([&](int i, int q_len, int ctx, int t) {
+    const int n_kv = kv_tiles_of(ctx, q_len, t, c), P = tile_parts_of(n_kv, c);
+    int first_partial = -1;
+    if (P > 1) {
+      // A cut q-tile: its partials (one per query token and partition) sit behind the row
+      // path's items; the order in which q-tiles take their ranges does not matter.
+      const int ntok = min(c.tile_tokens, q_len - t * c.tile_tokens);
+      first_partial = row_items + atomicAdd(&split_items, ntok * P);
+      w.split_rec[atomicAdd(&split_count, 1)] = make_int4(i, t * c.tile_tokens, P, first_partial);
+    }
+    const int base_kv = n_kv / P, rem = n_kv - base_kv * P;
+    const int pos_long = rem ? atomicAdd(&tile_slot[tile_bucket(base_kv + 1)], rem) : 0;
+    const int pos_short = atomicAdd(&tile_slot[tile_bucket(base_kv)], P - rem);
+    for (int pp = 0; pp < P; ++pp) {
+      const int pos = pp < rem ? pos_long + pp : pos_short + (pp - rem);
+      w.tile_seq[pos] = i;
+      w.tile_q0[pos] = t * c.tile_tokens;
+      w.tile_part[pos] = pp | (P << 16);
+      w.tile_item0[pos] = first_partial;
+      w.tile_rec[2 * pos] = make_int4(i, t * c.tile_tokens, pp | (P << 16), first_partial);
+      w.tile_rec[2 * pos + 1] = make_int4(q_offsets[i], q_len, ctx, stage ? w.stage_rows[i] : i);
+    }
+  });
+
   // Second pass, all threads: the id of each item's first block, so that the row kernel can
   // request its first K/V block as soon as it has read the item record.
   // The same pass lists the items in dispatch order, those with the most blocks first (counting
@@ -834,7 +854,7 @@ int run_attention(Phase phase, dsv_attn_plan* plan, bool kv8, float k_scale, flo
   if (phase != Phase::kRunPlanned) {
     EventScope ev(DSV_KERNEL_PLAN, stream);
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, q_offsets, ctx_lens,
-                       block_tables, max_blocks_per_seq, num_seqs, cfg, w, n.tiles == 0 ? 0 : (n.stage_segs <= kPlanThreads ? 2 : 1),
+                       block_tables, max_blocks_per_seq, num_seqs, cfg, w, tile_list_mode(n),
                        stage ? 1 : 0, (int32_t)n.items);
     if ((rc = launch_status())) return rc;
   }

@@ -39,6 +39,7 @@ struct PlanCounts {
   int64_t split_qtiles = 0;   // q-tiles cut into more than one partition
   int64_t tile_split_items = 0;  // (query token, partition) partials of those q-tiles
   int32_t max_parts = 0;
+  int32_t max_qtiles = 0;  // most query tiles of one segment on the MFMA path
   // Filled only for a cache of 8-bit codes: the MFMA path then reads a bf16 copy of the whole
   // context of every segment it serves.
   int64_t stage_segs = 0;        // segments on the MFMA path
@@ -60,6 +61,12 @@ struct WorkLists {
                            // partition p -> item tile_item0 + j * partitions + p), counted
                            // after the row path's items; -1 for uncut q-tiles
   int4*    split_rec;      // [split_qtiles] {seq, q0 of the tile, partitions, first partial}
+  int4*    tile_rec;       // [tiles][2]: everything a work item of the MFMA kernel needs, in one
+                           // 32-byte scalar read: {seq, q0 of the tile, partition | partitions << 16,
+                           // first partial or -1} {first query token of the segment, q_len, ctx_len,
+                           // block-table row that serves the segment}
+  int32_t* tile_ctr;       // [64] counters of the persistent MFMA grid (next item per KV head,
+                           // workgroups finished); zero between launches
   uint32_t* zero_line;     // 256 bytes of zeros (stands in for V rows that must not be read)
   int32_t* item_blk0;      // [items] pool block id of the item's first block
   int32_t* item_order;     // [items] the items in dispatch order: most blocks to stream first

@@ -112,6 +112,13 @@ struct TileGeom {
   static constexpr int TILE_BYTES = 2 * TENSOR_BYTES;
   static constexpr int RING_BYTES = kRing * TILE_BYTES;
   static constexpr int LDS_BYTES = RING_BYTES + 16;  // the ring, then the workgroup's overflow flag
+  // Persistent form: output rows are staged through LDS, 4 KiB per wave.  A tile buffer of that
+  // size (head_dim 128) lends itself, being free at that moment; smaller ones (head_dim 64) get an
+  // area of their own behind the flags.
+  static constexpr int STAGE_BYTES = kWaves * 4096;
+  static constexpr bool STAGE_IN_RING = TILE_BYTES >= STAGE_BYTES;
+  static constexpr int STAGE_OFFSET = RING_BYTES + 256;
+  static constexpr int LDS_BYTES_PERSISTENT = STAGE_IN_RING ? LDS_BYTES : STAGE_OFFSET + STAGE_BYTES;
   static constexpr int PPW = PPB / kWavesPerBlock;   // pieces per wave
   static constexpr int LOADS = 2 * PPW;      // direct loads per wave per tile (its share of a block of K and of V)
 };
@@ -291,19 +298,18 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
   bool head_ok[NH];
   int head[NH];
   uint4 qf[NH][KS];
+  static_assert(D * 2 <= 256, "a query row fits the zero line");
 #pragma unroll
   for (int c = 0; c < NH; ++c) {
     const int hsub = flat ? bz * gh + row_in_item % gh : bz * 4 + hp * NH + c;
     head_ok[c] = hsub < prm.G && jq < q_len && (!flat || row_in_item < prm.tile_q * gh);
     head[c] = kvh * prm.G + (hsub < prm.G ? hsub : 0);
-    const int64_t off = ((int64_t)(q0 + (jq < q_len ? jq : 0)) * a.Hq + head[c]) * D + hh * 8;
+    // A row that does not exist reads the zero line: the choice is made on the address, so the
+    // loads stay in flight next to the tile requests below instead of being waited for here.
+    const uint16_t* src = head_ok[c] ? a.q + (((int64_t)(q0 + jq) * a.Hq + head[c]) * D + hh * 8)
+                                     : reinterpret_cast<const uint16_t*>(prm.w.zero_line) + hh * 8;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      // Unconditional (the address is clamped to a valid row), so that all loads are in flight
-      // together; rows that do not exist are zeroed afterwards.
-      qf[c][ks] = *reinterpret_cast<const uint4*>(a.q + off + ks * 16);
-      if (!head_ok[c]) qf[c][ks] = make_uint4(0u, 0u, 0u, 0u);
-    }
+    for (int ks = 0; ks < KS; ++ks) qf[c][ks] = *reinterpret_cast<const uint4*>(src + ks * 16);
   }
 
   // ---- direct global->LDS loads: waves 2i and 2i+1 fetch one half each of block 4t+i of tile t ----
@@ -709,44 +715,91 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
   __syncthreads();
   if (wg_overflow) attend(std::true_type{});
 
-  // A cut q-tile writes unnormalised partials (accumulators, and the reference / sum pair per
-  // row and head) for the merge kernel; token j of the tile, partition p -> partial
-  // first + j * partitions + p.
-  const int first_partial = nparts > 1 ? prm.w.tile_item0[tile] : -1;
-#pragma unroll
-  for (int c = 0; c < NH; ++c) {
-    const float l_tot = other_half_sum(l_run[c]);
-    if (!head_ok[c]) continue;
-    if (nparts > 1) {
-      const int64_t ph = ((int64_t)first_partial + (int64_t)(jq - j0) * nparts + part) * a.Hq + head[c];
-      float* pa = prm.w.part_acc + ph * D;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int aa = 0; aa < 4; ++aa)
-          *reinterpret_cast<float4*>(pa + db * 32 + aa * 8 + hh * 4) =
-              make_float4(o[c][db][aa * 4 + 0], o[c][db][aa * 4 + 1], o[c][db][aa * 4 + 2], o[c][db][aa * 4 + 3]);
-      if (hh == 0) *reinterpret_cast<float2*>(prm.w.part_ml + ph * 2) = make_float2(m_run[c], l_tot);
-      continue;
+  // Output.  A lane holds its query row's values four dims at a time, 32 rows per wave: stored as
+  // they are, every store instruction would touch 32 rows with 16 or 32 bytes each.  The values go
+  // through LDS instead (the ring is free: every request has landed and every wave is past its
+  // last fragment read; 4 KiB per wave), 32 rows x 128 bytes per pass, and come back as eight rows x
+  // 128 contiguous bytes per store instruction: whole cache lines.  Staged rows are XOR-swizzled by
+  // 16-byte chunk so that neither side has bank conflicts.
+  // A cut q-tile writes unnormalised partials (accumulators, and the reference / sum pair per row
+  // and head) for the merge kernel; token j of the tile, partition p -> partial
+  // first + j * partitions + p.  An uncut one writes the normalised output, fp32 or bf16.
+  static_assert(NH == 1 && kWaves * 4096 <= Geo::RING_BYTES, "one head per wave; the staging area fits the ring");
+  __syncthreads();
+  {
+    const float l_tot = other_half_sum(l_run[0]);
+    if (!wave_has_rows) return;                                   // (wave-uniform)
+    const bool partial = nparts > 1;
+    const int first_partial = partial ? prm.w.tile_item0[tile] : -1;
+    const float inv = partial ? 1.0f : a.out_scale / l_tot;
+    if (partial && head_ok[0] && hh == 0) {
+      const int64_t ph = ((int64_t)first_partial + (int64_t)(jq - j0) * nparts + part) * a.Hq + head[0];
+      *reinterpret_cast<float2*>(prm.w.part_ml + ph * 2) = make_float2(m_run[0], l_tot);
     }
-    const float inv = a.out_scale / l_tot;
-    const int64_t o_row = ((int64_t)(q0 + jq) * a.Hq + head[c]) * D;
+    const uint32_t stage = lds0 + (uint32_t)wave * 4096u;
+    const uint32_t w_row = stage + (uint32_t)jrow * 128u;
+    const uint32_t w_swz = (uint32_t)((jrow >> 1) & 7);
+    const int rr = lane / 8, ch = lane % 8;               // reading side: chunk ch of rows rr + 8 * pass
+    uint32_t r_adr[4];
+    int64_t r_dst[4];                                             // element offset of the row in its destination
+    bool r_ok[4];
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int ps = 0; ps < 4; ++ps) {
+      const int row = ps * 8 + rr;
+      r_adr[ps] = stage + (uint32_t)row * 128u + (uint32_t)((ch ^ ((row >> 1) & 7)) * 16);
+      const int r_item = 32 * wave + row;
+      const int jq_r = flat ? j0 + r_item / gh : j0 + 32 * tg + row;
+      const int hsub = flat ? bz * gh + r_item % gh : bz * 4 + hp * NH;
+      r_ok[ps] = hsub < prm.G && jq_r < q_len && (!flat || r_item < prm.tile_q * gh);
+      const int head_r = kvh * prm.G + (hsub < prm.G ? hsub : 0);
+      r_dst[ps] = partial ? (((int64_t)first_partial + (int64_t)(jq_r - j0) * nparts + part) * a.Hq + head_r) * D
+                          : ((int64_t)(q0 + jq_r) * a.Hq + head_r) * D;
+    }
+    const bool as_bf16 = !partial && a.out_bf16;
+    if (!as_bf16) {
+      float* const dst = partial ? prm.w.part_acc : reinterpret_cast<float*>(a.out);
 #pragma unroll
-      for (int aa = 0; aa < 4; ++aa) {
-        const int dim = db * 32 + aa * 8 + hh * 4;
-        const float x0 = o[c][db][aa * 4 + 0] * inv, x1 = o[c][db][aa * 4 + 1] * inv;
-        const float x2 = o[c][db][aa * 4 + 2] * inv, x3 = o[c][db][aa * 4 + 3] * inv;
-        if (a.out_bf16) {
-          uint2 pk;
-          pk.x = pack_bf16(x0, x1);
-          pk.y = pack_bf16(x2, x3);
-          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + o_row + dim) = pk;
-        } else {
-          *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + o_row + dim) = make_float4(x0, x1, x2, x3);
+      for (int db = 0; db < DB; ++db) {
+#pragma unroll
+        for (int aa = 0; aa < 4; ++aa) {
+          const u32x4_t v = {__float_as_uint(o[0][db][aa * 4 + 0] * inv), __float_as_uint(o[0][db][aa * 4 + 1] * inv),
+                             __float_as_uint(o[0][db][aa * 4 + 2] * inv), __float_as_uint(o[0][db][aa * 4 + 3] * inv)};
+          const uint32_t adr = w_row + (((uint32_t)(aa * 2 + hh) ^ w_swz) * 16u);
+          asm volatile("ds_write_b128 %0, %1" ::"v"(adr), "v"(v) : "memory");
         }
+        u32x4_t r0, r1, r2, r3;
+        lds_issue4_b128<0>(r_adr[0], r_adr[1], r_adr[2], r_adr[3], r0, r1, r2, r3);   // (LDS serves a wave in order)
+        lds_wait<0>();
+        lds_ready4(r0, r1, r2, r3);
+        const u32x4_t rv[4] = {r0, r1, r2, r3};
+#pragma unroll
+        for (int ps = 0; ps < 4; ++ps)
+          if (r_ok[ps]) *reinterpret_cast<u32x4_t*>(dst + r_dst[ps] + db * 32 + ch * 4) = rv[ps];
       }
+    } else {
+      uint16_t* const dst = reinterpret_cast<uint16_t*>(a.out);
+#pragma unroll
+      for (int dp = 0; dp < DB; dp += 2) {
+#pragma unroll
+        for (int dl = 0; dl < 2; ++dl)
+#pragma unroll
+          for (int aa = 0; aa < 4; ++aa) {
+            const int db = dp + dl;
+            const u32x2_t v = {pack_bf16(o[0][db][aa * 4 + 0] * inv, o[0][db][aa * 4 + 1] * inv),
+                               pack_bf16(o[0][db][aa * 4 + 2] * inv, o[0][db][aa * 4 + 3] * inv)};
+            const uint32_t adr = w_row + (((uint32_t)(dl * 4 + aa) ^ w_swz) * 16u) + (uint32_t)hh * 8u;
+            asm volatile("ds_write_b64 %0, %1" ::"v"(adr), "v"(v) : "memory");
+          }
+        u32x4_t r0, r1, r2, r3;
+        lds_issue4_b128<0>(r_adr[0], r_adr[1], r_adr[2], r_adr[3], r0, r1, r2, r3);
+        lds_wait<0>();
+        lds_ready4(r0, r1, r2, r3);
+        const u32x4_t rv[4] = {r0, r1, r2, r3};
+#pragma unroll
+        for (int ps = 0; ps < 4; ++ps)
+          if (r_ok[ps]) *reinterpret_cast<u32x4_t*>(dst + r_dst[ps] + dp * 32 + ch * 8) = rv[ps];
+      }
+    }
   }
 }
 
