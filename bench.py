@@ -5,12 +5,21 @@
                     [--no-cpu-baseline]
 
 A step is one attn_mixed_batch call (plan + attention kernels + merge) over one seeded synthetic
-batch that is already resident in HBM.  The headline workload is the decode-heavy batch
-(256 decodes, 32/8 heads, D=128, lognormal contexts); `value` is query tokens per second.  The
-same JSON line carries the roofline of the dominant kernel (HIP events recorded around that
-kernel on its own stream) and the fp64 CPU oracle timed on this machine's host cores.  Short extra
-measurements of the other workloads (prefill-heavy, micro-request, hand-off copy) are attached
-under "extras".
+batch that is already resident in HBM.  The headline workload is the largest of the five
+configurations: config 5's attention, 64 decodes on contexts of 16K-128K tokens, 14.6 GB of KV
+streamed per step (32/8 heads, D=128); `value` is query tokens per second.  The same JSON line
+carries
+  roofline      the dominant kernel of the headline step (HIP events recorded around that kernel
+                on its own stream, over the timed steps),
+  rooflines     one entry per target kernel and workload: the row kernel on configs 2 and 5, the
+                MFMA kernel on config 3 (and with 40/8 heads), the mixed launch on config 4 against
+                its overlap bound, pack / unpack / append, the 8-bit cache,
+  ceilings      what this GPU delivers on plain streaming and MFMA loops (the library's
+                calibration kernels), next to the nominal peaks the fractions are taken against,
+  cpu_baseline  the fp64 oracle timed on this machine's host cores on a bounded sample of the headline
+                workload; cpu_baselines: the same for the other configurations and the hand-off,
+  extras        further short measurements (two streams at config 5's full size, shared plan,
+                chunk-pipelined hand-off, profile table, ...).
 """
 from __future__ import annotations
 
@@ -27,9 +36,23 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 METRIC = "mixed-batch attention tokens/s; decode HBM GB/s & prefill MFMA util vs peak"
-# HBM bytes per rows_kernel launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the
-# counter reads for a plain 1 GiB copy (profiles/rows_kernel_c2_decode_heavy.md).
-MEASURED_TRAFFIC_BYTES = {"c2_decode_heavy": 1.495e9}
+PROFILES = os.path.join(ROOT, "profiles")
+
+
+def profile_traffic(kernel: str, workload: str):
+    """HBM bytes per launch of a kernel on a workload as measured with rocprofv3 counters (two
+    --pmc runs, FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size): NOT measured in
+    this run, read from the committed summary profiles/<kernel>_<workload>.md, from its line
+    `traffic_bytes_per_launch: N`.  (None, None) if the summary has no such line."""
+    import re
+    path = os.path.join(PROFILES, "%s_%s.md" % (kernel, workload))
+    try:
+        m = re.search(r"^traffic_bytes_per_launch\s*[:=]\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
+    except OSError:
+        return None, None
+    return (float(m.group(1)), "profiles/%s (rocprofv3 --pmc, separate run)" % os.path.basename(path)) if m else (None, None)
+
+
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
@@ -121,13 +144,21 @@ def attn_step(d):
                          b.q_offsets, b.ctx_lens, b.Hq, b.scale, d.workspace)
 
 
-def time_attention(d, steps, warmup, kernel_ids, hev):
+def time_attention(d, steps, warmup, kernel_ids, hev, min_warm_ms=0.0):
     """Wall time of `steps` calls between device synchronisations, plus per-kernel event times."""
     import torch
     import paper_2504_09285_amd as dsv
     for _ in range(warmup):
         attn_step(d)
     torch.cuda.synchronize()
+    if min_warm_ms:
+        # Short steps: the untimed calls go on until the GPU has been busy for a while, so that its
+        # clocks have left their idle state before anything is timed.
+        t_w = time.perf_counter()
+        while (time.perf_counter() - t_w) * 1e3 < min_warm_ms:
+            for _ in range(10):
+                attn_step(d)
+            torch.cuda.synchronize()
     evs = {k: [(hev.create(), hev.create()) for _ in range(steps)] for k in kernel_ids}
     t0 = time.perf_counter()
     for s in range(steps):
@@ -158,7 +189,7 @@ def timed_step(d, steps, warmup, hev, ids=None):
     if ids is None:
         ids = [dsv.KERNEL_ROWS, dsv.KERNEL_TILES, dsv.KERNEL_MERGE, dsv.KERNEL_PLAN, dsv.KERNEL_MIXED,
                dsv.KERNEL_STAGE]
-    _, probe = time_attention(d, max(min(steps, 5), 2), warmup, ids, hev)
+    _, probe = time_attention(d, max(min(steps, 5), 2), warmup, ids, hev, min_warm_ms=20.0)
     dominant = max((k for k in ids if probe[k] is not None), key=lambda k: probe[k])
     sec, main = time_attention(d, steps, 2, [dominant], hev)
     per_kernel = dict(probe)
@@ -368,6 +399,31 @@ def bench_fp8kv(steps, warmup, hev):
     return out
 
 
+def bench_tiles_cu_sweep(threads, hev):
+    """Config 3's four prefill spans alone (no decodes: the MFMA kernel's own launch, persistent
+    workgroups), with the grid held to 256, 128 and 64 workgroups (DSV_TILES_WGS): kernel time and
+    TFLOP/s per compute unit in use."""
+    import paper_2504_09285_amd as dsv
+    from workloads import gen
+    full = gen.config3(threads=threads)
+    n = 4
+    b = gen.AttnBatch("c3_spans_only", full.Hq, full.Hkv, full.D, full.scale, full.q[:full.q_offsets[n]], full.k_pool,
+                      full.v_pool, full.block_tables[:n], full.q_offsets[:n + 1], full.ctx_lens[:n])
+    d = upload(b)
+    flops = prefill_flops(b)
+    out = {}
+    for wgs in (256, 128, 64):
+        os.environ["DSV_TILES_WGS"] = str(wgs)
+        try:
+            _, pk = time_attention(d, 20, 3, [dsv.KERNEL_TILES], hev, min_warm_ms=30.0)
+        finally:
+            del os.environ["DSV_TILES_WGS"]
+        ms = pk[dsv.KERNEL_TILES]
+        out["%d_workgroups" % wgs] = {"ms": ms, "TFLOP/s": flops / (ms * 1e-3) / 1e12,
+                                      "TFLOP/s_per_compute_unit": flops / (ms * 1e-3) / 1e12 / wgs}
+    return out
+
+
 def bench_config4(threads, steps, warmup, hev):
     """Config 4: the split prompt's prefix reaches its second span through GPU pack/unpack, then
     one mixed batch (two prefill spans + 128 decodes).  Reports the hand-off time and the step."""
@@ -408,25 +464,45 @@ def bench_config4(threads, steps, warmup, hev):
             "handoff_pack_unpack_ms": handoff_ms, "handoff_chunks": int(len(sp.chunks)),
             "decode": {"GB/s": nbytes / (rows_ms * 1e-3) / 1e9, "frac_hbm_peak": nbytes / (rows_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
             "prefill": {"TFLOP/s": flops / (tiles_ms * 1e-3) / 1e12, "frac_mfma_peak": flops / (tiles_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
-            "bound_ms": {"hbm": t_mem * 1e3, "mfma": t_mfma * 1e3},
+            "bound_ms": {"hbm": t_mem * 1e3, "mfma": t_mfma * 1e3}, "decode_bytes": nbytes, "prefill_flops": flops,
             "frac_of_overlap_bound": max(t_mem, t_mfma) / sec}
 
 
+def device_handoff(h):
+    """Device side of a hand-off whose pools are not generated on the host (gen ... pools=False):
+    the pools are filled with seeded N(0,1) on the device."""
+    import torch
+    import paper_2504_09285_amd as dsv
+    g = torch.Generator(device="cuda")
+    g.manual_seed(92855)
+
+    def pool(shape):
+        t = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+        for l in range(shape[0]):                              # layer by layer: no fp32 copy of the whole pool
+            t[l] = torch.randn(shape[1:], generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        return t
+    d = argparse.Namespace()
+    d.h = h
+    d.src = dsv.KVPool(pool(h.src_k), pool(h.src_v))
+    d.dst = dsv.KVPool(pool(h.dst_k), pool(h.dst_v))
+    d.st, d.dt = torch.from_numpy(h.src_tables).cuda(), torch.from_numpy(h.dst_tables).cuda()
+    d.descs = dsv.ChunkDescs(h.chunks)
+    d.buf = torch.empty(h.chunk_elems, dtype=torch.bfloat16, device="cuda")
+    return d
+
+
 def bench_concurrent(b, h, rounds, hev):
-    """Attention on one stream, pack+unpack on a second one (config 5): each alone, then together."""
+    """Config 5 as stated: attention on one stream while the hand-off (pack + unpack of every
+    layer) runs on a second one.  Each alone, then together: wall time of the whole, and the
+    attention step's own latency (events on its stream) alone and under the concurrent hand-off,
+    for the full-rate copy and for copies held to a share of the compute units
+    (DSV_COPY_MAX_WGS: resident workgroups of the copy kernel)."""
     import torch
     import paper_2504_09285_amd as dsv
     d = upload(b)
-
-    def dev_bf16(u16):
-        return torch.from_numpy(np.ascontiguousarray(u16).view(np.int16)).cuda().view(torch.bfloat16)
-
-    src = dsv.KVPool(dev_bf16(h.src_k), dev_bf16(h.src_v))
-    dst = dsv.KVPool(dev_bf16(h.dst_k), dev_bf16(h.dst_v))
-    st, dt = torch.from_numpy(h.src_tables).cuda(), torch.from_numpy(h.dst_tables).cuda()
-    descs = dsv.ChunkDescs(h.chunks)
-    buf = torch.empty(h.chunk_elems, dtype=torch.bfloat16, device="cuda")
+    c = device_handoff(h)
     s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    p1, p2 = s1.cuda_stream, s2.cuda_stream
 
     def attn():
         bb = d.b
@@ -434,27 +510,109 @@ def bench_concurrent(b, h, rounds, hev):
                              bb.ctx_lens, bb.Hq, bb.scale, d.workspace, stream=s1)
 
     def copy():
-        dsv.kv_pack_chunks(src, st, descs, buf, stream=s2)
-        dsv.kv_unpack_chunks(buf, descs, dst, dt, stream=s2)
+        dsv.kv_pack_chunks(c.src, c.st, c.descs, c.buf, stream=s2)
+        dsv.kv_unpack_chunks(c.buf, c.descs, c.dst, c.dt, stream=s2)
 
-    def timed(fns):
+    def wall(fns, n):
         for f in fns:
             f()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(rounds):
+        for _ in range(n):
             for f in fns:
                 f()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / rounds
+        return (time.perf_counter() - t0) / n
 
-    ta, tc, tb = timed([attn]), timed([copy]), timed([attn, copy])
+    def attn_latency(with_copy, steps):
+        """Mean GPU time of an attention step (events around each call on its stream), with the
+        hand-off looping on the other stream or not."""
+        torch.cuda.synchronize()
+        evs = [(hev.create(), hev.create()) for _ in range(steps)]
+        if with_copy:
+            copy()                                           # in flight before the first step starts
+        for k, (e0, e1) in enumerate(evs):
+            hev.record(e0, p1)
+            attn()
+            hev.record(e1, p1)
+            if with_copy and k % 2 == 1:
+                copy()                                       # keep the second stream busy throughout
+        torch.cuda.synchronize()
+        ms = [hev.elapsed_ms(e0, e1) for e0, e1 in evs]
+        for e0, e1 in evs:
+            hev.destroy(e0)
+            hev.destroy(e1)
+        return float(np.mean(ms[1:])), float(np.max(ms[1:]))
+
+    ta, tc = wall([attn], rounds), wall([copy], max(rounds // 2, 2))
+    # together: one hand-off next to as many attention steps as fit its length
+    k = max(1, int(round(tc / ta)))
+    tb = wall([copy] + [attn] * k, max(rounds // 2, 2))
     ab, cb = decode_bytes(b, 2), 4 * h.payload_bytes
-    return {"attention": b.name, "handoff": h.name, "handoff_layers": h.L,
-            "attn_alone_ms": ta * 1e3, "handoff_alone_ms": tc * 1e3, "together_ms": tb * 1e3,
-            "attn_alone_GB/s": ab / ta / 1e9, "handoff_alone_GB/s": cb / tc / 1e9,
-            "together_GB/s": (ab + cb) / tb / 1e9, "together_frac_hbm_peak": (ab + cb) / tb / 1e9 / HBM_PEAK_GBS,
-            "overlap_gain": (ta + tc) / tb}
+    out = {"attention": b.name, "handoff": h.name, "handoff_layers": h.L, "handoff_payload_bytes": h.payload_bytes,
+           "attn_alone_ms": ta * 1e3, "handoff_alone_ms": tc * 1e3, "attn_steps_per_handoff": k,
+           "together_ms": tb * 1e3, "sum_alone_ms": (k * ta + tc) * 1e3,
+           "attn_alone_GB/s": ab / ta / 1e9, "handoff_alone_GB/s": cb / tc / 1e9,
+           "together_GB/s": (k * ab + cb) / tb / 1e9, "together_frac_hbm_peak": (k * ab + cb) / tb / 1e9 / HBM_PEAK_GBS,
+           "overlap_gain": (k * ta + tc) / tb}
+    lat = {}
+    lat["alone"] = dict(zip(("mean_ms", "max_ms"), attn_latency(False, 12)))
+    for share in (0, 128, 64, 32):                            # 0: the copy takes what it can get
+        if share:
+            os.environ["DSV_COPY_MAX_WGS"] = str(share * 8)  # workgroups of the copy kernel in flight
+        try:
+            mean, worst = attn_latency(True, 12)
+            t_copy = wall([copy], 2)
+        finally:
+            os.environ.pop("DSV_COPY_MAX_WGS", None)
+        lat["copy_unlimited" if not share else "copy_max_%d_workgroups" % (share * 8)] = {
+            "attn_mean_ms": mean, "attn_max_ms": worst, "handoff_alone_ms": t_copy * 1e3,
+            "handoff_alone_GB/s": cb / t_copy / 1e9}
+    out["attn_step_latency"] = lat
+    return out
+
+
+# ---------------------------------------------------------------------------- ceilings
+def measure_ceilings(hev):
+    """What this GPU delivers on the plainest loops, through the library's calibration kernels:
+    HBM read / write / copy over 2 GiB with kv_copy_kernel's launch shape and hints, and a
+    register-resident bf16 MFMA loop at the prefill kernel's occupancy."""
+    import torch
+    import paper_2504_09285_amd as dsv
+    n = 2 << 30
+    src = torch.full((n,), 1, dtype=torch.uint8, device="cuda")
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(16, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream or None
+
+    def timed(fn, reps=5):
+        fn()
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = hev.create(), hev.create()
+        best = 1e30
+        for _ in range(3):
+            hev.record(e0, stream)
+            for _ in range(reps):
+                fn()
+            hev.record(e1, stream)
+            torch.cuda.synchronize()
+            best = min(best, hev.elapsed_ms(e0, e1) / reps)
+        hev.destroy(e0)
+        hev.destroy(e1)
+        return best
+    out = {"nominal": {"hbm_GB/s": HBM_PEAK_GBS, "mfma_bf16_TFLOP/s": MFMA_BF16_PEAK_TFLOPS}, "bytes": n}
+    for name, mode, moved in (("read", 0, n), ("write", 1, n), ("copy", 2, 2 * n)):
+        ms = timed(lambda: dsv.dsv_calib_hbm(mode, dst, src, n))
+        out["hbm_%s_GB/s" % name] = moved / (ms * 1e-3) / 1e9
+    flops = [0.0]
+
+    def mfma():
+        flops[0] = dsv.dsv_calib_mfma(4000, sink)
+    ms = timed(mfma, reps=2)
+    out["mfma_bf16_TFLOP/s"] = flops[0] / (ms * 1e-3) / 1e12
+    del src, dst
+    return out
 
 
 # ---------------------------------------------------------------------------- CPU baseline
@@ -478,9 +636,29 @@ def cpu_baseline(b, target_seconds=12.0):
         done_tokens += int(qo[-1])
         used += len(idx)
     return {"value": done_tokens / elapsed, "unit": "tokens/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "seconds": elapsed,
+            "kind": "oracle", "seconds": elapsed, "workload": b.name,
             "sample": "%d sequences (%.1f passes over the %d of %s; %d query tokens), all heads"
                       % (used, used / n, n, b.name, done_tokens)}
+
+
+def cpu_baseline_handoff(threads):
+    """The oracle's pack + unpack (memcpy per token row) on config 5's hand-off geometry with two
+    of the 32 layers: 8 x 8,192 tokens in 256-token chunks, 0.54 GB of payload."""
+    import oracle
+    from workloads import gen
+    oracle.build()
+    h = gen.config5_handoff(layers=2, threads=threads)
+    buf = np.zeros(h.chunk_elems, np.uint16)
+    dk, dv = h.dst_k, h.dst_v
+    t0 = time.perf_counter()
+    oracle.kv_pack_chunks(h.src_k, h.src_v, h.src_tables, h.chunks, buf)
+    oracle.kv_unpack_chunks(buf, h.chunks, dk, dv, h.dst_tables)
+    sec = time.perf_counter() - t0
+    tok_layers = int(h.chunks[:, 2].sum()) * h.L
+    return {"value": 4 * h.payload_bytes / sec / 1e9, "unit": "GB/s (pack + unpack, bytes read + written)",
+            "kv_token_layers_per_s": 2 * tok_layers / sec, "cores": oracle.num_threads(), "kind": "oracle",
+            "seconds": sec, "workload": h.name,
+            "sample": "pack + unpack of 8 x 8192 tokens x 2 of 32 layers (%d bytes of payload)" % h.payload_bytes}
 
 
 # ---------------------------------------------------------------------------- main
@@ -499,15 +677,41 @@ def make_workload(name, threads):
     raise SystemExit("unknown workload " + name)
 
 
+def roofline_entry(kernel, workload, bound, achieved, unit, ms, algorithmic, note=None):
+    peak = HBM_PEAK_GBS if bound == "hbm" else MFMA_BF16_PEAK_TFLOPS
+    traffic, source = profile_traffic(kernel, workload)
+    e = {"kernel": kernel, "workload": workload, "bound": bound, "achieved": achieved, "peak": peak,
+         "unit": unit, "frac": achieved / peak, "ms": ms,
+         ("algorithmic_bytes" if bound == "hbm" else "algorithmic_flops"): algorithmic,
+         "traffic": traffic}
+    if source:
+        e["traffic_source"] = source
+    if note:
+        e["note"] = note
+    return e
+
+
+def attention_rooflines(res, b):
+    out = []
+    k = res["kernel_ms"]
+    if "decode" in res:
+        p = res["decode"]
+        out.append(roofline_entry("rows_kernel", b.name, "hbm", p["GB/s"], "GB/s", k["rows"], p["algorithmic_bytes"]))
+    if "prefill" in res:
+        p = res["prefill"]
+        out.append(roofline_entry("prefill_tiles_kernel", b.name, "mfma", p["TFLOP/s"], "TFLOP/s", k["tiles"],
+                                  p["algorithmic_flops"]))
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5", "lp"])
+    ap.add_argument("--workload", default="c5", choices=["c2", "c3", "c4", "c5", "lp"])
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--full-extras", action="store_true", help="config 5 at full context lengths (16 GB of KV)")
     ap.add_argument("--fp8kv-only", action="store_true",
                     help="run only the second workload (8-bit KV cache) and print its results")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -535,6 +739,7 @@ def main():
     if args.fp8kv_only:
         print(json.dumps({"fp8kv": bench_fp8kv(args.steps, args.warmup, hev)}))
         return
+    from workloads import gen
 
     b = make_workload(args.workload, threads)
     res, d = bench_attention(b, args.steps, args.warmup, hev)
@@ -548,74 +753,103 @@ def main():
                    "kv_tokens": int(b.ctx_lens.sum()), "out_dtype": "bf16"},
         "kernel_ms": res["kernel_ms"],
     }
-    if "prefill" in res and (args.workload in ("c3", "lp")):
-        p = res["prefill"]
-        line["roofline"] = {"bound": "mfma", "achieved": p["TFLOP/s"], "peak": MFMA_BF16_PEAK_TFLOPS,
-                            "unit": "TFLOP/s", "frac": p["frac_mfma_peak"], "traffic": None,
-                            "kernel": "prefill_tiles_kernel"}
-    elif "decode" in res:
-        p = res["decode"]
-        line["roofline"] = {"bound": "hbm", "achieved": p["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                            "frac": p["frac_hbm_peak"], "traffic": MEASURED_TRAFFIC_BYTES.get(b.name),
-                            "kernel": "rows_kernel",
-                            "algorithmic_bytes": p["algorithmic_bytes"]}
-    if "prefill" in res:
-        line["prefill"] = res["prefill"]
-    if "decode" in res:
-        line["decode"] = res["decode"]
+    own = attention_rooflines(res, b)
+    prefer = "prefill_tiles_kernel" if args.workload in ("c3", "lp") else "rows_kernel"
+    main_rf = next((e for e in own if e["kernel"] == prefer), own[0] if own else None)
+    if main_rf:
+        line["roofline"] = {k: main_rf[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel")}
+        for k in ("traffic_source", "algorithmic_bytes", "algorithmic_flops"):
+            if k in main_rf:
+                line["roofline"][k] = main_rf[k]
+    rooflines = list(own)
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(b, 10.0)
+    if args.workload == "c2" and not args.no_extras:
+        shared = bench_shared_plan(d, 32, 6, 1)
+    del d, b
 
     if not args.no_extras:
-        from workloads import gen
         extras = {}
-        if args.workload == "c2":
-            # the same batch with the work lists built once per 32 layer calls
-            extras["c2_one_plan_per_32_layers"] = bench_shared_plan(d, 32, 6, 1)
-        h = gen.config5_handoff(layers=4, threads=threads)     # 8 x 8192 tokens, 256-token chunks, 4 of 32 layers
-        extras["handoff_c5_4layers"] = bench_handoff(h, 10, 2, hev)
-        del h
-        if args.workload != "c3":
-            r3, d3 = bench_attention(gen.config3(threads=threads), 40, 5, hev)
-            extras["c3_prefill_heavy"] = {k: r3[k] for k in ("ms_per_step", "tokens_per_s", "mixed_launch_ms", "ms_per_step_kernels_apart", "kernel_ms", "prefill", "decode") if k in r3}
-            del d3
+        cpu = []
+        line["ceilings"] = measure_ceilings(hev)
         keys = ("ms_per_step", "tokens_per_s", "mixed_launch_ms", "ms_per_step_kernels_apart", "kernel_ms", "prefill", "decode")
+
+        def other(name, bb, steps, cpu_seconds=0.0, shared_plan=False):
+            r, dd = bench_attention(bb, steps, 5, hev)
+            extras[name] = {k: r[k] for k in keys if k in r}
+            rooflines.extend(attention_rooflines(r, bb))
+            if shared_plan:
+                extras[name + "_one_plan_per_32_layers"] = bench_shared_plan(dd, 32, 6, 1)
+            if cpu_seconds and not args.no_cpu_baseline:
+                cpu.append(cpu_baseline(bb, cpu_seconds))
+            del dd
+        if args.workload != "c2":
+            other("c2_decode_heavy", gen.config2(threads=threads), 100, 3.0, shared_plan=True)
+        else:
+            extras["c2_decode_heavy_one_plan_per_32_layers"] = shared
+        if args.workload != "c3":
+            other("c3_prefill_heavy", gen.config3(threads=threads), 40, 4.0)
+        if args.workload != "c5":
+            other("c5_long_context", gen.config5_attention(threads=threads), 20, 3.0)
         # config 3's segments with the head counts of the models the paper serves (Qwen-2.5-14B/32B:
         # 40 query heads on 8 KV heads, five per KV head)
-        rq, dq = bench_attention(gen.config3_heads(40, 8, threads=threads), 30, 5, hev)
-        extras["c3_segments_40q_8kv_heads"] = {k: rq[k] for k in keys if k in rq}
-        del dq
-        r1, d1 = bench_attention(gen.config1()[0], 20, 3, hev)          # the tiny case: launch-bound
-        extras["c1_tiny"] = {k: r1[k] for k in keys if k in r1}
-        del d1
-        if args.workload != "c5":
-            r5, d5 = bench_attention(gen.config5_attention(threads=threads), 20, 3, hev)   # full contexts, one layer
-            extras["c5_long_context"] = {k: r5[k] for k in keys if k in r5}
-            del d5
-        extras["kv_append_c3"] = bench_append(gen.config3(threads=threads), 20, 3, hev)
-        extras["c4_micro_request"] = bench_config4(threads, 40, 5, hev)
-        extras["fp8kv"] = bench_fp8kv(20, 3, hev)
+        other("c3_segments_40q_8kv_heads", gen.config3_heads(40, 8, threads=threads), 30)
+        other("c1_tiny", gen.config1()[0], 20, 1.0)              # the tiny case: launch-bound
         # A 512-token chunk on a 130,560-token prefix: eight query tiles, cut along the context.
-        rl, dl = bench_attention(gen.long_prefix_chunk(threads=threads), 30, 5, hev)
-        extras["long_prefix_chunk"] = {k: rl[k] for k in ("ms_per_step", "tokens_per_s", "kernel_ms", "prefill") if k in rl}
-        del dl
+        other("long_prefix_chunk", gen.long_prefix_chunk(threads=threads), 30)
+        # Config 4: the mixed batch against its overlap bound, and the two kernels apart.
+        c4 = bench_config4(threads, 40, 5, hev)
+        extras["c4_micro_request"] = c4
+        rooflines.append({"kernel": "mixed_kernel", "workload": c4["workload"], "bound": "max(hbm, mfma): perfect overlap",
+                          "t_hbm_ms": c4["bound_ms"]["hbm"], "t_mfma_ms": c4["bound_ms"]["mfma"], "ms": c4["ms_per_step"],
+                          "frac": c4["frac_of_overlap_bound"], "unit": "fraction of the step's overlap bound",
+                          "achieved": c4["frac_of_overlap_bound"], "peak": 1.0, "traffic": None})
+        rooflines.append(roofline_entry("rows_kernel", c4["workload"], "hbm", c4["decode"]["GB/s"], "GB/s",
+                                        c4["kernel_ms"]["rows"], c4["decode_bytes"], note="launched apart from the tiles"))
+        rooflines.append(roofline_entry("prefill_tiles_kernel", c4["workload"], "mfma", c4["prefill"]["TFLOP/s"], "TFLOP/s",
+                                        c4["kernel_ms"]["tiles"], c4["prefill_flops"], note="launched apart from the rows"))
+        if not args.no_cpu_baseline:
+            cpu.append(cpu_baseline(gen.config4(threads=threads)[0], 3.0))
+        # Hand-off with config 5's geometry, 4 of the 32 layers (2.15 GB moved per direction).
+        h = gen.config5_handoff(layers=4, threads=threads)
+        ho = bench_handoff(h, 10, 2, hev)
+        extras["handoff_c5_4layers"] = ho
+        for name in ("pack", "unpack"):
+            rooflines.append(roofline_entry("kv_copy_kernel_" + name, "c5_handoff", "hbm", ho[name]["GB/s"], "GB/s",
+                                            ho[name]["ms"], 2 * h.payload_bytes, note="4 of 32 layers"))
+        del h
+        ap3 = bench_append(gen.config3(threads=threads), 20, 3, hev)
+        extras["kv_append_c3"] = ap3
+        rooflines.append(roofline_entry("kv_append_kernel", "c3_prefill_heavy", "hbm", ap3["GB/s"], "GB/s", ap3["ms"], ap3["bytes"]))
+        f8 = bench_fp8kv(20, 3, hev)
+        extras["fp8kv"] = f8
+        r8 = f8["c2_decode_heavy_fp8kv"]
+        rooflines.append(roofline_entry("rows_kernel_fp8kv", "c2_decode_heavy", "hbm", r8["decode"]["GB/s"], "GB/s",
+                                        r8["kernel_ms"]["rows"], r8["decode"]["algorithmic_bytes"]))
+        if not args.no_cpu_baseline:
+            cpu.append(cpu_baseline_handoff(threads))
+        # Config 5 as stated: attention at full context lengths next to the 32-layer hand-off.
+        extras["c5_two_streams"] = bench_concurrent(gen.config5_attention(threads=threads),
+                                                    gen.config5_handoff(threads=threads, pools=False), 6, hev)
+        # The MFMA kernel on fewer compute units (config 3's spans alone): what a compute unit
+        # delivers when fewer of them run, i.e. how far the whole chip holds the kernel back.
+        extras["prefill_tiles_vs_compute_units"] = bench_tiles_cu_sweep(threads, hev)
         # Chunk-pipelined hand-off (paper section 4.3): transfer of chunk k next to computation of k+1.
         from paper_2504_09285_amd.chunk_pipeline import measure as measure_chunk_pipeline
         extras["chunk_pipelined_handoff"] = measure_chunk_pipeline(8192, 512, 8)
-        # The local scheduler's profile table (paper section 4.2) on the grid of the paper's
-        # batch-latency figure: prefill length x decode context x number of decodes -> step ms.
+        # The local scheduler's profile table (paper section 4.2): prefill length x decode context x
+        # number of decodes -> step ms, and the prefill budget it gives under latency targets.
         from paper_2504_09285_amd.local_scheduler import ProfileTable, sweep
-        tbl = sweep(ProfileTable(plen_step=512), plens=(0, 512, 1024), ctxs=(128, 1024), dnums=(8, 32, 64), steps=5)
+        tbl = sweep(ProfileTable(plen_step=512), plens=(0, 512, 1024, 2048, 4096), ctxs=(1024, 4096), dnums=(32, 128), steps=5)
         extras["profile_table_ms"] = {"plen=%d,ctx=%d,dnum=%d" % k: round(v, 4) for k, v in sorted(tbl.entries().items())}
-        extras["max_prefill_allowed"] = {"target_ms=0.1,ctx=1024,dnum=32": tbl.max_prefill_allowed(0.1, 1024, 32),
-                                         "target_ms=0.2,ctx=1024,dnum=32": tbl.max_prefill_allowed(0.2, 1024, 32)}
-        if args.full_extras:
-            extras["c5_two_streams"] = bench_concurrent(gen.config5_attention(threads=threads),
-                                                        gen.config5_handoff(layers=8, threads=threads), 5, hev)
-        else:
-            extras["c5_two_streams_quarter_contexts"] = bench_concurrent(
-                gen.config5_attention(shrink=4, threads=threads), gen.config5_handoff(layers=4, threads=threads), 5, hev)
+        extras["max_prefill_allowed"] = {"target_ms=%.2f,ctx=%d,dnum=%d" % (t, c, n): tbl.max_prefill_allowed(t, c, n)
+                                         for t in (0.1, 0.2, 0.4) for c, n in ((1024, 32), (4096, 128))}
+        line["rooflines"] = rooflines
+        if cpu:
+            line["cpu_baselines"] = cpu
         line["extras"] = extras
-    if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(b)
+    else:
+        line["rooflines"] = rooflines
     print(json.dumps(line))
 
 

@@ -10,6 +10,8 @@
 // block tables and queries from L2).  A
 // token's row (all KV heads) is num_kv_heads*head_dim*2 bytes, contiguous in the chunk and in
 // the pool; consecutive tokens are contiguous in the chunk and, inside one block, in the pool.
+#include <stdlib.h>
+
 #include "dsv_common.h"
 
 namespace dsv {
@@ -35,21 +37,24 @@ struct CopyParams {
   int32_t upr;                   // 16-byte units per token row
   int32_t upr_shift;             // log2(upr) or -1
   int32_t off_shift;             // chunk_offset (elements) -> units: 3 for 2-byte, 4 for 1-byte elements
+  uint32_t total_wgs;            // work items (chunk, plane, tile); the grid may be smaller and loop
 };
 
 // PACK = true: pool -> chunk.  PACK = false: chunk -> pool.
 template <bool PACK>
 __global__ __launch_bounds__(kCopyThreads) void kv_copy_kernel(CopyParams p) {
-  // blockIdx.x = (chunk * 2L + plane) * tiles_per_chunk + tile, plane = layer*2 + (K=0|V=1)
+  // work item w = (chunk * 2L + plane) * tiles_per_chunk + tile, plane = layer*2 + (K=0|V=1).
+  // Normally one workgroup per item; a launch held to fewer workgroups (see run_copy) strides.
   const uint32_t planes = 2u * (uint32_t)p.num_layers;
-  const uint32_t tile = blockIdx.x % (uint32_t)p.tiles_per_chunk;
-  const uint32_t cp = blockIdx.x / (uint32_t)p.tiles_per_chunk;
+  for (uint32_t w = blockIdx.x; w < p.total_wgs; w += gridDim.x) {
+  const uint32_t tile = w % (uint32_t)p.tiles_per_chunk;
+  const uint32_t cp = w / (uint32_t)p.tiles_per_chunk;
   const uint32_t plane = cp % planes;
   const uint32_t c = cp / planes;
 
   const dsv_chunk_desc d = p.descs[c];
   const int tok0 = (int)tile * p.tile_tokens;
-  if (tok0 >= d.num_tokens) return;
+  if (tok0 >= d.num_tokens) continue;
   const int ntok = min(p.tile_tokens, d.num_tokens - tok0);
 
   unit_t* pool = ((plane & 1u) ? p.pool_v : p.pool_k) + (int64_t)(plane >> 1) * p.layer_stride_u;
@@ -82,6 +87,7 @@ __global__ __launch_bounds__(kCopyThreads) void kv_copy_kernel(CopyParams p) {
       if (idx[k] < total) {
         __builtin_nontemporal_store(v[k], PACK ? &chunk[idx[k]] : &pool[pool_u[k]]);
       }
+  }
   }
 }
 
@@ -125,8 +131,16 @@ int run_copy(bool pack, const dsv_kv_pool* pool, const int32_t* block_tables, in
   p.tile_tokens = p.upr >= kTileUnits ? 1 : kTileUnits / p.upr;
   p.tiles_per_chunk = ceil_div(max_tokens, p.tile_tokens);
   p.upr_shift = (p.upr & (p.upr - 1)) == 0 ? __builtin_ctz((unsigned)p.upr) : -1;
-  const int64_t grid = (int64_t)num_chunks * 2 * pool->num_layers * p.tiles_per_chunk;
+  int64_t grid = (int64_t)num_chunks * 2 * pool->num_layers * p.tiles_per_chunk;
   if (grid > 0x7fffffffLL) return DSV_E_UNSUPPORTED;
+  p.total_wgs = (uint32_t)grid;
+  // A hand-off that runs next to attention on another stream (paper section 4.3: transfers must
+  // not stall computation) can be held to a number of workgroups in flight, which caps the
+  // share of the memory system it takes: DSV_COPY_MAX_WGS workgroups then stride over the items.
+  if (const char* e = getenv("DSV_COPY_MAX_WGS")) {
+    const long cap = atol(e);
+    if (cap > 0 && cap < grid) grid = cap;
+  }
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   begin_gpu_work();
   if (pack)

@@ -244,12 +244,16 @@ def make_chunks(ranges: Sequence[Tuple[int, int, int]], chunk_tokens: int, L: in
 
 def make_handoff(name: str, seed: int, L: int, Hkv: int, D: int, req_tokens: Sequence[int],
                  ranges: Sequence[Tuple[int, int, int]], chunk_tokens: int,
-                 free_frac: float = 0.10, threads: int = 8) -> Handoff:
+                 free_frac: float = 0.10, threads: int = 8, pools: bool = True) -> Handoff:
+    """``pools=False``: tables and chunk descriptors only; the four pool fields then hold the pools'
+    shapes (tuples) instead of arrays, for a caller that fills the pools on the device."""
     src_tables, nb_s = build_block_tables(seed, TID_SRC_PERM, req_tokens, free_frac)
     dst_tables, nb_d = build_block_tables(seed, TID_DST_PERM, req_tokens, free_frac)
     shp_s = (L, nb_s, BLOCK_SIZE, Hkv, D)
     shp_d = (L, nb_d, BLOCK_SIZE, Hkv, D)
     chunks, n_el = make_chunks(ranges, chunk_tokens, L, Hkv, D)
+    if not pools:
+        return Handoff(name, L, Hkv, D, shp_s, shp_s, src_tables, shp_d, shp_d, dst_tables, chunks, n_el)
     return Handoff(name, L, Hkv, D,
                    normal_bf16(seed, TID_SRC_K, shp_s, threads), normal_bf16(seed, TID_SRC_V, shp_s, threads),
                    src_tables,
@@ -351,14 +355,14 @@ def config5_attention(shrink: int = 1, threads: int = 8) -> AttnBatch:
                       threads=threads, meta={"shrink": shrink})
 
 
-def config5_handoff(shrink: int = 1, layers: int = 32, threads: int = 8) -> Handoff:
+def config5_handoff(shrink: int = 1, layers: int = 32, threads: int = 8, pools: bool = True) -> Handoff:
     """8 requests x 8192 tokens x 32 layers, 256-token chunks, into a second pool whose block
     table comes from a different seeded permutation."""
     seed = seed_for(5)
     n_req = max(8 // shrink, 2)
     tok = 8192 // shrink
     return make_handoff("c5_handoff", seed, layers, 8, 128, [tok] * n_req,
-                        [(r, 0, tok) for r in range(n_req)], 256, threads=threads)
+                        [(r, 0, tok) for r in range(n_req)], 256, threads=threads, pools=pools)
 
 
 # ---- the 8-bit KV variant of the same shapes (second workload) -----------------------------------
