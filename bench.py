@@ -317,8 +317,10 @@ def bench_handoff(h, steps, warmup, hev):
     buf = torch.empty(h.chunk_elems, dtype=torch.bfloat16, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream or None
     out = {}
+    ows = torch.empty(dsv.kv_unpack_chunks_ordered_workspace_bytes(dst.NB), dtype=torch.uint8, device="cuda")
     for name, fn in (("pack", lambda: dsv.kv_pack_chunks(src, st, descs, buf)),
-                     ("unpack", lambda: dsv.kv_unpack_chunks(buf, descs, dst, dt))):
+                     ("unpack", lambda: dsv.kv_unpack_chunks(buf, descs, dst, dt)),
+                     ("unpack_ordered", lambda: dsv.kv_unpack_chunks_ordered(buf, descs, dst, dt, ows))):
         for _ in range(warmup):
             fn()
         torch.cuda.synchronize()
@@ -814,7 +816,7 @@ def main():
         h = gen.config5_handoff(layers=4, threads=threads)
         ho = bench_handoff(h, 10, 2, hev)
         extras["handoff_c5_4layers"] = ho
-        for name in ("pack", "unpack"):
+        for name in ("pack", "unpack", "unpack_ordered"):
             rooflines.append(roofline_entry("kv_copy_kernel_" + name, "c5_handoff", "hbm", ho[name]["GB/s"], "GB/s",
                                             ho[name]["ms"], 2 * h.payload_bytes, note="4 of 32 layers"))
         del h

@@ -156,6 +156,26 @@ int kv_unpack_chunks(const void* chunk_buf, const dsv_chunk_desc* descs,
                      int32_t max_blocks_per_seq, void* hip_stream);
 
 /*
+ * kv_unpack_chunks with the destination written in ascending block order (paper section 4.3: the
+ * receiver places the chunks; a receiver that took most of a pool's blocks for a hand-off gets
+ * them filled at the rate of a sequential copy, whatever the order of its table).  Same arguments,
+ * same result byte for byte, plus a workspace for the inverse of the block table:
+ *   workspace   device, 8-byte aligned, at least kv_unpack_chunks_ordered_workspace_bytes(
+ *               dst->num_blocks) = 8 bytes per pool block; overwritten by every call
+ * The ordered sweep is used when every chunk starts on a block boundary (token_begin % 16 == 0)
+ * and the chunks cover at least half of the pool's blocks; any other hand-off runs exactly as
+ * kv_unpack_chunks does.  Two rows of the table must not name the same block for tokens of the
+ * hand-off (with kv_unpack_chunks the later writer would win; here the result is undefined).
+ * Errors as for kv_unpack_chunks, DSV_E_WORKSPACE for a workspace too small.
+ */
+size_t kv_unpack_chunks_ordered_workspace_bytes(int32_t num_blocks);
+int kv_unpack_chunks_ordered(const void* chunk_buf, const dsv_chunk_desc* descs,
+                             const dsv_chunk_desc* descs_host, int32_t num_chunks,
+                             const dsv_kv_pool* dst, const int32_t* dst_block_tables,
+                             int32_t max_blocks_per_seq, void* workspace, size_t workspace_bytes,
+                             void* hip_stream);
+
+/*
  * Write the keys/values of the batch's new tokens into layer `layer` of the paged pool, at the
  * positions they occupy (paper section 2.1: prefill populates the KV cache and every decode
  * step appends to it, before attention reads it).  For segment i and its j-th new token the

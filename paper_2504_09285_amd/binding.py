@@ -51,7 +51,7 @@ EXPORTS = ("attn_mixed_batch_workspace_bytes", "attn_mixed_batch", "kv_pack_chun
            "attn_mixed_batch_fp8kv", "kv_append_fp8", "kv_pack_chunks_fp8", "kv_unpack_chunks_fp8",
            "attn_mixed_batch_plan", "attn_mixed_batch_planned", "attn_mixed_batch_fp8kv_planned",
            "attn_mixed_batch_static", "attn_mixed_batch_static_max_bytes",
-           "dsv_check_block_tables", "dsv_calib_hbm", "dsv_calib_mfma", "dsv_profile_events", "dsv_build_info")
+           "kv_unpack_chunks_ordered", "kv_unpack_chunks_ordered_workspace_bytes", "dsv_check_block_tables", "dsv_calib_hbm", "dsv_calib_mfma", "dsv_profile_events", "dsv_build_info")
 KERNEL_PLAN, KERNEL_ROWS, KERNEL_TILES, KERNEL_MERGE, KERNEL_MIXED, KERNEL_STAGE = 0, 1, 2, 3, 4, 5
 
 
@@ -115,6 +115,10 @@ def load_library():
                                             i32p, i32p, C.c_int32, C.c_int32, C.c_float, C.c_int32, vp]
     lib.attn_mixed_batch_static_max_bytes.restype = C.c_size_t
     lib.attn_mixed_batch_static_max_bytes.argtypes = []
+    lib.kv_unpack_chunks_ordered_workspace_bytes.restype = C.c_size_t
+    lib.kv_unpack_chunks_ordered_workspace_bytes.argtypes = [C.c_int32]
+    lib.kv_unpack_chunks_ordered.restype = C.c_int
+    lib.kv_unpack_chunks_ordered.argtypes = [vp, vp, vp, C.c_int32, C.POINTER(_Pool), vp, C.c_int32, vp, C.c_size_t, vp]
     lib.dsv_check_block_tables.restype = C.c_int
     lib.dsv_check_block_tables.argtypes = [vp, C.c_int32, vp, C.c_int32, C.c_int32, vp, vp]
     lib.dsv_calib_hbm.restype = C.c_int
@@ -374,6 +378,22 @@ def kv_unpack_chunks(chunk_buf, descs: ChunkDescs, dst: KVPool, dst_block_tables
         dst_block_tables.data_ptr(), int(dst_block_tables.shape[1]), _stream_ptr(stream))
     if rc:
         raise DsvError("kv_unpack_chunks", rc)
+
+
+def kv_unpack_chunks_ordered_workspace_bytes(num_blocks: int) -> int:
+    return int(load_library().kv_unpack_chunks_ordered_workspace_bytes(int(num_blocks)))
+
+
+def kv_unpack_chunks_ordered(chunk_buf, descs: ChunkDescs, dst: KVPool, dst_block_tables, workspace,
+                             stream=None) -> None:
+    """See ``kv_unpack_chunks_ordered`` in include/dsv_attn.h."""
+    _copy_tensors(dst, dst_block_tables, descs, chunk_buf, 2)
+    rc = load_library().kv_unpack_chunks_ordered(
+        chunk_buf.data_ptr(), descs.dev.data_ptr(), descs.host.ctypes.data, descs.n, dst.c,
+        dst_block_tables.data_ptr(), int(dst_block_tables.shape[1]), workspace.data_ptr(), _nbytes(workspace),
+        _stream_ptr(stream))
+    if rc:
+        raise DsvError("kv_unpack_chunks_ordered", rc)
 
 
 def dsv_check_block_tables(block_tables, tokens_per_seq, num_blocks, result, stream=None) -> None:

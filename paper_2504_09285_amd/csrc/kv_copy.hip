@@ -91,9 +91,63 @@ __global__ __launch_bounds__(kCopyThreads) void kv_copy_kernel(CopyParams p) {
   }
 }
 
+// ---- unpack in the order of the destination ------------------------------------------------------
+// Scattered 32 KiB destination blocks cost the plain unpack a tenth of the rate a sequential
+// destination gets (writes that keep opening new DRAM rows; reads from scattered blocks, as in
+// pack, do not suffer).  When the hand-off fills most of the destination pool, sweeping the pool's
+// blocks in ascending order and fetching each one's tokens from wherever they sit in the chunk
+// buffer turns the scattered side into the read side.  That needs the inverse of the block table
+// for the blocks the chunks touch: inv[b] = (chunk, 16-token block within the chunk), built on the
+// device into a caller-provided workspace by the two small kernels below.
+__global__ void inv_init_kernel(int2* inv, int32_t num_blocks) {
+  const int b = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+  if (b < num_blocks) inv[b] = make_int2(-1, 0);
+}
+
+// grid (ceil(max blocks per chunk / 256), num_chunks)
+__global__ void inv_build_kernel(int2* inv, int32_t num_blocks, const dsv_chunk_desc* __restrict__ descs,
+                                 const int32_t* __restrict__ tables, int32_t max_blocks) {
+  const dsv_chunk_desc d = descs[blockIdx.y];
+  const int j = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+  if (j * kBlockSize >= d.num_tokens) return;
+  const int32_t b = tables[(int64_t)d.seq * max_blocks + d.token_begin / kBlockSize + j];
+  if (b >= 0 && b < num_blocks) inv[b] = make_int2((int)blockIdx.y, j);   // (an entry outside the pool is not followed)
+}
+
+// Work item w = (plane * num_blocks + block) * tiles_per_block + tile.
+__global__ __launch_bounds__(kCopyThreads) void kv_unpack_ordered_kernel(CopyParams p, const int2* __restrict__ inv,
+                                                                         int32_t num_blocks, int32_t tiles_per_block) {
+  for (uint32_t w = blockIdx.x; w < p.total_wgs; w += gridDim.x) {
+    const uint32_t tile = w % (uint32_t)tiles_per_block;
+    const uint32_t pb = w / (uint32_t)tiles_per_block;
+    const uint32_t b = pb % (uint32_t)num_blocks;
+    const uint32_t plane = pb / (uint32_t)num_blocks;
+    const int2 cj = inv[b];
+    if (cj.x < 0) continue;                                   // a block the hand-off does not touch
+    const dsv_chunk_desc d = p.descs[cj.x];
+    const int slot0 = (int)tile * p.tile_tokens;              // chunks start on block boundaries: slot = token % 16
+    const int tok0 = cj.y * kBlockSize + slot0;               // first token of this item, counted in the chunk
+    if (tok0 >= d.num_tokens) continue;
+    const int ntok = min(min(p.tile_tokens, kBlockSize - slot0), d.num_tokens - tok0);
+    unit_t* pool = ((plane & 1u) ? p.pool_v : p.pool_k) + (int64_t)(plane >> 1) * p.layer_stride_u +
+                   ((int64_t)b * kBlockSize + slot0) * p.upr;
+    const unit_t* chunk = p.chunk_buf + (d.chunk_offset >> p.off_shift) + ((int64_t)plane * d.num_tokens + tok0) * p.upr;
+    const int total = ntok * p.upr;                           // contiguous on both sides
+    for (int u0 = threadIdx.x; u0 < total; u0 += kCopyThreads * kUnroll) {
+      unit_t v[kUnroll];
+#pragma unroll
+      for (int k = 0; k < kUnroll; ++k)
+        if (u0 + k * kCopyThreads < total) v[k] = __builtin_nontemporal_load(&chunk[u0 + k * kCopyThreads]);
+#pragma unroll
+      for (int k = 0; k < kUnroll; ++k)
+        if (u0 + k * kCopyThreads < total) __builtin_nontemporal_store(v[k], &pool[u0 + k * kCopyThreads]);
+    }
+  }
+}
+
 int run_copy(bool pack, const dsv_kv_pool* pool, const int32_t* block_tables, int32_t max_blocks,
              const dsv_chunk_desc* descs, const dsv_chunk_desc* descs_host, int32_t num_chunks,
-             void* chunk_buf, void* hip_stream, int elem_bytes) {
+             void* chunk_buf, void* hip_stream, int elem_bytes, void* ordered_ws = nullptr) {
   // elem_bytes = 2 (bf16 cache) or 1 (8-bit codes): the copy itself only sees 16-byte units.
   const int epu = 16 / elem_bytes;                 // elements per unit
   int rc = check_pool(pool);
@@ -110,12 +164,16 @@ int run_copy(bool pack, const dsv_kv_pool* pool, const int32_t* block_tables, in
       pool->layer_stride < (int64_t)pool->num_blocks * kBlockSize * row_elems)
     return DSV_E_INVALID;
   int max_tokens = 0;
+  bool block_aligned = true;
+  int64_t touched_blocks = 0;
   for (int c = 0; c < num_chunks; ++c) {
     const dsv_chunk_desc& d = descs_host[c];
     if (d.seq < 0 || d.token_begin < 0 || d.num_tokens < 1 || d.reserved != 0) return DSV_E_INVALID;
     if (d.chunk_offset < 0 || (d.chunk_offset % epu)) return DSV_E_INVALID;
     if (ceil_div((int64_t)d.token_begin + d.num_tokens, kBlockSize) > max_blocks) return DSV_E_INVALID;
     if (d.num_tokens > max_tokens) max_tokens = d.num_tokens;
+    if (d.token_begin % kBlockSize) block_aligned = false;
+    touched_blocks += ceil_div(d.num_tokens, kBlockSize);
   }
   CopyParams p;
   p.pool_k = static_cast<unit_t*>(pool->k_base);
@@ -142,6 +200,32 @@ int run_copy(bool pack, const dsv_kv_pool* pool, const int32_t* block_tables, in
     if (cap > 0 && cap < grid) grid = cap;
   }
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  // The destination-ordered form pays when the chunks start on block boundaries (then no block is
+  // shared by two chunks) and fill at least half of the pool (else most of the sweep finds
+  // nothing to do, and blocks far apart share no DRAM row anyway); otherwise the plain form.
+  if (!pack && ordered_ws && block_aligned && 2 * touched_blocks >= pool->num_blocks) {
+    const int tile_tokens = p.tile_tokens < kBlockSize ? p.tile_tokens : kBlockSize;
+    const int tiles_per_block = ceil_div(kBlockSize, tile_tokens);
+    const int64_t items = (int64_t)2 * pool->num_layers * pool->num_blocks * tiles_per_block;
+    if (items <= 0x7fffffffLL) {
+      int2* inv = static_cast<int2*>(ordered_ws);
+      begin_gpu_work();
+      hipLaunchKernelGGL(inv_init_kernel, dim3((unsigned)ceil_div(pool->num_blocks, 256)), dim3(256), 0, stream, inv,
+                         pool->num_blocks);
+      hipLaunchKernelGGL(inv_build_kernel, dim3((unsigned)ceil_div(ceil_div(max_tokens, kBlockSize), 256), (unsigned)num_chunks),
+                         dim3(256), 0, stream, inv, pool->num_blocks, descs, block_tables, max_blocks);
+      p.tile_tokens = tile_tokens;
+      p.total_wgs = (uint32_t)items;
+      int64_t ogrid = items;
+      if (const char* e = getenv("DSV_COPY_MAX_WGS")) {
+        const long cap = atol(e);
+        if (cap > 0 && cap < ogrid) ogrid = cap;
+      }
+      hipLaunchKernelGGL(kv_unpack_ordered_kernel, dim3((unsigned)ogrid), dim3(kCopyThreads), 0, stream, p, inv,
+                         pool->num_blocks, tiles_per_block);
+      return launch_status();
+    }
+  }
   begin_gpu_work();
   if (pack)
     hipLaunchKernelGGL(kv_copy_kernel<true>, dim3((unsigned)grid), dim3(kCopyThreads), 0, stream, p);
@@ -183,4 +267,21 @@ extern "C" int kv_unpack_chunks_fp8(const void* chunk_buf, const dsv_chunk_desc*
                                     int32_t max_blocks_per_seq, void* hip_stream) {
   return dsv::run_copy(false, dst, dst_block_tables, max_blocks_per_seq, descs, descs_host,
                        num_chunks, const_cast<void*>(chunk_buf), hip_stream, 1);
+}
+
+extern "C" size_t kv_unpack_chunks_ordered_workspace_bytes(int32_t num_blocks) {
+  return num_blocks > 0 ? (size_t)num_blocks * sizeof(int2) : 0;
+}
+
+extern "C" int kv_unpack_chunks_ordered(const void* chunk_buf, const dsv_chunk_desc* descs,
+                                        const dsv_chunk_desc* descs_host, int32_t num_chunks,
+                                        const dsv_kv_pool* dst, const int32_t* dst_block_tables,
+                                        int32_t max_blocks_per_seq, void* workspace, size_t workspace_bytes,
+                                        void* hip_stream) {
+  if (!dst || !workspace || (reinterpret_cast<uintptr_t>(workspace) & 7)) return DSV_E_INVALID;
+  if (dst->num_blocks < 1) return DSV_E_INVALID;
+  if (num_chunks > 65535) workspace = nullptr;                 // (one grid row per chunk in the table inversion)
+  else if (workspace_bytes < kv_unpack_chunks_ordered_workspace_bytes(dst->num_blocks)) return DSV_E_WORKSPACE;
+  return dsv::run_copy(false, dst, dst_block_tables, max_blocks_per_seq, descs, descs_host,
+                       num_chunks, const_cast<void*>(chunk_buf), hip_stream, 2, workspace);
 }

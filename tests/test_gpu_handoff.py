@@ -155,3 +155,59 @@ def test_an_error_left_by_an_unrelated_hip_call_is_not_reported_as_a_failed_laun
     assert np.abs(out.cpu().numpy() - ref).max() <= 1e-2
     hip.hipEventDestroy(e0)
     hip.hipEventDestroy(e1)
+
+
+# ------------------------------------------------------------------ unpack in destination order
+def _unpack_ordered_check(h, expect_same_as_plain=True):
+    import torch
+    import paper_2504_09285_amd as dsv
+    from gpu_harness import DeviceHandoff, host_u16
+    d = DeviceHandoff(h)
+    d.pack()
+    ws = torch.full((dsv.kv_unpack_chunks_ordered_workspace_bytes(d.dst.NB) // 8,), -7, dtype=torch.int64, device="cuda")
+    dsv.kv_unpack_chunks_ordered(d.chunk_buf, d.descs, d.dst, d.dst_tables, ws)
+    torch.cuda.synchronize()
+    buf, dk, dv = oracle_handoff(h)
+    np.testing.assert_array_equal(host_u16(d.chunk_buf), buf)
+    np.testing.assert_array_equal(host_u16(d.dst.k), dk)          # every byte of the pool: copied and untouched alike
+    np.testing.assert_array_equal(host_u16(d.dst.v), dv)
+    return d
+
+
+@pytest.mark.parametrize("L,Hkv,D", [(3, 8, 128), (2, 1, 64), (1, 3, 128)])
+def test_unpack_in_destination_order_dense_pool(L, Hkv, D):
+    """Chunks on block boundaries that fill most of the destination pool: the ordered sweep runs.
+    Requests of ragged length (last chunks and last blocks short), 48-token chunks."""
+    req = [200, 77, 16, 1000, 333, 48]
+    h = gen.make_handoff("ord_dense", 51 + D, L, Hkv, D, req, [(r, 0, n) for r, n in enumerate(req)], 48, free_frac=0.05)
+    assert (h.chunks[:, 1] % 16 == 0).all()
+    assert 2 * sum(-(-int(n) // 16) for n in h.chunks[:, 2]) >= h.dst_k.shape[1]
+    _unpack_ordered_check(h)
+
+
+def test_unpack_in_destination_order_config5_geometry():
+    _unpack_ordered_check(gen.config5_handoff(shrink=8, layers=3))
+
+
+def test_unpack_ordered_falls_back_for_sparse_or_unaligned_hand_offs():
+    """A pool mostly untouched by the hand-off, and chunks that start inside blocks: the call runs
+    the plain unpack and gives the same bytes."""
+    req = [300, 90, 500]
+    sparse = gen.make_handoff("ord_sparse", 52, 2, 2, 64, req, [(r, 0, n) for r, n in enumerate(req)], 64, free_frac=3.0)
+    _unpack_ordered_check(sparse)
+    unaligned = gen.make_handoff("ord_unaligned", 53, 2, 2, 64, req, [(0, 5, 290), (1, 17, 80), (2, 0, 500)], 40,
+                                 free_frac=0.05)
+    assert (unaligned.chunks[:, 1] % 16 != 0).any()
+    _unpack_ordered_check(unaligned)
+
+
+def test_unpack_ordered_refuses_a_short_workspace():
+    import torch
+    import paper_2504_09285_amd as dsv
+    from gpu_harness import DeviceHandoff
+    h = gen.make_handoff("ord_ws", 54, 1, 2, 64, [64], [(0, 0, 64)], 32)
+    d = DeviceHandoff(h)
+    ws = torch.zeros(1, dtype=torch.int64, device="cuda")
+    with pytest.raises(dsv.DsvError) as e:
+        dsv.kv_unpack_chunks_ordered(d.chunk_buf, d.descs, d.dst, d.dst_tables, ws)
+    assert e.value.code == -3
