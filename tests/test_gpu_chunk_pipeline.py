@@ -16,11 +16,27 @@ def host_u16(t):
     return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-@pytest.mark.parametrize("pipelined", [True, False])
-def test_pipelined_handoff_matches_the_oracle(pipelined):
-    total, chunk, L, Hq, Hkv, D = 512, 64, 3, 8, 2, 128
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("pipelined,shape,graphs", [(True, (512, 64, 3, 8, 2, 128), False),
+                                                    (False, (512, 64, 3, 8, 2, 128), False),
+                                                    (True, (512, 64, 3, 8, 2, 128), True),
+                                                    (True, (4096, 512, 8, 8, 2, 128), True)])
+def test_pipelined_handoff_matches_the_oracle(pipelined, shape, graphs):
+    """Also with each chunk's computation replayed from a HIP graph (the GPU-bound regime), the
+    larger case at 4,096 tokens in 512-token chunks over 8 layers."""
+    total, chunk, L, Hq, Hkv, D = shape
     p = ChunkedPrefill(total, chunk, L, Hq, Hkv, D, seed=77, dst_fill=0x7FC0)
-    p.run(pipelined)
+    if graphs:
+        p.run(pipelined)                         # eager once: first-call set-up outside any capture
+        p.capture_graphs()
+        p.out.fill_(float("nan"))
+        p.dst.k.view(torch.int16).fill_(0x7FC0)
+        p.dst.v.view(torch.int16).fill_(0x7FC0)
+        p.recv_buf.view(torch.int16).fill_(0)
+        p.run(pipelined)
+        p.run(pipelined)                         # a second replay of every graph
+    else:
+        p.run(pipelined)
     k_new, v_new, q = host_u16(p.k_new), host_u16(p.v_new), host_u16(p.q)
     # Oracle: the source pool after appending every token, then pack + unpack of all chunks.
     nb = total // 16
