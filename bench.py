@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|lp] [--no-extras]
-                    [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c3h|c4|c5|lp] [--no-extras]
+                    [--no-cpu-baseline] [--handoff-only] [--fp8kv-only] [--calibrate-copy]
 
 A step is one attn_mixed_batch call (plan + attention kernels + merge) over one seeded synthetic
 batch that is already resident in HBM.  The headline workload is the largest of the five
@@ -676,6 +676,8 @@ def make_workload(name, threads):
         return gen.config5_attention(threads=threads)
     if name == "lp":
         return gen.long_prefix_chunk(threads=threads)
+    if name == "c3h":
+        return gen.config3_heads(40, 8, threads=threads)
     raise SystemExit("unknown workload " + name)
 
 
@@ -701,8 +703,8 @@ def attention_rooflines(res, b):
         out.append(roofline_entry("rows_kernel", b.name, "hbm", p["GB/s"], "GB/s", k["rows"], p["algorithmic_bytes"]))
     if "prefill" in res:
         p = res["prefill"]
-        out.append(roofline_entry("prefill_tiles_kernel", b.name, "mfma", p["TFLOP/s"], "TFLOP/s", k["tiles"],
-                                  p["algorithmic_flops"]))
+        out.append(roofline_entry("prefill_tiles_persistent_kernel", b.name, "mfma", p["TFLOP/s"], "TFLOP/s", k["tiles"],
+                                  p["algorithmic_flops"], note="the spans' MFMA kernel in a launch of its own"))
     return out
 
 
@@ -711,11 +713,13 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c5", choices=["c2", "c3", "c4", "c5", "lp"])
+    ap.add_argument("--workload", default="c5", choices=["c2", "c3", "c4", "c5", "lp", "c3h"])
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fp8kv-only", action="store_true",
                     help="run only the second workload (8-bit KV cache) and print its results")
+    ap.add_argument("--handoff-only", action="store_true",
+                    help="run only pack / unpack / ordered unpack on config 5's hand-off geometry (4 of 32 layers)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy, 10 times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -742,6 +746,10 @@ def main():
         print(json.dumps({"fp8kv": bench_fp8kv(args.steps, args.warmup, hev)}))
         return
     from workloads import gen
+    if args.handoff_only:
+        print(json.dumps({"handoff_c5_4layers": bench_handoff(gen.config5_handoff(layers=4, threads=threads),
+                                                              max(args.steps, 1), args.warmup, hev)}))
+        return
 
     b = make_workload(args.workload, threads)
     res, d = bench_attention(b, args.steps, args.warmup, hev)
@@ -756,7 +764,7 @@ def main():
         "kernel_ms": res["kernel_ms"],
     }
     own = attention_rooflines(res, b)
-    prefer = "prefill_tiles_kernel" if args.workload in ("c3", "lp") else "rows_kernel"
+    prefer = "prefill_tiles_persistent_kernel" if args.workload in ("c3", "c3h", "lp") else "rows_kernel"
     main_rf = next((e for e in own if e["kernel"] == prefer), own[0] if own else None)
     if main_rf:
         line["roofline"] = {k: main_rf[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel")}
@@ -808,7 +816,7 @@ def main():
                           "achieved": c4["frac_of_overlap_bound"], "peak": 1.0, "traffic": None})
         rooflines.append(roofline_entry("rows_kernel", c4["workload"], "hbm", c4["decode"]["GB/s"], "GB/s",
                                         c4["kernel_ms"]["rows"], c4["decode_bytes"], note="launched apart from the tiles"))
-        rooflines.append(roofline_entry("prefill_tiles_kernel", c4["workload"], "mfma", c4["prefill"]["TFLOP/s"], "TFLOP/s",
+        rooflines.append(roofline_entry("prefill_tiles_persistent_kernel", c4["workload"], "mfma", c4["prefill"]["TFLOP/s"], "TFLOP/s",
                                         c4["kernel_ms"]["tiles"], c4["prefill_flops"], note="launched apart from the rows"))
         if not args.no_cpu_baseline:
             cpu.append(cpu_baseline(gen.config4(threads=threads)[0], 3.0))
