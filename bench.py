@@ -165,11 +165,14 @@ def time_attention(d, steps, warmup, kernel_ids, hev, min_warm_ms=0.0):
         for k in kernel_ids:
             dsv.dsv_profile_events(k, *evs[k][s])
         attn_step(d)
+    t_enqueued = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     for k in kernel_ids:
         dsv.dsv_profile_events(k, None, None)
-    per_kernel = {}
+    # Host time per call (validation, plan choice, launches, binding), the GPU still working on
+    # earlier calls: what the host adds to a step only where the GPU would otherwise run dry.
+    per_kernel = {"host_enqueue_us": (t_enqueued - t0) / steps * 1e6}
     for k in kernel_ids:
         try:
             ms = [hev.elapsed_ms(a, b) for a, b in evs[k]]
@@ -194,6 +197,7 @@ def timed_step(d, steps, warmup, hev, ids=None):
     sec, main = time_attention(d, steps, 2, [dominant], hev)
     per_kernel = dict(probe)
     per_kernel[dominant] = main[dominant]
+    per_kernel["host_enqueue_us"] = main["host_enqueue_us"]
     return sec, per_kernel
 
 
@@ -209,7 +213,8 @@ def bench_attention(b, steps, warmup, hev):
     ids = [dsv.KERNEL_ROWS, dsv.KERNEL_TILES, dsv.KERNEL_MERGE, dsv.KERNEL_PLAN, dsv.KERNEL_MIXED]
     sec, per_kernel = timed_step(d, steps, warmup, hev, ids)
     res = {"workload": b.name, "ms_per_step": sec * 1e3, "tokens_per_s": b.total_q / sec,
-           "total_q": b.total_q, "num_seqs": b.num_seqs}
+           "total_q": b.total_q, "num_seqs": b.num_seqs,
+           "host_enqueue_us_per_call": per_kernel["host_enqueue_us"]}
     if per_kernel[dsv.KERNEL_MIXED] is not None:
         res["mixed_launch_ms"] = per_kernel[dsv.KERNEL_MIXED]
         os.environ["DSV_MIXED_LAUNCH"] = "0"
@@ -230,6 +235,30 @@ def bench_attention(b, steps, warmup, hev):
         tf = flops / (tiles_ms * 1e-3) / 1e12
         res["prefill"] = {"algorithmic_flops": flops, "TFLOP/s": tf, "frac_mfma_peak": tf / MFMA_BF16_PEAK_TFLOPS}
     return res, d
+
+
+def bench_block_placement(d, res, hev):
+    """The row kernel on the same batch and pool with each sequence's blocks at ascending
+    addresses instead of the seeded permutation: what the scattered 32 KiB blocks cost."""
+    import torch
+    import paper_2504_09285_amd as dsv
+    b = d.b
+    nblk = (b.ctx_lens.astype(np.int64) + 15) // 16
+    table = np.zeros_like(b.block_tables)
+    first = 0
+    for i, n in enumerate(nblk):
+        table[i, :n] = np.arange(first, first + n, dtype=np.int32)
+        first += int(n)
+    permuted = d.block_tables
+    d.block_tables = torch.from_numpy(table).cuda()
+    try:
+        _, per_kernel = timed_step(d, 20, 3, hev, [dsv.KERNEL_ROWS])
+    finally:
+        d.block_tables = permuted
+    nbytes = decode_bytes(b, 2)
+    ms = per_kernel[dsv.KERNEL_ROWS]
+    return {"seeded_permutation": {"rows_ms": res["kernel_ms"]["rows"], "GB/s": res["decode"]["GB/s"]},
+            "ascending_blocks": {"rows_ms": ms, "GB/s": nbytes / (ms * 1e-3) / 1e9}}
 
 
 def bench_shared_plan(d, layers, iterations, warmup):
@@ -761,7 +790,7 @@ def main():
         "config": {"workload": b.name, "num_seqs": b.num_seqs, "total_q": b.total_q,
                    "q_heads": b.Hq, "kv_heads": b.Hkv, "head_dim": b.D, "block_size": 16,
                    "kv_tokens": int(b.ctx_lens.sum()), "out_dtype": "bf16"},
-        "kernel_ms": res["kernel_ms"],
+        "kernel_ms": res["kernel_ms"], "host_enqueue_us_per_call": res["host_enqueue_us_per_call"],
     }
     own = attention_rooflines(res, b)
     prefer = "prefill_tiles_persistent_kernel" if args.workload in ("c3", "c3h", "lp") else "rows_kernel"
@@ -776,18 +805,24 @@ def main():
         line["cpu_baseline"] = cpu_baseline(b, 10.0)
     if args.workload == "c2" and not args.no_extras:
         shared = bench_shared_plan(d, 32, 6, 1)
+    placement = None
+    if args.workload == "c5" and not args.no_extras:
+        placement = bench_block_placement(d, res, hev)
     del d, b
 
     if not args.no_extras:
         extras = {}
         cpu = []
+        if placement:
+            extras["c5_rows_kernel_vs_block_placement"] = placement
         line["ceilings"] = measure_ceilings(hev)
-        keys = ("ms_per_step", "tokens_per_s", "mixed_launch_ms", "ms_per_step_kernels_apart", "kernel_ms", "prefill", "decode")
+        keys = ("ms_per_step", "tokens_per_s", "host_enqueue_us_per_call", "mixed_launch_ms", "ms_per_step_kernels_apart", "kernel_ms", "prefill", "decode")
 
         def other(name, bb, steps, cpu_seconds=0.0, shared_plan=False):
             r, dd = bench_attention(bb, steps, 5, hev)
             extras[name] = {k: r[k] for k in keys if k in r}
-            rooflines.extend(attention_rooflines(r, bb))
+            if bb.total_q >= 64:                     # a launch-bound toy batch has no roofline to speak of
+                rooflines.extend(attention_rooflines(r, bb))
             if shared_plan:
                 extras[name + "_one_plan_per_32_layers"] = bench_shared_plan(dd, 32, 6, 1)
             if cpu_seconds and not args.no_cpu_baseline:
