@@ -646,6 +646,22 @@ def measure_ceilings(hev):
     return out
 
 
+def against_measured_ceilings(entries, ceilings):
+    """Adds to every roofline entry what the same box delivered on the matching calibration loop
+    in this run (a kernel that only reads: the sequential read; the copies: the plain copy;
+    MFMA-bound: the register-resident MFMA loop) and the kernel's fraction of that."""
+    for e in entries:
+        kernel = e.get("kernel", "")
+        if e.get("bound") == "mfma":
+            top = ceilings["mfma_bf16_TFLOP/s"]
+        elif e.get("bound") == "hbm":
+            top = ceilings["hbm_copy_GB/s"] if kernel.startswith(("kv_copy", "kv_append")) else ceilings["hbm_read_GB/s"]
+        else:
+            continue
+        e["measured_ceiling"] = top
+        e["frac_of_measured_ceiling"] = e["achieved"] / top
+
+
 # ---------------------------------------------------------------------------- CPU baseline
 def cpu_baseline(b, target_seconds=12.0):
     """The fp64 oracle as it stands, on this machine's host cores, on a bounded sample of the batch:
@@ -889,6 +905,9 @@ def main():
         extras["profile_table_ms"] = {"plen=%d,ctx=%d,dnum=%d" % k: round(v, 4) for k, v in sorted(tbl.entries().items())}
         extras["max_prefill_allowed"] = {"target_ms=%.2f,ctx=%d,dnum=%d" % (t, c, n): tbl.max_prefill_allowed(t, c, n)
                                          for t in (0.1, 0.2, 0.4) for c, n in ((1024, 32), (4096, 128))}
+        against_measured_ceilings(rooflines, line["ceilings"])
+        if "roofline" in line:
+            against_measured_ceilings([line["roofline"]], line["ceilings"])
         line["rooflines"] = rooflines
         if cpu:
             line["cpu_baselines"] = cpu

@@ -152,11 +152,14 @@ __device__ __forceinline__ void prefill_tiles_persistent(const TilesParams& prm,
   int pos_req = 0;                     // ring position the next request fills
   int pos_use = 0;                     // ring position of the tile the computing side takes next
   int ahead = 0;                       // positions requested and not yet taken
+  // (Selects, no branches: a tile step must stay one basic block, so that its MFMAs and the
+  // softmax of the same step can be interleaved by the scheduler.)
   auto advance = [&](int& which, int& t) __attribute__((always_inline)) {
-    if (which == 2) return;
-    ++t;
-    if (which == 0 && t >= cur.n_tiles) { which = has_nxt ? 1 : 2; t = 0; }
-    else if (which == 1 && t >= nxt.n_tiles) { which = 2; t = 0; }
+    const int n = which == 1 ? nxt.n_tiles : cur.n_tiles;
+    const bool last = which != 2 && t + 1 >= n;
+    const int after = (which == 0 && has_nxt) ? 1 : 2;
+    t = (which == 2 || last) ? 0 : t + 1;
+    which = last ? after : which;
   };
   auto block_id_of = [&](int which, int t) __attribute__((always_inline)) -> int {
     const bool second = which == 1;
@@ -200,7 +203,7 @@ __device__ __forceinline__ void prefill_tiles_persistent(const TilesParams& prm,
       __builtin_amdgcn_global_load_lds((gbl_void_t)kp, (lds_void_t)(kdst + ii * 1024), 16, 0, 0);
       __builtin_amdgcn_global_load_lds((gbl_void_t)vp, (lds_void_t)(vdst + ii * 1024), 16, 0, 0);
     }
-    if (req_which == 2 && has_nxt) ++nxt.trailing;     // held back behind the next item's last tile
+    nxt.trailing += (req_which == 2 && has_nxt) ? 1 : 0;     // held back behind the next item's last tile
     ++pos_req;
     ++ahead;
     req_which = ahead_which; req_t = ahead_t;
@@ -471,6 +474,8 @@ __device__ __forceinline__ void prefill_tiles_persistent(const TilesParams& prm,
       pv(pfb[CUR ^ 1], 1);
     }
     softmax(scb[CUR], pfb[CUR], robust_c, std::integral_constant<bool, !with_pv>{});
+    // MFMAs and softmax interleaved one to four (measured: all MFMAs first, all softmax first,
+    // groups of four, and fixed instead of alternating wave priorities are within 1-4 % of this).
 #pragma unroll
     for (int i = 0; i < (with_pv ? 2 * KS : KS); ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
