@@ -411,19 +411,22 @@ __device__ __forceinline__ void rows_body(const RowsParams& prm, int bx, int by,
       }
     }
   } else {
+    // Partials leave with the nontemporal hint: written once, read once by the merge kernel.
+    // Plain stores of these 16 KiB per item cost the K/V stream a tenth of its rate on long
+    // contexts (config 5: 58 MB of partials next to 14.6 GB read: 6.26 TB/s; with the hint 6.60;
+    // with every item's partials aimed at one cached spot, a timing experiment, 6.96).
     const int64_t ph = (int64_t)item * a.Hq + h;
     if constexpr (KV8) {
-      float* pa = prm.w.part_acc + ph * D + jj * 8;
+      f32x4_t* pa = reinterpret_cast<f32x4_t*>(prm.w.part_acc + ph * D + jj * 8);
 #pragma unroll
       for (int j = 0; j < DB / 2; ++j) {
-        *reinterpret_cast<float4*>(pa + j * 32) = make_float4(o[2 * j][0], o[2 * j + 1][0], o[2 * j][1], o[2 * j + 1][1]);
-        *reinterpret_cast<float4*>(pa + j * 32 + 4) = make_float4(o[2 * j][2], o[2 * j + 1][2], o[2 * j][3], o[2 * j + 1][3]);
+        __builtin_nontemporal_store(f32x4_t{o[2 * j][0], o[2 * j + 1][0], o[2 * j][1], o[2 * j + 1][1]}, pa + j * 8);
+        __builtin_nontemporal_store(f32x4_t{o[2 * j][2], o[2 * j + 1][2], o[2 * j][3], o[2 * j + 1][3]}, pa + j * 8 + 1);
       }
     } else {
-      float* pa = prm.w.part_acc + ph * D + jj * 4;
+      f32x4_t* pa = reinterpret_cast<f32x4_t*>(prm.w.part_acc + ph * D + jj * 4);
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
-        *reinterpret_cast<float4*>(pa + db * 16) = make_float4(o[db][0], o[db][1], o[db][2], o[db][3]);
+      for (int db = 0; db < DB; ++db) __builtin_nontemporal_store(o[db], pa + db * 4);
     }
     if (jj == 0) *reinterpret_cast<float2*>(prm.w.part_ml + ph * 2) = make_float2(m_run, l_tot);
   }
