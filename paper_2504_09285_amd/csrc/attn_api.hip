@@ -222,6 +222,38 @@ PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8
   const int forced_t = env_int("DSV_TILE_PART_TILES", 0);
   if (forced_t > 0) c.tile_part_tiles = forced_t;
   if (forced_t < 0) c.tile_part_tiles = 0;
+  // Row work as one stream per workgroup.  A launch of row work alone with enough blocks per
+  // compute unit is cut into equal runs instead of (row, partition) items of a fixed size: no
+  // launch tail, one start-up per row instead of one per partition, and far fewer partials
+  // (rows + workgroups instead of one per 1,024 tokens: the partials' stores are what costs the
+  // K/V stream most, see attn_rows_stream.h).  DSV_ROWS_STREAM: 0 never; n >= 1 whenever the
+  // geometry allows, with n workgroups (tests).
+  c.stream_wgs = 0;
+  c.stream_row_cost = 2;        // a row's start-up, in blocks' worth of streaming time
+  c.stream_total = 0;
+  {
+    const int want = env_int("DSV_ROWS_STREAM", -1);
+    int64_t rows = 0, blocks = 0;
+    bool tiles = false;
+    for (int i = 0; i < S; ++i) {
+      const int q_len = qo[i + 1] - qo[i];
+      if (!on_row_path(q_len, cl[i], c)) { tiles = true; continue; }
+      rows += q_len;
+      for (int j = 0; j < q_len; ++j) blocks += ceil_div(cl[i] - q_len + j + 1, kBlockSize);
+    }
+    const bool apart = !tiles || env_int("DSV_MIXED_LAUNCH", 1) == 0;
+    const bool geometry = Hkv <= 8 && G <= 16 && c.row_nbuf == 2 && forced < 16;
+    const int64_t total = blocks + rows * c.stream_row_cost;
+    int wgs = c.num_cus;
+    if (want >= 1) wgs = want;
+    if (wgs > 4096) wgs = 4096;
+    if ((int64_t)wgs > blocks) wgs = (int)blocks;
+    if (rows > 0 && apart && geometry && want != 0 && wgs >= 1 &&
+        (want >= 1 || blocks >= (int64_t)16 * c.num_cus)) {
+      c.stream_wgs = wgs;
+      c.stream_total = total;
+    }
+  }
   return c;
 }
 
@@ -229,7 +261,12 @@ PlanCounts count_plan(int32_t S, const int32_t* qo, const int32_t* cl, const Pla
   PlanCounts n;
   for (int i = 0; i < S; ++i) {
     const int q_len = qo[i + 1] - qo[i];
-    if (on_row_path(q_len, cl[i], c)) {
+    if (on_row_path(q_len, cl[i], c) && c.stream_wgs > 0) {
+      // Stream form: a cut adds one item to the row it falls in; where the cuts fall is worked
+      // out on the device, the host only needs bounds (at most stream_wgs - 1 cuts in all).
+      n.rows += q_len;
+      n.items += q_len;
+    } else if (on_row_path(q_len, cl[i], c)) {
       n.rows += q_len;
       for (int j = 0; j < q_len; ++j) {
         const int np = parts_of(cl[i] - q_len + j + 1, c);
@@ -254,6 +291,11 @@ PlanCounts count_plan(int32_t S, const int32_t* qo, const int32_t* cl, const Pla
       n.stage_blocks += nblk;
       if (nblk > n.stage_max_blocks) n.stage_max_blocks = nblk;
     }
+  }
+  if (c.stream_wgs > 0 && n.rows > 0) {
+    n.items += c.stream_wgs - 1;
+    n.split_items = c.stream_wgs > 1 ? n.items : 0;
+    n.max_parts = max(n.max_parts, c.stream_wgs);
   }
   return n;
 }
@@ -281,6 +323,8 @@ size_t carve(const PlanCounts& n, int S, int Hq, int Hkv, int D, bool kv8, char*
   char* pz = take(256);
   char* pc = take(items * 4);
   char* po = take(items * 4);
+  char* psp = take(items * 16);
+  char* pwf = take((size_t)(4096 + 1) * 4);
   const size_t partials = items + (size_t)n.tile_split_items;    // row items first, then cut q-tiles
   char* p9 = take(partials * (size_t)Hq * D * 4);
   char* p10 = take(partials * (size_t)Hq * 2 * 4);
@@ -303,6 +347,7 @@ size_t carve(const PlanCounts& n, int S, int Hq, int Hkv, int D, bool kv8, char*
     w->zero_line = (uint32_t*)pz;
     w->item_blk0 = (int32_t*)pc;
     w->item_order = (int32_t*)po;
+    w->item_span = (int4*)psp; w->wg_first = (int32_t*)pwf;
     w->part_acc = (float*)p9; w->part_ml = (float*)p10;
   }
   return off + 256;
@@ -413,18 +458,39 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
   }
 
   int row_carry = 0, item_carry = 0, stage_carry = 0, sblk_carry = 0;
+  int64_t cost_carry = 0;                       // stream form: units of the row stream so far
+  const bool streamed = c.stream_wgs > 0;       // (uniform)
   for (int base = 0; base < S; base += kPlanThreads) {
     const int i = base + (int)threadIdx.x;
-    int q0 = 0, q_len = 0, ctx = 0, n_rows = 0, n_items = 0, n_tiles = 0;
+    int q0 = 0, q_len = 0, ctx = 0, n_rows = 0, n_items = 0, n_tiles = 0, seg_cost = 0;
     if (i < S) {
       q0 = q_offsets[i];
       q_len = q_offsets[i + 1] - q0;
       ctx = ctx_lens[i];
       if (on_row_path(q_len, ctx, c)) {
         n_rows = q_len;
-        for (int j = 0; j < q_len; ++j) n_items += parts_of(ctx - q_len + j + 1, c);
+        for (int j = 0; j < q_len; ++j) {
+          if (streamed) seg_cost += (ctx - q_len + j + kBlockSize) / kBlockSize + c.stream_row_cost;
+          else n_items += parts_of(ctx - q_len + j + 1, c);
+        }
       } else {
         n_tiles = (q_len + c.tile_tokens - 1) / c.tile_tokens;
+      }
+    }
+    // Stream form: a row occupies [pre, pre + cost) of the stream, its blocks the part behind the
+    // first stream_row_cost units; its first item belongs to the run that position pre +
+    // stream_row_cost falls in, and every later cut inside its blocks starts another item.
+    int64_t seg_pre = 0;
+    if (streamed) {
+      int tot_cost;
+      seg_pre = cost_carry + block_exclusive_scan(seg_cost, smem, &tot_cost);
+      cost_carry += tot_cost;
+      int64_t pre = seg_pre;
+      for (int j = 0; j < n_rows; ++j) {
+        const int nb = (ctx - q_len + j + kBlockSize) / kBlockSize;
+        const int64_t first = pre + c.stream_row_cost;
+        n_items += stream_run_of(first + nb - 1, c) - stream_run_of(first, c) + 1;
+        pre += nb + c.stream_row_cost;
       }
     }
     int tot_rows, tot_items;
@@ -432,12 +498,27 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
     int item0 = item_carry + block_exclusive_scan(n_items, smem, &tot_items);
     for (int j = 0; j < n_rows; ++j) {
       const int ctx_eff = ctx - q_len + j + 1;
-      const int np = parts_of(ctx_eff, c);
       const int r = row0 + j;
+      int np;
+      if (streamed) {
+        const int nb = (ctx_eff + kBlockSize - 1) / kBlockSize;
+        const int64_t first = seg_pre + c.stream_row_cost;
+        const int g0 = stream_run_of(first, c);
+        np = stream_run_of(first + nb - 1, c) - g0 + 1;
+        for (int p = 0; p < np; ++p) {
+          const int b0 = p == 0 ? 0 : (int)(stream_cut(g0 + p, c) - first);
+          const int b1 = p == np - 1 ? nb : (int)(stream_cut(g0 + p + 1, c) - first);
+          w.item_rec[item0 + p] = make_int4(i, q0 + j, ctx_eff, p | (np << 16));
+          w.item_span[item0 + p] = make_int4(b0, b1, 0, g0 + p);
+        }
+        seg_pre += nb + c.stream_row_cost;
+      } else {
+        np = parts_of(ctx_eff, c);
+        for (int p = 0; p < np; ++p) w.item_rec[item0 + p] = make_int4(i, q0 + j, ctx_eff, p | (np << 16));
+      }
       w.row_qtok[r] = q0 + j;
       w.row_item0[r] = item0;
       w.row_nparts[r] = np;
-      for (int p = 0; p < np; ++p) w.item_rec[item0 + p] = make_int4(i, q0 + j, ctx_eff, p | (np << 16));
       item0 += np;
     }
     row_carry += tot_rows;
@@ -495,6 +576,26 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
   // segments hold.  Most items are full partitions: a wave counts and places those with one
   // atomic per wave.  The order of equal keys is left to the atomics; it affects nothing but the
   // dispatch order.
+  if (streamed) {
+    // Stream form: each item's first block id, and the first item of every run.  Items are listed
+    // in stream order, so their runs never decrease; an item that opens runs (g_prev, g] is the
+    // first item of each of them (a run that starts inside a row's start-up units has no item of
+    // its own before the next row begins: it takes that row's first item too).
+    __syncthreads();
+    int32_t* span_words = reinterpret_cast<int32_t*>(w.item_span);
+    for (int it = (int)threadIdx.x; it < item_carry; it += kPlanThreads) {
+      const int4 rec = w.item_rec[it];
+      const int b0 = span_words[4 * it], g = span_words[4 * it + 3];
+      span_words[4 * it + 2] = block_tables[(int64_t)rec.x * max_blocks + b0];
+      const int g_prev = it > 0 ? span_words[4 * (it - 1) + 3] : -1;
+      for (int r = g_prev + 1; r <= g; ++r) w.wg_first[r] = it;
+    }
+    if (threadIdx.x == 0) {
+      const int g_last = item_carry > 0 ? span_words[4 * (item_carry - 1) + 3] : -1;
+      for (int r = g_last + 1; r <= c.stream_wgs; ++r) w.wg_first[r] = item_carry;
+    }
+    return;
+  }
   if (threadIdx.x <= kOrderBins) order_slot[threadIdx.x] = 0;
   __syncthreads();
   const int full_blocks = c.part_tokens / kBlockSize;
@@ -743,6 +844,8 @@ struct PlanStamp {
   int32_t num_seqs, Hq, Hkv, D, kv8, max_blocks;
   int32_t part_tokens, mfma_min_qlen, mfma_min_work, tile_tokens, tile_part_tiles, num_cus;
   int32_t flat_heads, head_groups;
+  int32_t stream_wgs, stream_row_cost;
+  int64_t stream_total;
 };
 static_assert(sizeof(PlanStamp) <= sizeof(dsv_attn_plan), "dsv_attn_plan too small");
 constexpr uint64_t kPlanMagic = 0x6473765f706c616eull;
@@ -768,6 +871,7 @@ PlanStamp make_stamp(const PlanConfig& c, bool kv8, const void* workspace, const
   st.part_tokens = c.part_tokens; st.mfma_min_qlen = c.mfma_min_qlen; st.mfma_min_work = c.mfma_min_work;
   st.flat_heads = c.flat_heads; st.head_groups = c.head_groups;
   st.tile_tokens = c.tile_tokens; st.tile_part_tiles = c.tile_part_tiles; st.num_cus = c.num_cus;
+  st.stream_wgs = c.stream_wgs; st.stream_row_cost = c.stream_row_cost; st.stream_total = c.stream_total;
   return st;
 }
 

@@ -29,7 +29,23 @@ struct PlanConfig {
   int32_t num_cus;         // compute units of the device (sizes the persistent grid)
   int32_t tile_part_tiles; // 0: query tiles are never cut along the context; else a query tile
                            // that visits n KV tiles is cut into ceil(n / tile_part_tiles) partitions
+  // Row work as one stream per workgroup (large row-only launches).  All rows' blocks, each row
+  // preceded by stream_row_cost units for its start-up, form one sequence of stream_total units;
+  // it is cut into stream_wgs equal runs, one per persistent workgroup, and a row that straddles a
+  // cut is partitioned there (part_tokens is not used).  0 workgroups: the item form above.
+  int32_t stream_wgs;
+  int32_t stream_row_cost;
+  int64_t stream_total;
 };
+
+// Position of the w-th cut of the row stream, and the run a position falls in.
+__host__ __device__ inline int64_t stream_cut(int64_t w, const PlanConfig& c) {
+  return (w * c.stream_total + c.stream_wgs - 1) / c.stream_wgs;
+}
+__host__ __device__ inline int stream_run_of(int64_t pos, const PlanConfig& c) {
+  const int64_t g = pos * c.stream_wgs / c.stream_total;      // largest w with stream_cut(w) <= pos
+  return (int)(g < c.stream_wgs ? g : c.stream_wgs - 1);
+}
 
 struct PlanCounts {
   int64_t rows = 0;        // query tokens on the row path
@@ -70,6 +86,9 @@ struct WorkLists {
   uint32_t* zero_line;     // 256 bytes of zeros (stands in for V rows that must not be read)
   int32_t* item_blk0;      // [items] pool block id of the item's first block
   int32_t* item_order;     // [items] the items in dispatch order: most blocks to stream first
+  int4*    item_span;      // [items] stream form: {first block, end block, pool id of the first
+                           // block, run (workgroup) the item belongs to}
+  int32_t* wg_first;       // [stream_wgs + 1] stream form: first item of each workgroup's run
   float*   part_acc;       // [items][Hq][D]  unnormalised partial outputs
   float*   part_ml;        // [items][Hq][2]  running max (log2 domain) and sum
   // bf16 copy of the MFMA path's contexts (cache of 8-bit codes only, else null)

@@ -79,7 +79,7 @@ int launch_mixed_t(const prefill_impl::TilesParams& tp, const rows_impl::RowsPar
 }  // namespace
 
 bool mixed_launch_supported(const AttnArgs& a, const PlanConfig& cfg, const PlanCounts& n) {
-  return n.tiles > 0 && n.items > 0 && cfg.row_nbuf == 2 && cfg.tile_tokens >= 32 && cfg.tile_tokens <= prefill_impl::kTileQ &&
+  return n.tiles > 0 && n.items > 0 && cfg.stream_wgs == 0 && cfg.row_nbuf == 2 && cfg.tile_tokens >= 32 && cfg.tile_tokens <= prefill_impl::kTileQ &&
          cfg.part_tokens <= 64 * kBlockSize && prefill_impl::kThreads == 512 && (a.D == 128 || a.D == 64);
 }
 

@@ -1,5 +1,6 @@
 // Launcher of the row kernel (see attn_rows_kernel.h for the kernel itself).
 #include "attn_rows_kernel.h"
+#include "attn_rows_stream.h"
 
 namespace dsv {
 namespace {
@@ -34,12 +35,43 @@ int launch_rows_t(const RowsParams& prm, dim3 grid, int waves, hipStream_t strea
   return launch_status();
 }
 
+// Stream form: one persistent workgroup per run of the row stream, one wave per KV head.
+template <int D, bool KV8>
+__global__ __launch_bounds__(512) void rows_stream_kernel(RowsParams prm) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  rows_stream_body<D, KV8>(prm, (int)blockIdx.x, smem);
+}
+
+template <int D, bool KV8>
+int launch_rows_stream_t(const RowsParams& prm, int wgs, int waves, hipStream_t stream) {
+  constexpr int kSlot = RowGeom<D, KV8 ? 1 : 2>::SLOT_BYTES;
+  constexpr int kQStage = RowGeom<D, KV8 ? 1 : 2>::KS * 1024;      // per wave: its query fragments
+  constexpr int kMaxLds = 8 * (2 * kSlot + kQStage);
+  static bool configured = false;     // idempotent; a race between two first calls is benign
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(rows_stream_kernel<D, KV8>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds) != hipSuccess)
+      return DSV_E_LAUNCH;
+    configured = true;
+  }
+  hipLaunchKernelGGL((rows_stream_kernel<D, KV8>), dim3((unsigned)wgs), dim3(waves * kWave), waves * (2 * kSlot + kQStage), stream, prm);
+  return launch_status();
+}
+
 }  // namespace
 
 int launch_rows(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, const PlanCounts& n,
                 hipStream_t stream) {
   if (cfg.part_tokens > 64 * kBlockSize) return DSV_E_UNSUPPORTED;   // one table vector per partition
   RowsParams prm{a, w, cfg.part_tokens, a.Hq / a.Hkv, 1};
+  if (cfg.stream_wgs > 0) {
+    if (a.Hkv > 8 || prm.G > kRowHeads) return DSV_E_UNSUPPORTED;      // the planner does not choose it then
+    if (a.D == 128 && !a.kv8) return launch_rows_stream_t<128, false>(prm, cfg.stream_wgs, a.Hkv, stream);
+    if (a.D == 128 && a.kv8) return launch_rows_stream_t<128, true>(prm, cfg.stream_wgs, a.Hkv, stream);
+    if (a.D == 64 && !a.kv8) return launch_rows_stream_t<64, false>(prm, cfg.stream_wgs, a.Hkv, stream);
+    if (a.D == 64 && a.kv8) return launch_rows_stream_t<64, true>(prm, cfg.stream_wgs, a.Hkv, stream);
+    return DSV_E_UNSUPPORTED;
+  }
   int waves = 1;
   // waves * slots * slot bytes (8 KiB of bf16, 4 KiB of codes) must fit in the 160 KB of LDS
   const int max_waves = cfg.row_nbuf <= (a.kv8 ? 4 : 2) ? 8 : 4;

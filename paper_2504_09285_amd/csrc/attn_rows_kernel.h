@@ -170,6 +170,93 @@ __device__ __forceinline__ void read_vt2(uint32_t a0, uint32_t a1, s16x4_t& v0, 
       : "memory");
 }
 
+// One 16-token block of a wave's KV head against the wave's query heads: scores, running softmax
+// and the update of the output accumulators.  `slot_lds` is the LDS address of the block's ring
+// slot (K rows, then V rows), k_off / v_off the lane's fragment offsets inside a slot (v_off
+// counted from the slot's start), `tok` the context position of the lane's first token
+// (block * 16 + 4 * lane group), t1 the end of the item's token range.
+template <int D, bool KV8>
+__device__ __forceinline__ void row_block_step(uint32_t slot_lds, const int (&k_off)[RowGeom<D, KV8 ? 1 : 2>::KS],
+                                               const uint32_t (&v_off)[KV8 ? RowGeom<D, 1>::DB / 2 : RowGeom<D, 2>::DB],
+                                               const bf16x8_t (&qf)[RowGeom<D, KV8 ? 1 : 2>::KS], int tok, int t1,
+                                               float scale, f32x4_t (&o)[RowGeom<D, KV8 ? 1 : 2>::DB], float& m_run,
+                                               float& l_run) {
+  constexpr int EB = KV8 ? 1 : 2;
+  using Geo = RowGeom<D, EB>;
+  constexpr int KS = Geo::KS, DB = Geo::DB;
+  constexpr int VT = KV8 ? DB / 2 : DB;                  // transpose reads per block
+  // S^T = K Q^T: lane (head qcol, jj) gets tokens 4jj..4jj+3 of the block.
+  f32x4_t s = {0.f, 0.f, 0.f, 0.f};
+  if constexpr (KV8) {
+    const uint32_t kb = slot_lds;
+    u32x2_t kc[KS];
+    if constexpr (KS == 4) read_k4(kb + k_off[0], kb + k_off[1], kb + k_off[2], kb + k_off[3], kc[0], kc[1], kc[2], kc[3]);
+    else read_k2(kb + k_off[0], kb + k_off[1], kc[0], kc[1]);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen8(kc[ks]), qf[ks], s, 0, 0, 0);
+  } else {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      typedef const __attribute__((address_space(3))) bf16x8_t* lds_frag_t;
+      const bf16x8_t kf = *(lds_frag_t)(uintptr_t)(slot_lds + (uint32_t)k_off[ks]);
+      s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[ks], s, 0, 0, 0);
+    }
+  }
+  if (tok + 3 >= t1) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (tok + e >= t1) s[e] = -INFINITY;
+  }
+  const float mx = cross16_max(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])));
+  const float m_new = fmaxf(m_run, mx * scale);
+  const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+  m_run = m_new;
+  float p[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], scale, -m_new));
+  const f32x2_t p01 = {p[0], p[1]}, p23 = {p[2], p[3]};
+  const bf16x2_t b01 = __builtin_convertvector(p01, bf16x2_t), b23 = __builtin_convertvector(p23, bf16x2_t);
+  const bf16x4_t pf = __builtin_shufflevector(b01, b23, 0, 1, 2, 3);
+  // The row sum is taken over the bf16-rounded probabilities that enter the PV product, so
+  // that the weights actually applied sum to one.
+  const uint32_t u01 = __builtin_bit_cast(uint32_t, b01), u23 = __builtin_bit_cast(uint32_t, b23);
+  l_run = l_run * corr + (__builtin_bit_cast(float, u01 << 16) + __builtin_bit_cast(float, u01 & 0xffff0000u)) +
+          (__builtin_bit_cast(float, u23 << 16) + __builtin_bit_cast(float, u23 & 0xffff0000u));
+
+  // O^T = O^T * corr + V^T P^T.
+  constexpr int VG = VT >= 4 ? 4 : 2;                  // transpose reads issued together
+#pragma unroll
+  for (int d4 = 0; d4 < VT; d4 += VG) {
+    s16x4_t vt[VG];
+    if constexpr (VG == 4)
+      read_vt4(slot_lds + v_off[d4], slot_lds + v_off[d4 + 1], slot_lds + v_off[d4 + 2],
+               slot_lds + v_off[d4 + 3], vt[0], vt[1], vt[2], vt[3]);
+    else
+      read_vt2(slot_lds + v_off[d4], slot_lds + v_off[d4 + 1], vt[0], vt[1]);
+#pragma unroll
+    for (int u = 0; u < VG; ++u) {
+      if constexpr (KV8) {
+        // vt[u]: 16-bit unit e = token 4jj+e, low byte dim 32(d4+u) + 2m, high byte the next
+        // dim (m = lane % 16).  Gather the even-dim and the odd-dim codes of the four tokens
+        // and widen them: two A fragments, rows m <-> dims 32(d4+u) + 2m (+1).
+        const u32x2_t w = __builtin_bit_cast(u32x2_t, vt[u]);
+        const uint32_t ev = __builtin_amdgcn_perm(w.y, w.x, 0x06040200u);
+        const uint32_t od = __builtin_amdgcn_perm(w.y, w.x, 0x07050301u);
+        const bf16x4_t a_ev = __builtin_shufflevector(widen2<false>(ev), widen2<true>(ev), 0, 1, 2, 3);
+        const bf16x4_t a_od = __builtin_shufflevector(widen2<false>(od), widen2<true>(od), 0, 1, 2, 3);
+        const int db = 2 * (d4 + u);
+        o[db] *= corr;
+        o[db + 1] *= corr;
+        o[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, a_ev), __builtin_bit_cast(s16x4_t, pf), o[db], 0, 0, 0);
+        o[db + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, a_od), __builtin_bit_cast(s16x4_t, pf), o[db + 1], 0, 0, 0);
+      } else {
+        o[d4 + u] *= corr;
+        o[d4 + u] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt[u], __builtin_bit_cast(s16x4_t, pf), o[d4 + u], 0, 0, 0);
+      }
+    }
+  }
+}
+
 // The kernel body as a device function, so that the same code serves the kernel of its own and
 // the launch that mixes row work with prefill tiles.  (bx, by, bz) stand in for the block
 // index, `waves` is the number of waves per workgroup that are given a KV head, `smem` the
@@ -276,7 +363,7 @@ __device__ __forceinline__ void rows_body(const RowsParams& prm, int bx, int by,
   uint32_t v_off[VT];
 #pragma unroll
   for (int db = 0; db < VT; ++db)
-    v_off[db] = ring_lds + Geo::TENSOR_BYTES + v_row * ROWB + (((2 * db + (lane % 4) / 2) ^ v_swz<D, EB>(v_row)) * 16) + (lane % 2) * 8;
+    v_off[db] = Geo::TENSOR_BYTES + v_row * ROWB + (((2 * db + (lane % 4) / 2) ^ v_swz<D, EB>(v_row)) * 16) + (lane % 2) * 8;
 
   // The first block is requested at once (its id came with the item); the table slice and the
   // query rows are only waited for where they are first used.
@@ -292,79 +379,8 @@ __device__ __forceinline__ void rows_body(const RowsParams& prm, int bx, int by,
     // cached 256 bytes) instead of fetching the last block from HBM once more.
     issue_block(b + R - 1, (b - b0 + R - 1) % R);
     wait_vmcnt<(R - 1) * Geo::LOADS_PER_BLOCK>();
-    const unsigned char* sl = ring + slot * Geo::SLOT_BYTES;
-
-    // S^T = K Q^T: lane (head qcol, jj) gets tokens 4jj..4jj+3 of the block.
-    f32x4_t s = {0.f, 0.f, 0.f, 0.f};
-    if constexpr (KV8) {
-      const uint32_t kb = ring_lds + (uint32_t)slot * Geo::SLOT_BYTES;
-      u32x2_t kc[KS];
-      if constexpr (KS == 4) read_k4(kb + k_off[0], kb + k_off[1], kb + k_off[2], kb + k_off[3], kc[0], kc[1], kc[2], kc[3]);
-      else read_k2(kb + k_off[0], kb + k_off[1], kc[0], kc[1]);
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen8(kc[ks]), qf[ks], s, 0, 0, 0);
-    } else {
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sl + k_off[ks]);
-        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[ks], s, 0, 0, 0);
-      }
-    }
-    const int tok = b * kBlockSize + jj * 4;
-    if (tok + 3 >= t1) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if (tok + e >= t1) s[e] = -INFINITY;
-    }
-    const float mx = cross16_max(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])));
-    const float m_new = fmaxf(m_run, mx * scale);
-    const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
-    float p[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], scale, -m_new));
-    const f32x2_t p01 = {p[0], p[1]}, p23 = {p[2], p[3]};
-    const bf16x2_t b01 = __builtin_convertvector(p01, bf16x2_t), b23 = __builtin_convertvector(p23, bf16x2_t);
-    const bf16x4_t pf = __builtin_shufflevector(b01, b23, 0, 1, 2, 3);
-    // The row sum is taken over the bf16-rounded probabilities that enter the PV product, so
-    // that the weights actually applied sum to one.
-    const uint32_t u01 = __builtin_bit_cast(uint32_t, b01), u23 = __builtin_bit_cast(uint32_t, b23);
-    l_run = l_run * corr + (__builtin_bit_cast(float, u01 << 16) + __builtin_bit_cast(float, u01 & 0xffff0000u)) +
-            (__builtin_bit_cast(float, u23 << 16) + __builtin_bit_cast(float, u23 & 0xffff0000u));
-
-    // O^T = O^T * corr + V^T P^T.
-    const uint32_t slot_off = (uint32_t)slot * Geo::SLOT_BYTES;
-    constexpr int VG = VT >= 4 ? 4 : 2;                  // transpose reads issued together
-#pragma unroll
-    for (int d4 = 0; d4 < VT; d4 += VG) {
-      s16x4_t vt[VG];
-      if constexpr (VG == 4)
-        read_vt4(v_off[d4] + slot_off, v_off[d4 + 1] + slot_off, v_off[d4 + 2] + slot_off,
-                 v_off[d4 + 3] + slot_off, vt[0], vt[1], vt[2], vt[3]);
-      else
-        read_vt2(v_off[d4] + slot_off, v_off[d4 + 1] + slot_off, vt[0], vt[1]);
-#pragma unroll
-      for (int u = 0; u < VG; ++u) {
-        if constexpr (KV8) {
-          // vt[u]: 16-bit unit e = token 4jj+e, low byte dim 32(d4+u) + 2m, high byte the next
-          // dim (m = lane % 16).  Gather the even-dim and the odd-dim codes of the four tokens
-          // and widen them: two A fragments, rows m <-> dims 32(d4+u) + 2m (+1).
-          const u32x2_t w = __builtin_bit_cast(u32x2_t, vt[u]);
-          const uint32_t ev = __builtin_amdgcn_perm(w.y, w.x, 0x06040200u);
-          const uint32_t od = __builtin_amdgcn_perm(w.y, w.x, 0x07050301u);
-          const bf16x4_t a_ev = __builtin_shufflevector(widen2<false>(ev), widen2<true>(ev), 0, 1, 2, 3);
-          const bf16x4_t a_od = __builtin_shufflevector(widen2<false>(od), widen2<true>(od), 0, 1, 2, 3);
-          const int db = 2 * (d4 + u);
-          o[db] *= corr;
-          o[db + 1] *= corr;
-          o[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, a_ev), __builtin_bit_cast(s16x4_t, pf), o[db], 0, 0, 0);
-          o[db + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, a_od), __builtin_bit_cast(s16x4_t, pf), o[db + 1], 0, 0, 0);
-        } else {
-          o[d4 + u] *= corr;
-          o[d4 + u] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt[u], __builtin_bit_cast(s16x4_t, pf), o[d4 + u], 0, 0, 0);
-        }
-      }
-    }
+    row_block_step<D, KV8>(ring_lds + (uint32_t)slot * Geo::SLOT_BYTES, k_off, v_off, qf, b * kBlockSize + jj * 4, t1,
+                           scale, o, m_run, l_run);
   }
   wait_vmcnt<0>();                               // drain the (duplicate) prefetches before exit
 

@@ -180,9 +180,9 @@ def test_static_entry_point_refuses_oversized_and_invalid_batches_on_the_host(li
     refusal needs no GPU: too large -> DSV_E_WORKSPACE, invalid -> DSV_E_INVALID, empty -> no-op."""
     assert dsv.attn_mixed_batch_static_max_bytes() == 64 << 20
     pool = binding._Pool(0x1000, 0x2000, 0, 1, 4, 16, 8, 128)
-    n = 96
+    n = 4096
     qo = np.arange(n + 1, dtype=np.int32)
-    cl = np.full(n, 32768, np.int32)
+    cl = np.full(n, 4096, np.int32)
     i32p = C.POINTER(C.c_int32)
 
     def call(qo, cl, n, Hq=64):

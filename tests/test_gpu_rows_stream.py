@@ -1,0 +1,77 @@
+"""The row path as one stream per workgroup (large decode-only launches): the rows' blocks are cut
+into equal runs, one per persistent workgroup, and a row that straddles a cut is partitioned
+there.  DSV_ROWS_STREAM forces the form (1: one run per compute unit, n > 1: n runs) on batches far
+smaller than those it is chosen for, so that every path of the run logic is crossed: rows much
+shorter than a run (many items per workgroup, one-block items among them), rows cut many times,
+cuts that fall on row starts, more runs than rows.  Every output against the fp64 oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import gen
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-2
+
+RAGGED = [(1, 1), (1, 15), (1, 16), (1, 17), (1, 3000), (1, 31), (1, 32), (1, 33), (1, 700), (1, 5000),
+          (1, 2), (1, 1024), (1, 1025), (1, 255), (1, 48), (1, 9000), (1, 1), (1, 64)]
+
+
+@pytest.mark.parametrize("runs", [1, 2, 3, 7, 40, 256, 1000])
+@pytest.mark.parametrize("Hq,Hkv,D", [(32, 8, 128), (8, 2, 64), (16, 1, 128), (5, 5, 64)])
+def test_decodes_of_every_length_in_any_number_of_runs(monkeypatch, runs, Hq, Hkv, D):
+    from gpu_harness import run_attention
+    monkeypatch.setenv("DSV_ROWS_STREAM", str(runs))
+    b = gen.make_batch("stream_ragged", 900 + runs + D, Hq, Hkv, D, RAGGED)
+    got = run_attention(b)
+    ref = oracle.attn_mixed_batch(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens, b.scale)
+    assert np.isfinite(got).all()
+    err = np.abs(got - ref)
+    assert err.max() <= TOL, (float(err.max()), np.unravel_index(int(err.argmax()), err.shape))
+
+
+@pytest.mark.parametrize("runs", [1, 5, 256])
+def test_short_spans_on_the_row_path_and_a_span_on_the_mfma_path(monkeypatch, runs):
+    """Spans of 2-15 tokens whose rows each have their own causal context, next to decodes; with a
+    long span in the batch the row work is streamed only when the two kernels are launched apart."""
+    from gpu_harness import run_attention
+    monkeypatch.setenv("DSV_ROWS_STREAM", str(runs))
+    monkeypatch.setenv("DSV_MIXED_LAUNCH", "0")
+    segs = [(3, 40), (1, 900), (15, 70), (2, 2), (7, 130), (1, 4000), (200, 260), (4, 100), (1, 16)]
+    b = gen.make_batch("stream_spans", 910 + runs, 32, 8, 128, segs)
+    got = run_attention(b)
+    ref = oracle.attn_mixed_batch(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens, b.scale)
+    assert np.isfinite(got).all() and np.abs(got - ref).max() <= TOL
+
+
+@pytest.mark.parametrize("runs", [3, 256])
+def test_bf16_output_and_8bit_cache(monkeypatch, runs):
+    import torch
+    from gpu_harness import run_attention, run_attention_fp8kv
+    monkeypatch.setenv("DSV_ROWS_STREAM", str(runs))
+    b = gen.make_batch("stream_bf16", 920 + runs, 32, 8, 128, RAGGED)
+    f32 = run_attention(b)
+    bf = run_attention(b, out_dtype=torch.bfloat16)
+    np.testing.assert_array_equal(bf, gen.f32_to_bf16_bits(f32))
+    b8 = gen.make_batch_fp8kv("stream_f8", 930 + runs, 32, 8, 128, RAGGED)
+    got = run_attention_fp8kv(b8)
+    ref = oracle.attn_mixed_batch_fp8kv(b8.q, b8.k_pool, b8.v_pool, b8.block_tables, b8.q_offsets, b8.ctx_lens, b8.scale,
+                                        b8.meta["k_scale"], b8.meta["v_scale"])
+    assert np.abs(got - ref).max() <= TOL
+
+
+def test_one_run_and_the_item_form_agree(monkeypatch):
+    """One run: no row is cut and every row is one item, as in the item form with a partition that
+    covers the whole row; the two forms share the per-block arithmetic, so the results are equal
+    bit for bit."""
+    from gpu_harness import run_attention
+    b = gen.make_batch("stream_same", 940, 32, 8, 128, [(1, c) for c in (1, 100, 1000, 1024, 513)])
+    monkeypatch.setenv("DSV_ROWS_STREAM", "0")
+    monkeypatch.setenv("DSV_PART_TOKENS", "1024")
+    items = run_attention(b)
+    monkeypatch.delenv("DSV_PART_TOKENS")
+    monkeypatch.setenv("DSV_ROWS_STREAM", "1")
+    stream = run_attention(b)
+    np.testing.assert_array_equal(stream, items)
+    ref = oracle.attn_mixed_batch(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens, b.scale)
+    assert np.abs(stream - ref).max() <= TOL

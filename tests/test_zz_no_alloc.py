@@ -52,11 +52,11 @@ def test_two_calls_in_a_row_the_second_smaller():
 
 
 def test_a_batch_beyond_the_fixed_array_is_refused_before_any_work():
-    """96 decodes on 32K contexts need more partial-result space than the array holds: the call
-    returns DSV_E_WORKSPACE and leaves the output untouched."""
+    """4,096 decodes with 64 query heads need more partial-result space than the array holds: the
+    call returns DSV_E_WORKSPACE and leaves the output untouched."""
     import torch
     import paper_2504_09285_amd as dsv
-    n, ctx, Hq, Hkv, D = 96, 32768, 64, 8, 128
+    n, ctx, Hq, Hkv, D = 4096, 4096, 64, 8, 128
     q_offsets = np.arange(n + 1, dtype=np.int32)
     ctx_lens = np.full(n, ctx, np.int32)
     assert dsv.attn_mixed_batch_workspace_bytes(q_offsets, ctx_lens, Hq, Hkv, D) > dsv.attn_mixed_batch_static_max_bytes()
