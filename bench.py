@@ -135,6 +135,17 @@ def upload(b):
     return d
 
 
+def size_workspace(d):
+    """(Re)allocates the workspace for the batch under the knobs in force now: what a call needs
+    depends on how the planner cuts the batch, which the environment knobs can change."""
+    import torch
+    import paper_2504_09285_amd as dsv
+    b = d.b
+    nbytes = dsv.attn_mixed_batch_workspace_bytes(b.q_offsets, b.ctx_lens, b.Hq, b.Hkv, b.D)
+    if getattr(d, "workspace", None) is None or d.workspace.numel() < nbytes:
+        d.workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+
+
 def attn_step(d):
     import paper_2504_09285_amd as dsv
     if getattr(d, "step", None) is not None:
@@ -219,6 +230,7 @@ def bench_attention(b, steps, warmup, hev):
         res["mixed_launch_ms"] = per_kernel[dsv.KERNEL_MIXED]
         os.environ["DSV_MIXED_LAUNCH"] = "0"
         try:
+            size_workspace(d)
             sec_apart, per_kernel = time_attention(d, max(steps // 2, 3), 2, ids, hev)
         finally:
             del os.environ["DSV_MIXED_LAUNCH"]
@@ -483,6 +495,7 @@ def bench_config4(threads, steps, warmup, hev):
     mixed_ms = pk[dsv.KERNEL_MIXED]
     os.environ["DSV_MIXED_LAUNCH"] = "0"                               # the two kernels apart, to time each
     try:
+        size_workspace(d)
         sec_apart, pk = time_attention(d, steps, warmup, ids, hev)
     finally:
         del os.environ["DSV_MIXED_LAUNCH"]

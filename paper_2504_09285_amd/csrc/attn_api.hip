@@ -233,22 +233,55 @@ PlanConfig choose_plan(int32_t S, const int32_t* qo, const int32_t* cl, bool kv8
   c.stream_total = 0;
   {
     const int want = env_int("DSV_ROWS_STREAM", -1);
-    int64_t rows = 0, blocks = 0;
-    bool tiles = false;
+    int64_t rows = 0, blocks = 0, q_tiles = 0;
     for (int i = 0; i < S; ++i) {
       const int q_len = qo[i + 1] - qo[i];
-      if (!on_row_path(q_len, cl[i], c)) { tiles = true; continue; }
+      if (!on_row_path(q_len, cl[i], c)) { q_tiles += ceil_div(q_len, c.tile_tokens); continue; }
       rows += q_len;
       for (int j = 0; j < q_len; ++j) blocks += ceil_div(cl[i] - q_len + j + 1, kBlockSize);
     }
+    const bool tiles = q_tiles > 0;
     const bool apart = !tiles || env_int("DSV_MIXED_LAUNCH", 1) == 0;
     const bool geometry = Hkv <= 8 && G <= 16 && c.row_nbuf == 2 && forced < 16;
     const int64_t total = blocks + rows * c.stream_row_cost;
-    int wgs = c.num_cus;
+    // Row work alone: three quarters of the compute units stream faster than all of them
+    // (config 5: 6.56 / 6.94 / 6.89 / 6.85 TB/s with 160 / 192 / 224 / 256 streams; config 2:
+    // 6.10 / 6.39 / 6.30 / 6.28): 192 streams already hold more bytes in flight than the memory
+    // system turns round, more only lengthen its queues.
+    int wgs = max(8, c.num_cus * 3 / 4 / 8 * 8);
+    if (!apart) {
+      // Rows and prefill tiles in one launch: the row streams take `wgs` compute units for the
+      // whole launch, the tiles' workgroups go through the others one item at a time.  The split
+      // that lets both sides end together, from what each side delivers on a share of the device
+      // (rows: 3.3 / 4.5 / 5.6 / 6.3 / 6.7 TB/s from 64 / 96 / 128 / 160 / 192 of 256 compute
+      // units, measured on config 4's decodes; tiles: 1.9 us per KV tile visited and 8 us per
+      // work item on a compute unit when all of them run tiles).  Too few row streams are the
+      // worse mistake: streams that end early hand their compute units to the tiles, tiles that
+      // end early cannot help the streams; and a compute unit runs tiles about 1.3 times faster
+      // when only a share of the device does (clocks).  Hence the factor on the tiles' side,
+      // set on config 4: 0.65 ms per step with 144-160 streams, 0.68 with 128, 0.67 with 192.
+      // (Both sides scale with the head size alike; 128 stands for it.)
+      const double row_gb = (double)blocks * (2.0 * kBlockSize * Hkv * 128 * (kv8 ? 1 : 2)) * 1e-9;
+      const double tile_cu_us = 0.7 * ((double)kv_visits * wgs_per_tile * 1.9 + (double)q_tiles * wgs_per_tile * 8.0);
+      static const double kShare[] = {0.0, 0.25, 0.375, 0.5, 0.625, 0.75, 1.0};
+      static const double kTBs[] = {0.0, 3.34, 4.52, 5.60, 6.33, 6.67, 6.67};
+      double best_t = 1e300;
+      for (int w8 = 8; w8 + 8 <= c.num_cus; w8 += 8) {
+        const double share = (double)w8 / c.num_cus;
+        int k = 0;
+        while (k < 5 && share > kShare[k + 1]) ++k;
+        const double tbs = kTBs[k] + (kTBs[k + 1] - kTBs[k]) * (share - kShare[k]) / (kShare[k + 1] - kShare[k]);
+        const double t_rows = row_gb / tbs * 1e3;                       // us
+        const double t_tiles = tile_cu_us / (c.num_cus - w8);
+        const double t = t_rows > t_tiles ? t_rows : t_tiles;
+        if (t < best_t) { best_t = t; wgs = w8; }
+      }
+    }
     if (want >= 1) wgs = want;
+    if (!apart) wgs = wgs / 8 * 8;          // whole groups of eight: the tiles keep KV head k on XCD k
     if (wgs > 4096) wgs = 4096;
     if ((int64_t)wgs > blocks) wgs = (int)blocks;
-    if (rows > 0 && apart && geometry && want != 0 && wgs >= 1 &&
+    if (rows > 0 && geometry && want != 0 && wgs >= 1 && (apart || (wgs >= 8 && wgs + 8 <= c.num_cus)) &&
         (want >= 1 || blocks >= (int64_t)16 * c.num_cus)) {
       c.stream_wgs = wgs;
       c.stream_total = total;

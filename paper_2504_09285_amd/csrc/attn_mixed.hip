@@ -12,6 +12,7 @@
 // attn_prefill_kernel.h), and heaviest-first tile order is kept.
 #include "attn_prefill_kernel.h"
 #include "attn_rows_kernel.h"
+#include "attn_rows_stream.h"
 
 namespace dsv {
 namespace {
@@ -76,10 +77,57 @@ int launch_mixed_t(const prefill_impl::TilesParams& tp, const rows_impl::RowsPar
   return launch_status();
 }
 
+// The other way to share the device: the row work as persistent streams (attn_rows_stream.h) on
+// the first row_wgs workgroups, which the hardware places first and which keep their compute
+// units to the end of the launch, and the tiles' workgroups behind them, one item each, going
+// through the remaining compute units as those free up.  Chosen by the planner for batches whose
+// row part is large (config 4: 128 decodes next to a 4,096-token prompt); row_wgs is a multiple
+// of eight, so a tile workgroup's KV head still falls on XCD (workgroup index mod 8).
+// (Measured on config 4, per step: this form 0.65 ms with 144-160 row streams; the interleaved
+// groups above 0.70 ms; persistent tile workgroups on the remaining compute units instead of one
+// workgroup per item 0.64 ms at their best split and 0.69-0.89 ms when the split is off by a few
+// streams, since tiles that stay put cannot take over the compute units of streams that end:
+// not kept.)
+template <int D, bool KV8>
+__global__ __launch_bounds__(512, 2) void mixed_stream_kernel(prefill_impl::TilesParams tp,
+                                                              rows_impl::RowsParams rp, uint32_t row_wgs) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  if (blockIdx.x < row_wgs) {
+    rows_impl::rows_stream_body<D, KV8>(rp, (int)blockIdx.x, smem);
+  } else {
+    int bx, bz;
+    prefill_impl::tile_work_item(blockIdx.x - row_wgs, tp.a.Hkv, tp.head_groups, bx, bz);
+    prefill_impl::prefill_tiles_body<D>(tp, bx, bz, smem);
+  }
+}
+
+template <int D, bool KV8>
+int launch_mixed_stream_t(const prefill_impl::TilesParams& tp, const rows_impl::RowsParams& rp, uint32_t row_wgs,
+                          uint32_t tile_wgs, hipStream_t stream) {
+  using RG = rows_impl::RowGeom<D, KV8 ? 1 : 2>;
+  constexpr int kRowsLds = 8 * (2 * RG::SLOT_BYTES + RG::KS * 1024);
+  constexpr int kTilesLds = (int)prefill_impl::TileGeom<D>::LDS_BYTES;
+  constexpr int kLds = kRowsLds > kTilesLds ? kRowsLds : kTilesLds;
+  static bool configured = false;     // idempotent; a race between two first calls is benign
+  if (!configured) {
+    hipFuncAttributes fa;               // no static LDS: the tile body's ring must start at LDS address 0
+    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(mixed_stream_kernel<D, KV8>)) != hipSuccess ||
+        fa.sharedSizeBytes != 0)
+      return DSV_E_LAUNCH;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(mixed_stream_kernel<D, KV8>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLds) != hipSuccess)
+      return DSV_E_LAUNCH;
+    configured = true;
+  }
+  hipLaunchKernelGGL((mixed_stream_kernel<D, KV8>), dim3(row_wgs + tile_wgs), dim3(512), kLds, stream, tp, rp, row_wgs);
+  return launch_status();
+}
+
 }  // namespace
 
 bool mixed_launch_supported(const AttnArgs& a, const PlanConfig& cfg, const PlanCounts& n) {
-  return n.tiles > 0 && n.items > 0 && cfg.stream_wgs == 0 && cfg.row_nbuf == 2 && cfg.tile_tokens >= 32 && cfg.tile_tokens <= prefill_impl::kTileQ &&
+  if (cfg.stream_wgs > 0 && (cfg.stream_wgs % 8 != 0 || a.Hkv > 8 || a.Hq / a.Hkv > rows_impl::kRowHeads)) return false;
+  return n.tiles > 0 && n.items > 0 && cfg.row_nbuf == 2 && cfg.tile_tokens >= 32 && cfg.tile_tokens <= prefill_impl::kTileQ &&
          cfg.part_tokens <= 64 * kBlockSize && prefill_impl::kThreads == 512 && (a.D == 128 || a.D == 64);
 }
 
@@ -89,6 +137,15 @@ int launch_mixed(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg, c
   const int G = a.Hq / a.Hkv;
   const prefill_impl::TilesParams tp = prefill_impl::make_tiles_params(a, w, cfg, n);
   rows_impl::RowsParams rp{a, w, cfg.part_tokens, G, 1};
+  if (cfg.stream_wgs > 0) {
+    const int64_t tile_wgs = n.tiles * a.Hkv * cfg.head_groups;
+    if (tile_wgs + cfg.stream_wgs > 0x7fffffffLL) return DSV_E_UNSUPPORTED;
+    const uint32_t rw = (uint32_t)cfg.stream_wgs, tw = (uint32_t)tile_wgs;
+    if (a.D == 128) return a.kv8 ? launch_mixed_stream_t<128, true>(tp, rp, rw, tw, stream)
+                                 : launch_mixed_stream_t<128, false>(tp, rp, rw, tw, stream);
+    return a.kv8 ? launch_mixed_stream_t<64, true>(tp, rp, rw, tw, stream)
+                 : launch_mixed_stream_t<64, false>(tp, rp, rw, tw, stream);
+  }
   int waves = 1;
   while (waves < a.Hkv && waves < 8) waves <<= 1;
   MixParams mp;

@@ -75,3 +75,31 @@ def test_one_run_and_the_item_form_agree(monkeypatch):
     np.testing.assert_array_equal(stream, items)
     ref = oracle.attn_mixed_batch(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens, b.scale)
     assert np.abs(stream - ref).max() <= TOL
+
+
+MIXED = [(300, 900), (1, 3000), (1, 17), (64, 64), (1, 5000), (2, 40), (1, 1), (1, 700), (130, 2130), (1, 2048), (9, 300)]
+
+
+@pytest.mark.parametrize("runs", [8, 64, 200])
+@pytest.mark.parametrize("Hq,Hkv,D", [(32, 8, 128), (64, 8, 128), (8, 2, 64)])
+def test_row_streams_and_prefill_tiles_in_one_launch(monkeypatch, runs, Hq, Hkv, D):
+    """A batch with prefill spans and decodes: the row work runs as `runs` persistent streams at the
+    head of the grid, the spans' tiles as one workgroup per item behind them."""
+    from gpu_harness import run_attention
+    monkeypatch.setenv("DSV_ROWS_STREAM", str(runs))
+    b = gen.make_batch("stream_mixed", 950 + runs + D + Hq, Hq, Hkv, D, MIXED)
+    got = run_attention(b)
+    ref = oracle.attn_mixed_batch(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens, b.scale)
+    assert np.isfinite(got).all()
+    err = np.abs(got - ref)
+    assert err.max() <= TOL, (float(err.max()), np.unravel_index(int(err.argmax()), err.shape))
+
+
+def test_row_streams_and_prefill_tiles_on_an_8bit_cache(monkeypatch):
+    from gpu_harness import run_attention_fp8kv
+    monkeypatch.setenv("DSV_ROWS_STREAM", "16")
+    b8 = gen.make_batch_fp8kv("stream_mixed_f8", 960, 32, 8, 128, MIXED)
+    got = run_attention_fp8kv(b8)
+    ref = oracle.attn_mixed_batch_fp8kv(b8.q, b8.k_pool, b8.v_pool, b8.block_tables, b8.q_offsets, b8.ctx_lens, b8.scale,
+                                        b8.meta["k_scale"], b8.meta["v_scale"])
+    assert np.abs(got - ref).max() <= TOL
