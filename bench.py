@@ -226,11 +226,18 @@ def bench_attention(b, steps, warmup, hev):
     res = {"workload": b.name, "ms_per_step": sec * 1e3, "tokens_per_s": b.total_q / sec,
            "total_q": b.total_q, "num_seqs": b.num_seqs,
            "host_enqueue_us_per_call": per_kernel["host_enqueue_us"]}
+    # Which kernels those were: the library says how it cuts the batch under the knobs in force.
+    info = dsv.attn_mixed_batch_plan_info(b.q_offsets, b.ctx_lens, b.Hq, b.Hkv, b.D)
+    res["plan"] = info
+    res["rows_kernel"] = "rows_stream_kernel" if info["row_streams"] else "rows_kernel"
     if per_kernel[dsv.KERNEL_MIXED] is not None:
         res["mixed_launch_ms"] = per_kernel[dsv.KERNEL_MIXED]
+        res["mixed_kernel"] = "mixed_stream_kernel" if info["row_streams"] else "mixed_kernel"
         os.environ["DSV_MIXED_LAUNCH"] = "0"
         try:
             size_workspace(d)
+            apart = dsv.attn_mixed_batch_plan_info(b.q_offsets, b.ctx_lens, b.Hq, b.Hkv, b.D)
+            res["rows_kernel"] = "rows_stream_kernel" if apart["row_streams"] else "rows_kernel"
             sec_apart, per_kernel = time_attention(d, max(steps // 2, 3), 2, ids, hev)
         finally:
             del os.environ["DSV_MIXED_LAUNCH"]
@@ -493,9 +500,11 @@ def bench_config4(threads, steps, warmup, hev):
     ids = [dsv.KERNEL_ROWS, dsv.KERNEL_TILES, dsv.KERNEL_MERGE, dsv.KERNEL_PLAN, dsv.KERNEL_MIXED]
     sec, pk = timed_step(d, steps, warmup, hev, ids)                   # as the library runs it: one mixed launch
     mixed_ms = pk[dsv.KERNEL_MIXED]
+    plan = dsv.attn_mixed_batch_plan_info(b.q_offsets, b.ctx_lens, b.Hq, b.Hkv, b.D)
     os.environ["DSV_MIXED_LAUNCH"] = "0"                               # the two kernels apart, to time each
     try:
         size_workspace(d)
+        apart = dsv.attn_mixed_batch_plan_info(b.q_offsets, b.ctx_lens, b.Hq, b.Hkv, b.D)
         sec_apart, pk = time_attention(d, steps, warmup, ids, hev)
     finally:
         del os.environ["DSV_MIXED_LAUNCH"]
@@ -503,6 +512,8 @@ def bench_config4(threads, steps, warmup, hev):
     t_mem, t_mfma = nbytes / (HBM_PEAK_GBS * 1e9), flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
     rows_ms, tiles_ms = pk[dsv.KERNEL_ROWS], pk[dsv.KERNEL_TILES]
     return {"workload": b.name, "split_k": sp.k, "ms_per_step": sec * 1e3, "tokens_per_s": b.total_q / sec,
+            "plan": plan, "mixed_kernel": "mixed_stream_kernel" if plan["row_streams"] else "mixed_kernel",
+            "rows_kernel": "rows_stream_kernel" if apart["row_streams"] else "rows_kernel",
             "mixed_launch_ms": mixed_ms, "ms_per_step_kernels_apart": sec_apart * 1e3,
             "kernel_ms": {"rows": rows_ms, "tiles": tiles_ms, "merge": pk[dsv.KERNEL_MERGE], "plan": pk[dsv.KERNEL_PLAN]},
             "handoff_pack_unpack_ms": handoff_ms, "handoff_chunks": int(len(sp.chunks)),
@@ -758,7 +769,8 @@ def attention_rooflines(res, b):
     k = res["kernel_ms"]
     if "decode" in res:
         p = res["decode"]
-        out.append(roofline_entry("rows_kernel", b.name, "hbm", p["GB/s"], "GB/s", k["rows"], p["algorithmic_bytes"]))
+        out.append(roofline_entry(res.get("rows_kernel", "rows_kernel"), b.name, "hbm", p["GB/s"], "GB/s", k["rows"],
+                                  p["algorithmic_bytes"]))
     if "prefill" in res:
         p = res["prefill"]
         out.append(roofline_entry("prefill_tiles_persistent_kernel", b.name, "mfma", p["TFLOP/s"], "TFLOP/s", k["tiles"],
@@ -822,8 +834,8 @@ def main():
         "kernel_ms": res["kernel_ms"], "host_enqueue_us_per_call": res["host_enqueue_us_per_call"],
     }
     own = attention_rooflines(res, b)
-    prefer = "prefill_tiles_persistent_kernel" if args.workload in ("c3", "c3h", "lp") else "rows_kernel"
-    main_rf = next((e for e in own if e["kernel"] == prefer), own[0] if own else None)
+    prefer = "prefill_tiles" if args.workload in ("c3", "c3h", "lp") else "rows_"
+    main_rf = next((e for e in own if e["kernel"].startswith(prefer)), own[0] if own else None)
     if main_rf:
         line["roofline"] = {k: main_rf[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel")}
         for k in ("traffic_source", "algorithmic_bytes", "algorithmic_flops"):
@@ -845,7 +857,8 @@ def main():
         if placement:
             extras["c5_rows_kernel_vs_block_placement"] = placement
         line["ceilings"] = measure_ceilings(hev)
-        keys = ("ms_per_step", "tokens_per_s", "host_enqueue_us_per_call", "mixed_launch_ms", "ms_per_step_kernels_apart", "kernel_ms", "prefill", "decode")
+        keys = ("ms_per_step", "tokens_per_s", "host_enqueue_us_per_call", "plan", "rows_kernel", "mixed_kernel", "mixed_launch_ms",
+                "ms_per_step_kernels_apart", "kernel_ms", "prefill", "decode")
 
         def other(name, bb, steps, cpu_seconds=0.0, shared_plan=False):
             r, dd = bench_attention(bb, steps, 5, hev)
@@ -874,11 +887,11 @@ def main():
         # Config 4: the mixed batch against its overlap bound, and the two kernels apart.
         c4 = bench_config4(threads, 40, 5, hev)
         extras["c4_micro_request"] = c4
-        rooflines.append({"kernel": "mixed_kernel", "workload": c4["workload"], "bound": "max(hbm, mfma): perfect overlap",
+        rooflines.append({"kernel": c4["mixed_kernel"], "workload": c4["workload"], "bound": "max(hbm, mfma): perfect overlap",
                           "t_hbm_ms": c4["bound_ms"]["hbm"], "t_mfma_ms": c4["bound_ms"]["mfma"], "ms": c4["ms_per_step"],
                           "frac": c4["frac_of_overlap_bound"], "unit": "fraction of the step's overlap bound",
                           "achieved": c4["frac_of_overlap_bound"], "peak": 1.0, "traffic": None})
-        rooflines.append(roofline_entry("rows_kernel", c4["workload"], "hbm", c4["decode"]["GB/s"], "GB/s",
+        rooflines.append(roofline_entry(c4["rows_kernel"], c4["workload"], "hbm", c4["decode"]["GB/s"], "GB/s",
                                         c4["kernel_ms"]["rows"], c4["decode_bytes"], note="launched apart from the tiles"))
         rooflines.append(roofline_entry("prefill_tiles_persistent_kernel", c4["workload"], "mfma", c4["prefill"]["TFLOP/s"], "TFLOP/s",
                                         c4["kernel_ms"]["tiles"], c4["prefill_flops"], note="launched apart from the rows"))
@@ -898,7 +911,7 @@ def main():
         f8 = bench_fp8kv(20, 3, hev)
         extras["fp8kv"] = f8
         r8 = f8["c2_decode_heavy_fp8kv"]
-        rooflines.append(roofline_entry("rows_kernel_fp8kv", "c2_decode_heavy", "hbm", r8["decode"]["GB/s"], "GB/s",
+        rooflines.append(roofline_entry("rows_stream_kernel_fp8kv", "c2_decode_heavy", "hbm", r8["decode"]["GB/s"], "GB/s",
                                         r8["kernel_ms"]["rows"], r8["decode"]["algorithmic_bytes"]))
         if not args.no_cpu_baseline:
             cpu.append(cpu_baseline_handoff(threads))

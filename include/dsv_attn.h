@@ -98,6 +98,27 @@ size_t attn_mixed_batch_workspace_bytes(int32_t num_seqs, const int32_t* q_offse
                                         int32_t num_kv_heads, int32_t head_dim);
 
 /*
+ * How the library would cut this batch into GPU work (paper section 4.2, Alg. 2: the batch is
+ * known on the host before the step; the cut depends on nothing else, apart from the tuning
+ * knobs in the environment).  Host only, no GPU call; for tests, benchmarks and logs.
+ *   kv_elem_bytes  2 (bf16 cache) or 1 (8-bit cache)
+ *   info           host, int32[8], filled on success:
+ *     [0] row streams: 0 = the row work (decodes and the smallest spans) is cut into items of
+ *         info[1] tokens of context, one workgroup each; n > 0 = it runs as n persistent
+ *         workgroups that each stream an equal share of all rows' KV blocks
+ *     [1] tokens per context partition of a row item (0 with row streams)
+ *     [2] query tokens on the row path   [3] row work items (with streams: an upper bound)
+ *     [4] work items of the prefill-span (matrix-core) path, per KV head and head group
+ *     [5] KV tiles per partition of a query tile cut along the context, 0 = not cut
+ *     [6] 1 if row work and prefill tiles go out in one launch   [7] query tokens per tile
+ * Returns DSV_OK, DSV_E_INVALID or DSV_E_UNSUPPORTED as attn_mixed_batch would.
+ */
+int attn_mixed_batch_plan_info(int32_t num_seqs, const int32_t* q_offsets_host,
+                               const int32_t* ctx_lens_host, int32_t num_q_heads,
+                               int32_t num_kv_heads, int32_t head_dim, int32_t kv_elem_bytes,
+                               int32_t* info);
+
+/*
  * Attention of one mixed batch (paper section 3.1 "Unified execution instances", section 4.2
  * and Alg. 2: each step runs one token-level batch holding all decode tokens plus prefill
  * spans; section 3.1 "Micro-request abstraction": a span is any contiguous token range of a

@@ -46,7 +46,7 @@ CHUNK_DTYPE = np.dtype([("seq", "<i4"), ("token_begin", "<i4"), ("num_tokens", "
                         ("reserved", "<i4"), ("chunk_offset", "<i8")])
 assert CHUNK_DTYPE.itemsize == 24
 
-EXPORTS = ("attn_mixed_batch_workspace_bytes", "attn_mixed_batch", "kv_pack_chunks",
+EXPORTS = ("attn_mixed_batch_workspace_bytes", "attn_mixed_batch_plan_info", "attn_mixed_batch", "kv_pack_chunks",
            "kv_unpack_chunks", "kv_append", "attn_mixed_batch_fp8kv_workspace_bytes",
            "attn_mixed_batch_fp8kv", "kv_append_fp8", "kv_pack_chunks_fp8", "kv_unpack_chunks_fp8",
            "attn_mixed_batch_plan", "attn_mixed_batch_planned", "attn_mixed_batch_fp8kv_planned",
@@ -79,6 +79,8 @@ def load_library():
     i32p, vp = C.POINTER(C.c_int32), C.c_void_p
     lib.attn_mixed_batch_workspace_bytes.restype = C.c_size_t
     lib.attn_mixed_batch_workspace_bytes.argtypes = [C.c_int32, i32p, i32p, C.c_int32, C.c_int32, C.c_int32]
+    lib.attn_mixed_batch_plan_info.restype = C.c_int
+    lib.attn_mixed_batch_plan_info.argtypes = [C.c_int32, i32p, i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, i32p]
     lib.attn_mixed_batch.restype = C.c_int
     lib.attn_mixed_batch.argtypes = [vp, vp, C.POINTER(_Pool), C.c_int32, vp, C.c_int32, vp, vp,
                                      i32p, i32p, C.c_int32, C.c_int32, C.c_float, C.c_int32,
@@ -266,6 +268,23 @@ def attn_mixed_batch_workspace_bytes(q_offsets_host, ctx_lens_host, num_q_heads,
     _require(qo.shape[0] == cl.shape[0] + 1, "q_offsets_host needs one entry more than ctx_lens_host")
     return int(load_library().attn_mixed_batch_workspace_bytes(
         cl.shape[0], _i32_ptr(qo), _i32_ptr(cl), num_q_heads, num_kv_heads, head_dim))
+
+
+PLAN_INFO_FIELDS = ("row_streams", "part_tokens", "rows", "row_items", "tile_items", "tile_part_tiles",
+                    "one_launch", "tile_tokens")
+
+
+def attn_mixed_batch_plan_info(q_offsets_host, ctx_lens_host, num_q_heads, num_kv_heads, head_dim,
+                               kv_elem_bytes=2) -> dict:
+    """See ``attn_mixed_batch_plan_info`` in include/dsv_attn.h; the eight integers by name."""
+    qo, cl = _host_i32(q_offsets_host), _host_i32(ctx_lens_host)
+    _require(qo.shape[0] == cl.shape[0] + 1, "q_offsets_host needs one entry more than ctx_lens_host")
+    info = np.zeros(8, np.int32)
+    rc = load_library().attn_mixed_batch_plan_info(cl.shape[0], _i32_ptr(qo), _i32_ptr(cl), int(num_q_heads),
+                                                   int(num_kv_heads), int(head_dim), int(kv_elem_bytes), _i32_ptr(info))
+    if rc:
+        raise DsvError("attn_mixed_batch_plan_info", rc)
+    return dict(zip(PLAN_INFO_FIELDS, (int(x) for x in info)))
 
 
 def attn_mixed_batch(q, out, pool: KVPool, layer, block_tables, q_offsets, ctx_lens,

@@ -1041,6 +1041,32 @@ extern "C" size_t attn_mixed_batch_workspace_bytes(int32_t num_seqs, const int32
                              num_kv_heads, head_dim);
 }
 
+extern "C" int attn_mixed_batch_plan_info(int32_t num_seqs, const int32_t* q_offsets_host,
+                                          const int32_t* ctx_lens_host, int32_t num_q_heads,
+                                          int32_t num_kv_heads, int32_t head_dim, int32_t kv_elem_bytes,
+                                          int32_t* info) {
+  if (!info || num_q_heads < 1 || num_kv_heads < 1 || num_q_heads % num_kv_heads) return DSV_E_INVALID;
+  if (head_dim != 64 && head_dim != 128) return DSV_E_UNSUPPORTED;
+  if (kv_elem_bytes != 1 && kv_elem_bytes != 2) return DSV_E_INVALID;
+  const int rc = validate_batch(num_seqs, q_offsets_host, ctx_lens_host, -1);
+  if (rc) return rc;
+  for (int k = 0; k < 8; ++k) info[k] = 0;
+  if (num_seqs == 0) return DSV_OK;
+  const PlanConfig c = choose_plan(num_seqs, q_offsets_host, ctx_lens_host, kv_elem_bytes == 1, num_kv_heads,
+                                   num_q_heads / num_kv_heads);
+  const PlanCounts n = count_plan(num_seqs, q_offsets_host, ctx_lens_host, c);
+  auto clip = [](int64_t v) { return (int32_t)(v > 0x7fffffffLL ? 0x7fffffffLL : v); };
+  info[0] = c.stream_wgs;
+  info[1] = c.stream_wgs > 0 ? 0 : c.part_tokens;
+  info[2] = clip(n.rows);
+  info[3] = clip(n.items);
+  info[4] = clip(n.tiles);
+  info[5] = c.tile_part_tiles;
+  info[6] = (n.tiles > 0 && n.items > 0 && env_int("DSV_MIXED_LAUNCH", 1) != 0) ? 1 : 0;
+  info[7] = c.tile_tokens;
+  return DSV_OK;
+}
+
 extern "C" size_t attn_mixed_batch_fp8kv_workspace_bytes(int32_t num_seqs, const int32_t* q_offsets_host,
                                                          const int32_t* ctx_lens_host,
                                                          int32_t num_q_heads, int32_t num_kv_heads,

@@ -195,3 +195,31 @@ def test_static_entry_point_refuses_oversized_and_invalid_batches_on_the_host(li
     bad = cl.copy()
     bad[3] = 0
     assert call(qo, bad, n) == -1
+
+
+def test_plan_info_says_how_a_batch_is_cut(lib, monkeypatch):
+    """attn_mixed_batch_plan_info is host-only.  Long decode-only batches run as row streams (three
+    quarters of the compute units; 256 are assumed where no device answers), small ones as items
+    of a partition size; a batch with a prefill span reports its tile items; the knob forces
+    streams; invalid batches are refused as by attn_mixed_batch."""
+    for k in ("DSV_ROWS_STREAM", "DSV_PART_TOKENS", "DSV_MIXED_LAUNCH"):
+        monkeypatch.delenv(k, raising=False)
+    qo = np.arange(65, dtype=np.int32)
+    cl = np.full(64, 40000, np.int32)
+    big = dsv.attn_mixed_batch_plan_info(qo, cl, 32, 8, 128)
+    assert big["row_streams"] > 0 and big["row_streams"] % 8 == 0 and big["part_tokens"] == 0
+    assert big["rows"] == 64 and big["row_items"] == 64 + big["row_streams"] - 1 and big["tile_items"] == 0
+    small = dsv.attn_mixed_batch_plan_info([0, 1, 2], [100, 200], 32, 8, 128)
+    assert small["row_streams"] == 0 and small["part_tokens"] % 16 == 0 and small["rows"] == 2
+    mixed = dsv.attn_mixed_batch_plan_info([0, 2048, 2049], [2048, 900], 32, 8, 128)
+    assert mixed["tile_items"] >= 32 and mixed["rows"] == 1 and mixed["one_launch"] == 1 and mixed["tile_tokens"] == 64
+    monkeypatch.setenv("DSV_ROWS_STREAM", "5")
+    assert dsv.attn_mixed_batch_plan_info([0, 1, 2], [100, 200], 32, 8, 128)["row_streams"] == 5
+    monkeypatch.setenv("DSV_ROWS_STREAM", "0")
+    assert dsv.attn_mixed_batch_plan_info(qo, cl, 32, 8, 128)["row_streams"] == 0
+    monkeypatch.delenv("DSV_ROWS_STREAM")
+    with pytest.raises(dsv.DsvError):
+        dsv.attn_mixed_batch_plan_info([0, 1], [0], 32, 8, 128)
+    with pytest.raises(dsv.DsvError):
+        dsv.attn_mixed_batch_plan_info([0, 1], [5], 32, 8, 96)
+    assert dsv.attn_mixed_batch_plan_info([0, 1], [5], 32, 8, 128, kv_elem_bytes=1)["rows"] == 1

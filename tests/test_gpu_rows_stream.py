@@ -21,8 +21,11 @@ RAGGED = [(1, 1), (1, 15), (1, 16), (1, 17), (1, 3000), (1, 31), (1, 32), (1, 33
 @pytest.mark.parametrize("Hq,Hkv,D", [(32, 8, 128), (8, 2, 64), (16, 1, 128), (5, 5, 64)])
 def test_decodes_of_every_length_in_any_number_of_runs(monkeypatch, runs, Hq, Hkv, D):
     from gpu_harness import run_attention
+    import paper_2504_09285_amd as dsv
     monkeypatch.setenv("DSV_ROWS_STREAM", str(runs))
     b = gen.make_batch("stream_ragged", 900 + runs + D, Hq, Hkv, D, RAGGED)
+    blocks = int(((b.ctx_lens + 15) // 16).sum())
+    assert dsv.attn_mixed_batch_plan_info(b.q_offsets, b.ctx_lens, Hq, Hkv, D)["row_streams"] == min(runs, blocks)
     got = run_attention(b)
     ref = oracle.attn_mixed_batch(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens, b.scale)
     assert np.isfinite(got).all()
@@ -86,8 +89,11 @@ def test_row_streams_and_prefill_tiles_in_one_launch(monkeypatch, runs, Hq, Hkv,
     """A batch with prefill spans and decodes: the row work runs as `runs` persistent streams at the
     head of the grid, the spans' tiles as one workgroup per item behind them."""
     from gpu_harness import run_attention
+    import paper_2504_09285_amd as dsv
     monkeypatch.setenv("DSV_ROWS_STREAM", str(runs))
     b = gen.make_batch("stream_mixed", 950 + runs + D + Hq, Hq, Hkv, D, MIXED)
+    info = dsv.attn_mixed_batch_plan_info(b.q_offsets, b.ctx_lens, Hq, Hkv, D)
+    assert info["row_streams"] == runs and info["one_launch"] == 1 and info["tile_items"] > 0
     got = run_attention(b)
     ref = oracle.attn_mixed_batch(b.q, b.k_pool, b.v_pool, b.block_tables, b.q_offsets, b.ctx_lens, b.scale)
     assert np.isfinite(got).all()
