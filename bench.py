@@ -630,8 +630,9 @@ def bench_concurrent(b, h, rounds, hev):
 # ---------------------------------------------------------------------------- ceilings
 def measure_ceilings(hev):
     """What this GPU delivers on the plainest loops, through the library's calibration kernels:
-    HBM read / write / copy over 2 GiB with kv_copy_kernel's launch shape and hints, and a
-    register-resident bf16 MFMA loop at the prefill kernel's occupancy."""
+    HBM read / write / copy over 2 GiB with kv_copy_kernel's launch shape and hints, a read of
+    2 x 2 GiB in the row kernel's access shape with no arithmetic, and a register-resident bf16
+    MFMA loop at the prefill kernel's occupancy."""
     import torch
     import paper_2504_09285_amd as dsv
     n = 2 << 30
@@ -660,6 +661,13 @@ def measure_ceilings(hev):
     for name, mode, moved in (("read", 0, n), ("write", 1, n), ("copy", 2, 2 * n)):
         ms = timed(lambda: dsv.dsv_calib_hbm(mode, dst, src, n))
         out["hbm_%s_GB/s" % name] = moved / (ms * 1e-3) / 1e9
+    # the row kernel's access shape (scattered 32 KiB blocks, one head's pieces per wave, through LDS)
+    moved = [0.0]
+
+    def paged():
+        moved[0] = dsv.dsv_calib_paged_read(src, dst, sink)
+    ms = timed(paged)
+    out["hbm_read_paged_rows_GB/s"] = moved[0] / (ms * 1e-3) / 1e9
     flops = [0.0]
 
     def mfma():
@@ -673,7 +681,8 @@ def measure_ceilings(hev):
 def against_measured_ceilings(entries, ceilings):
     """Adds to every roofline entry what the same box delivered on the matching calibration loop
     in this run (a kernel that only reads: the sequential read; the copies: the plain copy;
-    MFMA-bound: the register-resident MFMA loop) and the kernel's fraction of that."""
+    MFMA-bound: the register-resident MFMA loop) and the kernel's fraction of that; the row
+    kernels also against the paged read in their own access shape."""
     for e in entries:
         kernel = e.get("kernel", "")
         if e.get("bound") == "mfma":
@@ -684,6 +693,8 @@ def against_measured_ceilings(entries, ceilings):
             continue
         e["measured_ceiling"] = top
         e["frac_of_measured_ceiling"] = e["achieved"] / top
+        if kernel.startswith("rows_") and "hbm_read_paged_rows_GB/s" in ceilings:
+            e["frac_of_paged_read"] = e["achieved"] / ceilings["hbm_read_paged_rows_GB/s"]
 
 
 # ---------------------------------------------------------------------------- CPU baseline

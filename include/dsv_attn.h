@@ -401,9 +401,18 @@ int dsv_profile_events(int32_t kernel_id, void* start_event, void* stop_event);
  *                   accumulators per wave, two waves per SIMD (the prefill kernel's occupancy),
  *                   four workgroups per compute unit; *flops_out (host, may be NULL) receives the
  *                   floating-point operations one launch performs.  sink: device, 4 bytes.
- * Both enqueue one kernel on hip_stream and return; errors as for the other entry points.
+ *   dsv_calib_paged_read  the row kernel's access shape with nothing else: k and v (device,
+ *                   bytes_each bytes each, a power-of-two number of 32 KiB blocks, at least 64) are
+ *                   read as pools of [16 tokens][8 heads][256 bytes] blocks visited in a scattered
+ *                   order, by workgroups of eight waves that stream 64 blocks each, every wave
+ *                   fetching one head's 256-byte pieces global->LDS into a ring of two 8 KiB slots,
+ *                   one block ahead.  *bytes_out (host, may be NULL) receives the bytes one launch
+ *                   reads.  sink: device, 4 bytes.
+ * Each enqueues one kernel on hip_stream and returns; errors as for the other entry points.
  */
 int dsv_calib_hbm(int32_t mode, void* dst, const void* src, size_t bytes, void* hip_stream);
+int dsv_calib_paged_read(const void* k, const void* v, size_t bytes_each, void* sink, double* bytes_out,
+                         void* hip_stream);
 int dsv_calib_mfma(int32_t iters, void* sink, double* flops_out, void* hip_stream);
 
 /* Library build identification: a static string, e.g. "dsv_attn gfx950 <date>". */

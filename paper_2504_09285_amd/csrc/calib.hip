@@ -68,8 +68,79 @@ __global__ __launch_bounds__(512, 2) void mfma_kernel(float* sink, int iters) {
   if (s == -1.0f) sink[0] = s;                   // never true: sums of non-negative products
 }
 
+// The row kernel's access shape with nothing else: both buffers are read as pools of 32 KiB
+// blocks ([16 tokens][8 heads][256 bytes]) visited in a scattered order; a workgroup of eight
+// waves streams 64 blocks, wave w fetching the 256-byte pieces of head w of every token, 16 bytes
+// per lane, global->LDS, into a ring of two 8 KiB slots of its own (K piece, V piece), one block
+// ahead of the one it waits for.  Block i of the sweep is pool block (i * 40503 + 977) mod blocks
+// (blocks is a power of two, so the map is a permutation).
+constexpr int kPagedBlock = 32768;
+constexpr int kPagedPerItem = 64;
+constexpr int kCalibStreamOnce = 2;     // cache-policy bits of the load: nontemporal, as the row kernel streams K/V
+__global__ __launch_bounds__(512) void paged_read_kernel(const unsigned char* __restrict__ kbuf,
+                                                         const unsigned char* __restrict__ vbuf, uint32_t blocks,
+                                                         unsigned* sink) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  typedef __attribute__((address_space(3))) void* lds_void_t;
+  typedef const __attribute__((address_space(1))) void* gbl_void_t;
+  const int wave = (int)threadIdx.x / 64, lane = (int)threadIdx.x % 64;
+  unsigned char* ring = smem + wave * 16384;
+  uint32_t off[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) off[i] = (uint32_t)((i * 4 + lane / 16) * 2048 + wave * 256 + (lane % 16) * 16);
+  const uint32_t first = blockIdx.x * kPagedPerItem;
+  auto issue = [&](uint32_t i, int slot) {
+    const size_t base = (size_t)((i * 40503u + 977u) & (blocks - 1)) * kPagedBlock;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      __builtin_amdgcn_global_load_lds((gbl_void_t)(kbuf + base + off[r]), (lds_void_t)(ring + slot * 8192 + r * 1024), 16, 0, kCalibStreamOnce);
+      __builtin_amdgcn_global_load_lds((gbl_void_t)(vbuf + base + off[r]), (lds_void_t)(ring + slot * 8192 + 4096 + r * 1024), 16, 0, kCalibStreamOnce);
+    }
+  };
+  unsigned acc = 0;
+  issue(first, 0);
+  for (int b = 0; b < kPagedPerItem; ++b) {
+    const int slot = b & 1;
+    if (b + 1 < kPagedPerItem) {
+      issue(first + b + 1, slot ^ 1);
+      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    unsigned x;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                 : "=v"(x)
+                 : "v"((uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)(ring + slot * 8192 + lane * 16))
+                 : "memory");
+    acc ^= x;
+  }
+  if (acc == 0x9e3779b9u && blocks == 3u) sink[0] = acc;       // never true: blocks is a power of two
+}
+
 }  // namespace
 }  // namespace dsv
+
+extern "C" int dsv_calib_paged_read(const void* k, const void* v, size_t bytes_each, void* sink, double* bytes_out,
+                                    void* hip_stream) {
+  using namespace dsv;
+  if (!k || !v || !sink || (reinterpret_cast<uintptr_t>(k) & 15) || (reinterpret_cast<uintptr_t>(v) & 15)) return DSV_E_INVALID;
+  const uint64_t blocks = bytes_each / kPagedBlock;
+  if (blocks < (uint64_t)kPagedPerItem || (blocks & (blocks - 1)) || blocks * kPagedBlock != bytes_each) return DSV_E_INVALID;
+  if (blocks > 0x40000000ull) return DSV_E_UNSUPPORTED;
+  static bool configured = false;       // raising the dynamic-LDS limit is idempotent; races are benign
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(paged_read_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            128 * 1024) != hipSuccess)
+      return DSV_E_LAUNCH;
+    configured = true;
+  }
+  if (bytes_out) *bytes_out = 2.0 * (double)bytes_each;
+  begin_gpu_work();
+  hipLaunchKernelGGL(paged_read_kernel, dim3((unsigned)(blocks / kPagedPerItem)), dim3(512), 128 * 1024,
+                     static_cast<hipStream_t>(hip_stream), static_cast<const unsigned char*>(k),
+                     static_cast<const unsigned char*>(v), (uint32_t)blocks, static_cast<unsigned*>(sink));
+  return launch_status();
+}
 
 extern "C" int dsv_calib_hbm(int32_t mode, void* dst, const void* src, size_t bytes, void* hip_stream) {
   using namespace dsv;
