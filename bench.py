@@ -627,6 +627,126 @@ def bench_concurrent(b, h, rounds, hev):
     return out
 
 
+# ---------------------------------------------------------------------------- board power
+class BoardSensors:
+    """The card's power sensor and shader-clock state as the amdgpu driver shows them in sysfs
+    (readable without privileges); every reading is None where the files are absent."""
+
+    def __init__(self):
+        import glob
+        self.power = (glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") +
+                      glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average") + [None])[0]
+        self.sclk = (glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk") + [None])[0]
+        cap = self.power and os.path.join(os.path.dirname(self.power), "power1_cap")
+        self.cap_W = self._read_uW(cap)
+
+    @staticmethod
+    def _read_uW(path):
+        try:
+            return int(open(path).read()) / 1e6
+        except (OSError, ValueError, TypeError):
+            return None
+
+    def watts(self):
+        return self._read_uW(self.power)
+
+    def mhz(self):
+        try:
+            for ln in open(self.sclk).read().splitlines():
+                if "*" in ln:
+                    return float(ln.split(":")[1].strip().lower().split("mhz")[0])
+        except (OSError, ValueError, TypeError, IndexError):
+            pass
+        return None
+
+
+def power_under(fn, sensors, seconds=2.0, batch=20):
+    """Loops fn for `seconds` while a thread samples the board sensors every 50 ms; the first third
+    of the samples (clock and power still settling) is dropped."""
+    import threading
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    watts, mhz, stop = [], [], [False]
+
+    def sampler():
+        while not stop[0]:
+            watts.append(sensors.watts())
+            mhz.append(sensors.mhz())
+            time.sleep(0.05)
+    th = threading.Thread(target=sampler)
+    th.start()
+    t0 = time.perf_counter()
+    n = 0
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(batch):
+            fn()
+        torch.cuda.synchronize()
+        n += batch
+    dt = time.perf_counter() - t0
+    stop[0] = True
+    th.join()
+
+    def mean(xs):
+        xs = [x for x in xs[len(xs) // 3:] if x is not None]
+        return float(np.mean(xs)) if xs else None
+    w = mean(watts)
+    return {"ms_per_call": dt / n * 1e3, "board_W": w, "sclk_MHz": mean(mhz),
+            "mJ_per_call": None if w is None else w * dt / n * 1e3}
+
+
+def bench_power(threads, hev):
+    """Board power and shader clock under each kind of work, looped for two seconds each: the
+    calibration loops, config 4's decodes alone, its prefill spans alone, and the mixed batch.
+    With every loop at the board's power limit, the time of a step is its energy over that limit,
+    and two kinds of work that each fill the limit cannot overlap for free."""
+    import torch
+    import paper_2504_09285_amd as dsv
+    from workloads import gen
+    sensors = BoardSensors()
+    out = {"power_cap_W": sensors.cap_W}
+    if sensors.power is None:
+        out["note"] = "no power sensor readable on this box"
+        return out
+    torch.cuda.synchronize()
+    time.sleep(1.0)
+    out["W_after_1s_idle"] = sensors.watts()
+    sink = torch.zeros(16, dtype=torch.float32, device="cuda")
+    n = 1 << 30
+    src = torch.full((n,), 1, dtype=torch.uint8, device="cuda")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(92856)
+    operands = torch.randn(1 << 20, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    flops = [0.0]
+
+    def mfma_fixed():
+        flops[0] = dsv.dsv_calib_mfma(4000, sink)
+
+    def mfma_data():
+        flops[0] = dsv.dsv_calib_mfma_data(4000, operands, sink)
+    r = power_under(mfma_fixed, sensors, batch=4)
+    r["TFLOP/s"] = flops[0] / (r["ms_per_call"] * 1e-3) / 1e12
+    out["mfma_loop_fixed_operands"] = r
+    r = power_under(mfma_data, sensors, batch=4)
+    r["TFLOP/s"] = flops[0] / (r["ms_per_call"] * 1e-3) / 1e12
+    out["mfma_loop_random_operands"] = r
+    r = power_under(lambda: dsv.dsv_calib_hbm(0, sink, src, n), sensors)
+    r["GB/s"] = n / (r["ms_per_call"] * 1e-3) / 1e9
+    out["hbm_read_loop"] = r
+    del src
+    b4, _ = gen.config4(threads=threads)
+    segs = list(zip(np.diff(b4.q_offsets).tolist(), b4.ctx_lens.tolist()))
+    parts = {"c4_decodes_alone": [sg for sg in segs if sg[0] == 1], "c4_prefill_spans_alone": [sg for sg in segs if sg[0] > 1]}
+    d4 = upload(b4)
+    out["c4_mixed_batch"] = power_under(lambda: attn_step(d4), sensors)
+    del d4
+    for name, sub in parts.items():
+        dd = upload(gen.make_batch(name, 92857, b4.Hq, b4.Hkv, b4.D, sub, threads=threads))
+        out[name] = power_under(lambda: attn_step(dd), sensors)
+        del dd
+    return out
+
+
 # ---------------------------------------------------------------------------- ceilings
 def measure_ceilings(hev):
     """What this GPU delivers on the plainest loops, through the library's calibration kernels:
@@ -674,6 +794,18 @@ def measure_ceilings(hev):
         flops[0] = dsv.dsv_calib_mfma(4000, sink)
     ms = timed(mfma, reps=2)
     out["mfma_bf16_TFLOP/s"] = flops[0] / (ms * 1e-3) / 1e12
+    # the same loop on N(0,1) operands that change from MFMA to MFMA: what the board's power limit
+    # leaves of the matrix cores' rate on data like the attention kernel's
+    g = torch.Generator(device="cuda")
+    g.manual_seed(92856)
+    operands = torch.randn(1 << 20, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+
+    def mfma_data():
+        flops[0] = dsv.dsv_calib_mfma_data(4000, operands, sink)
+    for _ in range(20):                       # the clock settles under the load before anything is timed
+        mfma_data()
+    ms = timed(mfma_data, reps=4)
+    out["mfma_bf16_random_operands_TFLOP/s"] = flops[0] / (ms * 1e-3) / 1e12
     del src, dst
     return out
 
@@ -693,6 +825,8 @@ def against_measured_ceilings(entries, ceilings):
             continue
         e["measured_ceiling"] = top
         e["frac_of_measured_ceiling"] = e["achieved"] / top
+        if e.get("bound") == "mfma" and "mfma_bf16_random_operands_TFLOP/s" in ceilings:
+            e["frac_of_mfma_on_random_operands"] = e["achieved"] / ceilings["mfma_bf16_random_operands_TFLOP/s"]
         if kernel.startswith("rows_") and "hbm_read_paged_rows_GB/s" in ceilings:
             e["frac_of_paged_read"] = e["achieved"] / ceilings["hbm_read_paged_rows_GB/s"]
 
@@ -898,6 +1032,7 @@ def main():
         # Config 4: the mixed batch against its overlap bound, and the two kernels apart.
         c4 = bench_config4(threads, 40, 5, hev)
         extras["c4_micro_request"] = c4
+        extras["board_power"] = bench_power(threads, hev)
         rooflines.append({"kernel": c4["mixed_kernel"], "workload": c4["workload"], "bound": "max(hbm, mfma): perfect overlap",
                           "t_hbm_ms": c4["bound_ms"]["hbm"], "t_mfma_ms": c4["bound_ms"]["mfma"], "ms": c4["ms_per_step"],
                           "frac": c4["frac_of_overlap_bound"], "unit": "fraction of the step's overlap bound",

@@ -12,6 +12,6 @@ from .binding import (  # noqa: F401
     kv_append_fp8, kv_pack_chunks_fp8, kv_unpack_chunks_fp8, AttnPlan, attn_mixed_batch_plan,
     attn_mixed_batch_planned, attn_mixed_batch_fp8kv_planned, attn_mixed_batch_static,
     attn_mixed_batch_static_max_bytes, dsv_check_block_tables, kv_unpack_chunks_ordered,
-    kv_unpack_chunks_ordered_workspace_bytes, dsv_calib_hbm, dsv_calib_mfma, dsv_calib_paged_read,
+    kv_unpack_chunks_ordered_workspace_bytes, dsv_calib_hbm, dsv_calib_mfma, dsv_calib_mfma_data, dsv_calib_paged_read,
     attn_mixed_batch_plan_info,
 )

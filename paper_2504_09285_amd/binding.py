@@ -51,7 +51,7 @@ EXPORTS = ("attn_mixed_batch_workspace_bytes", "attn_mixed_batch_plan_info", "at
            "attn_mixed_batch_fp8kv", "kv_append_fp8", "kv_pack_chunks_fp8", "kv_unpack_chunks_fp8",
            "attn_mixed_batch_plan", "attn_mixed_batch_planned", "attn_mixed_batch_fp8kv_planned",
            "attn_mixed_batch_static", "attn_mixed_batch_static_max_bytes",
-           "kv_unpack_chunks_ordered", "kv_unpack_chunks_ordered_workspace_bytes", "dsv_check_block_tables", "dsv_calib_hbm", "dsv_calib_mfma", "dsv_calib_paged_read", "dsv_profile_events", "dsv_build_info")
+           "kv_unpack_chunks_ordered", "kv_unpack_chunks_ordered_workspace_bytes", "dsv_check_block_tables", "dsv_calib_hbm", "dsv_calib_mfma", "dsv_calib_mfma_data", "dsv_calib_paged_read", "dsv_profile_events", "dsv_build_info")
 KERNEL_PLAN, KERNEL_ROWS, KERNEL_TILES, KERNEL_MERGE, KERNEL_MIXED, KERNEL_STAGE = 0, 1, 2, 3, 4, 5
 
 
@@ -127,6 +127,8 @@ def load_library():
     lib.dsv_calib_hbm.argtypes = [C.c_int32, vp, vp, C.c_size_t, vp]
     lib.dsv_calib_mfma.restype = C.c_int
     lib.dsv_calib_mfma.argtypes = [C.c_int32, vp, C.POINTER(C.c_double), vp]
+    lib.dsv_calib_mfma_data.restype = C.c_int
+    lib.dsv_calib_mfma_data.argtypes = [C.c_int32, vp, C.c_size_t, vp, C.POINTER(C.c_double), vp]
     lib.dsv_calib_paged_read.restype = C.c_int
     lib.dsv_calib_paged_read.argtypes = [vp, vp, C.c_size_t, vp, C.POINTER(C.c_double), vp]
     lib.dsv_profile_events.restype = C.c_int
@@ -450,6 +452,17 @@ def dsv_calib_mfma(iters: int, sink, stream=None) -> float:
     rc = load_library().dsv_calib_mfma(int(iters), sink.data_ptr(), C.byref(flops), _stream_ptr(stream))
     if rc:
         raise DsvError("dsv_calib_mfma", rc)
+    return float(flops.value)
+
+
+def dsv_calib_mfma_data(iters: int, operands, sink, stream=None) -> float:
+    """See ``dsv_calib_mfma_data`` in include/dsv_attn.h; returns the flops of the launch."""
+    _require(operands.is_contiguous(), "operands must be contiguous")
+    flops = C.c_double()
+    rc = load_library().dsv_calib_mfma_data(int(iters), operands.data_ptr(), _nbytes(operands), sink.data_ptr(),
+                                            C.byref(flops), _stream_ptr(stream))
+    if rc:
+        raise DsvError("dsv_calib_mfma_data", rc)
     return float(flops.value)
 
 
