@@ -164,12 +164,12 @@ __device__ __forceinline__ void rows_stream_body(const RowsParams& prm, int wg, 
   const float scale = a.scale_log2e;
 
   // Output of an item: the row itself if it has one partition, else its partial for the merge
-  // kernel (nontemporal: written once, read once; see rows_body).  An item that ends in the
-  // middle of a run costs the workgroup about 5.5 us (measured: 1,024 rows of 352 tokens against
-  // 256 rows of 1,408; without the stores the two take the same time): operations complete in
-  // issue order, so the K/V loads requested after the stores cannot be seen to have landed
-  // before the stores have, and a store's way through a memory system saturated with reads is
-  // long.  The planner prices a row's start at two blocks for that reason.
+  // kernel (nontemporal: written once, read once; see rows_body).  The stores are what an item
+  // costs beyond its blocks (measured: 1,024 rows of 352 tokens 244 us against 226 for 256 rows of
+  // 1,408; without the partials 235 and 221, without any store 221 and 220), and it is their
+  // number that costs, not where in the run they are issued: with finished items' results held in
+  // registers and stored at the end of the run the times were the same.  The planner prices a
+  // row's start at two blocks for them.
   auto finish = [&](const Item& x, int item) __attribute__((always_inline)) {
     const float l_tot = cross16_sum(l_run);
     if (qcol >= nh) return;
