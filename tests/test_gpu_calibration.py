@@ -55,3 +55,21 @@ def test_mfma_loop_reports_its_flops():
     flops = dsv.dsv_calib_mfma(10, sink)
     torch.cuda.synchronize()
     assert flops > 0 and float(sink.abs().max()) == 0.0
+
+
+def test_mfma_loop_on_caller_operands_reports_its_flops_and_checks_its_arguments():
+    import torch
+    import paper_2504_09285_amd as dsv
+    sink = torch.zeros(16, dtype=torch.float32, device="cuda")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    ops = torch.randn(4096, generator=g, device="cuda").to(torch.bfloat16)
+    keep = ops.clone()
+    fixed = dsv.dsv_calib_mfma(16, sink)
+    assert dsv.dsv_calib_mfma_data(16, ops, sink) == fixed      # same launch shape, same count
+    torch.cuda.synchronize()
+    assert torch.equal(ops, keep) and float(sink.abs().max()) == 0.0
+    for iters, operands in ((12, ops), (0, ops), (16, ops[:64]), (16, ops[1:4001])):   # not a multiple of 8; too few; misaligned
+        with pytest.raises(dsv.DsvError):
+            dsv.dsv_calib_mfma_data(iters, operands, sink)
+    torch.cuda.synchronize()
