@@ -6,10 +6,11 @@
  *
  * Conventions for every entry point
  *   - Plain C, no exceptions, thread-compatible.  State the library keeps between calls, all
- *     of it host-side and none of it derived from a caller's buffers: a per-process cache of the
- *     device's compute-unit count, one flag per kernel saying that its dynamic-LDS limit has been
- *     raised, the per-device address of the fixed array of attn_mixed_batch_static, and, per host
- *     thread, the event handles set with dsv_profile_events (until cleared).
+ *     of it host-side and none of it derived from a caller's buffers, per device (up to 64
+ *     devices in a process): the compute-unit count, one flag per kernel saying that its
+ *     dynamic-LDS limit has been raised on that device, and the address of the fixed array of
+ *     attn_mixed_batch_static; and, per host thread, the event handles set with
+ *     dsv_profile_events (until cleared).
  *   - "device" pointers are HIP device memory on the current device; "host" pointers are
  *     ordinary host memory.  All buffers are caller-owned; the library allocates no device
  *     memory and keeps no pointer after the call returns.
@@ -21,8 +22,8 @@
  *     replayed.  A replay reads every device buffer afresh; what the host derived from the
  *     host-side arrays (grid sizes, workspace layout) is frozen, so a graph is valid for
  *     batches with the same host-side arrays.  Make one call of the same entry point, with the
- *     same head geometry and cache element size, outside the capture first: the first launch of
- *     each kernel variant raises that kernel's dynamic-LDS limit (once, to the largest value any
+ *     same head geometry and cache element size, on the same device, outside the capture first: the
+ *     first launch of each kernel variant on a device raises that kernel's dynamic-LDS limit (once, to the largest value any
  *     batch can need), which is not a capturable operation.
  *   - A call that enqueues work first clears the calling thread's HIP last-error state
  *     (hipGetLastError), so that an error left by an earlier, unrelated HIP call is not

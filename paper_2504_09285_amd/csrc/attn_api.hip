@@ -40,13 +40,14 @@ int env_int(const char* name, int fallback) {
 
 // Compute units of the current device (256 on MI355X); falls back to that when no device answers.
 int device_cus() {
-  static int cached = 0;
-  if (cached > 0) return cached;
+  static int cached[kMaxDevices] = {};
   int dev = 0, n = 0;
-  if (hipGetDevice(&dev) == hipSuccess &&
-      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) {
-    cached = n;
-    return n;
+  if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) {
+    if (cached[dev] > 0) return cached[dev];
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) {
+      cached[dev] = n;
+      return n;
+    }
   }
   (void)hipGetLastError();
   return 256;

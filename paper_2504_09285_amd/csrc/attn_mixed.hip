@@ -61,9 +61,11 @@ int launch_mixed_t(const prefill_impl::TilesParams& tp, const rows_impl::RowsPar
   constexpr int kRowsMax = 8 * 2 * rows_impl::RowGeom<D, KV8 ? 1 : 2>::SLOT_BYTES;
   constexpr int kMaxLds = kRowsMax > (int)prefill_impl::TileGeom<D>::LDS_BYTES ? kRowsMax
                                                                               : (int)prefill_impl::TileGeom<D>::LDS_BYTES;
-  static bool configured = false;     // idempotent; a race between two first calls is benign
+  static OncePerDevice once;     // idempotent; a race between two first calls is benign
+  bool* const configured = once.flag();
+  if (!configured) return DSV_E_LAUNCH;
   if (lds > kMaxLds) return DSV_E_UNSUPPORTED;
-  if (!configured) {
+  if (!*configured) {
     hipFuncAttributes fa;               // no static LDS: the tile body's ring must start at LDS address 0
     if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(mixed_kernel<D, KV8>)) != hipSuccess ||
         fa.sharedSizeBytes != 0)
@@ -71,7 +73,7 @@ int launch_mixed_t(const prefill_impl::TilesParams& tp, const rows_impl::RowsPar
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(mixed_kernel<D, KV8>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds) != hipSuccess)
       return DSV_E_LAUNCH;
-    configured = true;
+    *configured = true;
   }
   hipLaunchKernelGGL((mixed_kernel<D, KV8>), dim3(mp.total_groups * kGroup), dim3(512), lds, stream, tp, rp, mp);
   return launch_status();
@@ -108,8 +110,10 @@ int launch_mixed_stream_t(const prefill_impl::TilesParams& tp, const rows_impl::
   constexpr int kRowsLds = 8 * (2 * RG::SLOT_BYTES + RG::KS * 1024);
   constexpr int kTilesLds = (int)prefill_impl::TileGeom<D>::LDS_BYTES;
   constexpr int kLds = kRowsLds > kTilesLds ? kRowsLds : kTilesLds;
-  static bool configured = false;     // idempotent; a race between two first calls is benign
-  if (!configured) {
+  static OncePerDevice once;     // idempotent; a race between two first calls is benign
+  bool* const configured = once.flag();
+  if (!configured) return DSV_E_LAUNCH;
+  if (!*configured) {
     hipFuncAttributes fa;               // no static LDS: the tile body's ring must start at LDS address 0
     if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(mixed_stream_kernel<D, KV8>)) != hipSuccess ||
         fa.sharedSizeBytes != 0)
@@ -117,7 +121,7 @@ int launch_mixed_stream_t(const prefill_impl::TilesParams& tp, const rows_impl::
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(mixed_stream_kernel<D, KV8>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kLds) != hipSuccess)
       return DSV_E_LAUNCH;
-    configured = true;
+    *configured = true;
   }
   hipLaunchKernelGGL((mixed_stream_kernel<D, KV8>), dim3(row_wgs + tile_wgs), dim3(512), kLds, stream, tp, rp, row_wgs);
   return launch_status();

@@ -25,8 +25,10 @@ __global__ __launch_bounds__(kThreads, kThreads / 256) void prefill_tiles_persis
 
 template <int D>
 int launch_persistent_t(const TilesParams& prm, int grid, hipStream_t stream) {
-  static bool configured = false;       // raising the dynamic-LDS limit is idempotent; races are benign
-  if (!configured) {
+  static OncePerDevice once;       // raising the dynamic-LDS limit is idempotent; races are benign
+  bool* const configured = once.flag();
+  if (!configured) return DSV_E_LAUNCH;
+  if (!*configured) {
     hipFuncAttributes fa;               // no static LDS: the ring must start at LDS address 0
     if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(prefill_tiles_persistent_kernel<D>)) != hipSuccess ||
         fa.sharedSizeBytes != 0)
@@ -34,7 +36,7 @@ int launch_persistent_t(const TilesParams& prm, int grid, hipStream_t stream) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_tiles_persistent_kernel<D>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, TileGeom<D>::LDS_BYTES_PERSISTENT) != hipSuccess)
       return DSV_E_LAUNCH;
-    configured = true;
+    *configured = true;
   }
   hipLaunchKernelGGL((prefill_tiles_persistent_kernel<D>), dim3((unsigned)grid), dim3(kThreads), TileGeom<D>::LDS_BYTES_PERSISTENT,
                      stream, prm);
@@ -43,8 +45,10 @@ int launch_persistent_t(const TilesParams& prm, int grid, hipStream_t stream) {
 
 template <int D>
 int launch_t(const TilesParams& prm, dim3 grid, hipStream_t stream) {
-  static bool configured = false;       // raising the dynamic-LDS limit is idempotent; races are benign
-  if (!configured) {
+  static OncePerDevice once;       // raising the dynamic-LDS limit is idempotent; races are benign
+  bool* const configured = once.flag();
+  if (!configured) return DSV_E_LAUNCH;
+  if (!*configured) {
     // The kernel steps through its LDS ring by address bits: the ring must start at LDS
     // address 0, i.e. the kernel must have no static LDS in front of the dynamic part.
     hipFuncAttributes fa;
@@ -54,7 +58,7 @@ int launch_t(const TilesParams& prm, dim3 grid, hipStream_t stream) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_tiles_kernel<D>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, TileGeom<D>::LDS_BYTES) != hipSuccess)
       return DSV_E_LAUNCH;
-    configured = true;
+    *configured = true;
   }
   hipLaunchKernelGGL((prefill_tiles_kernel<D>), grid, dim3(kThreads), TileGeom<D>::LDS_BYTES, stream, prm);
   return launch_status();

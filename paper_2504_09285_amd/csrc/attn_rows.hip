@@ -23,13 +23,15 @@ int launch_rows_t(const RowsParams& prm, dim3 grid, int waves, hipStream_t strea
   constexpr int kMaxLds = 8 * R * RowGeom<D, KV8 ? 1 : 2>::SLOT_BYTES <= 160 * 1024
                               ? 8 * R * RowGeom<D, KV8 ? 1 : 2>::SLOT_BYTES
                               : 4 * R * RowGeom<D, KV8 ? 1 : 2>::SLOT_BYTES;
-  static bool configured = false;     // idempotent; a race between two first calls is benign
+  static OncePerDevice once;     // idempotent; a race between two first calls is benign
+  bool* const configured = once.flag();
+  if (!configured) return DSV_E_LAUNCH;
   if (lds > kMaxLds) return DSV_E_UNSUPPORTED;
-  if (!configured) {
+  if (!*configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(rows_kernel<D, R, KV8>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds) != hipSuccess)
       return DSV_E_LAUNCH;
-    configured = true;
+    *configured = true;
   }
   hipLaunchKernelGGL((rows_kernel<D, R, KV8>), grid, dim3(waves * kWave), lds, stream, prm);
   return launch_status();
@@ -47,12 +49,14 @@ int launch_rows_stream_t(const RowsParams& prm, int wgs, int waves, hipStream_t 
   constexpr int kSlot = RowGeom<D, KV8 ? 1 : 2>::SLOT_BYTES;
   constexpr int kQStage = RowGeom<D, KV8 ? 1 : 2>::KS * 1024;      // per wave: its query fragments
   constexpr int kMaxLds = 8 * (2 * kSlot + kQStage);
-  static bool configured = false;     // idempotent; a race between two first calls is benign
-  if (!configured) {
+  static OncePerDevice once;     // idempotent; a race between two first calls is benign
+  bool* const configured = once.flag();
+  if (!configured) return DSV_E_LAUNCH;
+  if (!*configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(rows_stream_kernel<D, KV8>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds) != hipSuccess)
       return DSV_E_LAUNCH;
-    configured = true;
+    *configured = true;
   }
   hipLaunchKernelGGL((rows_stream_kernel<D, KV8>), dim3((unsigned)wgs), dim3(waves * kWave), waves * (2 * kSlot + kQStage), stream, prm);
   return launch_status();

@@ -163,12 +163,14 @@ extern "C" int dsv_calib_paged_read(const void* k, const void* v, size_t bytes_e
   const uint64_t blocks = bytes_each / kPagedBlock;
   if (blocks < (uint64_t)kPagedPerItem || (blocks & (blocks - 1)) || blocks * kPagedBlock != bytes_each) return DSV_E_INVALID;
   if (blocks > 0x40000000ull) return DSV_E_UNSUPPORTED;
-  static bool configured = false;       // raising the dynamic-LDS limit is idempotent; races are benign
-  if (!configured) {
+  static OncePerDevice once;       // raising the dynamic-LDS limit is idempotent; races are benign
+  bool* const configured = once.flag();
+  if (!configured) return DSV_E_LAUNCH;
+  if (!*configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(paged_read_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                             128 * 1024) != hipSuccess)
       return DSV_E_LAUNCH;
-    configured = true;
+    *configured = true;
   }
   if (bytes_out) *bytes_out = 2.0 * (double)bytes_each;
   begin_gpu_work();

@@ -38,4 +38,21 @@ inline int launch_status() {
   return hipGetLastError() == hipSuccess ? DSV_OK : DSV_E_LAUNCH;
 }
 
+// Set-up that HIP keeps per device (a kernel's dynamic-LDS limit) is done once per device: a
+// launcher owns one of these as a function-local static and asks it for the current device's
+// flag.  Setting the same limit twice is harmless, so two first calls that race are too.
+constexpr int kMaxDevices = 64;
+struct OncePerDevice {
+  bool done[kMaxDevices] = {};
+  // The current device's flag, or nullptr when HIP names no device (or one beyond kMaxDevices).
+  bool* flag() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    return &done[dev];
+  }
+};
+
 }  // namespace dsv
