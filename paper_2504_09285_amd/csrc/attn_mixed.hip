@@ -10,7 +10,7 @@
 // Groups are eight consecutive workgroups: the hardware deals consecutive workgroups to the
 // eight XCDs in turn, so a group of tile workgroups still puts KV head k on XCD k (see
 // attn_prefill_kernel.h), and heaviest-first tile order is kept.
-#include "attn_prefill_kernel.h"
+#include "attn_prefill_kernel16.h"
 #include "attn_rows_kernel.h"
 #include "attn_rows_stream.h"
 
@@ -43,7 +43,7 @@ __global__ __launch_bounds__(512, 2) void mixed_kernel(prefill_impl::TilesParams
     if (wg >= mp.tile_wgs) return;                               // uniform for the workgroup
     int bx, bz;
     prefill_impl::tile_work_item(wg, tp.a.Hkv, tp.head_groups, bx, bz);
-    prefill_impl::prefill_tiles_body<D>(tp, bx, bz, smem);
+    prefill_impl::prefill_tiles_item<D>(tp, bx, bz, smem);
   } else {
     const uint32_t wg = (g - t0) * kGroup + lane_in_group;
     if (wg >= mp.row_wgs) return;
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(512, 2) void mixed_stream_kernel(prefill_impl::Tile
   } else {
     int bx, bz;
     prefill_impl::tile_work_item(blockIdx.x - row_wgs, tp.a.Hkv, tp.head_groups, bx, bz);
-    prefill_impl::prefill_tiles_body<D>(tp, bx, bz, smem);
+    prefill_impl::prefill_tiles_item<D>(tp, bx, bz, smem);
   }
 }
 
