@@ -723,13 +723,19 @@ def bench_power(threads, hev):
         flops[0] = dsv.dsv_calib_mfma(4000, sink)
 
     def mfma_data():
-        flops[0] = dsv.dsv_calib_mfma_data(4000, operands, sink)
+        flops[0] = dsv.dsv_calib_mfma_data(4000, operands, sink, shape=1)
+
+    def mfma_data32():
+        flops[0] = dsv.dsv_calib_mfma_data(4000, operands, sink, shape=0)
     r = power_under(mfma_fixed, sensors, batch=4)
     r["TFLOP/s"] = flops[0] / (r["ms_per_call"] * 1e-3) / 1e12
     out["mfma_loop_fixed_operands"] = r
     r = power_under(mfma_data, sensors, batch=4)
     r["TFLOP/s"] = flops[0] / (r["ms_per_call"] * 1e-3) / 1e12
     out["mfma_loop_random_operands"] = r
+    r = power_under(mfma_data32, sensors, batch=4)
+    r["TFLOP/s"] = flops[0] / (r["ms_per_call"] * 1e-3) / 1e12
+    out["mfma_loop_32x32x16_random_operands"] = r
     r = power_under(lambda: dsv.dsv_calib_hbm(0, sink, src, n), sensors)
     r["GB/s"] = n / (r["ms_per_call"] * 1e-3) / 1e9
     out["hbm_read_loop"] = r
@@ -800,12 +806,14 @@ def measure_ceilings(hev):
     g.manual_seed(92856)
     operands = torch.randn(1 << 20, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
 
-    def mfma_data():
-        flops[0] = dsv.dsv_calib_mfma_data(4000, operands, sink)
-    for _ in range(20):                       # the clock settles under the load before anything is timed
-        mfma_data()
-    ms = timed(mfma_data, reps=4)
-    out["mfma_bf16_random_operands_TFLOP/s"] = flops[0] / (ms * 1e-3) / 1e12
+    # (16x16x32 is the MFMA the head_dim-128 prefill kernels are built on; 32x32x16 for comparison)
+    for key, shape in (("mfma_bf16_random_operands_TFLOP/s", 1), ("mfma_bf16_32x32x16_random_operands_TFLOP/s", 0)):
+        def mfma_data():
+            flops[0] = dsv.dsv_calib_mfma_data(4000, operands, sink, shape=shape)
+        for _ in range(20):                   # the clock settles under the load before anything is timed
+            mfma_data()
+        ms = timed(mfma_data, reps=4)
+        out[key] = flops[0] / (ms * 1e-3) / 1e12
     del src, dst
     return out
 
@@ -909,6 +917,12 @@ def roofline_entry(kernel, workload, bound, achieved, unit, ms, algorithmic, not
     return e
 
 
+def prefill_kernel_name(head_dim):
+    """The kernel that runs prefill spans in a launch of their own: built on the 16x16x32 MFMA for
+    head_dim 128, on the 32x32x16 one for head_dim 64."""
+    return "prefill_tiles_persistent16_kernel" if head_dim == 128 else "prefill_tiles_persistent_kernel"
+
+
 def attention_rooflines(res, b):
     out = []
     k = res["kernel_ms"]
@@ -918,7 +932,7 @@ def attention_rooflines(res, b):
                                   p["algorithmic_bytes"]))
     if "prefill" in res:
         p = res["prefill"]
-        out.append(roofline_entry("prefill_tiles_persistent_kernel", b.name, "mfma", p["TFLOP/s"], "TFLOP/s", k["tiles"],
+        out.append(roofline_entry(prefill_kernel_name(b.D), b.name, "mfma", p["TFLOP/s"], "TFLOP/s", k["tiles"],
                                   p["algorithmic_flops"], note="the spans' MFMA kernel in a launch of its own"))
     return out
 
@@ -1039,7 +1053,7 @@ def main():
                           "achieved": c4["frac_of_overlap_bound"], "peak": 1.0, "traffic": None})
         rooflines.append(roofline_entry(c4["rows_kernel"], c4["workload"], "hbm", c4["decode"]["GB/s"], "GB/s",
                                         c4["kernel_ms"]["rows"], c4["decode_bytes"], note="launched apart from the tiles"))
-        rooflines.append(roofline_entry("prefill_tiles_persistent_kernel", c4["workload"], "mfma", c4["prefill"]["TFLOP/s"], "TFLOP/s",
+        rooflines.append(roofline_entry(prefill_kernel_name(128), c4["workload"], "mfma", c4["prefill"]["TFLOP/s"], "TFLOP/s",
                                         c4["kernel_ms"]["tiles"], c4["prefill_flops"], note="launched apart from the rows"))
         if not args.no_cpu_baseline:
             cpu.append(cpu_baseline(gen.config4(threads=threads)[0], 3.0))

@@ -407,7 +407,9 @@ int dsv_profile_events(int32_t kernel_id, void* start_event, void* stop_event);
  *                   of bf16 values the caller chose, 256 .. 2^30, a multiple of 16) and cycles
  *                   through them.  The power the matrix cores draw follows the operand bits that
  *                   toggle, so on random data this loop, not dsv_calib_mfma's fixed operands, shows
- *                   what the chip sustains within its power limit.  iters: a multiple of 8.
+ *                   what the chip sustains within its power limit.  shape 0: 32x32x16 MFMAs,
+ *                   1: 16x16x32 (what the head_dim-128 prefill kernels use; the same flops per
+ *                   launch).  iters: a multiple of 8.
  *   dsv_calib_paged_read  the row kernel's access shape with nothing else: k and v (device,
  *                   bytes_each bytes each, a power-of-two number of 32 KiB blocks, at least 64) are
  *                   read as pools of [16 tokens][8 heads][256 bytes] blocks visited in a scattered
@@ -418,8 +420,8 @@ int dsv_profile_events(int32_t kernel_id, void* start_event, void* stop_event);
  * Each enqueues one kernel on hip_stream and returns; errors as for the other entry points.
  */
 int dsv_calib_hbm(int32_t mode, void* dst, const void* src, size_t bytes, void* hip_stream);
-int dsv_calib_mfma_data(int32_t iters, const void* operands, size_t operand_bytes, void* sink, double* flops_out,
-                        void* hip_stream);
+int dsv_calib_mfma_data(int32_t shape, int32_t iters, const void* operands, size_t operand_bytes, void* sink,
+                        double* flops_out, void* hip_stream);
 int dsv_calib_paged_read(const void* k, const void* v, size_t bytes_each, void* sink, double* bytes_out,
                          void* hip_stream);
 int dsv_calib_mfma(int32_t iters, void* sink, double* flops_out, void* hip_stream);

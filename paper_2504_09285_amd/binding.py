@@ -128,7 +128,7 @@ def load_library():
     lib.dsv_calib_mfma.restype = C.c_int
     lib.dsv_calib_mfma.argtypes = [C.c_int32, vp, C.POINTER(C.c_double), vp]
     lib.dsv_calib_mfma_data.restype = C.c_int
-    lib.dsv_calib_mfma_data.argtypes = [C.c_int32, vp, C.c_size_t, vp, C.POINTER(C.c_double), vp]
+    lib.dsv_calib_mfma_data.argtypes = [C.c_int32, C.c_int32, vp, C.c_size_t, vp, C.POINTER(C.c_double), vp]
     lib.dsv_calib_paged_read.restype = C.c_int
     lib.dsv_calib_paged_read.argtypes = [vp, vp, C.c_size_t, vp, C.POINTER(C.c_double), vp]
     lib.dsv_profile_events.restype = C.c_int
@@ -455,11 +455,12 @@ def dsv_calib_mfma(iters: int, sink, stream=None) -> float:
     return float(flops.value)
 
 
-def dsv_calib_mfma_data(iters: int, operands, sink, stream=None) -> float:
-    """See ``dsv_calib_mfma_data`` in include/dsv_attn.h; returns the flops of the launch."""
+def dsv_calib_mfma_data(iters: int, operands, sink, shape: int = 1, stream=None) -> float:
+    """See ``dsv_calib_mfma_data`` in include/dsv_attn.h (shape 0: 32x32x16 MFMAs, 1: 16x16x32);
+    returns the flops of the launch."""
     _require(operands.is_contiguous(), "operands must be contiguous")
     flops = C.c_double()
-    rc = load_library().dsv_calib_mfma_data(int(iters), operands.data_ptr(), _nbytes(operands), sink.data_ptr(),
+    rc = load_library().dsv_calib_mfma_data(int(shape), int(iters), operands.data_ptr(), _nbytes(operands), sink.data_ptr(),
                                             C.byref(flops), _stream_ptr(stream))
     if rc:
         raise DsvError("dsv_calib_mfma_data", rc)

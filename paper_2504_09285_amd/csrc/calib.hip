@@ -70,17 +70,15 @@ __global__ __launch_bounds__(512, 2) void mfma_kernel(float* sink, int iters) {
 
 // The same loop on operands that change from one MFMA to the next, as they do in a real product:
 // every lane loads eight A and eight B fragments (16 bytes each) from a buffer of bf16 values the
-// caller filled, and MFMA (i, j) of an unrolled group of 64 multiplies A[(i + j) % 8] with B[j] into
+// caller filled, and MFMA (i, j) of an unrolled group multiplies A[(i + j) % 8] with B[j] into
 // accumulator i.  What the matrix cores draw depends on how many operand bits toggle, so this loop,
 // not the one above, shows what the chip sustains within its power limit on data like the
-// attention kernel's.
+// attention kernel's.  SHAPE 0: 32x32x16 MFMAs on eight accumulators; 1: 16x16x32 on sixteen
+// (the same flops per iteration and per launch).
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+template <int SHAPE>
 __global__ __launch_bounds__(512, 2) void mfma_data_kernel(const uint4* __restrict__ operands, uint32_t frags,
                                                            float* sink, int iters) {
-  f32x16_t acc[kMfmaPerIter];
-#pragma unroll
-  for (int i = 0; i < kMfmaPerIter; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
   uint4 a[8], b[8];
   const uint32_t first = (blockIdx.x * 512u + threadIdx.x) * 16u;
 #pragma unroll
@@ -88,19 +86,42 @@ __global__ __launch_bounds__(512, 2) void mfma_data_kernel(const uint4* __restri
     a[i] = operands[(first + (uint32_t)i) % frags];
     b[i] = operands[(first + 8u + (uint32_t)i) % frags];
   }
-  for (int it = 0; it < iters; it += 8) {
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-#pragma unroll
-      for (int i = 0; i < kMfmaPerIter; ++i)
-        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a[(i + j) % 8]),
-                                                         __builtin_bit_cast(bf16x8_t, b[j]), acc[i], 0, 0, 0);
-  }
   float s = 0.f;
+  if constexpr (SHAPE == 0) {
+    f32x16_t acc[kMfmaPerIter];
 #pragma unroll
-  for (int i = 0; i < kMfmaPerIter; ++i)
+    for (int i = 0; i < kMfmaPerIter; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s += acc[i][r];
+      for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    for (int it = 0; it < iters; it += 8) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int i = 0; i < kMfmaPerIter; ++i)
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a[(i + j) % 8]),
+                                                           __builtin_bit_cast(bf16x8_t, b[j]), acc[i], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < kMfmaPerIter; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s += acc[i][r];
+  } else {
+    f32x4_t acc[2 * kMfmaPerIter];
+#pragma unroll
+    for (int i = 0; i < 2 * kMfmaPerIter; ++i) acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; it += 8) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int i = 0; i < 2 * kMfmaPerIter; ++i)
+          acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[(i + j) % 8]),
+                                                           __builtin_bit_cast(bf16x8_t, b[j]), acc[i], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 2 * kMfmaPerIter; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) s += acc[i][r];
+  }
   if (s == 1.2345678e-30f) sink[0] = s;          // practically never: keeps the accumulators alive
 }
 
@@ -197,10 +218,10 @@ extern "C" int dsv_calib_hbm(int32_t mode, void* dst, const void* src, size_t by
   return launch_status();
 }
 
-extern "C" int dsv_calib_mfma_data(int32_t iters, const void* operands, size_t operand_bytes, void* sink,
+extern "C" int dsv_calib_mfma_data(int32_t shape, int32_t iters, const void* operands, size_t operand_bytes, void* sink,
                                    double* flops_out, void* hip_stream) {
   using namespace dsv;
-  if (iters < 8 || (iters & 7) || !sink || !operands || operand_bytes < 256 || (operand_bytes & 15) ||
+  if (shape < 0 || shape > 1 || iters < 8 || (iters & 7) || !sink || !operands || operand_bytes < 256 || (operand_bytes & 15) ||
       operand_bytes > 0x40000000ull || (reinterpret_cast<uintptr_t>(operands) & 15))
     return DSV_E_INVALID;
   int dev = 0, cus = 0;
@@ -212,8 +233,12 @@ extern "C" int dsv_calib_mfma_data(int32_t iters, const void* operands, size_t o
   const int grid = cus * 4;
   if (flops_out) *flops_out = (double)grid * 8 /*waves*/ * iters * kMfmaPerIter * (2.0 * 32 * 32 * 16);
   begin_gpu_work();
-  hipLaunchKernelGGL(mfma_data_kernel, dim3((unsigned)grid), dim3(512), 0, static_cast<hipStream_t>(hip_stream),
-                     static_cast<const uint4*>(operands), (uint32_t)(operand_bytes / 16), static_cast<float*>(sink), iters);
+  if (shape == 0)
+    hipLaunchKernelGGL(mfma_data_kernel<0>, dim3((unsigned)grid), dim3(512), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<const uint4*>(operands), (uint32_t)(operand_bytes / 16), static_cast<float*>(sink), iters);
+  else
+    hipLaunchKernelGGL(mfma_data_kernel<1>, dim3((unsigned)grid), dim3(512), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<const uint4*>(operands), (uint32_t)(operand_bytes / 16), static_cast<float*>(sink), iters);
   return launch_status();
 }
 

@@ -66,7 +66,10 @@ def test_mfma_loop_on_caller_operands_reports_its_flops_and_checks_its_arguments
     ops = torch.randn(4096, generator=g, device="cuda").to(torch.bfloat16)
     keep = ops.clone()
     fixed = dsv.dsv_calib_mfma(16, sink)
-    assert dsv.dsv_calib_mfma_data(16, ops, sink) == fixed      # same launch shape, same count
+    assert dsv.dsv_calib_mfma_data(16, ops, sink, shape=0) == fixed      # same launch shape, same count
+    assert dsv.dsv_calib_mfma_data(16, ops, sink, shape=1) == fixed      # 16x16x32: twice the MFMAs of half the size
+    with pytest.raises(dsv.DsvError):
+        dsv.dsv_calib_mfma_data(16, ops, sink, shape=2)
     torch.cuda.synchronize()
     assert torch.equal(ops, keep) and float(sink.abs().max()) == 0.0
     for iters, operands in ((12, ops), (0, ops), (16, ops[:64]), (16, ops[1:4001])):   # not a multiple of 8; too few; misaligned
