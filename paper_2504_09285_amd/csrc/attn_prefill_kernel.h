@@ -17,6 +17,10 @@
 // at LDS address 0 (the kernel owns no static LDS; the launchers check), so the fragment read
 // addresses step from buffer to buffer by an XOR of two address bits.
 //
+// (This header holds the tile geometry, the ring, the helpers and the body built on the 32x32x16
+// MFMA, which serves head_dim 64; head_dim 128 runs the same schedule on the 16x16x32 MFMA:
+// attn_prefill_kernel16.h, attn_prefill_persistent16.h.)
+//
 // The products are computed transposed, S^T = K Q^T and O^T = V^T P^T, with the 32x32x16 MFMA:
 //   - the query row is the MFMA column, so a lane owns one query row for the whole kernel: row
 //     max / sum / rescale are per-lane scalars (one exchange with the lane holding the other 16

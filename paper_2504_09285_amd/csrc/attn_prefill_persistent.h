@@ -1,5 +1,8 @@
 // Attention of long prefill spans on the matrix cores, persistent form.
 //
+// (This is the form on the 32x32x16 MFMA, which serves head_dim 64; attn_prefill_persistent16.h is
+// the same kernel on the 16x16x32 MFMA for head_dim 128.)
+//
 // The computation, the tile shapes, the LDS ring, the fragment layouts and the software pipeline
 // over 32-token sub-tiles are those of attn_prefill_kernel.h (read that header first).  What
 // changes is who runs a work item: here a workgroup stays on its compute unit and takes one item
