@@ -7,7 +7,7 @@
 // operands like these cost about a tenth less energy per flop than the 32x32x16 ones, and this
 // kernel runs at the board's power limit.
 //
-// A wave still owns 32 query rows of one head, now as two 16-row MFMA columns blocks (qt = 0, 1):
+// A wave still owns 32 query rows of one head, now as two 16-row blocks of MFMA columns (qt = 0, 1):
 // lane l holds query rows 16*qt + l%16 and, of every 16-token group, the tokens 4*(l/16) .. +3.
 //   - K fragment (A operand, 16 tokens x 32 dims): lane (token l%16, dims 8*(l/16) .. +7 of the
 //     k-step), one ds_read_b128; each is used for both query blocks.
@@ -54,7 +54,7 @@ __device__ __forceinline__ void prefill_tiles_persistent16(const TilesParams& pr
   };
   const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave);
   // The lane index, made afresh wherever the code between two items needs it (and what derives
-  // from it: row jrow = lane % 32 of the wave's 32 query rows, half hh = lane / 32), so that none
+  // from it: row lane % 16 of a 16-row query block, lane group lane / 16), so that none
   // of it occupies a vector register across the tile loop, which has none to spare.
   auto lane_id = [&]() __attribute__((always_inline)) -> int {
     int l = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
