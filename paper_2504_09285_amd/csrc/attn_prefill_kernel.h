@@ -86,13 +86,21 @@ struct TilesParams {
   int32_t tile_q;              // query tokens per work item (64, or 256 / flat_heads)
   int32_t flat_heads;          // see PlanConfig
   int32_t head_groups;
+  int32_t flat_magic;          // ceil(65536 / flat_heads) (0 if flat_heads is 0): see flat_div()
 };
+
+// Row r (< 256) of a flat work item is the pair (token r / gh, head r % gh).  The quotient comes
+// from a multiplication, not from the thirty-odd instructions of an integer division (the row
+// geometry is worked out for a dozen rows at every item boundary, where no MFMA hides it): with
+// magic = ceil(65536 / gh), (r * magic) >> 16 == r / gh for every r < 256 and gh < 256.
+__host__ __device__ inline int flat_div(int r, int magic) { return (r * magic) >> 16; }
 
 // Parameters of a launch over the tile list.  A cache of 8-bit codes is attended through the
 // staged bf16 copy of the spans' contexts and its own block table.
 inline TilesParams make_tiles_params(const AttnArgs& a, const WorkLists& w, const PlanConfig& cfg,
                                      const PlanCounts& n) {
-  TilesParams prm{a, w, (int32_t)n.tiles, a.Hq / a.Hkv, nullptr, cfg.tile_tokens, cfg.flat_heads, cfg.head_groups};
+  TilesParams prm{a, w, (int32_t)n.tiles, a.Hq / a.Hkv, nullptr, cfg.tile_tokens, cfg.flat_heads, cfg.head_groups,
+                  cfg.flat_heads > 0 ? (65536 + cfg.flat_heads - 1) / cfg.flat_heads : 0};
   if (a.kv8) {
     prm.a.k_pool = w.stage_k;
     prm.a.v_pool = w.stage_v;
@@ -264,7 +272,8 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
   const int gh = prm.flat_heads;
   const bool flat = gh > 0;
   const int row_in_item = 32 * wave + jrow;
-  const int wave_first_tok = flat ? (32 * wave) / gh : 32 * tg;     // first query token of the wave, from j0
+  const int fmagic = prm.flat_magic;
+  const int wave_first_tok = flat ? flat_div(32 * wave, fmagic) : 32 * tg;   // first query token of the wave, from j0
 
   // Workgroups are dispatched in index order (bx) and dealt round-robin to the eight XCDs: the
   // KV head is the fastest index, so the heaviest tiles (the list is sorted) of every head start
@@ -294,7 +303,7 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
   const int NS = 2 * n_tiles;                                  // 32-token sub-tiles
 
   // Query fragments: B operand of S^T = K Q^T; lane (jrow, hh) holds dims 16*ks + 8*hh .. +8.
-  const int jq = flat ? j0 + row_in_item / gh : j0 + 32 * tg + jrow;    // new-token index of this lane's query row
+  const int jq = flat ? j0 + flat_div(row_in_item, fmagic) : j0 + 32 * tg + jrow;    // new-token index of this lane's query row
   const int p_j = prefix + jq - pos0;    // its position, counted from the partition's first token
   // (wave-uniform) Does any of this wave's 32 query rows, for any of its heads, exist?
   const bool wave_has_rows = flat ? (j0 + wave_first_tok < q_len && 32 * wave < prm.tile_q * gh)
@@ -305,7 +314,7 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
   static_assert(D * 2 <= 256, "a query row fits the zero line");
 #pragma unroll
   for (int c = 0; c < NH; ++c) {
-    const int hsub = flat ? bz * gh + row_in_item % gh : bz * 4 + hp * NH + c;
+    const int hsub = flat ? bz * gh + (row_in_item - flat_div(row_in_item, fmagic) * gh) : bz * 4 + hp * NH + c;
     head_ok[c] = hsub < prm.G && jq < q_len && (!flat || row_in_item < prm.tile_q * gh);
     head[c] = kvh * prm.G + (hsub < prm.G ? hsub : 0);
     // A row that does not exist reads the zero line: the choice is made on the address, so the
@@ -752,8 +761,8 @@ __device__ __forceinline__ void prefill_tiles_body(const TilesParams& prm, int b
       const int row = ps * 8 + rr;
       r_adr[ps] = stage + (uint32_t)row * 128u + (uint32_t)((ch ^ ((row >> 1) & 7)) * 16);
       const int r_item = 32 * wave + row;
-      const int jq_r = flat ? j0 + r_item / gh : j0 + 32 * tg + row;
-      const int hsub = flat ? bz * gh + r_item % gh : bz * 4 + hp * NH;
+      const int jq_r = flat ? j0 + flat_div(r_item, fmagic) : j0 + 32 * tg + row;
+      const int hsub = flat ? bz * gh + (r_item - flat_div(r_item, fmagic) * gh) : bz * 4 + hp * NH;
       r_ok[ps] = hsub < prm.G && jq_r < q_len && (!flat || r_item < prm.tile_q * gh);
       const int head_r = kvh * prm.G + (hsub < prm.G ? hsub : 0);
       r_dst[ps] = partial ? (((int64_t)first_partial + (int64_t)(jq_r - j0) * nparts + part) * a.Hq + head_r) * D

@@ -45,7 +45,8 @@ __device__ __forceinline__ void prefill_tiles_body16(const TilesParams& prm, int
   // position, its head's rows of Q and of the output) is per lane already.
   const int gh = prm.flat_heads;
   const bool flat = gh > 0;
-  const int wave_first_tok = flat ? (32 * wave) / gh : 32 * tg;     // first query token of the wave, from j0
+  const int fmagic = prm.flat_magic;
+  const int wave_first_tok = flat ? flat_div(32 * wave, fmagic) : 32 * tg;   // first query token of the wave, from j0
 
   // Workgroups are dispatched in index order (bx) and dealt round-robin to the eight XCDs: the
   // KV head is the fastest index, so the heaviest tiles (the list is sorted) of every head start
@@ -86,9 +87,9 @@ __device__ __forceinline__ void prefill_tiles_body16(const TilesParams& prm, int
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
     const int row = 16 * qt + r16, r_item = 32 * wave + row;
-    jq[qt] = flat ? j0 + r_item / gh : j0 + 32 * tg + row;       // new-token index of this query row
+    jq[qt] = flat ? j0 + flat_div(r_item, fmagic) : j0 + 32 * tg + row;       // new-token index of this query row
     p_j[qt] = prefix + jq[qt] - pos0 - 4 * g;                    // its position in the partition, the lane's group folded in
-    const int hsub = flat ? bz * gh + r_item % gh : bz * 4 + hp * NH;
+    const int hsub = flat ? bz * gh + (r_item - flat_div(r_item, fmagic) * gh) : bz * 4 + hp * NH;
     head_ok[qt] = hsub < prm.G && jq[qt] < q_len && (!flat || r_item < prm.tile_q * gh);
     head[qt] = kvh * prm.G + (hsub < prm.G ? hsub : 0);
     // A row that does not exist reads the zero line: the choice is made on the address, so the
@@ -509,8 +510,8 @@ __device__ __forceinline__ void prefill_tiles_body16(const TilesParams& prm, int
       const int row = ps * 8 + rr;
       r_adr[ps] = stage_lds + (uint32_t)row * 128u + (uint32_t)((ch ^ ((row >> 1) & 7)) * 16);
       const int r_item = 32 * wave + row;
-      const int jq_r = flat ? j0 + r_item / gh : j0 + 32 * tg + row;
-      const int hsub = flat ? bz * gh + r_item % gh : bz * 4 + hp * NH;
+      const int jq_r = flat ? j0 + flat_div(r_item, fmagic) : j0 + 32 * tg + row;
+      const int hsub = flat ? bz * gh + (r_item - flat_div(r_item, fmagic) * gh) : bz * 4 + hp * NH;
       r_ok[ps] = hsub < prm.G && jq_r < q_len && (!flat || r_item < prm.tile_q * gh);
       const int head_r = kvh * prm.G + (hsub < prm.G ? hsub : 0);
       r_dst[ps] = partial ? (((int64_t)first_partial + (int64_t)(jq_r - j0) * nparts + part) * a.Hq + head_r) * D

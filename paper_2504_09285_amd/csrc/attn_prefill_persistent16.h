@@ -244,25 +244,26 @@ __device__ __forceinline__ void prefill_tiles_persistent16(const TilesParams& pr
   // exists, its first token, and which of the two waves of its SIMD it is.
   auto row_geometry = [&](const Item& it, int row, int& jq_o, int& head_o, bool& ok_o) __attribute__((always_inline)) {
     const params_ptr pp = P();
-    const int gh = pp->flat_heads, tile_q = pp->tile_q;
+    const int gh = pp->flat_heads, tile_q = pp->tile_q, fmagic = pp->flat_magic;
     const bool flat = gh > 0;
     const bool few_heads = G - it.bz * 4 <= 2;
     const int tg = few_heads ? wave % 2 : wave / kHeadWaves;
     const int hp = few_heads ? wave / 2 : wave % kHeadWaves;
     const int r_item = 32 * wave + row;
-    jq_o = flat ? it.j0 + r_item / gh : it.j0 + 32 * tg + row;
-    const int hsub = flat ? it.bz * gh + r_item % gh : it.bz * 4 + hp * NH;
+    const int jq_flat = flat_div(r_item, fmagic);
+    jq_o = flat ? it.j0 + jq_flat : it.j0 + 32 * tg + row;
+    const int hsub = flat ? it.bz * gh + (r_item - jq_flat * gh) : it.bz * 4 + hp * NH;
     ok_o = hsub < G && jq_o < it.q_len && (!flat || r_item < tile_q * gh);
     head_o = kvh * G + (hsub < G ? hsub : 0);
   };
   auto wave_geometry = [&](const Item& it, bool& rows_o, int& first_tok_o, int& prio_o) __attribute__((always_inline)) {
     const params_ptr pp = P();
-    const int gh = pp->flat_heads, tile_q = pp->tile_q;
+    const int gh = pp->flat_heads, tile_q = pp->tile_q, fmagic = pp->flat_magic;
     const bool flat = gh > 0;
     const bool few_heads = G - it.bz * 4 <= 2;
     const int tg = few_heads ? wave % 2 : wave / kHeadWaves;
     const int hp = few_heads ? wave / 2 : wave % kHeadWaves;
-    first_tok_o = flat ? (32 * wave) / gh : 32 * tg;
+    first_tok_o = flat ? flat_div(32 * wave, fmagic) : 32 * tg;
     rows_o = flat ? (it.j0 + first_tok_o < it.q_len && 32 * wave < tile_q * gh)
                   : (it.j0 + 32 * tg < it.q_len && it.bz * 4 + hp * NH < G);
     prio_o = flat ? wave / 4 : tg;
